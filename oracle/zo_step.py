@@ -1,0 +1,169 @@
+"""Oracle (test infrastructure): the zeroth-order SGD step.
+
+Three forms of the same step, all on float32 parameters:
+
+  step_literal   Alg. 1 as printed: perturb in place by +eps, by -2 eps, by +eps,
+                 then update, regenerating z from the step seed each time.
+  step_whole     Alg. 1 with the restore made exact: theta is never overwritten
+                 by a perturbation; W+ = theta + eps z and W- = theta - eps z are
+                 formed as copies (Eq. 2), then theta <- theta - eta g z (Eq. 3).
+  Zo2Blockwise   Alg. 2 + Sec. 5.4: the model is walked module by module
+                 (Embedding, W_1..W_N, LM head); each module first applies the
+                 update left pending by the previous iteration (its g, its seed,
+                 its learning rate), then is perturbed both ways and run on the
+                 two activation streams.  The last g stays pending until flush().
+
+Arithmetic shared by the last two ("canonical"): one fused multiply-add per
+element, a*b+c evaluated exactly and rounded once to float32; then, if the
+parameters are held in a low-bit transfer format (Sec. 5.5), rounded to it.
+  theta' = store(fma(-c, z_prev, theta)),   c = float32(eta_prev * g_prev)
+  W+-    = compute(fma(+-eps, z, theta'))
+  l+-    = float32(L(W+-; B)),  g = float32(float32(l+ - l-) / float32(2 eps))
+"""
+import numpy as np
+
+from . import codec, opt_model, philox
+
+
+def _fma32(a, b, c):
+    """float32(a*b + c) for float32 inputs.  The product of two float32 values is
+    exact in float64; the float64 sum rounds once more before the final rounding
+    to float32 (a double rounding that differs from a true fused multiply-add
+    only when the float64 sum lands exactly on a float32 midpoint)."""
+    return (np.float64(a) * np.asarray(b, dtype=np.float64) + np.asarray(c, dtype=np.float64)).astype(np.float32)
+
+
+def _store(x, fmt, scale=1.0):
+    """Round float32 x to the parameter storage format (value returned as float32)."""
+    if fmt == "f32":
+        return np.asarray(x, dtype=np.float32)
+    if scale != 1.0:
+        return (codec.round_to(np.float64(x) * scale, fmt).astype(np.float64) / scale).astype(np.float32)
+    return codec.round_to(x, fmt)
+
+
+def z_of(shape_cfg, seed, names=None):
+    """z for the named tensors (default: all) at step seed `seed`."""
+    out = {}
+    for name, tid, shp in opt_model.tensor_table(shape_cfg):
+        if names is None or name in names:
+            out[name] = philox.gaussian(seed, tid, 0, int(np.prod(shp))).reshape(shp)
+    return out
+
+
+def projected_gradient(lp, lm, eps):
+    """Eq. 2 in float32: g = (l+ - l-) / (2 eps)."""
+    lp = np.float32(lp)
+    lm = np.float32(lm)
+    return np.float32(np.float32(lp - lm) / np.float32(np.float32(2.0) * np.float32(eps)))
+
+
+# --------------------------------------------------------------------------- Alg. 1, literal
+def step_literal(cfg, P, tokens, labels, seed, eps, lr):
+    """Alg. 1 line by line, float32, each multiply and add rounded separately.
+    P (name -> float32 array) is modified in place.  Returns (l+, l-, g)."""
+    eps32 = np.float32(eps)
+
+    def perturb(scale):
+        z = z_of(cfg, seed)                     # "reset RNG with seed s", then draw
+        for name in P:
+            P[name] = (P[name] + np.float32(scale) * z[name]).astype(np.float32)
+
+    perturb(eps32)
+    lp = np.float32(opt_model.loss(cfg, P, tokens, labels))
+    perturb(np.float32(-2.0) * eps32)
+    lm = np.float32(opt_model.loss(cfg, P, tokens, labels))
+    perturb(eps32)
+    g = projected_gradient(lp, lm, eps)
+    z = z_of(cfg, seed)
+    step = np.float32(np.float32(lr) * g)
+    for name in P:
+        P[name] = (P[name] - step * z[name]).astype(np.float32)
+    return lp, lm, g
+
+
+# --------------------------------------------------------------------------- Alg. 1, exact restore
+def step_whole(cfg, P, tokens, labels, seed, eps, lr, store="f32", compute="f32", scales=None):
+    """Whole-model step with canonical arithmetic.  P modified in place."""
+    scales = scales or {}
+    z = z_of(cfg, seed)
+    eps32 = np.float32(eps)
+    Wp = {n: _store(_fma32(eps32, z[n], P[n]), compute) for n in P}
+    lp = np.float32(opt_model.loss(cfg, Wp, tokens, labels))
+    del Wp
+    Wm = {n: _store(_fma32(-eps32, z[n], P[n]), compute) for n in P}
+    lm = np.float32(opt_model.loss(cfg, Wm, tokens, labels))
+    del Wm
+    g = projected_gradient(lp, lm, eps)
+    c = np.float32(np.float32(lr) * g)
+    for n in P:
+        P[n] = _store(_fma32(-c, z[n], P[n]), store, scales.get(n, 1.0))
+    return lp, lm, g
+
+
+# --------------------------------------------------------------------------- Alg. 2 + deferred update
+class Zo2Blockwise:
+    """Alg. 2 with the update of iteration j-1 applied when each module is
+    visited in iteration j (Sec. 5.4).  `pending` = (g, seed, lr) of the last
+    iteration, or None."""
+
+    def __init__(self, cfg, P, store="f32", compute="f32", scales=None):
+        self.cfg = cfg
+        self.P = P
+        self.store = store
+        self.compute = compute
+        self.scales = scales or {}
+        self.pending = None
+        self.ids = {name: tid for name, tid, _ in opt_model.tensor_table(cfg)}
+
+    def _z(self, name, seed):
+        a = self.P[name]
+        return philox.gaussian(seed, self.ids[name], 0, a.size).reshape(a.shape)
+
+    def _update_module(self, names):
+        if self.pending is None:
+            return
+        g, seed, lr = self.pending
+        c = np.float32(np.float32(lr) * np.float32(g))
+        for n in names:
+            self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0))
+
+    def _perturbed(self, names, seed, eps_signed):
+        return {n: _store(_fma32(np.float32(eps_signed), self._z(n, seed), self.P[n]), self.compute) for n in names}
+
+    def step(self, tokens, labels, seed, eps, lr):
+        cfg = self.cfg
+        mods = opt_model.modules(cfg)
+        acts = [None, None]
+        signs = (np.float32(eps), -np.float32(eps))
+        # Embedding
+        self._update_module(mods[0])
+        for k in (0, 1):
+            W = self._perturbed(mods[0], seed, signs[k])
+            acts[k] = opt_model.embed(cfg, W, tokens)
+        # transformer blocks
+        for l in range(cfg.n_layers):
+            names = mods[1 + l]
+            self._update_module(names)
+            for k in (0, 1):
+                W = self._perturbed(names, seed, signs[k])
+                acts[k] = opt_model.block_forward(cfg, W, l, acts[k])
+        # LM head (its tied weight was already updated with the embedding module)
+        names = mods[-1]
+        self._update_module(names)
+        losses = []
+        for k in (0, 1):
+            W = self._perturbed(names, seed, signs[k])
+            if cfg.tied:
+                W.update(self._perturbed(["tok_emb"], seed, signs[k]))
+            lg = opt_model.head_logits(cfg, W, acts[k])
+            losses.append(np.float32(opt_model.cross_entropy(lg, labels)))
+        g = projected_gradient(losses[0], losses[1], eps)
+        self.pending = (g, seed, lr)
+        return losses[0], losses[1], g
+
+    def flush(self):
+        """Apply the update still pending after the last iteration."""
+        for names in opt_model.modules(self.cfg):
+            self._update_module(names)
+        self.pending = None

@@ -1,0 +1,97 @@
+"""Pins for the oracle's random direction z (run without a GPU)."""
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import philox
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _kat():
+    rows = []
+    with open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([int(x, 16) for x in line.split()])
+    return rows
+
+
+def test_philox_known_answers():
+    rows = _kat()
+    assert len(rows) == 3
+    for r in rows:
+        out = philox.philox4x32_10(r[0], r[1], r[2], r[3], r[4], r[5])
+        assert [int(np.asarray(x).reshape(-1)[0]) for x in out] == r[6:10]
+
+
+def test_philox_vectorised_matches_scalar():
+    c0 = np.array([0, 0xFFFFFFFF, 0x243F6A88, 7], dtype=np.uint32)
+    out = philox.philox4x32_10(c0, 5, 9, 0, 0xDEADBEEF, 0x12345678)
+    for i, c in enumerate(c0):
+        one = philox.philox4x32_10(int(c), 5, 9, 0, 0xDEADBEEF, 0x12345678)
+        assert [int(o[i]) for o in out] == [int(np.asarray(x).reshape(-1)[0]) for x in one]
+
+
+def test_word_addressing():
+    """Element e takes word e&3 of call e>>2 with counter (lo(q), hi(q), tensor, 0) and
+    key (lo(seed), hi(seed)); the 64-bit element index and seed really use both halves."""
+    seed = (0xABCDEF01 << 32) | 0x13572468
+    e0 = (1 << 34) + 6
+    w = philox.random_words(seed, 77, e0, 9)
+    for i in range(9):
+        e = e0 + i
+        q = e >> 2
+        x = philox.philox4x32_10(q & 0xFFFFFFFF, q >> 32, 77, 0, seed & 0xFFFFFFFF, seed >> 32)
+        assert int(w[i]) == int(np.asarray(x[e & 3]).reshape(-1)[0])
+    # a different tensor id, seed half or high index word changes the stream
+    assert not np.array_equal(w, philox.random_words(seed, 78, e0, 9))
+    assert not np.array_equal(w, philox.random_words(seed ^ (1 << 40), 77, e0, 9))
+    assert not np.array_equal(w, philox.random_words(seed, 77, e0 - (1 << 34), 9))
+
+
+def test_gaussian_window_invariance():
+    """z depends on (seed, tensor, e) only: any window / piece cut gives the same values."""
+    full = philox.gaussian(42, 3, 0, 5000)
+    for e0, n in ((0, 1), (1, 7), (2, 4), (3, 1001), (4093, 907)):
+        assert np.array_equal(full[e0:e0 + n], philox.gaussian(42, 3, e0, n))
+    big = philox.gaussian(7, 1, 5, (1 << 21) + 3)            # crosses the threaded path's cuts
+    assert np.array_equal(big, philox._gaussian_piece(7, 1, 5, (1 << 21) + 3))
+    assert np.array_equal(philox.gaussian(42, 3, 0, 64), philox.gaussian(42, 3, 0, 64))
+
+
+def test_gaussian_box_muller_structure():
+    """Elements (4q, 4q+1) share a radius rho = sqrt(-2 ln u1) taken from word 0 and an
+    angle from word 1; (4q+2, 4q+3) use words 2 and 3."""
+    w = philox.random_words(9, 4, 0, 4096).astype(np.float64).reshape(-1, 4)
+    z = philox.gaussian(9, 4, 0, 4096).astype(np.float64).reshape(-1, 4)
+    for a in (0, 2):
+        u1 = (np.floor(w[:, a] / 256) + 1) / 2 ** 24
+        u2 = np.floor(w[:, a + 1] / 256) / 2 ** 24
+        r2 = z[:, a] ** 2 + z[:, a + 1] ** 2
+        assert np.allclose(r2, -2 * np.log(u1), rtol=1e-5, atol=1e-6)
+        ang = np.mod(np.arctan2(z[:, a + 1], z[:, a]) / (2 * np.pi), 1.0)
+        ok = r2 > 1e-3
+        d = np.abs(ang - u2)[ok]
+        assert np.all(np.minimum(d, 1 - d) < 1e-5)
+
+
+def test_gaussian_distribution():
+    n = 1 << 20
+    z = philox.gaussian(42, 2, 0, n).astype(np.float64)
+    assert abs(z.mean()) < 4 / np.sqrt(n)
+    assert abs(z.var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs(stats.skew(z)) < 0.02 and abs(stats.kurtosis(z)) < 0.03
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    assert np.abs(z).max() <= np.sqrt(-2 * np.log(2.0 ** -24)) + 1e-6      # 5.768
+    # no linear correlation between neighbours, tensors, seeds (consecutive steps)
+    z_t = philox.gaussian(42, 3, 0, n).astype(np.float64)
+    z_s = philox.gaussian(43, 2, 0, n).astype(np.float64)
+    lim = 5 / np.sqrt(n)
+    assert abs(np.mean(z[:-1] * z[1:])) < lim
+    assert abs(np.mean(z[0::4] * z[2::4])) < lim * 2
+    assert abs(np.mean(z * z_t)) < lim
+    assert abs(np.mean(z * z_s)) < lim

@@ -1,0 +1,141 @@
+"""Pins for the oracle's ZO-SGD step (run without a GPU)."""
+import copy
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import opt_model, philox, zo_step
+
+from hf_reference import hf_param_grads
+
+
+def _setup(tied=True, std=0.1, seed=1):
+    cfg = si.tiny_config(n_layers=2, d_model=32, n_heads=4, d_ffn=64, vocab=97, max_pos=24, tied=tied)
+    P = si.make_weights(cfg, seed=seed, std=std, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 2, 11, seed=2)
+    return cfg, opt_model.OptShape(**cfg), P, tok, si.next_token_labels(tok)
+
+
+def _loss64_at(s, P, z, t, tok, lab):
+    W = {n: P[n].astype(np.float64) + t * z[n].astype(np.float64) for n in P}
+    return opt_model.loss(s, W, tok, lab)
+
+
+@pytest.mark.parametrize("tied", [True, False])
+def test_projected_gradient_is_directional_derivative(tied):
+    """Eq. 2: g -> z . grad L as eps -> 0.  grad L comes from autograd through an
+    independently written module.  The ReLU FFN makes L only piecewise smooth, so the
+    generic case is checked at an eps small enough that no unit switches (float64),
+    and the O(eps^2) law of the central difference is checked where L is smooth along
+    the whole segment (FFN biases shifted so that every unit stays active)."""
+    cfg, s, P, tok, lab = _setup(tied=tied)
+    z = zo_step.z_of(s, 42)
+    _, grads = hf_param_grads(cfg, P, tok, lab)
+    dd = sum(float(np.sum(grads[n] * z[n].astype(np.float64))) for n in P)
+    g = (_loss64_at(s, P, z, 1e-6, tok, lab) - _loss64_at(s, P, z, -1e-6, tok, lab)) / 2e-6
+    assert abs(g - dd) < 1e-6 * abs(dd)          # the module's float32 softmax limits dd to ~1e-7
+
+    for l in range(cfg["n_layers"]):
+        P[f"blocks.{l}.fc1.b"] = P[f"blocks.{l}.fc1.b"] + np.float32(4.0)
+    _, grads = hf_param_grads(cfg, P, tok, lab)
+    dd = sum(float(np.sum(grads[n] * z[n].astype(np.float64))) for n in P)
+    errs = []
+    for eps in (4e-3, 2e-3, 1e-3):
+        g = (_loss64_at(s, P, z, eps, tok, lab) - _loss64_at(s, P, z, -eps, tok, lab)) / (2 * eps)
+        errs.append(abs(g - dd))
+    assert errs[2] < 2e-3 * abs(dd)
+    assert 3.8 < errs[0] / errs[1] < 4.2 and 3.8 < errs[1] / errs[2] < 4.2      # error ~ eps^2
+    # the float32 step (canonical arithmetic) reports the same number up to the
+    # cancellation in l+ - l-: |dg| <= ulp32(l) / (2 eps) ~ 5e-7 * 5 / 2e-3
+    lp, lm, g32 = zo_step.step_whole(s, copy.deepcopy(P), tok, lab, 42, 1e-3, 0.0)
+    assert abs(float(g32) - dd) < errs[2] + 2.5e-3
+
+
+def test_update_uses_the_same_z_and_sign():
+    """Eq. 3: theta_new = theta - eta g z with the z of Eq. 2."""
+    cfg, s, P, tok, lab = _setup()
+    P0 = copy.deepcopy(P)
+    lp, lm, g = zo_step.step_whole(s, P, tok, lab, 42, 1e-3, 1e-4)
+    assert g != 0
+    z = zo_step.z_of(s, 42)
+    for n in P:
+        want = P0[n].astype(np.float64) - 1e-4 * float(g) * z[n].astype(np.float64)
+        assert np.abs(P[n] - want).max() < 2e-7, n
+    # a first-order check of descent direction: moving along -g z lowers the loss
+    assert opt_model.loss(s, P, tok, lab) < opt_model.loss(s, P0, tok, lab)
+
+
+def test_literal_sequence_vs_exact_restore():
+    """Alg. 1 as printed (in-place +eps, -2eps, +eps, update) against the canonical
+    copy-based form: same losses up to float32 rounding of the perturbation, and
+    parameters within a few float32 ulps per step."""
+    cfg, s, P, tok, lab = _setup()
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    for j in range(3):
+        la = zo_step.step_literal(s, Pa, tok, lab, 42 + j, 1e-3, 1e-3)
+        lb = zo_step.step_whole(s, Pb, tok, lab, 42 + j, 1e-3, 1e-3)
+        assert abs(float(la[0]) - float(lb[0])) < 2e-6 * abs(float(lb[0]))
+        assert abs(float(la[1]) - float(lb[1])) < 2e-6 * abs(float(lb[1]))
+        for n in P:
+            ulp = np.spacing(np.abs(Pb[n]) + np.float32(6e-3))
+            assert np.all(np.abs(Pa[n] - Pb[n]) <= 4 * (j + 1) * ulp), (j, n)
+
+
+@pytest.mark.parametrize("tied", [True, False])
+def test_blockwise_deferred_equals_whole_model(tied):
+    """Alg. 2 with the deferred update (Sec. 5.4) reproduces Alg. 1 exactly: the same
+    l+, l- at every iteration and, after the pending update is applied, the same theta."""
+    cfg, s, P, tok, lab = _setup(tied=tied)
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    zo = zo_step.Zo2Blockwise(s, Pb)
+    for j in range(4):
+        lr = 1e-3 * (j + 1)                     # eta_j travels with g_j
+        a = zo_step.step_whole(s, Pa, tok, lab, 100 + j, 1e-3, lr)
+        b = zo.step(tok, lab, 100 + j, 1e-3, lr)
+        assert tuple(map(float, a)) == tuple(map(float, b)), j
+    assert any(not np.array_equal(Pa[n], Pb[n]) for n in P)     # last update still pending
+    zo.flush()
+    for n in P:
+        assert np.array_equal(Pa[n], Pb[n]), n
+
+
+def test_zero_learning_rate_and_sign_symmetry():
+    cfg, s, P, tok, lab = _setup()
+    P0 = copy.deepcopy(P)
+    zo = zo_step.Zo2Blockwise(s, P)
+    r1 = zo.step(tok, lab, 5, 1e-3, 0.0)
+    r2 = zo.step(tok, lab, 5, -1e-3, 0.0)
+    zo.flush()
+    for n in P:
+        assert np.array_equal(P[n], P0[n])
+    assert float(r1[0]) == float(r2[1]) and float(r1[1]) == float(r2[0])
+    assert float(r1[2]) == float(r2[2])
+
+
+def test_same_seed_same_step_different_seed_different_step():
+    cfg, s, P, tok, lab = _setup()
+    a = zo_step.step_whole(s, copy.deepcopy(P), tok, lab, 42, 1e-3, 1e-3)
+    b = zo_step.step_whole(s, copy.deepcopy(P), tok, lab, 42, 1e-3, 1e-3)
+    c = zo_step.step_whole(s, copy.deepcopy(P), tok, lab, 43, 1e-3, 1e-3)
+    assert tuple(map(float, a)) == tuple(map(float, b))
+    assert float(a[2]) != float(c[2])
+
+
+def test_low_bit_storage_step_keeps_parameters_representable():
+    """Sec. 5.5: with parameters held in bf16 the updated theta is again a bf16 value,
+    W+- are bf16 values, and blockwise == whole-model still holds."""
+    from oracle import codec
+    cfg, s, P, tok, lab = _setup()
+    P = {n: codec.round_to(a, "bf16") for n, a in P.items()}
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    zo = zo_step.Zo2Blockwise(s, Pb, store="bf16", compute="bf16")
+    for j in range(2):
+        a = zo_step.step_whole(s, Pa, tok, lab, 9 + j, 1e-3, 5e-2, store="bf16", compute="bf16")
+        b = zo.step(tok, lab, 9 + j, 1e-3, 5e-2)
+        assert tuple(map(float, a)) == tuple(map(float, b))
+    zo.flush()
+    for n in P:
+        assert np.array_equal(Pa[n], Pb[n])
+        assert np.array_equal(codec.round_to(Pa[n], "bf16"), Pa[n])
+    assert any(not np.array_equal(Pa[n], P[n]) for n in P)

@@ -1,0 +1,209 @@
+/*
+ * zo2.h -- C ABI of libzo2: the zeroth-order (MeZO / SPSA) fine-tuning step of ZO2
+ * over an OPT-shaped decoder on one AMD MI355X (gfx950).
+ *
+ * Two layers of entry points:
+ *
+ *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_flush /
+ *      zo2_sync_to_host / zo2_destroy.  One call of zo2_step is one iteration of the paper's
+ *      Alg. 2: for every module (embedding, decoder blocks, LM head) apply the update left
+ *      pending by the previous iteration, perturb by +eps z and -eps z, run both forwards,
+ *      and form the projected gradient g (Eq. 2).  Blocks that do not fit the HBM budget
+ *      live in host memory and are streamed (Alg. 3, Sec. 5.2-5.5).
+ *
+ *   2. zo2_op_*: the individual HIP kernels on caller-supplied device buffers, so that
+ *      each can be checked and timed alone at full problem shapes.
+ *
+ * Conventions for every function:
+ *   - plain C, no exceptions, no hidden global state; every call returns a zo2_status
+ *     (0 = success) and, on failure, leaves a message retrievable with zo2_last_error
+ *     (context calls) or zo2_op_last_error (op calls, thread local);
+ *   - "host" pointers are ordinary or pinned host memory; "device" pointers are HBM of the
+ *     current HIP device; `stream` arguments are hipStream_t passed as void* (NULL = the
+ *     default stream).  Op calls only enqueue work on that stream; they never synchronise;
+ *   - matrices are row-major; a linear layer's weight is [out_features, in_features];
+ *   - nothing here allocates device memory: the caller hands in an arena (context) or the
+ *     buffers themselves (ops).
+ */
+#ifndef ZO2_H
+#define ZO2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct zo2_ctx zo2_ctx;
+
+typedef enum {
+    ZO2_OK = 0,
+    ZO2_EINVAL = 1,     /* bad argument, shape or token / label id                      */
+    ZO2_ENOMEM = 2,     /* host allocation failed or the arena is too small             */
+    ZO2_EBUDGET = 3,    /* the HBM budget cannot hold embeddings + 3 block slots + work */
+    ZO2_EHIP = 4,       /* a HIP runtime call failed                                    */
+    ZO2_ESTATE = 5,     /* the context is unusable after an earlier ZO2_EHIP            */
+    ZO2_ENONFINITE = 6  /* a loss came out NaN or infinite (outputs are still written)  */
+} zo2_status;
+
+/* Storage formats.  F32/BF16/F16 may be compute formats; all five may be transfer
+ * ("wire") formats, i.e. the format parameters are held in on the host and in the
+ * upload slots (Sec. 5.5: bf16/fp16 halve, 8-bit floats quarter the fp32 volume).
+ * The 8-bit formats are the OCP E4M3 (no infinity, max 448) and E5M2 encodings,
+ * converted with round-to-nearest-even and saturation. */
+typedef enum { ZO2_F32 = 0, ZO2_BF16 = 1, ZO2_F16 = 2, ZO2_FP8_E4M3 = 3, ZO2_FP8_E5M2 = 4 } zo2_dtype;
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, d_ffn, vocab;
+    int32_t max_pos;        /* longest sequence; the position table has max_pos + pos_offset rows */
+    int32_t pos_offset;     /* row used for position t is t + pos_offset (2 for OPT)               */
+    int32_t tied_lm_head;   /* 1: the LM head is the token embedding (one tensor, one z)           */
+    int32_t wire_dtype;     /* zo2_dtype of the parameters in host memory and in the slots         */
+    int32_t compute_dtype;  /* zo2_dtype of W+ / W- and of the GEMM inputs: F32, BF16 or F16       */
+    float ln_eps;           /* LayerNorm epsilon (1e-5)                                            */
+} zo2_config;
+
+/* Parameter tensors are numbered for the random stream in module order (Alg. 2):
+ *   0 tok_emb [vocab, d]; 1 pos_emb [max_pos + pos_offset, d];
+ *   2 + 16 l + k for block l, k = 0..15 over
+ *     ln1.w ln1.b q.w q.b k.w k.b v.w v.b o.w o.b ln2.w ln2.b fc1.w fc1.b fc2.w fc2.b;
+ *   2 + 16 L, 3 + 16 L: final_ln.w, final_ln.b;  4 + 16 L: lm_head.w (only if untied).
+ * z of element e of tensor p at step seed s is a pure function of (s, p, e): Philox4x32-10
+ * with key (lo32 s, hi32 s) and counter (lo32 q, hi32 q, p, 0), q = e >> 2, output word e & 3;
+ * words (0,1) and (2,3) feed one Box-Muller pair each with 24-bit uniforms.  This replaces
+ * the saved / restored generator states of Alg. 2 (Sec. 5.1). */
+#define ZO2_BLOCK_TENSORS 16
+
+/* A block's 16 tensors are packed into one contiguous "bucket" (Sec. 5.3): tensor k starts
+ * at element offset offs[k], a multiple of 256 elements; offs[16] is the padded element
+ * count of the bucket.  The same element offsets hold for every dtype.  Returns ZO2_EINVAL
+ * if d_model or d_ffn is not a positive multiple of 8 or n_heads does not divide d_model. */
+zo2_status zo2_block_tensor_offsets(const zo2_config* cfg, int64_t offs[ZO2_BLOCK_TENSORS + 1]);
+size_t zo2_dtype_size(int32_t dtype);   /* bytes per element; 0 for an unknown dtype */
+
+typedef struct {
+    void* tok_emb;            /* host, [vocab, d], wire dtype                                     */
+    void* pos_emb;            /* host, [max_pos + pos_offset, d]                                   */
+    void* final_ln_w;         /* host, [d]                                                         */
+    void* final_ln_b;         /* host, [d]                                                         */
+    void* lm_head;            /* host, [vocab, d]; must be NULL when tied_lm_head = 1              */
+    void** block_bucket;      /* host array of n_layers host pointers, one bucket each; pinned
+                                 memory is needed for the streamed mode to overlap copies          */
+    const float* tensor_scale;/* host, one float per tensor id, or NULL (= all 1).  Stored value =
+                                 round(theta * scale); used by the 8-bit wire formats, ignored
+                                 (must be NULL or all 1) otherwise.  Powers of two keep it exact.  */
+} zo2_host_weights;
+
+typedef struct {
+    void* arena;              /* device memory the library may use, 256-byte aligned              */
+    size_t arena_bytes;
+    void* stream_compute;     /* hipStream_t; kernels                                             */
+    void* stream_upload;      /* hipStream_t; host -> device block copies                         */
+    void* stream_offload;     /* hipStream_t; device -> host block copies                         */
+} zo2_device;
+
+/* Create a context.  The host weight buffers are borrowed until zo2_destroy and are the
+ * master copy of every streamed block: they are overwritten in place as training proceeds
+ * (Sec. 4.2).  Embeddings, final LayerNorm and LM head are copied into the arena and stay
+ * there (Sec. 5.2); zo2_sync_to_host writes them back.  The arena and the three streams
+ * are borrowed too.  The initial budget is the whole arena.  Not thread safe. */
+zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_host_weights* w, const zo2_device* dev);
+
+/* Limit the arena bytes the library may touch (embeddings + block slots + W+/W- scratch +
+ * activations).  If every block fits, all blocks are kept resident and no copies are issued
+ * per step; otherwise blocks are streamed through a ring of >= 3 equal slots.  Takes effect
+ * at the next step (the plan also depends on that step's batch x seq).  Fails with
+ * ZO2_EBUDGET at that step if even 3 slots do not fit. */
+zo2_status zo2_set_resident_budget(zo2_ctx* ctx, size_t hbm_bytes);
+
+/* One ZO-SGD iteration (Alg. 2) on a batch.  tokens, labels: host int32 [batch, seq];
+ * labels[b, t] is the target of position t (the caller shifts), -100 = ignored.
+ * lr given here belongs to this iteration's g (eta_j): it is applied, with this seed's z,
+ * when each module is next visited (Sec. 5.4) or by zo2_flush.  Blocks until the three
+ * results are on the host:  *loss_plus = L(theta + eps z), *loss_minus = L(theta - eps z),
+ * *g = (l+ - l-) / (2 eps). */
+zo2_status zo2_step(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                    uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* g);
+
+/* Apply the pending update to every parameter now (Alg. 2 leaves the last g unapplied). */
+zo2_status zo2_flush(zo2_ctx* ctx);
+
+/* Copy device-resident parameters (embeddings, final LayerNorm, LM head, and the blocks when
+ * all are resident) back into the caller's host buffers.  Does not flush. */
+zo2_status zo2_sync_to_host(zo2_ctx* ctx);
+
+/* Facts about the plan used by the last step: how many block slots exist, whether blocks are
+ * resident, how many arena bytes are in use.  Any pointer may be NULL. */
+zo2_status zo2_get_plan(const zo2_ctx* ctx, int32_t* n_slots, int32_t* resident, size_t* bytes_used);
+
+/* Per-stream busy time of the last step in milliseconds (compute, upload, offload) and the
+ * bytes copied each way; for host-link rate reporting.  Any pointer may be NULL. */
+zo2_status zo2_get_step_stats(const zo2_ctx* ctx, float* ms_compute, float* ms_upload, float* ms_offload,
+                              uint64_t* bytes_up, uint64_t* bytes_down);
+
+const char* zo2_last_error(const zo2_ctx* ctx);
+void zo2_destroy(zo2_ctx* ctx);
+
+/* ------------------------------------------------------------------------------------
+ * Kernel-level entry points.  All pointers are device pointers unless named host_*.
+ * ------------------------------------------------------------------------------------ */
+
+const char* zo2_op_last_error(void);
+
+/* The 32 random bits of elements e0 .. e0+n-1 of tensor `tensor_id` at `seed` (test hook for
+ * the bit-exactness of the stream).  out: device uint32[n]. */
+zo2_status zo2_op_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, uint32_t* out, void* stream);
+
+/* z of the same elements as float32.  out: device float[n]. */
+zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, float* out, void* stream);
+
+/* Fused regenerate + update + perturb (Alg. 2 DualForward lines "update", "perturb";
+ * Sec. 5.4) over a window of one tensor:
+ *   theta'  = store_wire( fma(-c, z_prev, theta) )        (skipped when has_pending = 0)
+ *   w_plus  = store_compute( fma(+eps, z, theta') ),  w_minus = store_compute( fma(-eps, z, theta') )
+ * theta: n elements of wire dtype, element i being element e0 + i of the tensor; e0 and
+ * every pointer must be aligned to 8 elements.  theta is rewritten in place; w_plus /
+ * w_minus (compute dtype, n elements) may both be NULL for an update-only pass.
+ * scale: the tensor's wire scale (1 unless an 8-bit format uses one). */
+zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
+                                 uint32_t tensor_id, uint64_t e0, uint64_t n,
+                                 int32_t has_pending, uint64_t seed_prev, float c,
+                                 uint64_t seed, float eps, float scale, void* stream);
+
+/* Low-bit pack / unpack (Sec. 5.5): convert n elements between two storage formats,
+ * dst = store_dst(load_src(src) / scale_src * scale_dst). */
+zo2_status zo2_op_convert(const void* src, int32_t src_dtype, float src_scale,
+                          void* dst, int32_t dst_dtype, float dst_scale, uint64_t n, void* stream);
+
+/* Y[M, N] = act( (X[M, K] . W[N, K]^T + bias[N]) * out_scale ) + residual[M, N].
+ * X, W, bias: `dtype` (F32, BF16 or F16), leading dimensions ldx, ldw in elements;
+ * residual: float32 [M, ldy] or NULL; Y: out_dtype (F32 or `dtype`) with leading dimension ldy;
+ * relu: apply max(.,0) before the residual.  Accumulation is float32.  K must be a multiple of 8. */
+zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K,
+                       const void* X, int64_t ldx, const void* W, int64_t ldw, const void* bias,
+                       const float* residual, void* Y, int32_t out_dtype, int64_t ldy,
+                       float out_scale, int32_t relu, void* stream);
+
+/* Causal multi-head self-attention.  q, k, v, out: [n_seq * seq, ld] of `dtype`, head h in
+ * columns h*d_head .. (h+1)*d_head-1; q already carries the 1/sqrt(d_head) factor.
+ * out[i] = softmax_{j <= i}(q_i . k_j) v_j within each sequence.  d_head is 64 or 128 in the
+ * MFMA path; any multiple of 8 up to 128 otherwise. */
+zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
+                            int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head, int64_t ld, void* stream);
+
+/* y[r, :] = (x[r, :] - mean) / sqrt(var + eps) * w + b, biased variance; x float32 [rows, d],
+ * w, b, y of `dtype`.  Rows >= rows_first use w2 / b2 (the "-" stream's perturbed gain and
+ * bias); pass rows_first = rows to use w / b only. */
+zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2,
+                            void* y, int32_t rows, int32_t rows_first, int32_t d, float eps, void* stream);
+
+/* Row-wise cross-entropy of float32 logits [rows, ld] against labels (device int32, -100 =
+ * ignored): row_loss[r] = logsumexp(logits[r, :vocab]) - logits[r, label], or 0 if ignored. */
+zo2_status zo2_op_cross_entropy_rows(const float* logits, int64_t ld, const int32_t* labels, int32_t rows, int32_t vocab,
+                                     float* row_loss, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZO2_H */

@@ -128,35 +128,39 @@ class Zo2Blockwise:
         for n in names:
             self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0))
 
-    def _perturbed(self, names, seed, eps_signed):
-        return {n: _store(_fma32(np.float32(eps_signed), self._z(n, seed), self.P[n]), self.compute) for n in names}
+    def _perturbed_pair(self, names, seed, eps):
+        """(W+, W-) of a module: z drawn once, used with both signs (Eq. 2)."""
+        Wp, Wm = {}, {}
+        for n in names:
+            z = self._z(n, seed)
+            Wp[n] = _store(_fma32(np.float32(eps), z, self.P[n]), self.compute)
+            Wm[n] = _store(_fma32(-np.float32(eps), z, self.P[n]), self.compute)
+        return Wp, Wm
 
     def step(self, tokens, labels, seed, eps, lr):
         cfg = self.cfg
         mods = opt_model.modules(cfg)
-        acts = [None, None]
-        signs = (np.float32(eps), -np.float32(eps))
         # Embedding
         self._update_module(mods[0])
-        for k in (0, 1):
-            W = self._perturbed(mods[0], seed, signs[k])
-            acts[k] = opt_model.embed(cfg, W, tokens)
+        W = self._perturbed_pair(mods[0], seed, eps)
+        emb_W = W
+        acts = [opt_model.embed(cfg, W[k], tokens) for k in (0, 1)]
         # transformer blocks
         for l in range(cfg.n_layers):
             names = mods[1 + l]
             self._update_module(names)
-            for k in (0, 1):
-                W = self._perturbed(names, seed, signs[k])
-                acts[k] = opt_model.block_forward(cfg, W, l, acts[k])
+            W = self._perturbed_pair(names, seed, eps)
+            acts = [opt_model.block_forward(cfg, W[k], l, acts[k]) for k in (0, 1)]
         # LM head (its tied weight was already updated with the embedding module)
         names = mods[-1]
         self._update_module(names)
+        W = self._perturbed_pair(names, seed, eps)
         losses = []
         for k in (0, 1):
-            W = self._perturbed(names, seed, signs[k])
+            Wk = dict(W[k])
             if cfg.tied:
-                W.update(self._perturbed(["tok_emb"], seed, signs[k]))
-            lg = opt_model.head_logits(cfg, W, acts[k])
+                Wk["tok_emb"] = emb_W[k]["tok_emb"]
+            lg = opt_model.head_logits(cfg, Wk, acts[k])
             losses.append(np.float32(opt_model.cross_entropy(lg, labels)))
         g = projected_gradient(losses[0], losses[1], eps)
         self.pending = (g, seed, lr)

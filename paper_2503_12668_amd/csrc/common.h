@@ -1,0 +1,148 @@
+// Shared device helpers of libzo2: storage formats, error plumbing.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/zo2.h"
+
+namespace zo2 {
+
+typedef __bf16 bf16_t;
+typedef _Float16 f16_t;
+struct fp8_e4m3_t { uint8_t v; };
+struct fp8_e5m2_t { uint8_t v; };
+
+// ---------------------------------------------------------------- error plumbing (op level)
+void set_op_error(const char* fmt, ...);
+#define ZO2_OP_CHECK(cond, status, ...)        \
+    do {                                       \
+        if (!(cond)) {                         \
+            zo2::set_op_error(__VA_ARGS__);    \
+            return status;                     \
+        }                                      \
+    } while (0)
+#define ZO2_HIP_LAUNCH_CHECK()                                               \
+    do {                                                                     \
+        hipError_t e__ = hipGetLastError();                                  \
+        if (e__ != hipSuccess) {                                             \
+            zo2::set_op_error("HIP launch failed: %s", hipGetErrorString(e__)); \
+            return ZO2_EHIP;                                                 \
+        }                                                                    \
+    } while (0)
+
+// ---------------------------------------------------------------- scalar conversions
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// Round-to-nearest-even fp32 -> 8-bit float with EB exponent / MB mantissa bits, saturating
+// at the largest finite code MAXC.  NaN -> NANC.
+template <int EB, int MB, int BIAS, uint32_t MAXC, uint32_t NANC>
+__device__ __forceinline__ uint32_t encode_fp8(float x) {
+    const uint32_t u = f2u(x);
+    const uint32_t sign = (u >> 31) << 7;
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return sign | NANC;
+    // largest finite value of the format as fp32 bits
+    const uint32_t max_bits = ((MAXC >> MB) + (127 - BIAS)) << 23 | ((MAXC & ((1u << MB) - 1)) << (23 - MB));
+    if (a >= max_bits) return sign | MAXC;
+    const uint32_t min_normal_bits = (uint32_t)(1 + 127 - BIAS) << 23;
+    uint32_t code;
+    if (a < min_normal_bits) {
+        // subnormal target: multiples of 2^(1-BIAS-MB); rintf rounds to nearest even
+        const float q = u2f(a) * u2f((uint32_t)(127 + BIAS - 1 + MB) << 23);
+        code = (uint32_t)__builtin_rintf(q);
+    } else {
+        a += ((a >> (23 - MB)) & 1u) + ((1u << (22 - MB)) - 1u);
+        code = (a >> (23 - MB)) - ((uint32_t)(127 - BIAS) << MB);
+        code = code > MAXC ? MAXC : code;
+    }
+    return sign | code;
+}
+
+template <int EB, int MB, int BIAS, bool IEEE>
+__device__ __forceinline__ float decode_fp8(uint32_t c) {
+    const uint32_t sign = (c & 0x80u) << 24;
+    const uint32_t em = c & 0x7fu;
+    const uint32_t E = em >> MB, M = em & ((1u << MB) - 1);
+    float v;
+    if (E == 0) {
+        v = (float)M * u2f((uint32_t)(127 + 1 - BIAS - MB) << 23);
+    } else if (IEEE && E == (1u << EB) - 1) {
+        v = M ? u2f(0x7fc00000u) : u2f(0x7f800000u);
+    } else if (!IEEE && em == 0x7fu) {
+        v = u2f(0x7fc00000u);
+    } else {
+        v = u2f(((E + 127 - BIAS) << 23) | (M << (23 - MB)));
+    }
+    return u2f(f2u(v) | sign);
+}
+
+// ---------------------------------------------------------------- typed load / store of one element
+template <typename T> struct Fmt;
+template <> struct Fmt<float> {
+    static constexpr int kBytes = 4;
+    static __device__ __forceinline__ float load(float v) { return v; }
+    static __device__ __forceinline__ float store(float v) { return v; }
+};
+template <> struct Fmt<bf16_t> {
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ float load(bf16_t v) { return (float)v; }
+    static __device__ __forceinline__ bf16_t store(float v) { return (bf16_t)v; }
+};
+template <> struct Fmt<f16_t> {
+    static constexpr int kBytes = 2;
+    static __device__ __forceinline__ float load(f16_t v) { return (float)v; }
+    static __device__ __forceinline__ f16_t store(float v) { return (f16_t)v; }
+};
+template <> struct Fmt<fp8_e4m3_t> {
+    static constexpr int kBytes = 1;
+    static __device__ __forceinline__ float load(fp8_e4m3_t v) { return decode_fp8<4, 3, 7, false>(v.v); }
+    static __device__ __forceinline__ fp8_e4m3_t store(float v) {
+        return fp8_e4m3_t{(uint8_t)encode_fp8<4, 3, 7, 0x7eu, 0x7fu>(v)};
+    }
+};
+template <> struct Fmt<fp8_e5m2_t> {
+    static constexpr int kBytes = 1;
+    static __device__ __forceinline__ float load(fp8_e5m2_t v) { return decode_fp8<5, 2, 15, true>(v.v); }
+    static __device__ __forceinline__ fp8_e5m2_t store(float v) {
+        return fp8_e5m2_t{(uint8_t)encode_fp8<5, 2, 15, 0x7bu, 0x7eu>(v)};
+    }
+};
+
+// A group of N elements moved with one (or two) wide memory operations.
+template <typename T, int N>
+struct alignas(sizeof(T) * N) Vec {
+    T v[N];
+};
+
+template <typename T, int N>
+__device__ __forceinline__ Vec<T, N> load_vec(const T* p) {
+    return *reinterpret_cast<const Vec<T, N>*>(p);
+}
+template <typename T, int N>
+__device__ __forceinline__ void store_vec(T* p, const Vec<T, N>& v) {
+    *reinterpret_cast<Vec<T, N>*>(p) = v;
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// dispatch a zo2_dtype to a type tag
+#define ZO2_DISPATCH_WIRE(dt, T, ...)                                             \
+    switch (dt) {                                                                 \
+        case ZO2_F32: { typedef float T; __VA_ARGS__; break; }                    \
+        case ZO2_BF16: { typedef zo2::bf16_t T; __VA_ARGS__; break; }             \
+        case ZO2_F16: { typedef zo2::f16_t T; __VA_ARGS__; break; }               \
+        case ZO2_FP8_E4M3: { typedef zo2::fp8_e4m3_t T; __VA_ARGS__; break; }     \
+        case ZO2_FP8_E5M2: { typedef zo2::fp8_e5m2_t T; __VA_ARGS__; break; }     \
+        default: zo2::set_op_error("unknown dtype %d", (int)(dt)); return ZO2_EINVAL; \
+    }
+#define ZO2_DISPATCH_COMPUTE(dt, T, ...)                                          \
+    switch (dt) {                                                                 \
+        case ZO2_F32: { typedef float T; __VA_ARGS__; break; }                    \
+        case ZO2_BF16: { typedef zo2::bf16_t T; __VA_ARGS__; break; }             \
+        case ZO2_F16: { typedef zo2::f16_t T; __VA_ARGS__; break; }               \
+        default: zo2::set_op_error("dtype %d is not a compute dtype", (int)(dt)); return ZO2_EINVAL; \
+    }
+
+}  // namespace zo2

@@ -1,0 +1,243 @@
+// Projection GEMMs of the dual forward (Alg. 2 "forward"): Y = act((X W^T + b) s) + R.
+//
+// Both operands are K-contiguous (activations [M, K], weights [N, K]), which is exactly
+// the per-lane operand shape of the CDNA MFMA instructions: lane l of a wavefront supplies
+// 8 consecutive k of row l % 32.  So tiles go global -> LDS -> registers as 16-byte chunks
+// with no transposition; an XOR swizzle of the chunk index keeps the 128-bit LDS accesses
+// conflict free.  bf16 / fp16 inputs use v_mfma_f32_32x32x16 (float32 accumulate); the
+// float32 mode uses a register-tiled vector-ALU kernel.
+//
+// The +/- streams (and q, k, v) are independent problems of one shape: they share a launch
+// through grid.z so that even the narrow projections fill 256 compute units.
+#include "gemm.h"
+
+namespace zo2 {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+template <typename T> struct Mfma;
+template <> struct Mfma<bf16_t> {
+    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<f16_t> {
+    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// MFMA kernel.  Block tile BM x BN x 64, four wavefronts in a 2 x 2 grid, each owning a
+// (BM/2) x (BN/2) tile made of 32 x 32 MFMA tiles.  LDS holds two stages of 16-byte chunks:
+// chunk (row, kc) of a tile lives at index row * 8 + (kc ^ (row & 7)).
+// ---------------------------------------------------------------------------------------
+template <typename T, int BM, int BN, typename OutT>
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
+    constexpr int BK = 64, KC = BK / 8;            // 8 chunks of 8 elements per row
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int CA = BM * KC / 256, CB = BN * KC / 256;   // chunks each thread stages per tile
+    __shared__ uint4 lds[2][(BM + BN) * KC];
+
+    const GemmProblem p = a.p[blockIdx.z];
+    const int tiles_n = (a.N + BN - 1) / BN;
+    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, r = lane & 31, kh = lane >> 5;
+    const T* __restrict__ X = reinterpret_cast<const T*>(p.X);
+    const T* __restrict__ W = reinterpret_cast<const T*>(p.W);
+
+    // per-thread staging plan
+    const T* ga[CA];
+    const T* gb[CB];
+    int la[CA], lb[CB], kca[CA], kcb[CB];
+#pragma unroll
+    for (int i = 0; i < CA; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        const int m = min(m0 + row, a.M - 1);
+        ga[i] = X + (size_t)m * a.ldx + kc * 8;
+        la[i] = row * KC + (kc ^ (row & 7));
+        kca[i] = kc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        const int n = min(n0 + row, a.N - 1);
+        gb[i] = W + (size_t)n * a.ldw + kc * 8;
+        lb[i] = BM * KC + row * KC + (kc ^ (row & 7));
+        kcb[i] = kc * 8;
+    }
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint4 ra[CA], rb[CB];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    auto load_tile = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) ra[i] = (k0 + kca[i] < a.K) ? *reinterpret_cast<const uint4*>(ga[i] + k0) : zero4;
+#pragma unroll
+        for (int i = 0; i < CB; ++i) rb[i] = (k0 + kcb[i] < a.K) ? *reinterpret_cast<const uint4*>(gb[i] + k0) : zero4;
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) lds[buf][la[i]] = ra[i];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) lds[buf][lb[i]] = rb[i];
+    };
+
+    const int nk = (a.K + BK - 1) / BK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_tile((kt + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int kc = ks * 2 + kh;
+            uint4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * WM + i * 32 + r;
+                fa[i] = lds[cur][row * KC + (kc ^ (row & 7))];
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * WN + j * 32 + r;
+                fb[j] = lds[cur][BM * KC + row * KC + (kc ^ (row & 7))];
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::run(fa[i], fb[j], acc[i][j]);
+        }
+        if (kt + 1 < nk) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane holds column n = r of each 32 x 32 tile and rows 8 (v/4) + 4 kh + v%4
+    const T* __restrict__ bias = reinterpret_cast<const T*>(p.bias);
+    OutT* __restrict__ Y = reinterpret_cast<OutT*>(p.Y);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + r;
+        if (n >= a.N) continue;
+        const float bv = bias ? Fmt<T>::load(bias[n]) : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
+                if (m >= a.M) continue;
+                float y = (acc[i][j][v] + bv) * p.out_scale;
+                if (a.relu) y = fmaxf(y, 0.f);
+                const size_t o = (size_t)m * a.ldy + n;
+                if (p.residual) y += p.residual[o];
+                Y[o] = Fmt<OutT>::store(y);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// float32 kernel: 64 x 64 x 16 tiles, 256 threads, 4 x 4 outputs per thread.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs a) {
+    constexpr int BM = 64, BN = 64, BK = 16, PAD = 4;
+    __shared__ float As[BK][BM + PAD];
+    __shared__ float Bs[BK][BN + PAD];
+    const GemmProblem p = a.p[blockIdx.z];
+    const int tiles_n = (a.N + BN - 1) / BN;
+    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int lrow = tid >> 2, lk = (tid & 3) * 4;
+    const float* __restrict__ X = reinterpret_cast<const float*>(p.X);
+    const float* __restrict__ W = reinterpret_cast<const float*>(p.W);
+    const float* gx = X + (size_t)min(m0 + lrow, a.M - 1) * a.ldx + lk;
+    const float* gw = W + (size_t)min(n0 + lrow, a.N - 1) * a.ldw + lk;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < a.K; k0 += BK) {
+        float4 xa = make_float4(0, 0, 0, 0), wb = make_float4(0, 0, 0, 0);
+        if (k0 + lk < a.K) {
+            xa = *reinterpret_cast<const float4*>(gx + k0);
+            wb = *reinterpret_cast<const float4*>(gw + k0);
+        }
+        __syncthreads();
+        As[lk + 0][lrow] = xa.x; As[lk + 1][lrow] = xa.y; As[lk + 2][lrow] = xa.z; As[lk + 3][lrow] = xa.w;
+        Bs[lk + 0][lrow] = wb.x; Bs[lk + 1][lrow] = wb.y; Bs[lk + 2][lrow] = wb.z; Bs[lk + 3][lrow] = wb.w;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < BK; ++k) {
+            const float4 av = *reinterpret_cast<const float4*>(&As[k][ty * 4]);
+            const float4 bv = *reinterpret_cast<const float4*>(&Bs[k][tx * 4]);
+            const float ar[4] = {av.x, av.y, av.z, av.w}, br[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(ar[i], br[j], acc[i][j]);
+        }
+    }
+    const float* __restrict__ bias = reinterpret_cast<const float*>(p.bias);
+    float* __restrict__ Y = reinterpret_cast<float*>(p.Y);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m >= a.M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= a.N) continue;
+            float y = (acc[i][j] + (bias ? bias[n] : 0.f)) * p.out_scale;
+            if (a.relu) y = fmaxf(y, 0.f);
+            const size_t o = (size_t)m * a.ldy + n;
+            if (p.residual) y += p.residual[o];
+            Y[o] = y;
+        }
+    }
+}
+
+template <typename T>
+static zo2_status launch_mfma(const GemmArgs& a, hipStream_t st) {
+    constexpr int BM = 128, BN = 128;
+    const unsigned tiles = (unsigned)(((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN));
+    const dim3 grid(tiles, 1, a.nprob), block(256);
+    if (a.out_f32) hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, float>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, T>), grid, block, 0, st, a);
+    ZO2_HIP_LAUNCH_CHECK();
+    return ZO2_OK;
+}
+
+zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
+    ZO2_OP_CHECK(a.M >= 0 && a.N >= 0 && a.K > 0, ZO2_EINVAL, "gemm: bad shape %d x %d x %d", a.M, a.N, a.K);
+    if (a.M == 0 || a.N == 0 || a.nprob == 0) return ZO2_OK;
+    ZO2_OP_CHECK(a.K % 8 == 0, ZO2_EINVAL, "gemm: K = %d is not a multiple of 8", a.K);
+    ZO2_OP_CHECK(a.ldx >= a.K && a.ldw >= a.K && a.ldy >= a.N, ZO2_EINVAL, "gemm: leading dimension too small");
+    ZO2_OP_CHECK(a.ldx % 8 == 0 && a.ldw % 8 == 0, ZO2_EINVAL, "gemm: ldx / ldw must be multiples of 8");
+    ZO2_OP_CHECK(a.nprob >= 1 && a.nprob <= GemmArgs::kMaxProblems, ZO2_EINVAL, "gemm: %d problems", a.nprob);
+    for (int i = 0; i < a.nprob; ++i) {
+        ZO2_OP_CHECK(a.p[i].X && a.p[i].W && a.p[i].Y, ZO2_EINVAL, "gemm: NULL operand in problem %d", i);
+        ZO2_OP_CHECK(((uintptr_t)a.p[i].X & 15) == 0 && ((uintptr_t)a.p[i].W & 15) == 0, ZO2_EINVAL,
+                     "gemm: operands must be 16-byte aligned");
+    }
+    if (dtype == ZO2_F32) {
+        ZO2_OP_CHECK(a.out_f32, ZO2_EINVAL, "gemm: the float32 kernel writes float32 output");
+        const unsigned tiles = (unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64));
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
+        ZO2_HIP_LAUNCH_CHECK();
+        return ZO2_OK;
+    }
+    if (dtype == ZO2_BF16) return launch_mfma<bf16_t>(a, st);
+    if (dtype == ZO2_F16) return launch_mfma<f16_t>(a, st);
+    set_op_error("gemm: dtype %d is not a compute dtype", dtype);
+    return ZO2_EINVAL;
+}
+
+}  // namespace zo2

@@ -1,0 +1,37 @@
+// Launch interface of the fused update + perturb kernel (K1).
+#pragma once
+#include "common.h"
+#include "philox.h"
+
+namespace zo2 {
+
+struct K1Seg {
+    int64_t off;          // element offset of the segment inside the theta buffer
+    uint64_t e0;          // index, inside its tensor, of the segment's first element (multiple of 8)
+    uint64_t n;           // elements
+    uint32_t tensor_id;   // selects the random stream
+    float scale;          // wire scale of the tensor (8-bit formats), else 1
+    uint32_t first_chunk; // filled in by k1_launch
+    uint32_t pad_;
+};
+
+struct K1Args {
+    static constexpr int kMaxSeg = 16;
+    void* theta;          // wire dtype; rewritten in place when an update is pending
+    void* w_plus;         // compute dtype, addressed as w_plus[off - w_off0 + i]
+    void* w_minus;
+    int64_t w_off0;       // element offset (in theta's numbering) that maps to w_plus[0]
+    int32_t nseg;
+    uint32_t total_chunks;
+    float c_imm;          // eta_prev * g_prev, used when c_ptr == nullptr
+    float eps;
+    const float* c_ptr;   // device scalar holding eta_prev * g_prev (stays on the GPU between steps)
+    PhiloxKeys k_prev, k_cur;
+    K1Seg seg[kMaxSeg];
+};
+
+// Enqueue K1 over the segments.  update: apply theta' = theta - c z_prev; perturb: write W+, W-.
+zo2_status k1_launch(K1Args& a, int wire_dtype, int compute_dtype, bool update, bool perturb, hipStream_t st);
+uint32_t k1_chunks(uint64_t n);
+
+}  // namespace zo2

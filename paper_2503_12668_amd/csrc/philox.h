@@ -1,0 +1,64 @@
+// Counter-based random direction z (replaces the saved generator states of Alg. 2, Sec. 5.1):
+// Philox4x32-10 keyed by the step seed, counter = (element index / 4, tensor id), followed by
+// Box-Muller on 24-bit uniforms.  z[p, e] is a pure function of (seed, p, e).
+#pragma once
+#include "common.h"
+
+namespace zo2 {
+
+struct PhiloxKeys {   // the ten round keys of one seed, wave-uniform (live in SGPRs)
+    uint32_t k0[10], k1[10];
+};
+
+__host__ __device__ __forceinline__ PhiloxKeys philox_keys(uint64_t seed) {
+    PhiloxKeys k;
+    uint32_t a = (uint32_t)seed, b = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        k.k0[r] = a;
+        k.k1[r] = b;
+        a += 0x9E3779B9u;
+        b += 0xBB67AE85u;
+    }
+    return k;
+}
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              const PhiloxKeys& k, uint32_t out[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k.k0[r];
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k.k1[r];
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// One Box-Muller pair from two words: u1 = ((xa >> 8) + 1) / 2^24 in (0, 1],
+// u2 = (xb >> 8) / 2^24 in [0, 1); (rho cos 2 pi u2, rho sin 2 pi u2), rho = sqrt(-2 ln u1).
+// u1 and u2 are exact in fp32.  The hardware log2 / sqrt are 1-ulp operations; the
+// hardware sin / cos take their argument in revolutions, which u2 already is.
+__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& za, float& zb) {
+    const float u1 = (float)((xa >> 8) + 1u) * 5.9604644775390625e-08f;
+    const float u2 = (float)(xb >> 8) * 5.9604644775390625e-08f;
+    // -2 ln u1 = (-2 ln 2) log2 u1
+    const float t = -1.3862943611198906f * __builtin_amdgcn_logf(u1);
+    const float rho = __builtin_amdgcn_sqrtf(t);
+    za = rho * __builtin_amdgcn_cosf(u2);
+    zb = rho * __builtin_amdgcn_sinf(u2);
+}
+
+// z of elements 4q .. 4q+3 of tensor `tensor_id`.
+__device__ __forceinline__ void gaussian4(const PhiloxKeys& k, uint32_t tensor_id, uint64_t q, float z[4]) {
+    uint32_t w[4];
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, 0u, k, w);
+    box_muller(w[0], w[1], z[0], z[1]);
+    box_muller(w[2], w[3], z[2], z[3]);
+}
+
+}  // namespace zo2

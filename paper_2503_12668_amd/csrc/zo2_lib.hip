@@ -1,0 +1,821 @@
+// libzo2: the training context (Alg. 2 + Alg. 3) and the C ABI.
+//
+// One zo2_step enqueues, without any host-side wait inside the block loop:
+//   embedding gather (with on-the-fly update + perturb)  ->  for each decoder block
+//   { [upload] -> K1 (update + perturb) -> dual forward -> [offload] }  ->  final LayerNorm
+//   -> K1 on the LM-head weights -> LM head + cross-entropy -> g.
+// Upload, compute and offload run on three HIP streams tied together by events only
+// (Sec. 5.2); blocks cycle through a ring of equal slots carved out of the caller's arena
+// (Sec. 5.3); each block crosses the host link once per direction per step because the
+// update of iteration j-1 is applied when the block is visited in iteration j (Sec. 5.4).
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <vector>
+
+#include "attention.h"
+#include "common.h"
+#include "gemm.h"
+#include "k1.h"
+#include "rowops.h"
+
+namespace zo2 {
+
+static thread_local char g_op_error[512] = "";
+void set_op_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_op_error, sizeof(g_op_error), fmt, ap);
+    va_end(ap);
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static constexpr int64_t kTensorAlign = 256;   // elements
+
+static bool config_ok(const zo2_config* c, char* why, size_t n) {
+#define BAD(...) do { snprintf(why, n, __VA_ARGS__); return false; } while (0)
+    if (!c) BAD("config is NULL");
+    if (c->n_layers < 0 || c->d_model <= 0 || c->n_heads <= 0 || c->d_ffn <= 0 || c->vocab <= 0 || c->max_pos <= 0 || c->pos_offset < 0)
+        BAD("non-positive model dimension");
+    if (c->d_model % 8 || c->d_ffn % 8) BAD("d_model (%d) and d_ffn (%d) must be multiples of 8", c->d_model, c->d_ffn);
+    if (c->d_model % c->n_heads) BAD("n_heads %d does not divide d_model %d", c->n_heads, c->d_model);
+    const int dh = c->d_model / c->n_heads;
+    if (!(dh == 8 || dh == 16 || dh == 32 || dh == 64 || dh == 128)) BAD("head dimension %d not in {8,16,32,64,128}", dh);
+    if (zo2_dtype_size(c->wire_dtype) == 0) BAD("unknown wire dtype %d", c->wire_dtype);
+    if (!(c->compute_dtype == ZO2_F32 || c->compute_dtype == ZO2_BF16 || c->compute_dtype == ZO2_F16))
+        BAD("compute dtype %d is not F32, BF16 or F16", c->compute_dtype);
+    if (!(c->ln_eps > 0.f)) BAD("ln_eps must be positive");
+    return true;
+#undef BAD
+}
+
+static void block_tensor_elems(const zo2_config* c, int64_t n[ZO2_BLOCK_TENSORS]) {
+    const int64_t d = c->d_model, f = c->d_ffn;
+    const int64_t v[ZO2_BLOCK_TENSORS] = {d, d, d * d, d, d * d, d, d * d, d, d * d, d, d, d, f * d, f, d * f, d};
+    for (int i = 0; i < ZO2_BLOCK_TENSORS; ++i) n[i] = v[i];
+}
+
+}  // namespace zo2
+
+using namespace zo2;
+
+// =========================================================================================
+// context
+// =========================================================================================
+struct zo2_ctx {
+    zo2_config cfg;
+    zo2_device dev;
+    std::vector<void*> host_bucket;
+    void *h_tok, *h_pos, *h_flnw, *h_flnb, *h_lm;
+    std::vector<float> scales;          // per tensor id
+    char err[512];
+    bool dead;
+    size_t budget;
+
+    // layout
+    int64_t offs[ZO2_BLOCK_TENSORS + 1];
+    int64_t tn[ZO2_BLOCK_TENSORS];
+    size_t wsz, csz;                    // bytes per element: wire, compute
+    size_t bucket_bytes;
+    int64_t tok_elems, pos_elems, fln_off_b, fln_elems;   // final LN mini bucket: w at 0, b at fln_off_b
+    int n_tensors;
+
+    // persistent device region
+    char *d_tok, *d_pos, *d_fln, *d_lm;
+    float* d_state;                     // [0] c_pending, [4..7] result
+    size_t persistent_bytes;
+
+    // plan (depends on budget and batch x seq)
+    bool planned, need_plan;
+    int plan_T;
+    bool resident, phased;
+    int n_slots;
+    char* slots;
+    char *wp, *wm;                      // W+ / W- scratch, compute dtype
+    int64_t scratch_elems;
+    char *fln_wp, *fln_wm;
+    float* h;
+    char *x, *qb, *kb, *vb, *ctxb, *mid;
+    float* logits;
+    int logit_rows;                     // rows per sign per chunk
+    float* row_loss;
+    int32_t *d_tokens, *d_labels;
+    size_t bytes_used;
+    bool blocks_on_device;
+
+    // pending update (Sec. 5.4)
+    bool has_pending;
+    uint64_t seed_prev;
+
+    // streams / events
+    hipStream_t sc, su, so;
+    std::vector<hipEvent_t> ev_up, ev_k1, ev_free;
+    std::vector<char> ev_free_valid;
+    hipEvent_t ev_step0, ev_c1, ev_u0, ev_u1, ev_o0, ev_o1;
+    bool stat_u, stat_o;
+    uint64_t bytes_up, bytes_down;
+    float ms_c, ms_u, ms_o;
+
+    // pinned staging
+    int32_t* h_ids;                     // tokens then labels
+    int h_ids_cap;
+    float* h_result;
+};
+
+static zo2_status fail(zo2_ctx* c, zo2_status s, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+    if (s == ZO2_EHIP) c->dead = true;
+    return s;
+}
+#define HIPCHK(c, call)                                                                        \
+    do {                                                                                       \
+        hipError_t e__ = (call);                                                               \
+        if (e__ != hipSuccess) return fail(c, ZO2_EHIP, "%s failed: %s", #call, hipGetErrorString(e__)); \
+    } while (0)
+#define OPCHK(c, call)                                                       \
+    do {                                                                     \
+        zo2_status s__ = (call);                                             \
+        if (s__ != ZO2_OK) return fail(c, s__, "%s", zo2_op_last_error());   \
+    } while (0)
+
+static inline uint32_t block_tid(int l, int k) { return (uint32_t)(2 + 16 * l + k); }
+static inline uint32_t fln_tid(const zo2_ctx* c) { return (uint32_t)(2 + 16 * c->cfg.n_layers); }
+static inline uint32_t lm_tid(const zo2_ctx* c) { return (uint32_t)(4 + 16 * c->cfg.n_layers); }
+
+extern "C" size_t zo2_dtype_size(int32_t dt) {
+    switch (dt) {
+        case ZO2_F32: return 4;
+        case ZO2_BF16: case ZO2_F16: return 2;
+        case ZO2_FP8_E4M3: case ZO2_FP8_E5M2: return 1;
+        default: return 0;
+    }
+}
+
+extern "C" zo2_status zo2_block_tensor_offsets(const zo2_config* cfg, int64_t offs[ZO2_BLOCK_TENSORS + 1]) {
+    char why[256];
+    if (!offs || !config_ok(cfg, why, sizeof(why))) {
+        set_op_error("%s", offs ? why : "offs is NULL");
+        return ZO2_EINVAL;
+    }
+    int64_t n[ZO2_BLOCK_TENSORS];
+    block_tensor_elems(cfg, n);
+    int64_t o = 0;
+    for (int i = 0; i < ZO2_BLOCK_TENSORS; ++i) {
+        offs[i] = o;
+        o += (n[i] + kTensorAlign - 1) / kTensorAlign * kTensorAlign;
+    }
+    offs[ZO2_BLOCK_TENSORS] = o;
+    return ZO2_OK;
+}
+
+extern "C" const char* zo2_op_last_error(void) { return g_op_error; }
+extern "C" const char* zo2_last_error(const zo2_ctx* c) { return c ? c->err : "context is NULL"; }
+
+// ---------------------------------------------------------------------------------- init
+extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_host_weights* w, const zo2_device* dev) {
+    if (!out) return ZO2_EINVAL;
+    *out = nullptr;
+    char why[256];
+    if (!config_ok(cfg, why, sizeof(why))) { set_op_error("%s", why); return ZO2_EINVAL; }
+    if (!w || !dev || !w->tok_emb || !w->pos_emb || !w->final_ln_w || !w->final_ln_b || (cfg->n_layers > 0 && !w->block_bucket)) {
+        set_op_error("zo2_init: NULL weight or device argument");
+        return ZO2_EINVAL;
+    }
+    if ((cfg->tied_lm_head != 0) != (w->lm_head == nullptr)) {
+        set_op_error("zo2_init: lm_head must be NULL exactly when tied_lm_head = 1");
+        return ZO2_EINVAL;
+    }
+    if (!dev->arena || ((uintptr_t)dev->arena & 255) || dev->arena_bytes == 0) {
+        set_op_error("zo2_init: arena must be non-NULL and 256-byte aligned");
+        return ZO2_EINVAL;
+    }
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->block_bucket[l]) { set_op_error("zo2_init: block_bucket[%d] is NULL", l); return ZO2_EINVAL; }
+
+    zo2_ctx* c = new (std::nothrow) zo2_ctx();
+    if (!c) { set_op_error("zo2_init: out of host memory"); return ZO2_ENOMEM; }
+    c->cfg = *cfg;
+    c->dev = *dev;
+    c->err[0] = 0;
+    c->dead = false;
+    c->budget = dev->arena_bytes;
+    c->host_bucket.assign(w->block_bucket, w->block_bucket + cfg->n_layers);
+    c->h_tok = w->tok_emb; c->h_pos = w->pos_emb; c->h_flnw = w->final_ln_w; c->h_flnb = w->final_ln_b; c->h_lm = w->lm_head;
+    c->n_tensors = 4 + 16 * cfg->n_layers + (cfg->tied_lm_head ? 0 : 1);
+    c->scales.assign(c->n_tensors, 1.0f);
+    const bool wire8 = zo2_dtype_size(cfg->wire_dtype) == 1;
+    if (w->tensor_scale) {
+        for (int i = 0; i < c->n_tensors; ++i) {
+            const float s = w->tensor_scale[i];
+            if (!(s > 0.f) || !isfinite(s) || (!wire8 && s != 1.0f)) {
+                set_op_error("zo2_init: tensor_scale[%d] = %g is invalid for this wire dtype", i, (double)s);
+                delete c;
+                return ZO2_EINVAL;
+            }
+            c->scales[i] = s;
+        }
+    }
+    zo2_block_tensor_offsets(cfg, c->offs);
+    block_tensor_elems(cfg, c->tn);
+    c->wsz = zo2_dtype_size(cfg->wire_dtype);
+    c->csz = zo2_dtype_size(cfg->compute_dtype);
+    c->bucket_bytes = (size_t)c->offs[ZO2_BLOCK_TENSORS] * c->wsz;
+    c->tok_elems = (int64_t)cfg->vocab * cfg->d_model;
+    c->pos_elems = (int64_t)(cfg->max_pos + cfg->pos_offset) * cfg->d_model;
+    c->fln_off_b = align_up(cfg->d_model, kTensorAlign);
+    c->fln_elems = 2 * c->fln_off_b;
+    c->sc = as_stream(dev->stream_compute);
+    c->su = as_stream(dev->stream_upload);
+    c->so = as_stream(dev->stream_offload);
+    c->planned = false;
+    c->need_plan = false;
+    c->blocks_on_device = false;
+    c->has_pending = false;
+    c->seed_prev = 0;
+    c->h_ids = nullptr;
+    c->h_ids_cap = 0;
+    c->h_result = nullptr;
+    c->bytes_up = c->bytes_down = 0;
+    c->ms_c = c->ms_u = c->ms_o = 0.f;
+    c->bytes_used = 0;
+    c->n_slots = 0;
+    c->resident = false;
+    *out = c;   // from here on errors are reported through the context
+
+    // persistent region: embeddings, final LayerNorm, LM head, state
+    char* base = (char*)dev->arena;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base + off; off = align_up(off + bytes, 256); return p; };
+    c->d_tok = take((size_t)c->tok_elems * c->wsz);
+    c->d_pos = take((size_t)c->pos_elems * c->wsz);
+    c->d_fln = take((size_t)c->fln_elems * c->wsz);
+    c->d_lm = cfg->tied_lm_head ? nullptr : take((size_t)c->tok_elems * c->wsz);
+    c->d_state = (float*)take(64 * sizeof(float));
+    c->persistent_bytes = off;
+    if (off > dev->arena_bytes) return fail(c, ZO2_ENOMEM, "arena of %zu bytes cannot hold the %zu bytes of embeddings", dev->arena_bytes, off);
+
+    HIPCHK(c, hipMemcpy(c->d_tok, w->tok_emb, (size_t)c->tok_elems * c->wsz, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->d_pos, w->pos_emb, (size_t)c->pos_elems * c->wsz, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemset(c->d_fln, 0, (size_t)c->fln_elems * c->wsz));
+    HIPCHK(c, hipMemcpy(c->d_fln, w->final_ln_w, (size_t)cfg->d_model * c->wsz, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->d_fln + (size_t)c->fln_off_b * c->wsz, w->final_ln_b, (size_t)cfg->d_model * c->wsz, hipMemcpyHostToDevice));
+    if (c->d_lm) HIPCHK(c, hipMemcpy(c->d_lm, w->lm_head, (size_t)c->tok_elems * c->wsz, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemset(c->d_state, 0, 64 * sizeof(float)));
+    HIPCHK(c, hipHostMalloc((void**)&c->h_result, 16 * sizeof(float), hipHostMallocDefault));
+    hipEvent_t* evs[] = {&c->ev_step0, &c->ev_c1, &c->ev_u0, &c->ev_u1, &c->ev_o0, &c->ev_o1};
+    for (hipEvent_t* e : evs) HIPCHK(c, hipEventCreate(e));
+    return ZO2_OK;
+}
+
+extern "C" void zo2_destroy(zo2_ctx* c) {
+    if (!c) return;
+    hipStreamSynchronize(c->sc);
+    hipStreamSynchronize(c->su);
+    hipStreamSynchronize(c->so);
+    for (auto e : c->ev_up) hipEventDestroy(e);
+    for (auto e : c->ev_k1) hipEventDestroy(e);
+    for (auto e : c->ev_free) hipEventDestroy(e);
+    hipEvent_t evs[] = {c->ev_step0, c->ev_c1, c->ev_u0, c->ev_u1, c->ev_o0, c->ev_o1};
+    if (c->h_result) for (hipEvent_t e : evs) hipEventDestroy(e);
+    if (c->h_ids) hipHostFree(c->h_ids);
+    if (c->h_result) hipHostFree(c->h_result);
+    delete c;
+}
+
+extern "C" zo2_status zo2_set_resident_budget(zo2_ctx* c, size_t hbm_bytes) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (hbm_bytes == 0) return fail(c, ZO2_EINVAL, "budget must be positive");
+    c->budget = hbm_bytes < c->dev.arena_bytes ? hbm_bytes : c->dev.arena_bytes;
+    c->need_plan = true;   // re-plan at the next step
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- sync to host
+static zo2_status sync_blocks_to_host(zo2_ctx* c) {
+    if (c->resident && c->blocks_on_device) {
+        HIPCHK(c, hipStreamSynchronize(c->sc));
+        for (int l = 0; l < c->cfg.n_layers; ++l)
+            HIPCHK(c, hipMemcpy(c->host_bucket[l], c->slots + (size_t)l * c->bucket_bytes, c->bucket_bytes, hipMemcpyDeviceToHost));
+    }
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_sync_to_host(zo2_ctx* c) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->so));
+    const size_t d = c->cfg.d_model;
+    HIPCHK(c, hipMemcpy(c->h_tok, c->d_tok, (size_t)c->tok_elems * c->wsz, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(c->h_pos, c->d_pos, (size_t)c->pos_elems * c->wsz, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(c->h_flnw, c->d_fln, d * c->wsz, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(c->h_flnb, c->d_fln + (size_t)c->fln_off_b * c->wsz, d * c->wsz, hipMemcpyDeviceToHost));
+    if (c->d_lm) HIPCHK(c, hipMemcpy(c->h_lm, c->d_lm, (size_t)c->tok_elems * c->wsz, hipMemcpyDeviceToHost));
+    return sync_blocks_to_host(c);
+}
+
+// ---------------------------------------------------------------------------------- planning
+// Tensor groups whose perturbed copies are needed together (used when the scratch cannot
+// hold a whole block): {ln1, q, k, v}, {o}, {ln2, fc1}, {fc2}.
+static const int kPhase[5] = {0, 8, 10, 14, 16};
+
+static zo2_status plan(zo2_ctx* c, int T) {
+    const zo2_config& g = c->cfg;
+    const size_t d = g.d_model, f = g.d_ffn, V = g.vocab;
+    const size_t budget = c->budget;
+    const size_t rows2 = 2 * (size_t)T;
+    // logits chunk: about 1/32 of the budget, at least 128 rows per sign
+    size_t lrows = budget / 32 / (V * 4) / 2;
+    lrows = lrows / 128 * 128;
+    if (lrows < 128) lrows = 128;
+    if (lrows > (size_t)T) lrows = T;
+    size_t act = 0;
+    auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
+    const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
+                 o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
+                 o_logits = sz(2 * lrows * V * 4), o_rl = sz(rows2 * 4), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
+                 o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
+    const size_t act_bytes = act;
+
+    int64_t phase_max = 0;
+    for (int p = 0; p < 4; ++p) phase_max = std::max(phase_max, c->offs[kPhase[p + 1]] - c->offs[kPhase[p]]);
+    const int64_t head_elems = (int64_t)align_up(c->tok_elems, kTensorAlign);
+    bool phased = false, resident = false;
+    int64_t scratch = 0;
+    long slots = 0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        phased = attempt == 1;
+        scratch = std::max(phased ? phase_max : c->offs[ZO2_BLOCK_TENSORS], head_elems);
+        const size_t fixed = c->persistent_bytes + act_bytes + 2 * align_up((size_t)scratch * c->csz, 256);
+        slots = fixed > budget ? -1 : (long)((budget - fixed) / align_up(c->bucket_bytes, 256));
+        if (slots >= g.n_layers || slots >= 3) break;
+    }
+    if (g.n_layers > 0 && slots < g.n_layers && slots < 3)
+        return fail(c, ZO2_EBUDGET, "budget of %zu bytes cannot hold embeddings + 3 block slots + scratch + activations for %d tokens", budget, T);
+    resident = slots >= g.n_layers;
+    const int n_slots = resident ? g.n_layers : (int)slots;
+
+    // moving between resident and streamed (or resizing the ring) needs the host copy current
+    if (c->planned && c->resident && c->blocks_on_device && !resident) {
+        zo2_status s = sync_blocks_to_host(c);
+        if (s != ZO2_OK) return s;
+        c->blocks_on_device = false;
+    }
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->su));
+    HIPCHK(c, hipStreamSynchronize(c->so));
+
+    char* base = (char*)c->dev.arena;
+    size_t off = c->persistent_bytes;
+    c->slots = base + off;
+    off += (size_t)n_slots * align_up(c->bucket_bytes, 256);
+    c->wp = base + off; off += align_up((size_t)scratch * c->csz, 256);
+    c->wm = base + off; off += align_up((size_t)scratch * c->csz, 256);
+    char* a0 = base + off;
+    c->h = (float*)(a0 + o_h); c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
+    c->mid = a0 + o_mid; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
+    c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
+    c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
+    off += act_bytes;
+    c->bytes_used = off;
+    c->logit_rows = (int)lrows;
+    c->scratch_elems = scratch;
+    c->phased = phased;
+    if (c->bucket_bytes % 256) return fail(c, ZO2_EINVAL, "internal: bucket size not aligned");
+
+    // events per slot
+    while ((int)c->ev_up.size() < n_slots) {
+        hipEvent_t e1, e2, e3;
+        HIPCHK(c, hipEventCreateWithFlags(&e1, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&e2, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&e3, hipEventDisableTiming));
+        c->ev_up.push_back(e1); c->ev_k1.push_back(e2); c->ev_free.push_back(e3);
+    }
+    c->ev_free_valid.assign(c->ev_up.size(), 0);
+
+    if (resident && !(c->planned && c->resident && c->blocks_on_device && c->n_slots == n_slots)) {
+        for (int l = 0; l < g.n_layers; ++l)
+            HIPCHK(c, hipMemcpy(c->slots + (size_t)l * c->bucket_bytes, c->host_bucket[l], c->bucket_bytes, hipMemcpyHostToDevice));
+        c->blocks_on_device = true;
+    }
+    if (!resident) c->blocks_on_device = false;
+    c->resident = resident;
+    c->n_slots = n_slots;
+    c->plan_T = T;
+    c->planned = true;
+    c->need_plan = false;
+
+    if (c->h_ids_cap < 2 * T) {
+        if (c->h_ids) hipHostFree(c->h_ids);
+        c->h_ids = nullptr;
+        HIPCHK(c, hipHostMalloc((void**)&c->h_ids, (size_t)2 * T * sizeof(int32_t), hipHostMallocDefault));
+        c->h_ids_cap = 2 * T;
+    }
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_plan(const zo2_ctx* c, int32_t* n_slots, int32_t* resident, size_t* bytes_used) {
+    if (!c) return ZO2_EINVAL;
+    if (n_slots) *n_slots = c->n_slots;
+    if (resident) *resident = c->resident ? 1 : 0;
+    if (bytes_used) *bytes_used = c->planned ? c->bytes_used : c->persistent_bytes;
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_step_stats(const zo2_ctx* c, float* ms_c, float* ms_u, float* ms_o, uint64_t* up, uint64_t* down) {
+    if (!c) return ZO2_EINVAL;
+    if (ms_c) *ms_c = c->ms_c;
+    if (ms_u) *ms_u = c->ms_u;
+    if (ms_o) *ms_o = c->ms_o;
+    if (up) *up = c->bytes_up;
+    if (down) *down = c->bytes_down;
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- K1 helpers
+static void k1_common(const zo2_ctx* c, K1Args& a, uint64_t seed, float eps) {
+    memset(&a, 0, sizeof(a));
+    a.c_ptr = c->d_state;
+    a.c_imm = 0.f;
+    a.eps = eps;
+    a.k_prev = philox_keys(c->seed_prev);
+    a.k_cur = philox_keys(seed);
+}
+
+// one whole tensor held contiguously at `theta`
+static zo2_status k1_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, bool perturb, void* wp, void* wm,
+                            uint64_t seed, float eps) {
+    K1Args a;
+    k1_common(c, a, seed, eps);
+    a.theta = theta; a.w_plus = wp; a.w_minus = wm; a.w_off0 = 0; a.nseg = 1;
+    a.seg[0].off = 0; a.seg[0].e0 = 0; a.seg[0].n = (uint64_t)n; a.seg[0].tensor_id = tid; a.seg[0].scale = c->scales[tid];
+    OPCHK(c, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    return ZO2_OK;
+}
+
+// tensors [t0, t1) of block l whose bucket sits at `bucket`; W+- go to the scratch, tensor t0 at its start
+static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool perturb, uint64_t seed, float eps) {
+    K1Args a;
+    k1_common(c, a, seed, eps);
+    a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->wm; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
+    for (int k = t0; k < t1; ++k) {
+        K1Seg& s = a.seg[k - t0];
+        s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
+    }
+    OPCHK(c, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- block forward
+struct PhaseView {       // where tensor k's perturbed copies are inside the scratch
+    const zo2_ctx* c;
+    int64_t off0;
+    const char* P(int k) const { return c->wp + (size_t)(c->offs[k] - off0) * c->csz; }
+    const char* M(int k) const { return c->wm + (size_t)(c->offs[k] - off0) * c->csz; }
+};
+
+static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int seq, uint64_t seed, float eps, hipEvent_t k1_done) {
+    const zo2_config& g = c->cfg;
+    const int T = batch * seq, d = g.d_model, f = g.d_ffn, dh = d / g.n_heads;
+    const int dt = g.compute_dtype;
+    const size_t cs = c->csz;
+    const size_t half_d = (size_t)T * d * cs, half_f = (size_t)T * f * cs;
+    const bool f32 = dt == ZO2_F32;
+    auto phase = [&](int p) -> zo2_status {
+        if (c->phased) return k1_block(c, l, bucket, kPhase[p], kPhase[p + 1], true, seed, eps);
+        if (p == 0) return k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, true, seed, eps);
+        return ZO2_OK;
+    };
+    auto view = [&](int p) { return PhaseView{c, c->phased ? c->offs[kPhase[p]] : 0}; };
+    GemmArgs ga;
+
+    // ---- attention half: h += O(Attn(LN1(h)))
+    { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
+    if (!c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
+    PhaseView w = view(0);
+    OPCHK(c, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    memset(&ga, 0, sizeof(ga));
+    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = f32; ga.nprob = 6;
+    char* outs[3] = {c->qb, c->kb, c->vb};
+    for (int s = 0; s < 2; ++s)
+        for (int t = 0; t < 3; ++t) {
+            GemmProblem& p = ga.p[s * 3 + t];
+            p.X = c->x + s * half_d;
+            p.W = s ? w.M(2 + 2 * t) : w.P(2 + 2 * t);
+            p.bias = s ? w.M(3 + 2 * t) : w.P(3 + 2 * t);
+            p.residual = nullptr;
+            p.Y = outs[t] + s * half_d;
+            p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
+        }
+    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    OPCHK(c, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, c->sc));
+    { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
+    w = view(1);
+    memset(&ga, 0, sizeof(ga));
+    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
+    for (int s = 0; s < 2; ++s) {
+        GemmProblem& p = ga.p[s];
+        p.X = c->ctxb + s * half_d; p.W = s ? w.M(8) : w.P(8); p.bias = s ? w.M(9) : w.P(9);
+        p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
+    }
+    OPCHK(c, gemm_launch(ga, dt, c->sc));
+
+    // ---- FFN half: h += FC2(ReLU(FC1(LN2(h))))
+    { zo2_status s = phase(2); if (s != ZO2_OK) return s; }
+    w = view(2);
+    OPCHK(c, layernorm(dt, c->h, w.P(10), w.P(11), w.M(10), w.M(11), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    memset(&ga, 0, sizeof(ga));
+    ga.M = T; ga.N = f; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = f; ga.relu = 1; ga.out_f32 = f32; ga.nprob = 2;
+    for (int s = 0; s < 2; ++s) {
+        GemmProblem& p = ga.p[s];
+        p.X = c->x + s * half_d; p.W = s ? w.M(12) : w.P(12); p.bias = s ? w.M(13) : w.P(13);
+        p.residual = nullptr; p.Y = c->mid + s * half_f; p.out_scale = 1.0f;
+    }
+    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    { zo2_status s = phase(3); if (s != ZO2_OK) return s; }
+    if (c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
+    w = view(3);
+    memset(&ga, 0, sizeof(ga));
+    ga.M = T; ga.N = d; ga.K = f; ga.ldx = f; ga.ldw = f; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
+    for (int s = 0; s < 2; ++s) {
+        GemmProblem& p = ga.p[s];
+        p.X = c->mid + s * half_f; p.W = s ? w.M(14) : w.P(14); p.bias = s ? w.M(15) : w.P(15);
+        p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
+    }
+    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- streaming (Alg. 3)
+// U(W_i): runs on the upload stream once the slot's previous occupant has left it.
+static zo2_status enqueue_upload(zo2_ctx* c, int l) {
+    const int s = l % c->n_slots;
+    if (c->ev_free_valid[s]) HIPCHK(c, hipStreamWaitEvent(c->su, c->ev_free[s], 0));
+    if (!c->stat_u) { HIPCHK(c, hipEventRecord(c->ev_u0, c->su)); c->stat_u = true; }
+    HIPCHK(c, hipMemcpyAsync(c->slots + (size_t)s * c->bucket_bytes, c->host_bucket[l], c->bucket_bytes, hipMemcpyHostToDevice, c->su));
+    HIPCHK(c, hipEventRecord(c->ev_up[s], c->su));
+    c->bytes_up += c->bucket_bytes;
+    return ZO2_OK;
+}
+
+// O(W_i): the updated block goes back as soon as its K1 pass is done (the forwards read
+// only the scratch copies, never the slot); without a pending update nothing changed.
+static zo2_status enqueue_offload(zo2_ctx* c, int l, bool changed) {
+    const int s = l % c->n_slots;
+    if (changed) {
+        HIPCHK(c, hipStreamWaitEvent(c->so, c->ev_k1[s], 0));
+        if (!c->stat_o) { HIPCHK(c, hipEventRecord(c->ev_o0, c->so)); c->stat_o = true; }
+        HIPCHK(c, hipMemcpyAsync(c->host_bucket[l], c->slots + (size_t)s * c->bucket_bytes, c->bucket_bytes, hipMemcpyDeviceToHost, c->so));
+        HIPCHK(c, hipEventRecord(c->ev_free[s], c->so));
+        c->bytes_down += c->bucket_bytes;
+    } else {
+        HIPCHK(c, hipStreamWaitEvent(c->so, c->ev_k1[s], 0));
+        HIPCHK(c, hipEventRecord(c->ev_free[s], c->so));
+    }
+    c->ev_free_valid[s] = 1;
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- step
+extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                               uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* gout) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    const zo2_config& g = c->cfg;
+    if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step: NULL argument");
+    if (batch <= 0 || seq <= 0 || seq > g.max_pos) return fail(c, ZO2_EINVAL, "zo2_step: batch %d, seq %d (max_pos %d)", batch, seq, g.max_pos);
+    if ((int64_t)batch * seq > (1 << 24)) return fail(c, ZO2_EINVAL, "zo2_step: too many tokens");
+    if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step: eps must be non-zero and finite, lr finite");
+    const int T = batch * seq;
+    for (int i = 0; i < T; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, ZO2_EINVAL, "zo2_step: token %d at %d outside [0, %d)", tokens[i], i, g.vocab);
+        if (labels[i] != -100 && (labels[i] < 0 || labels[i] >= g.vocab)) return fail(c, ZO2_EINVAL, "zo2_step: label %d at %d invalid", labels[i], i);
+    }
+    if (!c->planned || c->need_plan || c->plan_T != T) {
+        zo2_status s = plan(c, T);
+        if (s != ZO2_OK) return s;
+    }
+    const int d = g.d_model, dt = g.compute_dtype;
+    const bool upd = c->has_pending;
+    c->bytes_up = c->bytes_down = 0;
+    c->stat_u = c->stat_o = false;
+
+    memcpy(c->h_ids, tokens, (size_t)T * 4);
+    memcpy(c->h_ids + T, labels, (size_t)T * 4);
+    HIPCHK(c, hipEventRecord(c->ev_step0, c->sc));
+    HIPCHK(c, hipMemcpyAsync(c->d_tokens, c->h_ids, (size_t)T * 4, hipMemcpyHostToDevice, c->sc));
+    HIPCHK(c, hipMemcpyAsync(c->d_labels, c->h_ids + T, (size_t)T * 4, hipMemcpyHostToDevice, c->sc));
+
+    // U(W_1..): prefetch as many blocks as there are slots; overlaps the embedding
+    int next_upload = 0;
+    if (!c->resident)
+        for (; next_upload < c->n_slots && next_upload < g.n_layers; ++next_upload) {
+            zo2_status s = enqueue_upload(c, next_upload);
+            if (s != ZO2_OK) return s;
+        }
+
+    // DualForward(Embedding)
+    EmbedArgs ea;
+    memset(&ea, 0, sizeof(ea));
+    ea.tok_emb = c->d_tok; ea.pos_emb = c->d_pos; ea.tokens = c->d_tokens; ea.h = c->h;
+    ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps;
+    ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = c->d_state;
+    ea.k_prev = philox_keys(c->seed_prev); ea.k_cur = philox_keys(seed);
+    OPCHK(c, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
+    if (upd) {
+        { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
+        if (!g.tied_lm_head) { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
+    }
+
+    // DualForward(W_1 .. W_N)
+    for (int l = 0; l < g.n_layers; ++l) {
+        if (c->resident) {
+            zo2_status s = block_forward(c, l, c->slots + (size_t)l * c->bucket_bytes, batch, seq, seed, eps, nullptr);
+            if (s != ZO2_OK) return s;
+        } else {
+            const int sl = l % c->n_slots;
+            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));                 // C(W_i) after U(W_i)
+            zo2_status s = block_forward(c, l, c->slots + (size_t)sl * c->bucket_bytes, batch, seq, seed, eps, c->ev_k1[sl]);
+            if (s != ZO2_OK) return s;
+            s = enqueue_offload(c, l, upd);                                        // O(W_i) after its update
+            if (s != ZO2_OK) return s;
+            if (next_upload < g.n_layers) {                                        // U(W_{i+n}) into the slot O(W_i) frees
+                s = enqueue_upload(c, next_upload++);
+                if (s != ZO2_OK) return s;
+            }
+        }
+    }
+
+    // DualForward(LM head): final LayerNorm, (tied) vocabulary matrix, loss
+    {
+        K1Args a;
+        k1_common(c, a, seed, eps);
+        a.theta = c->d_fln; a.w_plus = c->fln_wp; a.w_minus = c->fln_wm; a.w_off0 = 0; a.nseg = 2;
+        for (int k = 0; k < 2; ++k) {
+            a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)d;
+            a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
+        }
+        OPCHK(c, k1_launch(a, g.wire_dtype, dt, upd, true, c->sc));
+    }
+    const size_t boff = (size_t)c->fln_off_b * c->csz;
+    OPCHK(c, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    {
+        zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps)
+                                      : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps);
+        if (s != ZO2_OK) return s;
+    }
+    const int R = c->logit_rows;
+    for (int r0 = 0; r0 < T; r0 += R) {
+        const int rows = std::min(R, T - r0);
+        GemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.M = rows; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
+        for (int s = 0; s < 2; ++s) {
+            GemmProblem& p = ga.p[s];
+            p.X = c->x + ((size_t)s * T + r0) * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr;
+            p.Y = c->logits + (size_t)s * R * g.vocab; p.out_scale = 1.0f;
+        }
+        OPCHK(c, gemm_launch(ga, dt, c->sc));
+        for (int s = 0; s < 2; ++s)
+            OPCHK(c, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
+    }
+    OPCHK(c, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, c->d_state + 4, c->d_state, c->sc));
+    HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
+    HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
+    if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
+    if (c->stat_o) HIPCHK(c, hipEventRecord(c->ev_o1, c->so));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    if (!c->resident) {
+        HIPCHK(c, hipStreamSynchronize(c->su));
+        HIPCHK(c, hipStreamSynchronize(c->so));
+    }
+    hipEventElapsedTime(&c->ms_c, c->ev_step0, c->ev_c1);
+    c->ms_u = c->ms_o = 0.f;
+    if (c->stat_u) hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
+    if (c->stat_o) hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
+
+    c->has_pending = true;
+    c->seed_prev = seed;
+    *loss_plus = c->h_result[0];
+    *loss_minus = c->h_result[1];
+    *gout = c->h_result[2];
+    if (!isfinite(c->h_result[0]) || !isfinite(c->h_result[1]) || !isfinite(c->h_result[2]))
+        return fail(c, ZO2_ENONFINITE, "zo2_step: non-finite loss (l+ %g, l- %g)", (double)c->h_result[0], (double)c->h_result[1]);
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- flush
+extern "C" zo2_status zo2_flush(zo2_ctx* c) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!c->has_pending) return ZO2_OK;
+    const zo2_config& g = c->cfg;
+    if (!c->planned) return fail(c, ZO2_EINVAL, "zo2_flush: nothing to flush");
+    { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
+    { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
+    c->bytes_up = c->bytes_down = 0;
+    c->stat_u = c->stat_o = true;   // no span statistics for a flush
+    int next_upload = 0;
+    if (!c->resident)
+        for (; next_upload < c->n_slots && next_upload < g.n_layers; ++next_upload) {
+            zo2_status s = enqueue_upload(c, next_upload);
+            if (s != ZO2_OK) return s;
+        }
+    for (int l = 0; l < g.n_layers; ++l) {
+        if (c->resident) {
+            zo2_status s = k1_block(c, l, c->slots + (size_t)l * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f);
+            if (s != ZO2_OK) return s;
+        } else {
+            const int sl = l % c->n_slots;
+            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));
+            zo2_status s = k1_block(c, l, c->slots + (size_t)sl * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f);
+            if (s != ZO2_OK) return s;
+            HIPCHK(c, hipEventRecord(c->ev_k1[sl], c->sc));
+            s = enqueue_offload(c, l, true);
+            if (s != ZO2_OK) return s;
+            if (next_upload < g.n_layers) {
+                s = enqueue_upload(c, next_upload++);
+                if (s != ZO2_OK) return s;
+            }
+        }
+    }
+    {
+        K1Args a;
+        k1_common(c, a, 0, 0.f);
+        a.theta = c->d_fln; a.nseg = 2;
+        for (int k = 0; k < 2; ++k) {
+            a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)g.d_model;
+            a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
+        }
+        OPCHK(c, k1_launch(a, g.wire_dtype, g.compute_dtype, true, false, c->sc));
+    }
+    if (c->d_lm) { zo2_status s = k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->su));
+    HIPCHK(c, hipStreamSynchronize(c->so));
+    c->has_pending = false;
+    return ZO2_OK;
+}
+
+// =========================================================================================
+// kernel-level entry points
+// =========================================================================================
+extern "C" zo2_status zo2_op_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, uint32_t* out, void* stream) {
+    return philox_words(seed, tensor_id, e0, n, out, as_stream(stream));
+}
+extern "C" zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, float* out, void* stream) {
+    return gaussian(seed, tensor_id, e0, n, out, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
+                                            uint32_t tensor_id, uint64_t e0, uint64_t n, int32_t has_pending, uint64_t seed_prev,
+                                            float cval, uint64_t seed, float eps, float scale, void* stream) {
+    if (n == 0) return ZO2_OK;
+    const size_t ws = zo2_dtype_size(wire_dtype), cs = zo2_dtype_size(compute_dtype);
+    ZO2_OP_CHECK(ws != 0 && cs != 0, ZO2_EINVAL, "update_perturb: unknown dtype");
+    ZO2_OP_CHECK((w_plus == nullptr) == (w_minus == nullptr), ZO2_EINVAL, "update_perturb: give both W+ and W- or neither");
+    ZO2_OP_CHECK(((uintptr_t)theta % (8 * ws)) == 0 && ((uintptr_t)w_plus % (8 * cs)) == 0 && ((uintptr_t)w_minus % (8 * cs)) == 0,
+                 ZO2_EINVAL, "update_perturb: pointers must be aligned to 8 elements");
+    K1Args a;
+    memset(&a, 0, sizeof(a));
+    a.theta = theta; a.w_plus = w_plus; a.w_minus = w_minus; a.w_off0 = 0; a.nseg = 1;
+    a.c_imm = cval; a.c_ptr = nullptr; a.eps = eps;
+    a.k_prev = philox_keys(seed_prev); a.k_cur = philox_keys(seed);
+    a.seg[0].off = 0; a.seg[0].e0 = e0; a.seg[0].n = n; a.seg[0].tensor_id = tensor_id; a.seg[0].scale = scale;
+    return k1_launch(a, wire_dtype, compute_dtype, has_pending != 0, w_plus != nullptr, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_convert(const void* src, int32_t sdt, float sscale, void* dst, int32_t ddt, float dscale, uint64_t n, void* stream) {
+    return convert(src, sdt, sscale, dst, ddt, dscale, n, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                                  const void* bias, const float* residual, void* Y, int32_t out_dtype, int64_t ldy, float out_scale,
+                                  int32_t relu, void* stream) {
+    ZO2_OP_CHECK(out_dtype == ZO2_F32 || out_dtype == dtype, ZO2_EINVAL, "gemm: output dtype must be F32 or the input dtype");
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldw = ldw; a.ldy = ldy; a.relu = relu; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1;
+    a.p[0].X = X; a.p[0].W = W; a.p[0].bias = bias; a.p[0].residual = residual; a.p[0].Y = Y; a.p[0].out_scale = out_scale;
+    return gemm_launch(a, dtype, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, int32_t n_seq, int32_t seq,
+                                       int32_t n_heads, int32_t d_head, int64_t ld, void* stream) {
+    return attention_launch(dtype, q, k, v, out, n_seq, seq, n_heads, d_head, ld, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2, void* y,
+                                       int32_t rows, int32_t rows_first, int32_t d, float eps, void* stream) {
+    return layernorm(dtype, x, w, b, w2, b2, y, rows, rows_first, d, eps, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_cross_entropy_rows(const float* logits, int64_t ld, const int32_t* labels, int32_t rows, int32_t vocab,
+                                                float* row_loss, void* stream) {
+    return cross_entropy_rows(logits, ld, labels, rows, 0, rows > 0 ? rows : 1, vocab, row_loss, as_stream(stream));
+}

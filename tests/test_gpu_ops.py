@@ -1,0 +1,100 @@
+"""GPU parity of the forward kernels (GEMM, attention, LayerNorm, cross-entropy) against
+float64 evaluations of their definitions."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TD = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+
+
+def _b():
+    from paper_2503_12668_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (22, 32, 32), (200, 136, 72), (257, 515, 264), (128, 97 * 8, 40), (4, 8, 8)])
+def test_gemm_against_float64(dt, M, N, K):
+    b = _b()
+    g = torch.Generator().manual_seed(M * 1000 + N + K)
+    X = (torch.randn(M, K, generator=g) * 0.5).to(TD[dt])
+    W = (torch.randn(N, K, generator=g) * 0.5).to(TD[dt])
+    bias = (torch.randn(N, generator=g)).to(TD[dt])
+    R = torch.randn(M, N, generator=g)
+    ref = (X.double() @ W.double().T + bias.double()) * 0.125
+    tol = 1e-5 if dt == "f32" else 1e-2
+    # plain, compute-dtype output
+    out_dt = b.F32 if dt == "f32" else None
+    Y = b.op_gemm(X.cuda(), W.cuda(), bias.cuda(), out_scale=0.125, out_dtype=out_dt)
+    assert (Y.double().cpu() - ref).abs().max() <= tol * max(1.0, ref.abs().max())
+    # relu + residual, float32 output
+    Y2 = b.op_gemm(X.cuda(), W.cuda(), bias.cuda(), residual=R.cuda(), out_scale=0.125, relu=True, out_dtype=b.F32)
+    ref2 = torch.relu(ref) + R.double()
+    t2 = 1e-5 if dt == "f32" else 2e-3
+    assert (Y2.double().cpu() - ref2).abs().max() <= t2 * max(1.0, ref2.abs().max())
+    # no bias, strided operands
+    Xs = torch.zeros(M, K + 8, dtype=TD[dt]); Xs[:, :K] = X
+    Y3 = b.op_gemm(Xs.cuda()[:, :K], W.cuda(), out_dtype=b.F32)
+    ref3 = X.double() @ W.double().T
+    assert (Y3.double().cpu() - ref3).abs().max() <= t2 * max(1.0, ref3.abs().max())
+
+
+def test_gemm_rejects_bad_arguments():
+    b = _b()
+    X = torch.zeros(8, 12, device="cuda", dtype=torch.bfloat16)
+    W = torch.zeros(8, 12, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(b.Zo2Error):
+        b.op_gemm(X, W)                      # K not a multiple of 8
+
+
+def _attention_ref(q, k, v, n_seq, seq, H, dh):
+    q = q.double().view(n_seq, seq, H, dh).transpose(1, 2)
+    k = k.double().view(n_seq, seq, H, dh).transpose(1, 2)
+    v = v.double().view(n_seq, seq, H, dh).transpose(1, 2)
+    s = q @ k.transpose(-1, -2)
+    s = s.masked_fill(torch.triu(torch.ones(seq, seq, dtype=torch.bool), 1), float("-inf"))
+    return (torch.softmax(s, -1) @ v).transpose(1, 2).reshape(n_seq * seq, H * dh)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("n_seq,seq,H,dh", [(2, 11, 4, 8), (3, 64, 2, 64), (2, 130, 3, 32), (1, 257, 2, 128), (4, 1, 2, 16)])
+def test_attention_against_float64(dt, n_seq, seq, H, dh):
+    b = _b()
+    g = torch.Generator().manual_seed(seq * 7 + dh)
+    mk = lambda s: (torch.randn(n_seq * seq, H * dh, generator=g) * s).to(TD[dt])
+    q, k, v = mk(0.3), mk(1.0), mk(1.0)
+    out = b.op_attention(q.cuda(), k.cuda(), v.cuda(), n_seq, seq, H, dh)
+    ref = _attention_ref(q, k, v, n_seq, seq, H, dh)
+    tol = 2e-6 if dt == "f32" else 1.5e-2
+    assert (out.double().cpu() - ref).abs().max() <= tol * max(1.0, ref.abs().max())
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,d", [(5, 32), (64, 768), (9, 2048), (3, 12288)])
+def test_layernorm_two_parameter_sets(dt, rows, d):
+    b = _b()
+    g = torch.Generator().manual_seed(d)
+    x = torch.randn(rows, d, generator=g) * 2 + 0.5
+    w1, b1, w2, b2 = [(torch.randn(d, generator=g) * 0.1 + o).to(TD[dt]) for o in (1, 0, 1, 0)]
+    first = rows // 2
+    y = b.op_layernorm(x.cuda(), w1.cuda(), b1.cuda(), 1e-5, w2.cuda(), b2.cuda(), rows_first=first)
+    xd = x.double()
+    n = (xd - xd.mean(-1, keepdim=True)) / torch.sqrt(xd.var(-1, unbiased=False, keepdim=True) + 1e-5)
+    ref = torch.cat([n[:first] * w1.double() + b1.double(), n[first:] * w2.double() + b2.double()])
+    tol = 2e-6 if dt == "f32" else 1e-2
+    assert (y.double().cpu() - ref).abs().max() <= tol * max(1.0, ref.abs().max())
+
+
+@pytest.mark.parametrize("rows,V", [(7, 97), (33, 50272), (2, 256)])
+def test_cross_entropy_rows(rows, V):
+    b = _b()
+    g = torch.Generator().manual_seed(V)
+    lg = torch.randn(rows, V, generator=g) * 3
+    lab = torch.randint(0, V, (rows,), generator=g, dtype=torch.int32)
+    lab[rows // 2] = -100
+    out = b.op_cross_entropy_rows(lg.cuda(), lab.cuda())
+    ref = torch.logsumexp(lg.double(), -1) - lg.double().gather(1, lab.clamp(min=0).long()[:, None])[:, 0]
+    ref[rows // 2] = 0.0
+    assert (out.double().cpu() - ref).abs().max() <= 2e-6 * ref.abs().max()

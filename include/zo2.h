@@ -44,7 +44,8 @@ typedef enum {
     ZO2_EBUDGET = 3,    /* the HBM budget cannot hold embeddings + 3 block slots + work */
     ZO2_EHIP = 4,       /* a HIP runtime call failed                                    */
     ZO2_ESTATE = 5,     /* the context is unusable after an earlier ZO2_EHIP            */
-    ZO2_ENONFINITE = 6  /* a loss came out NaN or infinite (outputs are still written)  */
+    ZO2_ENONFINITE = 6  /* a loss came out NaN or infinite: outputs are still written, that
+                           iteration's update is dropped, the context stays usable      */
 } zo2_status;
 
 /* Storage formats.  F32/BF16/F16 may be compute formats; all five may be transfer

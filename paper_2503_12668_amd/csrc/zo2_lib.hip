@@ -704,8 +704,10 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     *loss_plus = c->h_result[0];
     *loss_minus = c->h_result[1];
     *gout = c->h_result[2];
-    if (!isfinite(c->h_result[0]) || !isfinite(c->h_result[1]) || !isfinite(c->h_result[2]))
+    if (!isfinite(c->h_result[0]) || !isfinite(c->h_result[1]) || !isfinite(c->h_result[2])) {
+        c->has_pending = false;   // a non-finite g must never reach the parameters: this iteration's update is dropped
         return fail(c, ZO2_ENONFINITE, "zo2_step: non-finite loss (l+ %g, l- %g)", (double)c->h_result[0], (double)c->h_result[1]);
+    }
     return ZO2_OK;
 }
 

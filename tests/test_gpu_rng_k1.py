@@ -89,7 +89,7 @@ def test_update_perturb_window(wire, compute, scale, pending):
     def close(got, want, mult, fmt):
         d = np.abs(got.astype(np.float64) - want.astype(np.float64))
         if fmt == "f32":
-            return d.max() <= mult * Z_TOL + 2e-9
+            return bool(np.all(d <= mult * Z_TOL + np.spacing(np.abs(want).astype(np.float32))))
         step = np.abs(codec.round_to(np.abs(want) * 1.01 + 1e-30, fmt) - codec.round_to(np.abs(want) * 0.99, fmt)).astype(np.float64)
         frac_exact = np.mean(d == 0)
         return bool(np.all(d <= np.maximum(step, 1e-12) / (scale if fmt.startswith("fp8") else 1.0))) and frac_exact > 0.98
@@ -110,7 +110,8 @@ def test_update_only_and_small_windows():
         b.op_update_perturb(t, None, None, 3, 0, True, 5, 1e-3, 0, 0.0)
         from oracle.zo_step import _fma32
         want = _fma32(np.float32(-1e-3), philox.gaussian(5, 3, 0, n), raw)
-        assert np.abs(t.cpu().numpy() - want).max() <= 1e-3 * Z_TOL + 1e-9
+        # z error times c, plus one float32 rounding of the result
+        assert np.all(np.abs(t.cpu().numpy() - want) <= 1e-3 * Z_TOL + np.spacing(np.abs(want)))
     # n = 0 is a no-op
     t = torch.zeros(8, device="cuda")
     b.op_update_perturb(t, None, None, 3, 0, True, 5, 1e-3, 0, 0.0, n=0)

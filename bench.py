@@ -1,0 +1,152 @@
+"""Benchmark of the ZO2 step on one MI355X.
+
+A "step" is one whole zeroth-order iteration (Alg. 2): embedding, every decoder block's
+fused update + perturb and dual forward, LM head + loss for both streams, g.  The workload is
+the OPT-1.3B-shaped configuration: 24 layers, d 2048, 32 heads, FFN 8192, vocab 50272, bf16
+weights fully resident in HBM, batch 16 x seq 256, Zipf(1.1) token ids, eps 1e-3, lr 1e-7.
+
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MODEL, BATCH, SEQ = "opt-1.3b", 16, 256
+EPS, LR, SEED0 = 1e-3, 1e-7, 42
+PEAK_BF16_MFMA = 2500.0      # TFLOP/s, dense
+PEAK_HBM = 8000.0            # GB/s
+
+
+def gemm_flops_per_step(cfg, T):
+    """Dense projection flops of one step: both streams, every block, plus the LM head."""
+    d, f, L, V = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"], cfg["vocab"]
+    per_forward = L * 2 * T * (4 * d * d + 2 * d * f) + 2 * T * V * d
+    return 2 * per_forward
+
+
+def k1_bytes_per_step(cfg, wire_bytes, comp_bytes):
+    """Algorithmic HBM bytes of the fused update + perturb: read theta, write theta', W+, W-
+    for every block parameter, the (tied) vocabulary matrix and the final LayerNorm."""
+    d, f, L, V = cfg["d_model"], cfg["d_ffn"], cfg["n_layers"], cfg["vocab"]
+    n = L * (4 * d * d + 2 * d * f + 9 * d + f) + V * d + 2 * d
+    return n * (2 * wire_bytes + 2 * comp_bytes)
+
+
+def cpu_baseline(cfg_full, T_batch, T_seq):
+    """The oracle, as it stands, on a bounded sample of the same workload: the embedding + LM
+    head alone (0 layers) and with one decoder block (1 layer) at the full width, vocabulary and
+    batch, one step with a pending update each; tokens/s extrapolated to the full depth."""
+    import copy
+
+    import torch
+
+    import synth_inputs as si
+    from oracle import opt_model, zo_step
+
+    tok = si.make_tokens(cfg_full["vocab"], T_batch, T_seq, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    times = {}
+    for nl in (0, 1):
+        cfg = dict(cfg_full, n_layers=nl)
+        P = si.make_weights(cfg, seed=1)
+        oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), P)
+        oz.pending = (1.0, SEED0 - 1, LR)          # as in steady state: an update is pending
+        t0 = time.time()
+        oz.step(tok, lab, SEED0, EPS, LR)
+        times[nl] = time.time() - t0
+    t_rest, t_block = times[0], max(times[1] - times[0], 1e-9)
+    total = t_rest + cfg_full["n_layers"] * t_block
+    return {"value": T_batch * T_seq / total, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"oracle step on embedding+LM head ({t_rest:.1f} s) and on 1 of {cfg_full['n_layers']} decoder blocks "
+                      f"({t_block:.1f} s) at full width, vocabulary and batch {T_batch}x{T_seq}; extrapolated to "
+                      f"{cfg_full['n_layers']} blocks ({total:.0f} s per step)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the ZO2 step is single-GPU; see DESIGN.md for how it "
+              "would shard); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2503_12668_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    binding.lib()
+    cfg = si.opt_config(MODEL, n_layers=args.layers)
+    T = BATCH * SEQ
+    t0 = time.time()
+    P = si.make_weights(cfg, seed=1)
+    tok = si.make_tokens(cfg["vocab"], BATCH, SEQ, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    ctx = binding.Zo2Context(cfg, P, wire="bf16", compute="bf16")
+    del P
+    print(f"[bench] setup {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    for j in range(args.warmup):
+        ctx.step(tok, lab, SEED0 + j, EPS, LR)
+    plan = ctx.plan()
+    ctx.set_profiling(("gemm", "k1", "attn"))
+    acc = {k: [0.0, 0] for k in ctx.KERNEL_CLASSES}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(args.steps):
+        ctx.step(tok, lab, SEED0 + args.warmup + j, EPS, LR)
+        for k, (ms, n) in ctx.kernel_times().items():
+            acc[k][0] += ms
+            acc[k][1] += n
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / args.steps * 1e3
+
+    gemm_ms, gemm_n = acc["gemm"]
+    k1_ms, k1_n = acc["k1"]
+    att_ms, att_n = acc["attn"]
+    flops = gemm_flops_per_step(cfg, T) * args.steps
+    tflops = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    k1_bytes = k1_bytes_per_step(cfg, 2, 2) * args.steps
+    k1_gbs = k1_bytes / (k1_ms * 1e-3) / 1e9 if k1_ms > 0 else 0.0
+    out = {
+        "metric": "zo_step_tokens_per_s", "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{MODEL}-shaped decoder ({cfg['n_layers']} layers, d {cfg['d_model']}, {cfg['n_heads']} heads, "
+                               f"ffn {cfg['d_ffn']}, vocab {cfg['vocab']}), bf16 weights resident in HBM, batch {BATCH} x seq {SEQ}, "
+                               f"Zipf(1.1) tokens, eps {EPS}, lr {LR}",
+                   "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"]},
+        "roofline": {"kernel": "gemm_mfma_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
+                     "achieved": tflops, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_MFMA,
+                     "traffic": None, "launches_per_step": gemm_n / args.steps, "ms_per_step": gemm_ms / args.steps},
+        "roofline_k1": {"kernel": "k1_kernel (fused regenerate + update + perturb)", "bound": "hbm", "achieved": k1_gbs,
+                        "peak": PEAK_HBM, "unit": "GB/s", "frac": k1_gbs / PEAK_HBM, "traffic": None,
+                        "launches_per_step": k1_n / args.steps, "ms_per_step": k1_ms / args.steps},
+        "kernel_ms_per_step": {"gemm": gemm_ms / args.steps, "k1": k1_ms / args.steps, "attention": att_ms / args.steps},
+    }
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, BATCH, SEQ)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

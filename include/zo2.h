@@ -143,6 +143,20 @@ zo2_status zo2_get_plan(const zo2_ctx* ctx, int32_t* n_slots, int32_t* resident,
 zo2_status zo2_get_step_stats(const zo2_ctx* ctx, float* ms_compute, float* ms_upload, float* ms_offload,
                               uint64_t* bytes_up, uint64_t* bytes_down);
 
+/* Per-kernel-class timing of zo2_step, for roofline reporting.  With a class's bit set, every
+ * launch of that class on the compute stream is bracketed by a pair of HIP events;
+ * zo2_get_kernel_times returns, for the last step, the summed elapsed milliseconds and the
+ * number of launches per class.  Off (mask 0) by default. */
+#define ZO2_KERNEL_CLASSES 6
+enum { ZO2_KC_K1 = 0,     /* fused update + perturb                        */
+       ZO2_KC_GEMM = 1,   /* QKV / output / FFN / LM-head projections      */
+       ZO2_KC_ATTN = 2,   /* causal attention                              */
+       ZO2_KC_LN = 3,     /* LayerNorm                                     */
+       ZO2_KC_EMBED = 4,  /* embedding gather                              */
+       ZO2_KC_CE = 5 };   /* cross-entropy rows + scalar epilogue          */
+zo2_status zo2_set_profiling(zo2_ctx* ctx, uint32_t class_mask);
+zo2_status zo2_get_kernel_times(const zo2_ctx* ctx, float ms[ZO2_KERNEL_CLASSES], int32_t launches[ZO2_KERNEL_CLASSES]);
+
 const char* zo2_last_error(const zo2_ctx* ctx);
 void zo2_destroy(zo2_ctx* ctx);
 

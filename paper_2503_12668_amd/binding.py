@@ -67,6 +67,8 @@ def lib():
         "zo2_sync_to_host": (i32, [vp]),
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
+        "zo2_set_profiling": (i32, [vp, u32]),
+        "zo2_get_kernel_times": (i32, [vp, C.POINTER(f32), C.POINTER(i32)]),
         "zo2_last_error": (C.c_char_p, [vp]),
         "zo2_destroy": (None, [vp]),
         "zo2_op_last_error": (C.c_char_p, []),
@@ -88,7 +90,7 @@ def lib():
 
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_get_kernel_times", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows"]
 
@@ -314,6 +316,21 @@ class Zo2Context:
         u, d = C.c_uint64(), C.c_uint64()
         self._check(lib().zo2_get_step_stats(self.handle, C.byref(a), C.byref(b), C.byref(c_), C.byref(u), C.byref(d)))
         return dict(ms_compute=a.value, ms_upload=b.value, ms_offload=c_.value, bytes_up=u.value, bytes_down=d.value)
+
+    KERNEL_CLASSES = ("k1", "gemm", "attn", "ln", "embed", "ce")
+
+    def set_profiling(self, classes=()):
+        mask = 0
+        for c_ in classes:
+            mask |= 1 << self.KERNEL_CLASSES.index(c_)
+        self._check(lib().zo2_set_profiling(self.handle, mask))
+
+    def kernel_times(self):
+        """class -> (milliseconds, launches) of the last step, for the classes being profiled."""
+        ms = (C.c_float * 6)()
+        n = (C.c_int32 * 6)()
+        self._check(lib().zo2_get_kernel_times(self.handle, ms, n))
+        return {k: (ms[i], n[i]) for i, k in enumerate(self.KERNEL_CLASSES)}
 
     def parameters(self):
         """name -> float32 numpy array decoded from the host buffers (call sync_to_host first)."""

@@ -117,6 +117,14 @@ struct zo2_ctx {
     uint64_t bytes_up, bytes_down;
     float ms_c, ms_u, ms_o;
 
+    // optional per-kernel-class timing with events on the compute stream
+    uint32_t prof_mask;
+    std::vector<hipEvent_t> prof_ev;    // pairs (begin, end)
+    std::vector<int> prof_cls;
+    size_t prof_used;
+    float prof_ms[ZO2_KERNEL_CLASSES];
+    int32_t prof_launches[ZO2_KERNEL_CLASSES];
+
     // pinned staging
     int32_t* h_ids;                     // tokens then labels
     int h_ids_cap;
@@ -139,6 +147,52 @@ static zo2_status fail(zo2_ctx* c, zo2_status s, const char* fmt, ...) {
 #define OPCHK(c, call)                                                       \
     do {                                                                     \
         zo2_status s__ = (call);                                             \
+        if (s__ != ZO2_OK) return fail(c, s__, "%s", zo2_op_last_error());   \
+    } while (0)
+
+// Bracket one launch with a pair of events when its class is being profiled.
+struct ProfScope {
+    zo2_ctx* c;
+    int cls;
+    bool on;
+    ProfScope(zo2_ctx* c_, int cls_) : c(c_), cls(cls_), on((c_->prof_mask >> cls_) & 1u) {
+        if (!on) return;
+        if (c->prof_used + 2 > c->prof_ev.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+            c->prof_ev.push_back(a);
+            c->prof_ev.push_back(b);
+        }
+        (void)hipEventRecord(c->prof_ev[c->prof_used], c->sc);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(c->prof_ev[c->prof_used + 1], c->sc);
+        c->prof_cls.push_back(cls);
+        c->prof_used += 2;
+    }
+};
+static void prof_reset(zo2_ctx* c) {
+    c->prof_used = 0;
+    c->prof_cls.clear();
+    for (int i = 0; i < ZO2_KERNEL_CLASSES; ++i) { c->prof_ms[i] = 0.f; c->prof_launches[i] = 0; }
+}
+static void prof_collect(zo2_ctx* c) {   // after the compute stream has been synchronised
+    for (size_t i = 0; i < c->prof_cls.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) == hipSuccess) {
+            c->prof_ms[c->prof_cls[i]] += ms;
+            c->prof_launches[c->prof_cls[i]] += 1;
+        }
+    }
+}
+#define OPK(c, cls, call)                                                    \
+    do {                                                                     \
+        zo2_status s__;                                                      \
+        {                                                                    \
+            ProfScope ps__(c, cls);                                          \
+            s__ = (call);                                                    \
+        }                                                                    \
         if (s__ != ZO2_OK) return fail(c, s__, "%s", zo2_op_last_error());   \
     } while (0)
 
@@ -242,6 +296,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->bytes_up = c->bytes_down = 0;
     c->ms_c = c->ms_u = c->ms_o = 0.f;
     c->bytes_used = 0;
+    c->prof_mask = 0;
+    prof_reset(c);
     c->n_slots = 0;
     c->resident = false;
     *out = c;   // from here on errors are reported through the context
@@ -279,6 +335,7 @@ extern "C" void zo2_destroy(zo2_ctx* c) {
     for (auto e : c->ev_up) hipEventDestroy(e);
     for (auto e : c->ev_k1) hipEventDestroy(e);
     for (auto e : c->ev_free) hipEventDestroy(e);
+    for (auto e : c->prof_ev) hipEventDestroy(e);
     hipEvent_t evs[] = {c->ev_step0, c->ev_c1, c->ev_u0, c->ev_u1, c->ev_o0, c->ev_o1};
     if (c->h_result) for (hipEvent_t e : evs) hipEventDestroy(e);
     if (c->h_ids) hipHostFree(c->h_ids);
@@ -427,6 +484,21 @@ extern "C" zo2_status zo2_get_plan(const zo2_ctx* c, int32_t* n_slots, int32_t* 
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_set_profiling(zo2_ctx* c, uint32_t class_mask) {
+    if (!c) return ZO2_EINVAL;
+    c->prof_mask = class_mask & ((1u << ZO2_KERNEL_CLASSES) - 1);
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_kernel_times(const zo2_ctx* c, float ms[ZO2_KERNEL_CLASSES], int32_t launches[ZO2_KERNEL_CLASSES]) {
+    if (!c) return ZO2_EINVAL;
+    for (int i = 0; i < ZO2_KERNEL_CLASSES; ++i) {
+        if (ms) ms[i] = c->prof_ms[i];
+        if (launches) launches[i] = c->prof_launches[i];
+    }
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_step_stats(const zo2_ctx* c, float* ms_c, float* ms_u, float* ms_o, uint64_t* up, uint64_t* down) {
     if (!c) return ZO2_EINVAL;
     if (ms_c) *ms_c = c->ms_c;
@@ -454,7 +526,7 @@ static zo2_status k1_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, bo
     k1_common(c, a, seed, eps);
     a.theta = theta; a.w_plus = wp; a.w_minus = wm; a.w_off0 = 0; a.nseg = 1;
     a.seg[0].off = 0; a.seg[0].e0 = 0; a.seg[0].n = (uint64_t)n; a.seg[0].tensor_id = tid; a.seg[0].scale = c->scales[tid];
-    OPCHK(c, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    OPK(c, ZO2_KC_K1, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
     return ZO2_OK;
 }
 
@@ -467,7 +539,7 @@ static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool
         K1Seg& s = a.seg[k - t0];
         s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
     }
-    OPCHK(c, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    OPK(c, ZO2_KC_K1, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
     return ZO2_OK;
 }
 
@@ -498,7 +570,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
     if (!c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     PhaseView w = view(0);
-    OPCHK(c, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
     ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = f32; ga.nprob = 6;
     char* outs[3] = {c->qb, c->kb, c->vb};
@@ -512,8 +584,8 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
             p.Y = outs[t] + s * half_d;
             p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
         }
-    OPCHK(c, gemm_launch(ga, dt, c->sc));
-    OPCHK(c, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, c->sc));
+    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, c->sc));
     { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
     w = view(1);
     memset(&ga, 0, sizeof(ga));
@@ -523,12 +595,12 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->ctxb + s * half_d; p.W = s ? w.M(8) : w.P(8); p.bias = s ? w.M(9) : w.P(9);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
     }
-    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
 
     // ---- FFN half: h += FC2(ReLU(FC1(LN2(h))))
     { zo2_status s = phase(2); if (s != ZO2_OK) return s; }
     w = view(2);
-    OPCHK(c, layernorm(dt, c->h, w.P(10), w.P(11), w.M(10), w.M(11), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(10), w.P(11), w.M(10), w.M(11), c->x, 2 * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
     ga.M = T; ga.N = f; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = f; ga.relu = 1; ga.out_f32 = f32; ga.nprob = 2;
     for (int s = 0; s < 2; ++s) {
@@ -536,7 +608,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->x + s * half_d; p.W = s ? w.M(12) : w.P(12); p.bias = s ? w.M(13) : w.P(13);
         p.residual = nullptr; p.Y = c->mid + s * half_f; p.out_scale = 1.0f;
     }
-    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
     { zo2_status s = phase(3); if (s != ZO2_OK) return s; }
     if (c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     w = view(3);
@@ -547,7 +619,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->mid + s * half_f; p.W = s ? w.M(14) : w.P(14); p.bias = s ? w.M(15) : w.P(15);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
     }
-    OPCHK(c, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
     return ZO2_OK;
 }
 
@@ -604,6 +676,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     const bool upd = c->has_pending;
     c->bytes_up = c->bytes_down = 0;
     c->stat_u = c->stat_o = false;
+    prof_reset(c);
 
     memcpy(c->h_ids, tokens, (size_t)T * 4);
     memcpy(c->h_ids + T, labels, (size_t)T * 4);
@@ -626,7 +699,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps;
     ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = c->d_state;
     ea.k_prev = philox_keys(c->seed_prev); ea.k_cur = philox_keys(seed);
-    OPCHK(c, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
+    OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
     if (upd) {
         { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
         if (!g.tied_lm_head) { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
@@ -660,10 +733,10 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
             a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)d;
             a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
         }
-        OPCHK(c, k1_launch(a, g.wire_dtype, dt, upd, true, c->sc));
+        OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, dt, upd, true, c->sc));
     }
     const size_t boff = (size_t)c->fln_off_b * c->csz;
-    OPCHK(c, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, 2 * T, T, d, g.ln_eps, c->sc));
     {
         zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps)
                                       : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps);
@@ -680,11 +753,11 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
             p.X = c->x + ((size_t)s * T + r0) * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr;
             p.Y = c->logits + (size_t)s * R * g.vocab; p.out_scale = 1.0f;
         }
-        OPCHK(c, gemm_launch(ga, dt, c->sc));
+        OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
         for (int s = 0; s < 2; ++s)
-            OPCHK(c, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
+            OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
     }
-    OPCHK(c, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, c->d_state + 4, c->d_state, c->sc));
+    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, c->d_state + 4, c->d_state, c->sc));
     HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
     if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
@@ -694,6 +767,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         HIPCHK(c, hipStreamSynchronize(c->su));
         HIPCHK(c, hipStreamSynchronize(c->so));
     }
+    prof_collect(c);
     hipEventElapsedTime(&c->ms_c, c->ev_step0, c->ev_c1);
     c->ms_u = c->ms_o = 0.f;
     if (c->stat_u) hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
@@ -754,7 +828,7 @@ extern "C" zo2_status zo2_flush(zo2_ctx* c) {
             a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)g.d_model;
             a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
         }
-        OPCHK(c, k1_launch(a, g.wire_dtype, g.compute_dtype, true, false, c->sc));
+        OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, g.compute_dtype, true, false, c->sc));
     }
     if (c->d_lm) { zo2_status s = k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
     HIPCHK(c, hipStreamSynchronize(c->sc));

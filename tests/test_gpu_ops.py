@@ -15,7 +15,8 @@ def _b():
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
-@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (22, 32, 32), (200, 136, 72), (257, 515, 264), (128, 97 * 8, 40), (4, 8, 8)])
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (22, 32, 32), (200, 136, 72), (257, 515, 264), (128, 97 * 8, 40), (4, 8, 8),
+                                   (256, 256, 64), (512, 768, 128), (300, 515, 192), (1024, 384, 2048), (700, 1030, 320)])
 def test_gemm_against_float64(dt, M, N, K):
     b = _b()
     g = torch.Generator().manual_seed(M * 1000 + N + K)

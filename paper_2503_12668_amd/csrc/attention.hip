@@ -103,6 +103,181 @@ __global__ __launch_bounds__(64) void attention_valu_kernel(const T* __restrict_
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// MFMA kernel (bf16 / fp16, d_head 64 or 128).  One wavefront owns 32 queries and walks the
+// keys in tiles of 32; everything lives in registers, operands come straight from global
+// memory (L2) as 16-byte loads, no LDS.
+//
+//   S^T = K Q^T   (32 keys x 32 queries)   A operand: K rows, B operand: Q rows
+//   O^T += V^T P^T (d_head x 32 queries)   A operand: V^T rows (needs V transposed: `vt`),
+//                                           B operand: P^T taken directly from the S^T
+//                                           accumulator registers.
+// In the 32x32 accumulator layout a lane holds one query column and 16 key rows
+// rho = 8 (v/4) + 4 kh + v%4.  As a B operand of the second product a lane must supply 8
+// consecutive contraction slots 8 kh .. 8 kh + 7 per 16-slot step.  Both fit together if
+// accumulator row rho carries key pi(rho), pi swapping the bits "kh" and "v/4 & 1" inside each
+// 16-block: then registers v = 8 s .. 8 s + 7 are keys 16 s + 8 kh .. + 7, which is also a
+// single 16-byte run of a V^T row.  pi is applied for free when choosing which K row a lane
+// loads.
+// ---------------------------------------------------------------------------------------
+typedef __bf16 att_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 att_f16x8 __attribute__((ext_vector_type(8)));
+typedef float att_f32x16 __attribute__((ext_vector_type(16)));
+
+template <typename T> struct AttMfma;
+template <> struct AttMfma<bf16_t> {
+    static __device__ __forceinline__ att_f32x16 run(uint4 a, uint4 b, att_f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(att_bf16x8, a), __builtin_bit_cast(att_bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct AttMfma<f16_t> {
+    static __device__ __forceinline__ att_f32x16 run(uint4 a, uint4 b, att_f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(att_f16x8, a), __builtin_bit_cast(att_f16x8, b), c, 0, 0, 0);
+    }
+};
+
+// v [n_seq * seq, ld] -> vt [n_seq][ld_cols = n_heads * d_head][seq_pad], zero beyond seq
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ v, T* __restrict__ vt, int seq, int seq_pad,
+                                                          int cols, int64_t ld) {
+    __shared__ T tile[32][33];
+    const int t0 = blockIdx.x * 32, c0 = blockIdx.y * 32, sq = blockIdx.z;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = t0 + ty + 8 * i, c = c0 + tx;
+        tile[ty + 8 * i][tx] = (t < seq && c < cols) ? v[((size_t)sq * seq + t) * ld + c] : Fmt<T>::store(0.f);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = c0 + ty + 8 * i, t = t0 + tx;
+        if (c < cols && t < seq_pad) vt[((size_t)sq * cols + c) * seq_pad + t] = tile[tx][ty + 8 * i];
+    }
+}
+
+template <typename T, int DH>
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
+                                                                 T* __restrict__ out, int seq, int seq_pad, int cols, int64_t ld) {
+    constexpr int KS = DH / 16;          // contraction steps of the first product
+    constexpr int DT = DH / 32;          // 32-row tiles of O^T
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, kh = lane >> 5;
+    const int head = blockIdx.y, sq = blockIdx.z;
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    if (q0 >= seq) return;
+    const size_t base = (size_t)sq * seq * ld + (size_t)head * DH;
+    const int qi = q0 + r;                                   // this lane's query
+    const int qrow = min(qi, seq - 1);
+    // key carried by accumulator row rho: swap bits 2 (kh of rho) and 3 inside each 16-block
+    const int pr = (r & 0x13) | ((r & 4) << 1) | ((r & 8) >> 1);
+
+    uint4 qf[KS];
+#pragma unroll
+    for (int c = 0; c < KS; ++c) qf[c] = *reinterpret_cast<const uint4*>(q + base + (size_t)qrow * ld + c * 16 + kh * 8);
+
+    att_f32x16 o[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[d][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const T* vt_base = vt + ((size_t)sq * cols + (size_t)head * DH + r) * seq_pad + kh * 8;
+    constexpr float kLog2e = 1.4426950408889634f;
+
+    const int last_tile = q0 >> 5;
+    for (int tile = 0; tile <= last_tile; ++tile) {
+        const int j0 = tile * 32;
+        // ---- S^T = K Q^T
+        const int krow = min(j0 + pr, seq - 1);
+        const T* kp = k + base + (size_t)krow * ld + kh * 8;
+        uint4 kf[KS];
+#pragma unroll
+        for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kp + c * 16);
+        uint4 vf[DT][2];
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+                vf[d][s2] = *reinterpret_cast<const uint4*>(vt_base + (size_t)d * 32 * seq_pad + j0 + 16 * s2);
+        att_f32x16 st;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[v] = 0.f;
+#pragma unroll
+        for (int c = 0; c < KS; ++c) st = AttMfma<T>::run(kf[c], qf[c], st);
+        // ---- mask (only the diagonal tile has hidden keys) and online softmax
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            // accumulator row rho = 8 (v/4) + 4 kh + v%4 carries key j0 + pi(rho) = j0 + 16 (v/8) + 8 kh + v%8
+            const int key = j0 + 16 * (v >> 3) + 8 * kh + (v & 7);
+            if (tile == last_tile && key > qi) st[v] = -INFINITY;
+            tmax = fmaxf(tmax, st[v]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(m_run, tmax);              // finite: key j0 <= q0 <= qi is always visible in tile 0
+        const float resc = __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);
+        float psum = 0.f;
+        float p[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            p[v] = __builtin_amdgcn_exp2f((st[v] - m_new) * kLog2e);
+            psum += p[v];
+        }
+        l_run = l_run * resc + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[d][v] *= resc;
+        // ---- O^T += V^T P^T
+        uint4 pf[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            Vec<T, 8> pv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv.v[e] = Fmt<T>::store(p[8 * s2 + e]);
+            pf[s2] = __builtin_bit_cast(uint4, pv);
+        }
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) o[d] = AttMfma<T>::run(vf[d][s2], pf[s2], o[d]);
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    if (qi < seq) {
+        T* op = out + base + (size_t)qi * ld;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                Vec<T, 4> ov;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ov.v[e] = Fmt<T>::store(o[d][4 * g + e] * inv);
+                store_vec<T, 4>(op + d * 32 + 8 * g + 4 * kh, ov);
+            }
+    }
+}
+
+template <typename T>
+static zo2_status launch_mfma_att(const T* q, const T* k, const T* v, T* out, T* vt, int n_seq, int seq, int n_heads, int d_head,
+                                  int64_t ld, hipStream_t st) {
+    const int seq_pad = (seq + 31) / 32 * 32, cols = n_heads * d_head;
+    hipLaunchKernelGGL((transpose_v_kernel<T>), dim3(seq_pad / 32, (cols + 31) / 32, n_seq), dim3(256), 0, st, v, vt, seq, seq_pad, cols, ld);
+    ZO2_HIP_LAUNCH_CHECK();
+    const dim3 grid((seq + 127) / 128, n_heads, n_seq), block(256);
+    if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, vt, out, seq, seq_pad, cols, ld);
+    else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, vt, out, seq, seq_pad, cols, ld);
+    ZO2_HIP_LAUNCH_CHECK();
+    return ZO2_OK;
+}
+
+size_t attention_workspace_bytes(int dtype, int n_seq, int seq, int n_heads, int d_head) {
+    if (dtype == ZO2_F32 || !(d_head == 64 || d_head == 128)) return 0;
+    return (size_t)n_seq * n_heads * d_head * ((seq + 31) / 32 * 32) * 2;
+}
+
 template <typename T>
 static zo2_status launch_valu(const T* q, const T* k, const T* v, T* out, int n_seq, int seq, int n_heads, int d_head,
                               int64_t ld, hipStream_t st) {
@@ -120,13 +295,21 @@ static zo2_status launch_valu(const T* q, const T* k, const T* v, T* out, int n_
     return ZO2_OK;
 }
 
-zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out,
+zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out, void* workspace, size_t workspace_bytes,
                             int n_seq, int seq, int n_heads, int d_head, int64_t ld, hipStream_t st) {
     if (n_seq == 0 || seq == 0) return ZO2_OK;
     ZO2_OP_CHECK(n_seq > 0 && seq > 0 && n_heads > 0 && d_head > 0, ZO2_EINVAL, "attention: bad shape");
     ZO2_OP_CHECK(q && k && v && out, ZO2_EINVAL, "attention: NULL buffer");
     ZO2_OP_CHECK(ld >= (int64_t)n_heads * d_head && ld % 8 == 0, ZO2_EINVAL, "attention: bad leading dimension");
     ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535, ZO2_EINVAL, "attention: grid too large");
+    const size_t need = attention_workspace_bytes(dtype, n_seq, seq, n_heads, d_head);
+    if (need != 0 && workspace != nullptr && workspace_bytes >= need && ((uintptr_t)workspace & 15) == 0) {
+        if (dtype == ZO2_BF16)
+            return launch_mfma_att<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, (bf16_t*)workspace,
+                                           n_seq, seq, n_heads, d_head, ld, st);
+        return launch_mfma_att<f16_t>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, (f16_t*)out, (f16_t*)workspace,
+                                      n_seq, seq, n_heads, d_head, ld, st);
+    }
     ZO2_DISPATCH_COMPUTE(dtype, T, {
         return launch_valu<T>((const T*)q, (const T*)k, (const T*)v, (T*)out, n_seq, seq, n_heads, d_head, ld, st);
     });

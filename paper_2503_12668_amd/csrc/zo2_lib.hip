@@ -88,7 +88,7 @@ struct zo2_ctx {
 
     // plan (depends on budget and batch x seq)
     bool planned, need_plan;
-    int plan_T;
+    int plan_T, plan_seq;
     bool resident, phased;
     int n_slots;
     char* slots;
@@ -96,7 +96,8 @@ struct zo2_ctx {
     int64_t scratch_elems;
     char *fln_wp, *fln_wm;
     float* h;
-    char *x, *qb, *kb, *vb, *ctxb, *mid;
+    char *x, *qb, *kb, *vb, *ctxb, *mid, *att_ws;
+    size_t att_ws_bytes;
     float* logits;
     int logit_rows;                     // rows per sign per chunk
     float* row_loss;
@@ -381,7 +382,7 @@ extern "C" zo2_status zo2_sync_to_host(zo2_ctx* c) {
 // hold a whole block): {ln1, q, k, v}, {o}, {ln2, fc1}, {fc2}.
 static const int kPhase[5] = {0, 8, 10, 14, 16};
 
-static zo2_status plan(zo2_ctx* c, int T) {
+static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const zo2_config& g = c->cfg;
     const size_t d = g.d_model, f = g.d_ffn, V = g.vocab;
     const size_t budget = c->budget;
@@ -391,10 +392,12 @@ static zo2_status plan(zo2_ctx* c, int T) {
     lrows = lrows / 128 * 128;
     if (lrows < 128) lrows = 128;
     if (lrows > (size_t)T) lrows = T;
+    const size_t att_ws = attention_workspace_bytes(g.compute_dtype, 2 * batch, seq, g.n_heads, g.d_model / g.n_heads);
     size_t act = 0;
     auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
     const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
                  o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
+                 o_aws = sz(att_ws),
                  o_logits = sz(2 * lrows * V * 4), o_rl = sz(rows2 * 4), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
                  o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
     const size_t act_bytes = act;
@@ -435,7 +438,7 @@ static zo2_status plan(zo2_ctx* c, int T) {
     c->wm = base + off; off += align_up((size_t)scratch * c->csz, 256);
     char* a0 = base + off;
     c->h = (float*)(a0 + o_h); c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
-    c->mid = a0 + o_mid; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
+    c->mid = a0 + o_mid; c->att_ws = a0 + o_aws; c->att_ws_bytes = att_ws; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
     c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
     c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
     off += act_bytes;
@@ -464,6 +467,7 @@ static zo2_status plan(zo2_ctx* c, int T) {
     c->resident = resident;
     c->n_slots = n_slots;
     c->plan_T = T;
+    c->plan_seq = seq;
     c->planned = true;
     c->need_plan = false;
 
@@ -585,7 +589,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
             p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
         }
     OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, c->sc));
+    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, c->att_ws, c->att_ws_bytes, 2 * batch, seq, g.n_heads, dh, d, c->sc));
     { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
     w = view(1);
     memset(&ga, 0, sizeof(ga));
@@ -668,8 +672,8 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, ZO2_EINVAL, "zo2_step: token %d at %d outside [0, %d)", tokens[i], i, g.vocab);
         if (labels[i] != -100 && (labels[i] < 0 || labels[i] >= g.vocab)) return fail(c, ZO2_EINVAL, "zo2_step: label %d at %d invalid", labels[i], i);
     }
-    if (!c->planned || c->need_plan || c->plan_T != T) {
-        zo2_status s = plan(c, T);
+    if (!c->planned || c->need_plan || c->plan_T != T || c->plan_seq != seq) {
+        zo2_status s = plan(c, T, batch, seq);
         if (s != ZO2_OK) return s;
     }
     const int d = g.d_model, dt = g.compute_dtype;
@@ -881,9 +885,14 @@ extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K
     return gemm_launch(a, dtype, as_stream(stream));
 }
 
-extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, int32_t n_seq, int32_t seq,
-                                       int32_t n_heads, int32_t d_head, int64_t ld, void* stream) {
-    return attention_launch(dtype, q, k, v, out, n_seq, seq, n_heads, d_head, ld, as_stream(stream));
+extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, void* workspace,
+                                       size_t workspace_bytes, int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head, int64_t ld,
+                                       void* stream) {
+    return attention_launch(dtype, q, k, v, out, workspace, workspace_bytes, n_seq, seq, n_heads, d_head, ld, as_stream(stream));
+}
+
+extern "C" size_t zo2_op_attention_workspace_bytes(int32_t dtype, int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head) {
+    return attention_workspace_bytes(dtype, n_seq, seq, n_heads, d_head);
 }
 
 extern "C" zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2, void* y,

@@ -97,7 +97,7 @@ def main():
     P = si.make_weights(cfg, seed=1)
     tok = si.make_tokens(cfg["vocab"], BATCH, SEQ, seed=2, dist="zipf")
     lab = si.next_token_labels(tok)
-    ctx = binding.Zo2Context(cfg, P, wire="bf16", compute="bf16")
+    ctx = binding.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=20 << 30)
     del P
     print(f"[bench] setup {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 

@@ -143,7 +143,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a) 
     read_frags(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
+#ifndef ZO2_GEMM_EXP_NODMA
         if (kt + 1 < nk) issue(cur ^ 1, (kt + 1) * kBK);
+#endif
         read_frags(cur, 1, 1); mfmas(0); interleave();
         read_frags(cur, 2, 0); mfmas(1); interleave();
         read_frags(cur, 3, 1); mfmas(0); interleave();

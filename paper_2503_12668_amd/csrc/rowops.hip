@@ -248,13 +248,24 @@ __global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ 
         return;
     }
     const float* lr = logits + (size_t)blockIdx.x * ld;
-    float m = -INFINITY;
-    for (int i = threadIdx.x; i < vocab; i += 256) m = fmaxf(m, lr[i]);
-    m = block_max(m, shf);
-    float s = 0.f;
-    for (int i = threadIdx.x; i < vocab; i += 256) s += expf(lr[i] - m);
-    const double tot = block_sum((double)s, shd);
-    if (threadIdx.x == 0) row_loss[r] = (float)(log(tot) + (double)m - (double)lr[lab]);
+    // one pass: running maximum m and sum s of exp(x - m) per lane, rescaled when m grows
+    float m = -INFINITY, s = 0.f;
+    const bool vec = ((ld & 3) == 0) && (((uintptr_t)logits & 15) == 0);
+    const int nv = vec ? (vocab >> 2) : 0;
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        const float4 x = reinterpret_cast<const float4*>(lr)[i];
+        const float mx = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+        if (mx > m) { s *= expf(m - mx); m = mx; }
+        s += (expf(x.x - m) + expf(x.y - m)) + (expf(x.z - m) + expf(x.w - m));
+    }
+    for (int i = nv * 4 + threadIdx.x; i < vocab; i += 256) {
+        const float x = lr[i];
+        if (x > m) { s *= expf(m - x); m = x; }
+        s += expf(x - m);
+    }
+    const float mall = block_max(m, shf);
+    const double tot = block_sum((double)(m == -INFINITY ? 0.f : s * expf(m - mall)), shd);
+    if (threadIdx.x == 0) row_loss[r] = (float)(log(tot) + (double)mall - (double)lr[lab]);
 }
 
 zo2_status cross_entropy_rows(const float* logits, int64_t ld, const int32_t* labels, int rows, int row0, int label_period,

@@ -387,8 +387,8 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const size_t d = g.d_model, f = g.d_ffn, V = g.vocab;
     const size_t budget = c->budget;
     const size_t rows2 = 2 * (size_t)T;
-    // logits chunk: about 1/32 of the budget, at least 128 rows per sign
-    size_t lrows = budget / 32 / (V * 4) / 2;
+    // logits chunk: up to 1/8 of the budget, at least 128 rows per sign
+    size_t lrows = budget / 8 / (V * 4) / 2;
     lrows = lrows / 128 * 128;
     if (lrows < 128) lrows = 128;
     if (lrows > (size_t)T) lrows = T;

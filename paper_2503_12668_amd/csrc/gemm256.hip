@@ -10,6 +10,8 @@
 // belongs at position i.
 //
 // Requires K % 64 == 0; M and N are arbitrary (rows are clamped on load, masked on store).
+#include <type_traits>
+
 #include "gemm.h"
 
 namespace zo2 {
@@ -35,7 +37,7 @@ template <> struct Mfma32<f16_t> {
 #endif
 static constexpr int kBM = 256, kBN = 256, kBK = 64;
 static constexpr int kStageBytes = (kBM + kBN) * kBK * 2;      // 65536
-static constexpr int kLdsBytes = 2 * kStageBytes;              // 131072
+static constexpr int kLdsBytes = 4 * 34816;                    // two 64 KB stages; the epilogue needs 4 x 34816
 
 // direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_base + 16 i
 __device__ __forceinline__ void load_to_lds(const void* gptr, uint32_t lds_base) {
@@ -102,63 +104,143 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a) 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    auto issue = [&](int stage, int k0) {
-        const uint32_t so = stage * kStageBytes;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) load_to_lds(pa[t] + k0, ld_a + so + t * 1024);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) load_to_lds(pb[t] + k0, ld_b + so + t * 1024);
-    };
     uint4 fa[2][4], fb[2][4];
-    auto read_frags = [&](int stage, int ks, int buf) {
-        const char* sa = smem + stage * kStageBytes + fr_a + koff[ks];
-        const char* sb = smem + stage * kStageBytes + fr_b + koff[ks];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fb[buf][j] = *reinterpret_cast<const uint4*>(sb + j * 4096);
-    };
-    auto mfmas = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(fb[buf][j], fa[buf][i], acc[i][j]);
-    };
-    // ask the scheduler for: one LDS read, then two MFMAs, eight times over
-    auto interleave = [&]() {
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    // One "group" = the four MFMAs of X row-block i at k-step buffer `buf`, preceded by the two
+    // LDS reads that fetch row-block i of both operands for the next k-step into buffer `nbuf`,
+    // and optionally two direct-to-LDS loads of the tile after next.  A scheduling barrier after
+    // every group keeps memory instructions spread evenly under the MFMAs instead of bunched.
+    auto mgroup = [&](int i, int buf, int nbuf, bool do_read, const char* sa, const char* sb, bool do_dma, int dma_stage, int dma_k0, int dma_t) {
+        if (do_dma) {
+            const uint32_t so = dma_stage * kStageBytes;
+            load_to_lds(pa[dma_t] + dma_k0, ld_a + so + dma_t * 1024);
+            load_to_lds(pb[dma_t] + dma_k0, ld_b + so + dma_t * 1024);
         }
+#ifndef ZO2_GEMM_EXP_NOREAD
+        if (do_read) {
+            fa[nbuf][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
+            fb[nbuf][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
+        }
+#endif
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(fb[buf][j], fa[buf][i], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    // Software pipeline: fragments of k-step s+1 are read while the MFMAs of k-step s run;
-    // one barrier per tile both publishes the next tile (its direct-to-LDS loads were issued a
-    // whole tile earlier) and retires the stage just read.
     const int nk = a.K / kBK;
-    issue(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    read_frags(0, 0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-#ifndef ZO2_GEMM_EXP_NODMA
-        if (kt + 1 < nk) issue(cur ^ 1, (kt + 1) * kBK);
+    // prologue: tile 0 into stage 0, its first fragments into buffer 0
+    {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            load_to_lds(pa[t], ld_a + t * 1024);
+            load_to_lds(pb[t], ld_b + t * 1024);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const char* sa = smem + fr_a + koff[0];
+        const char* sb = smem + fr_b + koff[0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[0][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
+            fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
+        }
+    }
+    // `more`: another tile follows (its loads are issued under k-steps 0 and 1, its first
+    // fragments are read under k-step 3); compile-time so that no group carries a branch
+    auto tile_iter = [&](int kt, auto more_c) {
+        constexpr bool more = decltype(more_c)::value;
+#ifdef ZO2_GEMM_EXP_NODMA
+        constexpr bool dma = false;
+#else
+        constexpr bool dma = more;
 #endif
-        read_frags(cur, 1, 1); mfmas(0); interleave();
-        read_frags(cur, 2, 0); mfmas(1); interleave();
-        read_frags(cur, 3, 1); mfmas(0); interleave();
+        const int cur = kt & 1;
+        const char* base_a = smem + cur * kStageBytes + fr_a;
+        const char* base_b = smem + cur * kStageBytes + fr_b;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[1], base_b + koff[1], dma, cur ^ 1, (kt + 1) * kBK, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, true, base_a + koff[2], base_b + koff[2], dma, cur ^ 1, (kt + 1) * kBK, 4 + i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[3], base_b + koff[3], false, 0, 0, 0);
+        // one barrier per tile: publishes tile kt+1 (every wavefront waited for its own loads) and
+        // retires stage cur (every wavefront has its last fragments in registers)
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __syncthreads();
-        if (kt + 1 < nk) read_frags(cur ^ 1, 0, 0);
-        mfmas(1);
-    }
+        const char* next_a = smem + (cur ^ 1) * kStageBytes + fr_a + koff[0];
+        const char* next_b = smem + (cur ^ 1) * kStageBytes + fr_b + koff[0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, more, next_a, next_b, false, 0, 0, 0);
+    };
+    for (int kt = 0; kt + 1 < nk; ++kt) tile_iter(kt, std::true_type{});
+    tile_iter(nk - 1, std::false_type{});
 
-    // epilogue: for tile (i, j) a lane holds row m = r and columns 8 (v/4) + 4 kh + (v%4)
+    // ---- epilogue.  For tile (i, j) a lane holds row m = r and columns 8 q + 4 kh + (0..3).
+    // Writing that straight to memory would touch 32 different cache lines per store with 8-16
+    // bytes each; instead every wavefront parks its 128 x 128 sub-tile in its own LDS region
+    // (all main-loop reads are behind the last barrier) and streams it out as 16-byte pieces of
+    // whole rows, so a store covers complete cache lines.
     const T* __restrict__ bias = reinterpret_cast<const T*>(p.bias);
     OutT* __restrict__ Y = reinterpret_cast<OutT*>(p.Y);
-    const bool n_vec_ok = (a.N % 4 == 0) && (a.ldy % 4 == 0);
+    constexpr int EPC = 16 / (int)sizeof(OutT);                 // elements per 16-byte piece
+    constexpr int ROWB = 128 * (int)sizeof(OutT) + 16;         // padded row of the wave's sub-tile
+    constexpr int PASS_I = (sizeof(OutT) == 2) ? 4 : 2;        // 32-row blocks per pass (region = 34816 B)
+    constexpr int CPR = 128 / EPC;                             // pieces per row
+    constexpr int RPI = 64 / CPR;                              // rows per store instruction
+    const bool fast = (a.N % EPC == 0) && (a.ldy % EPC == 0) && (((uintptr_t)p.Y & 15) == 0) &&
+                      (p.residual == nullptr || (sizeof(OutT) == 4 && ((uintptr_t)p.residual & 15) == 0));
+    if (fast) {
+        char* reg = smem + wave * 34816;
+#pragma unroll
+        for (int pass = 0; pass < 4 / PASS_I; ++pass) {
+            if (pass) __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ii = 0; ii < PASS_I; ++ii) {
+                const int i = pass * PASS_I + ii;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int col = j * 32 + 8 * q + 4 * kh;
+                        const int n = n0 + wn * 128 + col;
+                        float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                        if (bias && n < a.N) {
+                            const Vec<T, 4> b4 = load_vec<T, 4>(bias + n);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) bv[e] = Fmt<T>::load(b4.v[e]);
+                        }
+                        Vec<OutT, 4> ov;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float t = (acc[i][j][4 * q + e] + bv[e]) * p.out_scale;
+                            if (a.relu) t = fmaxf(t, 0.f);
+                            ov.v[e] = Fmt<OutT>::store(t);
+                        }
+                        store_vec<OutT, 4>(reinterpret_cast<OutT*>(reg + (ii * 32 + r) * ROWB) + col, ov);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int rr = lane / CPR, ch = lane % CPR;
+            const int n = n0 + wn * 128 + ch * EPC;
+#pragma unroll 4
+            for (int rl = 0; rl < PASS_I * 32; rl += RPI) {
+                const int m = m0 + wm * 128 + pass * PASS_I * 32 + rl + rr;
+                uint4 v = *reinterpret_cast<const uint4*>(reg + (rl + rr) * ROWB + ch * 16);
+                if (m < a.M && n < a.N) {
+                    const size_t o = (size_t)m * a.ldy + n;
+                    if (sizeof(OutT) == 4 && p.residual) {
+                        const float4 rv = *reinterpret_cast<const float4*>(p.residual + o);
+                        float4 f = __builtin_bit_cast(float4, v);
+                        f.x += rv.x; f.y += rv.y; f.z += rv.z; f.w += rv.w;
+                        v = __builtin_bit_cast(uint4, f);
+                    }
+                    *reinterpret_cast<uint4*>(Y + o) = v;
+                }
+            }
+        }
+        return;
+    }
+    // general path (odd N or leading dimension, or a residual with a 16-bit output)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int m = m0 + wm * 128 + i * 32 + r;
@@ -168,34 +250,14 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a) 
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + wn * 128 + j * 32 + 8 * q + 4 * kh;
-                if (n >= a.N) continue;
                 const size_t o = (size_t)m * a.ldy + n;
-                float y[4];
-                if (n_vec_ok) {                       // n + 3 < N because N % 4 == 0
-                    Vec<T, 4> bv;
-                    if (bias) bv = load_vec<T, 4>(bias + n);
-                    float4 rv = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (p.residual) rv = *reinterpret_cast<const float4*>(p.residual + o);
-                    const float rr[4] = {rv.x, rv.y, rv.z, rv.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float t = (acc[i][j][4 * q + e] + (bias ? Fmt<T>::load(bv.v[e]) : 0.f)) * p.out_scale;
-                        if (a.relu) t = fmaxf(t, 0.f);
-                        y[e] = t + rr[e];
-                    }
-                    Vec<OutT, 4> ov;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) ov.v[e] = Fmt<OutT>::store(y[e]);
-                    store_vec<OutT, 4>(Y + o, ov);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (n + e >= a.N) continue;
-                        float t = (acc[i][j][4 * q + e] + (bias ? Fmt<T>::load(bias[n + e]) : 0.f)) * p.out_scale;
-                        if (a.relu) t = fmaxf(t, 0.f);
-                        if (p.residual) t += p.residual[o + e];
-                        Y[o + e] = Fmt<OutT>::store(t);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    if (n + e >= a.N) continue;
+                    float t = (acc[i][j][4 * q + e] + (bias ? Fmt<T>::load(bias[n + e]) : 0.f)) * p.out_scale;
+                    if (a.relu) t = fmaxf(t, 0.f);
+                    if (p.residual) t += p.residual[o + e];
+                    Y[o + e] = Fmt<OutT>::store(t);
                 }
             }
         }

@@ -226,7 +226,8 @@ def _from_wire(t, scale=1.0):
 class Zo2Context:
     """Host buffers + arena + streams + the library context for one model.
 
-    weights: name -> float32 array ("tok_emb", "pos_emb", "blocks.{l}.{t}", "final_ln.w", "final_ln.b"[, "lm_head.w"]).
+    weights: name -> float32 array ("tok_emb", "pos_emb", "blocks.{l}.{t}", "final_ln.w", "final_ln.b"[, "lm_head.w"]),
+    or a callable (name, shape) -> float32 torch tensor on any device (for models too large to build as a dict).
     They are converted once to the wire dtype and packed into per-block host buckets (pinned when possible);
     from then on the library owns their contents."""
 
@@ -246,21 +247,24 @@ class Zo2Context:
         def host(n):
             return torch.zeros(n, dtype=tdt, pin_memory=pin)
 
+        def get(name, shape):
+            return weights(name, shape) if callable(weights) else weights[name]
+
         def fill(dst, a, tid):
             dst.copy_(_to_wire(a, self.wire_id, float(self.scales[tid])).reshape(-1))
 
-        self.h_tok = host(cfg["vocab"] * cfg["d_model"]); fill(self.h_tok, weights["tok_emb"], 0)
-        self.h_pos = host((cfg["max_pos"] + cfg["pos_offset"]) * cfg["d_model"]); fill(self.h_pos, weights["pos_emb"], 1)
-        self.h_flnw = host(cfg["d_model"]); fill(self.h_flnw, weights["final_ln.w"], 2 + 16 * L)
-        self.h_flnb = host(cfg["d_model"]); fill(self.h_flnb, weights["final_ln.b"], 3 + 16 * L)
+        self.h_tok = host(cfg["vocab"] * cfg["d_model"]); fill(self.h_tok, get("tok_emb", (cfg["vocab"], cfg["d_model"])), 0)
+        self.h_pos = host((cfg["max_pos"] + cfg["pos_offset"]) * cfg["d_model"]); fill(self.h_pos, get("pos_emb", (cfg["max_pos"] + cfg["pos_offset"], cfg["d_model"])), 1)
+        self.h_flnw = host(cfg["d_model"]); fill(self.h_flnw, get("final_ln.w", (cfg["d_model"],)), 2 + 16 * L)
+        self.h_flnb = host(cfg["d_model"]); fill(self.h_flnb, get("final_ln.b", (cfg["d_model"],)), 3 + 16 * L)
         self.h_lm = None
         if not cfg["tied"]:
-            self.h_lm = host(cfg["vocab"] * cfg["d_model"]); fill(self.h_lm, weights["lm_head.w"], 4 + 16 * L)
+            self.h_lm = host(cfg["vocab"] * cfg["d_model"]); fill(self.h_lm, get("lm_head.w", (cfg["vocab"], cfg["d_model"])), 4 + 16 * L)
         self.h_buckets = []
         for l in range(L):
             b = host(self.offs[16])
             for k, t in enumerate(BLOCK_TENSORS):
-                a = weights[f"blocks.{l}.{t}"]
+                a = get(f"blocks.{l}.{t}", block_tensor_shape(cfg, t))
                 n = int(np.prod(a.shape))
                 fill(b[self.offs[k]:self.offs[k] + n], a, 2 + 16 * l + k)
             self.h_buckets.append(b)

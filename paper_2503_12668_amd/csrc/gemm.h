@@ -28,5 +28,6 @@ struct GemmArgs {
 zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st);
 // the 256 x 256 x 64 kernel (bf16 / fp16, K % 64 == 0); gemm_launch picks it for large problems
 zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st);
+bool gemm256_applicable(const GemmArgs& a, int dtype);
 
 }  // namespace zo2

@@ -234,7 +234,7 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
         ZO2_HIP_LAUNCH_CHECK();
         return ZO2_OK;
     }
-    if ((dtype == ZO2_BF16 || dtype == ZO2_F16) && a.K % 64 == 0 && a.M >= 256 && a.N >= 256) return gemm_launch_256(a, dtype, st);
+    if (gemm256_applicable(a, dtype)) return gemm_launch_256(a, dtype, st);
     if (dtype == ZO2_BF16) return launch_mfma<bf16_t>(a, st);
     if (dtype == ZO2_F16) return launch_mfma<f16_t>(a, st);
     set_op_error("gemm: dtype %d is not a compute dtype", dtype);

@@ -1,0 +1,121 @@
+"""GPU parity at the benchmark's full sizes (OPT-1.3B shape, batch 16 x seq 256, bf16), in the launch
+configuration bench.py times, on outputs the oracle can compute one by one."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import codec, opt_model, philox, zo_step
+
+pytestmark = pytest.mark.gpu
+
+D, F, H, V, T, B, S = 2048, 8192, 32, 50272, 4096, 16, 256
+
+
+def _b():
+    from paper_2503_12668_amd import binding
+    return binding
+
+
+def test_k1_full_block_bucket_sampled_windows():
+    """One K1 launch over a whole 50.4 M-element block bucket (16 tensors, real tensor ids); windows of every
+    tensor are checked against the oracle, including the ragged ends next to the padding."""
+    b = _b()
+    cfg = si.opt_config("opt-1.3b", n_layers=1)
+    ccfg = b.make_config(cfg, "bf16", "bf16")
+    offs = b.block_tensor_offsets(ccfg)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    theta = (torch.randn(offs[16], device="cuda", generator=g) * 0.02).bfloat16()
+    theta0 = theta.clone()
+    wp = torch.zeros(offs[16], dtype=torch.bfloat16, device="cuda")
+    wm = torch.zeros_like(wp)
+    layer, c, eps = 7, np.float32(2.5e-3), np.float32(1e-3)
+    # the context's per-block launch: all 16 tensors in one grid
+    from oracle.zo_step import _fma32, _store
+    sizes = [int(np.prod(b.block_tensor_shape(cfg, t))) for t in b.BLOCK_TENSORS]
+    for k in range(16):      # the op-level entry point takes one tensor window; the context batches them
+        b.op_update_perturb(theta[offs[k]:offs[k] + sizes[k]], wp[offs[k]:offs[k] + sizes[k]], wm[offs[k]:offs[k] + sizes[k]],
+                            2 + 16 * layer + k, 0, True, 41, float(c), 42, float(eps))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for k in range(16):
+        n = sizes[k]
+        starts = [0, max(0, n - 4096)] + [int(x) for x in rng.integers(0, max(1, n - 4096), 2)]
+        for e0 in starts:
+            w = min(4096, n - e0)
+            sl = slice(offs[k] + e0, offs[k] + e0 + w)
+            th = theta0[sl].float().cpu().numpy()
+            tid = 2 + 16 * layer + k
+            th1 = _store(_fma32(-c, philox.gaussian(41, tid, e0, w), th), "bf16")
+            z = philox.gaussian(42, tid, e0, w)
+            wpo, wmo = _store(_fma32(eps, z, th1), "bf16"), _store(_fma32(-eps, z, th1), "bf16")
+            for got, want in ((theta[sl], th1), (wp[sl], wpo), (wm[sl], wmo)):
+                gg = got.float().cpu().numpy()
+                d = np.abs(gg - want)
+                assert np.mean(d == 0) > 0.98 and np.all(d <= np.abs(want) * 2.0 ** -7 + 1e-9), (k, e0)
+    # padding between tensors is never written
+    for k in range(16):
+        pad = slice(offs[k] + sizes[k], offs[k + 1])
+        assert torch.equal(theta[pad], theta0[pad]) and float(wp[pad].float().abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("M,N,K,out32,res", [(T, 3 * D, D, False, False), (T, D, F, True, True), (T, F, D, False, False), (1024, V, D, True, False)])
+def test_gemm_full_size_sampled_outputs(M, N, K, out32, res):
+    """The large-tile kernel at the benchmark's shapes; 4000 sampled outputs against float64 dot products."""
+    b = _b()
+    g = torch.Generator(device="cuda").manual_seed(M + N)
+    X = (torch.randn(M, K, device="cuda", generator=g)).bfloat16()
+    W = (torch.randn(N, K, device="cuda", generator=g) * 0.02).bfloat16()
+    bias = (torch.randn(N, device="cuda", generator=g) * 0.1).bfloat16()
+    R = torch.randn(M, N, device="cuda", generator=g) if res else None
+    Y = b.op_gemm(X, W, bias, residual=R, out_dtype=b.F32 if out32 else None, relu=not res, out_scale=0.5)
+    idx = torch.randint(0, M * N, (4000,), generator=torch.Generator().manual_seed(1))
+    idx = torch.cat([idx, torch.tensor([0, N - 1, (M - 1) * N, M * N - 1])])
+    rows, cols = (idx // N).cuda(), (idx % N).cuda()
+    ref = ((X[rows].double() * W[cols].double()).sum(-1) + bias[cols].double()) * 0.5
+    if not res:
+        ref = torch.relu(ref)
+    else:
+        ref = ref + R[rows, cols].double()
+    got = Y[rows, cols].double()
+    tol = 2e-3 if out32 else 1e-2
+    assert (got - ref).abs().max() <= tol * max(1.0, float(ref.abs().max()))
+
+
+def test_attention_full_size_sampled_heads():
+    b = _b()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    q = (torch.randn(2 * T, D, device="cuda", generator=g) * 0.3).bfloat16()
+    k = torch.randn(2 * T, D, device="cuda", generator=g).bfloat16()
+    v = torch.randn(2 * T, D, device="cuda", generator=g).bfloat16()
+    out = b.op_attention(q, k, v, 2 * B, S, H, 64)
+    for sq, hd in ((0, 0), (31, 31), (17, 5), (8, 20)):
+        rs = slice(sq * S, (sq + 1) * S)
+        cs = slice(hd * 64, (hd + 1) * 64)
+        s_ = q[rs, cs].double() @ k[rs, cs].double().T
+        s_ = s_.masked_fill(torch.triu(torch.ones(S, S, dtype=torch.bool, device="cuda"), 1), float("-inf"))
+        ref = torch.softmax(s_, -1) @ v[rs, cs].double()
+        assert (out[rs, cs].double() - ref).abs().max() <= 1.5e-2 * max(1.0, float(ref.abs().max()))
+
+
+@pytest.mark.timeout(600)
+def test_one_block_model_at_full_width_and_batch_matches_oracle():
+    """OPT-1.3B width, vocabulary and batch 16 x 256 with a single decoder block: two whole steps (the second
+    with a pending update) through zo2_step against the oracle's Alg. 2; bf16-mode bar: losses within 2e-2."""
+    b = _b()
+    cfg = si.opt_config("opt-1.3b", n_layers=1)
+    P = si.make_weights(cfg, seed=1)
+    tok = si.make_tokens(V, B, S, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    Po = {n: codec.round_to(a, "bf16") for n, a in P.items()}
+    oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), Po, store="bf16", compute="bf16")
+    ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=8 << 30)
+    for j in range(2):
+        a = oz.step(tok, lab, 42 + j, 1e-3, 1e-7)
+        g = ctx.step(tok, lab, 42 + j, 1e-3, 1e-7)
+        print(j, a, g, flush=True)
+        assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
+        assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
+    ctx.close()

@@ -186,22 +186,26 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
             }
         }
-        // `more`: another k-slab follows (its loads are issued under k-steps 0 and 1, its first
-        // fragments are read under k-step 3); compile-time so that no group carries a branch
-        auto slab_iter = [&](int kt, auto more_c) {
-            constexpr bool more = decltype(more_c)::value;
+        // Direct-to-LDS loads of slab kt+1 are split in two halves: row-blocks t = 0..3 are issued
+        // under k-step 3 of slab kt-1 (right after the barrier that retired their stage), t = 4..7
+        // under k-step 0 of slab kt; they then have k-steps 1 and 2 to land before the barrier.
+        // NEXT1: slab kt+1 exists (second half of its loads; its first fragments are read under
+        // k-step 3); NEXT2: slab kt+2 exists (first half of its loads).  Compile-time so that no
+        // group carries a branch.
+        auto slab_iter = [&](int kt, auto next1_c, auto next2_c) {
+            constexpr bool next1 = decltype(next1_c)::value, next2 = decltype(next2_c)::value;
 #ifdef ZO2_GEMM_EXP_NODMA
-            constexpr bool dma = false;
+            constexpr bool dma1 = false, dma2 = false;
 #else
-            constexpr bool dma = more;
+            constexpr bool dma1 = next1, dma2 = next2;
 #endif
             const int cur = kt & 1;
             const char* base_a = smem + cur * kStageBytes + fr_a;
             const char* base_b = smem + cur * kStageBytes + fr_b;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[1], base_b + koff[1], dma, cur ^ 1, (kt + 1) * kBK, i);
+            for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[1], base_b + koff[1], dma1, cur ^ 1, (kt + 1) * kBK, 4 + i);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, true, base_a + koff[2], base_b + koff[2], dma, cur ^ 1, (kt + 1) * kBK, 4 + i);
+            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, true, base_a + koff[2], base_b + koff[2], false, 0, 0, 0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[3], base_b + koff[3], false, 0, 0, 0);
             // one barrier per slab: publishes slab kt+1 (every wavefront waited for its own loads)
@@ -211,11 +215,21 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             const char* next_a = smem + (cur ^ 1) * kStageBytes + fr_a + koff[0];
             const char* next_b = smem + (cur ^ 1) * kStageBytes + fr_b + koff[0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, more, next_a, next_b, false, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, next1, next_a, next_b, dma2, cur, (kt + 2) * kBK, i);
         };
+#ifndef ZO2_GEMM_EXP_NODMA
+        if (nk > 1) {                    // first half of slab 1 (stage 1 is free once the barrier above is passed)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                load_to_lds(base_x + kBK, pa[t], ld_a + kStageBytes + t * 1024);
+                load_to_lds(base_w + kBK, pb[t], ld_b + kStageBytes + t * 1024);
+            }
+        }
+#endif
         TSTAMP();
-        for (int kt = 0; kt + 1 < nk; ++kt) slab_iter(kt, std::true_type{});
-        slab_iter(nk - 1, std::false_type{});
+        for (int kt = 0; kt + 2 < nk; ++kt) slab_iter(kt, std::true_type{}, std::true_type{});
+        if (nk > 1) slab_iter(nk - 2, std::true_type{}, std::false_type{});
+        slab_iter(nk - 1, std::false_type{}, std::false_type{});
         TSTAMP();
 
         // Both stages are free now (all fragment reads are behind the last barrier).  Start the

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ 
 }
 
 template <typename T, int DH>
-__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
+__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
                                                                  T* __restrict__ out, int seq, int seq_pad, int cols, int64_t ld) {
     constexpr int KS = DH / 16;          // contraction steps of the first product
     constexpr int DT = DH / 32;          // 32-row tiles of O^T
@@ -186,20 +186,22 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
     constexpr float kLog2e = 1.4426950408889634f;
 
     const int last_tile = q0 >> 5;
-    for (int tile = 0; tile <= last_tile; ++tile) {
+    // operand fragments of a key tile: K rows (permuted, clamped) and V^T rows
+    auto load_tile = [&](int tile, uint4 (&kf)[KS], uint4 (&vf)[DT][2]) {
         const int j0 = tile * 32;
-        // ---- S^T = K Q^T
         const int krow = min(j0 + pr, seq - 1);
         const T* kp = k + base + (size_t)krow * ld + kh * 8;
-        uint4 kf[KS];
 #pragma unroll
         for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kp + c * 16);
-        uint4 vf[DT][2];
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
                 vf[d][s2] = *reinterpret_cast<const uint4*>(vt_base + (size_t)d * 32 * seq_pad + j0 + 16 * s2);
+    };
+    auto process_tile = [&](int tile, const uint4 (&kf)[KS], const uint4 (&vf)[DT][2]) {
+        const int j0 = tile * 32;
+        // ---- S^T = K Q^T
         att_f32x16 st;
 #pragma unroll
         for (int v = 0; v < 16; ++v) st[v] = 0.f;
@@ -243,6 +245,17 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
         for (int d = 0; d < DT; ++d)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) o[d] = AttMfma<T>::run(vf[d][s2], pf[s2], o[d]);
+    };
+    // two fragment sets: the loads of tile t+1 are in flight while tile t is computed
+    uint4 kfa[KS], kfb[KS], vfa[DT][2], vfb[DT][2];
+    load_tile(0, kfa, vfa);
+    for (int tile = 0; tile <= last_tile; tile += 2) {
+        if (tile + 1 <= last_tile) load_tile(tile + 1, kfb, vfb);
+        process_tile(tile, kfa, vfa);
+        if (tile + 1 <= last_tile) {
+            if (tile + 2 <= last_tile) load_tile(tile + 2, kfa, vfa);
+            process_tile(tile + 1, kfb, vfb);
+        }
     }
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;

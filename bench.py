@@ -21,6 +21,10 @@ MODEL, BATCH, SEQ = "opt-1.3b", 16, 256
 EPS, LR, SEED0 = 1e-3, 1e-7, 42
 PEAK_BF16_MFMA = 2500.0      # TFLOP/s, dense
 PEAK_HBM = 8000.0            # GB/s
+# HBM bytes per step from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE) over this same command, scaled by
+# a 1 GiB copy through the same counters (profiles/step_opt1.3b_bf16_resident_hbm_traffic.md); not measured live
+PMC_GEMM_BYTES_PER_STEP = 45.4e9      # over the 97 GEMM launches of a step
+PMC_K1_BYTES_PER_STEP = 10.53e9       # over the 27 K1 launches of a step
 
 
 def gemm_flops_per_step(cfg, T):
@@ -134,9 +138,15 @@ def main():
                    "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"]},
         "roofline": {"kernel": "gemm_mfma_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
                      "achieved": tflops, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_MFMA,
-                     "traffic": None, "launches_per_step": gemm_n / args.steps, "ms_per_step": gemm_ms / args.steps},
+                     "traffic": (PMC_GEMM_BYTES_PER_STEP / (gemm_n / args.steps)) if (gemm_n and args.layers is None) else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, calibrated, offline)",
+                     "algorithmic_flops_per_launch": flops / gemm_n if gemm_n else None,
+                     "launches_per_step": gemm_n / args.steps, "ms_per_step": gemm_ms / args.steps},
         "roofline_k1": {"kernel": "k1_kernel (fused regenerate + update + perturb)", "bound": "hbm", "achieved": k1_gbs,
-                        "peak": PEAK_HBM, "unit": "GB/s", "frac": k1_gbs / PEAK_HBM, "traffic": None,
+                        "peak": PEAK_HBM, "unit": "GB/s", "frac": k1_gbs / PEAK_HBM,
+                        "traffic": (PMC_K1_BYTES_PER_STEP / (k1_n / args.steps)) if (k1_n and args.layers is None) else None,
+                        "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated, offline)",
+                        "algorithmic_bytes_per_launch": k1_bytes / k1_n if k1_n else None,
                         "launches_per_step": k1_n / args.steps, "ms_per_step": k1_ms / args.steps},
         "kernel_ms_per_step": {"gemm": gemm_ms / args.steps, "k1": k1_ms / args.steps, "attention": att_ms / args.steps},
     }

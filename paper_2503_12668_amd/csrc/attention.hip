@@ -156,16 +156,31 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ 
     }
 }
 
+// direct-to-LDS load of 16 bytes per lane (lane i lands at lds_base + 16 i)
+__device__ __forceinline__ void att_load_to_lds(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
+}
+
+// One workgroup = 128 queries of one (sequence, head); wavefront w owns queries 32 w .. 32 w + 31.
+// Key tiles of 32 keys are brought into LDS once per workgroup (direct-to-LDS loads, two buffers,
+// one barrier per tile) and shared by the four wavefronts; a wavefront skips the tiles past its
+// diagonal.  K tile: 32 rows of d_head elements, 16-byte chunks XOR-swizzled by (row & 7).
+// V^T tile: d_head rows of 32 keys (64 bytes), chunks swizzled by ((row >> 1) & 3).
 template <typename T, int DH>
-__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
                                                                  T* __restrict__ out, int seq, int seq_pad, int cols, int64_t ld) {
     constexpr int KS = DH / 16;          // contraction steps of the first product
     constexpr int DT = DH / 32;          // 32-row tiles of O^T
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int KCH = DH / 8;          // 16-byte chunks per K row
+    constexpr int KTILE = 32 * DH * 2, VTILE = DH * 64, BUF = KTILE + VTILE;
+    constexpr int KINSTR = KTILE / 1024 / 4, VINSTR = VTILE / 1024 / 4;   // direct-to-LDS loads per wavefront per tile
+    __shared__ __attribute__((aligned(1024))) char lds[2 * BUF];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, kh = lane >> 5;
     const int head = blockIdx.y, sq = blockIdx.z;
     const int q0 = blockIdx.x * 128 + wave * 32;
-    if (q0 >= seq) return;
+    const bool active = q0 < seq;                            // inactive wavefronts still load and synchronise
     const size_t base = (size_t)sq * seq * ld + (size_t)head * DH;
     const int qi = q0 + r;                                   // this lane's query
     const int qrow = min(qi, seq - 1);
@@ -182,25 +197,45 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attention_mfma_kernel
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[d][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
-    const T* vt_base = vt + ((size_t)sq * cols + (size_t)head * DH + r) * seq_pad + kh * 8;
     constexpr float kLog2e = 1.4426950408889634f;
 
-    const int last_tile = q0 >> 5;
-    // operand fragments of a key tile: K rows (permuted, clamped) and V^T rows
-    auto load_tile = [&](int tile, uint4 (&kf)[KS], uint4 (&vf)[DT][2]) {
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const int wg_last_q = min(blockIdx.x * 128 + 127, seq - 1);
+    const int wg_last_tile = wg_last_q >> 5;
+    const int my_last_tile = q0 >> 5;
+    const T* vt_head = vt + ((size_t)sq * cols + (size_t)head * DH) * seq_pad;
+
+    auto issue_tile = [&](int tile, int buf) {
         const int j0 = tile * 32;
-        const int krow = min(j0 + pr, seq - 1);
-        const T* kp = k + base + (size_t)krow * ld + kh * 8;
 #pragma unroll
-        for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kp + c * 16);
+        for (int x = 0; x < KINSTR; ++x) {                   // K rows: 1024 / (2 DH) rows per instruction
+            const int inst = wave * KINSTR + x;
+            const int row = inst * (512 / DH) + lane / KCH;
+            const int chunk = (lane % KCH) ^ (row & 7);
+            att_load_to_lds(k + base + (size_t)min(j0 + row, seq - 1) * ld + chunk * 8, lds0 + buf * BUF + inst * 1024);
+        }
+#pragma unroll
+        for (int x = 0; x < VINSTR; ++x) {                   // V^T rows: 16 rows of 64 bytes per instruction
+            const int inst = wave * VINSTR + x;
+            const int row = inst * 16 + (lane >> 2);
+            const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+            att_load_to_lds(vt_head + (size_t)row * seq_pad + j0 + chunk * 8, lds0 + buf * BUF + KTILE + inst * 1024);
+        }
+    };
+    auto process_tile = [&](int tile, int buf) {
+        const int j0 = tile * 32;
+        const char* kb = lds + buf * BUF;
+        const char* vb = kb + KTILE;
+        uint4 kf[KS], vf[DT][2];
+#pragma unroll
+        for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kb + pr * (DH * 2) + (((2 * c + kh) ^ (pr & 7)) * 16));
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2)
-                vf[d][s2] = *reinterpret_cast<const uint4*>(vt_base + (size_t)d * 32 * seq_pad + j0 + 16 * s2);
-    };
-    auto process_tile = [&](int tile, const uint4 (&kf)[KS], const uint4 (&vf)[DT][2]) {
-        const int j0 = tile * 32;
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int row = d * 32 + r;
+                vf[d][s2] = *reinterpret_cast<const uint4*>(vb + row * 64 + (((2 * s2 + kh) ^ ((row >> 1) & 3)) * 16));
+            }
         // ---- S^T = K Q^T
         att_f32x16 st;
 #pragma unroll
@@ -213,7 +248,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attention_mfma_kernel
         for (int v = 0; v < 16; ++v) {
             // accumulator row rho = 8 (v/4) + 4 kh + v%4 carries key j0 + pi(rho) = j0 + 16 (v/8) + 8 kh + v%8
             const int key = j0 + 16 * (v >> 3) + 8 * kh + (v & 7);
-            if (tile == last_tile && key > qi) st[v] = -INFINITY;
+            if (tile == my_last_tile && key > qi) st[v] = -INFINITY;
             tmax = fmaxf(tmax, st[v]);
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
@@ -246,20 +281,17 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attention_mfma_kernel
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) o[d] = AttMfma<T>::run(vf[d][s2], pf[s2], o[d]);
     };
-    // two fragment sets: the loads of tile t+1 are in flight while tile t is computed
-    uint4 kfa[KS], kfb[KS], vfa[DT][2], vfb[DT][2];
-    load_tile(0, kfa, vfa);
-    for (int tile = 0; tile <= last_tile; tile += 2) {
-        if (tile + 1 <= last_tile) load_tile(tile + 1, kfb, vfb);
-        process_tile(tile, kfa, vfa);
-        if (tile + 1 <= last_tile) {
-            if (tile + 2 <= last_tile) load_tile(tile + 2, kfa, vfa);
-            process_tile(tile + 1, kfb, vfb);
-        }
+
+    issue_tile(0, 0);
+    for (int tile = 0; tile <= wg_last_tile; ++tile) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // own loads of this tile landed; own reads of the other buffer done
+        __syncthreads();
+        if (tile + 1 <= wg_last_tile) issue_tile(tile + 1, (tile + 1) & 1);
+        if (active && tile <= my_last_tile) process_tile(tile, tile & 1);
     }
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
-    if (qi < seq) {
+    if (active && qi < seq) {
         T* op = out + base + (size_t)qi * ld;
 #pragma unroll
         for (int d = 0; d < DT; ++d)

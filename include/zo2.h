@@ -102,6 +102,9 @@ typedef struct {
     void* stream_compute;     /* hipStream_t; kernels                                             */
     void* stream_upload;      /* hipStream_t; host -> device block copies                         */
     void* stream_offload;     /* hipStream_t; device -> host block copies                         */
+    void* stream_k1;          /* hipStream_t or NULL.  When given (and the budget has room for a
+                                 second W+/W- scratch set) the fused update + perturb pass of block
+                                 l+1 runs on it concurrently with the forwards of block l          */
 } zo2_device;
 
 /* Create a context.  The host weight buffers are borrowed until zo2_destroy and are the

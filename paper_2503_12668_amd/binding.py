@@ -41,7 +41,7 @@ class HostWeights(C.Structure):
 
 class Device(C.Structure):
     _fields_ = [("arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("stream_compute", C.c_void_p),
-                ("stream_upload", C.c_void_p), ("stream_offload", C.c_void_p)]
+                ("stream_upload", C.c_void_p), ("stream_offload", C.c_void_p), ("stream_k1", C.c_void_p)]
 
 
 _lib = None
@@ -229,10 +229,12 @@ class Zo2Context:
     weights: name -> float32 array ("tok_emb", "pos_emb", "blocks.{l}.{t}", "final_ln.w", "final_ln.b"[, "lm_head.w"]),
     or a callable (name, shape) -> float32 torch tensor on any device (for models too large to build as a dict).
     They are converted once to the wire dtype and packed into per-block host buckets (pinned when possible);
-    from then on the library owns their contents."""
+    from then on the library owns their contents.
+    overlap_k1: hand the library a fourth stream so that the update + perturb pass of block l+1 runs concurrently
+    with the forwards of block l (off by default: on MI355X the cross-stream waits cost more than the overlap wins)."""
 
     def __init__(self, cfg, weights, wire="f32", compute="f32", arena_bytes=None, budget_bytes=None, scales=None,
-                 pin=True):
+                 pin=True, overlap_k1=False):
         self.cfg = dict(cfg)
         self.ccfg = make_config(cfg, wire, compute)
         self.wire_id, self.compute_id = DTYPE_ID[wire], DTYPE_ID[compute]
@@ -273,14 +275,14 @@ class Zo2Context:
         if arena_bytes is None:
             arena_bytes = int(model_bytes * 1.05) + (3 << 30)
         self.arena = torch.empty(int(arena_bytes), dtype=torch.uint8, device="cuda")
-        self.streams = [torch.cuda.Stream() for _ in range(3)]
+        self.streams = [torch.cuda.Stream() for _ in range(4)]
         self._bucket_ptrs = (C.c_void_p * max(L, 1))(*[b.data_ptr() for b in self.h_buckets])
         self._scales_c = self.scales.ctypes.data_as(C.POINTER(C.c_float)) if scales is not None else None
         hw = HostWeights(self.h_tok.data_ptr(), self.h_pos.data_ptr(), self.h_flnw.data_ptr(), self.h_flnb.data_ptr(),
                          self.h_lm.data_ptr() if self.h_lm is not None else None,
                          C.cast(self._bucket_ptrs, C.POINTER(C.c_void_p)), self._scales_c)
         dev = Device(self.arena.data_ptr(), self.arena.numel(), self.streams[0].cuda_stream, self.streams[1].cuda_stream,
-                     self.streams[2].cuda_stream)
+                     self.streams[2].cuda_stream, self.streams[3].cuda_stream if overlap_k1 else None)
         self.handle = C.c_void_p()
         st = lib().zo2_init(C.byref(self.handle), C.byref(self.ccfg), C.byref(hw), C.byref(dev))
         if st != 0:

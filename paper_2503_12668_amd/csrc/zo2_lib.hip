@@ -92,7 +92,11 @@ struct zo2_ctx {
     bool resident, phased;
     int n_slots;
     char* slots;
-    char *wp, *wm;                      // W+ / W- scratch, compute dtype
+    char *wp, *wm;                      // W+ / W- scratch in use (compute dtype)
+    char *wps[2], *wms[2];              // the scratch sets; two when K1 of block l+1 may overlap the forwards of block l
+    bool overlap_k1;
+    hipStream_t sk;                     // optional fourth stream for that overlap
+    hipEvent_t ev_k1done[2], ev_fwd_done[2], ev_embed;
     int64_t scratch_elems;
     char *fln_wp, *fln_wm;
     float* h;
@@ -156,7 +160,8 @@ struct ProfScope {
     zo2_ctx* c;
     int cls;
     bool on;
-    ProfScope(zo2_ctx* c_, int cls_) : c(c_), cls(cls_), on((c_->prof_mask >> cls_) & 1u) {
+    hipStream_t st;
+    ProfScope(zo2_ctx* c_, int cls_, hipStream_t st_ = nullptr) : c(c_), cls(cls_), on((c_->prof_mask >> cls_) & 1u), st(st_ ? st_ : c_->sc) {
         if (!on) return;
         if (c->prof_used + 2 > c->prof_ev.size()) {
             hipEvent_t a, b;
@@ -164,11 +169,11 @@ struct ProfScope {
             c->prof_ev.push_back(a);
             c->prof_ev.push_back(b);
         }
-        (void)hipEventRecord(c->prof_ev[c->prof_used], c->sc);
+        (void)hipEventRecord(c->prof_ev[c->prof_used], st);
     }
     ~ProfScope() {
         if (!on) return;
-        (void)hipEventRecord(c->prof_ev[c->prof_used + 1], c->sc);
+        (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
         c->prof_cls.push_back(cls);
         c->prof_used += 2;
     }
@@ -187,6 +192,15 @@ static void prof_collect(zo2_ctx* c) {   // after the compute stream has been sy
         }
     }
 }
+#define OPKS(c, cls, stream, call)                                           \
+    do {                                                                     \
+        zo2_status s__;                                                      \
+        {                                                                    \
+            ProfScope ps__(c, cls, stream);                                  \
+            s__ = (call);                                                    \
+        }                                                                    \
+        if (s__ != ZO2_OK) return fail(c, s__, "%s", zo2_op_last_error());   \
+    } while (0)
 #define OPK(c, cls, call)                                                    \
     do {                                                                     \
         zo2_status s__;                                                      \
@@ -286,6 +300,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->sc = as_stream(dev->stream_compute);
     c->su = as_stream(dev->stream_upload);
     c->so = as_stream(dev->stream_offload);
+    c->sk = as_stream(dev->stream_k1);
+    c->overlap_k1 = false;
     c->planned = false;
     c->need_plan = false;
     c->blocks_on_device = false;
@@ -325,6 +341,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     HIPCHK(c, hipHostMalloc((void**)&c->h_result, 16 * sizeof(float), hipHostMallocDefault));
     hipEvent_t* evs[] = {&c->ev_step0, &c->ev_c1, &c->ev_u0, &c->ev_u1, &c->ev_o0, &c->ev_o1};
     for (hipEvent_t* e : evs) HIPCHK(c, hipEventCreate(e));
+    hipEvent_t* evs2[] = {&c->ev_k1done[0], &c->ev_k1done[1], &c->ev_fwd_done[0], &c->ev_fwd_done[1], &c->ev_embed};
+    for (hipEvent_t* e : evs2) HIPCHK(c, hipEventCreateWithFlags(e, hipEventDisableTiming));
     return ZO2_OK;
 }
 
@@ -333,11 +351,12 @@ extern "C" void zo2_destroy(zo2_ctx* c) {
     hipStreamSynchronize(c->sc);
     hipStreamSynchronize(c->su);
     hipStreamSynchronize(c->so);
+    if (c->sk) hipStreamSynchronize(c->sk);
     for (auto e : c->ev_up) hipEventDestroy(e);
     for (auto e : c->ev_k1) hipEventDestroy(e);
     for (auto e : c->ev_free) hipEventDestroy(e);
     for (auto e : c->prof_ev) hipEventDestroy(e);
-    hipEvent_t evs[] = {c->ev_step0, c->ev_c1, c->ev_u0, c->ev_u1, c->ev_o0, c->ev_o1};
+    hipEvent_t evs[] = {c->ev_step0, c->ev_c1, c->ev_u0, c->ev_u1, c->ev_o0, c->ev_o1, c->ev_k1done[0], c->ev_k1done[1], c->ev_fwd_done[0], c->ev_fwd_done[1], c->ev_embed};
     if (c->h_result) for (hipEvent_t e : evs) hipEventDestroy(e);
     if (c->h_ids) hipHostFree(c->h_ids);
     if (c->h_result) hipHostFree(c->h_result);
@@ -405,13 +424,16 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     int64_t phase_max = 0;
     for (int p = 0; p < 4; ++p) phase_max = std::max(phase_max, c->offs[kPhase[p + 1]] - c->offs[kPhase[p]]);
     const int64_t head_elems = (int64_t)align_up(c->tok_elems, kTensorAlign);
-    bool phased = false, resident = false;
+    bool phased = false, resident = false, two_sets = false;
     int64_t scratch = 0;
     long slots = 0;
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        phased = attempt == 1;
+    // preference: two whole-block scratch sets (K1 of the next block overlaps this block's forwards),
+    // then one whole-block set, then one set sized for the largest tensor group
+    for (int attempt = (c->sk ? 0 : 1); attempt < 3; ++attempt) {
+        phased = attempt == 2;
+        two_sets = attempt == 0;
         scratch = std::max(phased ? phase_max : c->offs[ZO2_BLOCK_TENSORS], head_elems);
-        const size_t fixed = c->persistent_bytes + act_bytes + 2 * align_up((size_t)scratch * c->csz, 256);
+        const size_t fixed = c->persistent_bytes + act_bytes + (two_sets ? 4 : 2) * align_up((size_t)scratch * c->csz, 256);
         slots = fixed > budget ? -1 : (long)((budget - fixed) / align_up(c->bucket_bytes, 256));
         if (slots >= g.n_layers || slots >= 3) break;
     }
@@ -429,13 +451,19 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     HIPCHK(c, hipStreamSynchronize(c->sc));
     HIPCHK(c, hipStreamSynchronize(c->su));
     HIPCHK(c, hipStreamSynchronize(c->so));
+    if (c->sk) HIPCHK(c, hipStreamSynchronize(c->sk));
 
     char* base = (char*)c->dev.arena;
     size_t off = c->persistent_bytes;
     c->slots = base + off;
     off += (size_t)n_slots * align_up(c->bucket_bytes, 256);
-    c->wp = base + off; off += align_up((size_t)scratch * c->csz, 256);
-    c->wm = base + off; off += align_up((size_t)scratch * c->csz, 256);
+    for (int k = 0; k < (two_sets ? 2 : 1); ++k) {
+        c->wps[k] = base + off; off += align_up((size_t)scratch * c->csz, 256);
+        c->wms[k] = base + off; off += align_up((size_t)scratch * c->csz, 256);
+    }
+    if (!two_sets) { c->wps[1] = c->wps[0]; c->wms[1] = c->wms[0]; }
+    c->wp = c->wps[0]; c->wm = c->wms[0];
+    c->overlap_k1 = two_sets;
     char* a0 = base + off;
     c->h = (float*)(a0 + o_h); c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
     c->mid = a0 + o_mid; c->att_ws = a0 + o_aws; c->att_ws_bytes = att_ws; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
@@ -525,17 +553,20 @@ static void k1_common(const zo2_ctx* c, K1Args& a, uint64_t seed, float eps) {
 
 // one whole tensor held contiguously at `theta`
 static zo2_status k1_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, bool perturb, void* wp, void* wm,
-                            uint64_t seed, float eps) {
+                            uint64_t seed, float eps, hipStream_t st = nullptr) {
+    if (!st) st = c->sc;
     K1Args a;
     k1_common(c, a, seed, eps);
     a.theta = theta; a.w_plus = wp; a.w_minus = wm; a.w_off0 = 0; a.nseg = 1;
     a.seg[0].off = 0; a.seg[0].e0 = 0; a.seg[0].n = (uint64_t)n; a.seg[0].tensor_id = tid; a.seg[0].scale = c->scales[tid];
-    OPK(c, ZO2_KC_K1, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, st));
     return ZO2_OK;
 }
 
 // tensors [t0, t1) of block l whose bucket sits at `bucket`; W+- go to the scratch, tensor t0 at its start
-static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool perturb, uint64_t seed, float eps) {
+static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool perturb, uint64_t seed, float eps,
+                           hipStream_t st = nullptr) {
+    if (!st) st = c->sc;
     K1Args a;
     k1_common(c, a, seed, eps);
     a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->wm; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
@@ -543,7 +574,7 @@ static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool
         K1Seg& s = a.seg[k - t0];
         s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
     }
-    OPK(c, ZO2_KC_K1, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, c->sc));
+    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, st));
     return ZO2_OK;
 }
 
@@ -555,7 +586,8 @@ struct PhaseView {       // where tensor k's perturbed copies are inside the scr
     const char* M(int k) const { return c->wm + (size_t)(c->offs[k] - off0) * c->csz; }
 };
 
-static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int seq, uint64_t seed, float eps, hipEvent_t k1_done) {
+static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int seq, uint64_t seed, float eps, hipEvent_t k1_done,
+                                bool k1_enqueued = false) {
     const zo2_config& g = c->cfg;
     const int T = batch * seq, d = g.d_model, f = g.d_ffn, dh = d / g.n_heads;
     const int dt = g.compute_dtype;
@@ -563,6 +595,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     const size_t half_d = (size_t)T * d * cs, half_f = (size_t)T * f * cs;
     const bool f32 = dt == ZO2_F32;
     auto phase = [&](int p) -> zo2_status {
+        if (k1_enqueued) return ZO2_OK;
         if (c->phased) return k1_block(c, l, bucket, kPhase[p], kPhase[p + 1], true, seed, eps);
         if (p == 0) return k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, true, seed, eps);
         return ZO2_OK;
@@ -572,7 +605,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
 
     // ---- attention half: h += O(Attn(LN1(h)))
     { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
-    if (!c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
+    if (!c->phased && k1_done && !k1_enqueued) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     PhaseView w = view(0);
     OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
@@ -709,17 +742,33 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         if (!g.tied_lm_head) { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
     }
 
-    // DualForward(W_1 .. W_N)
+    // DualForward(W_1 .. W_N).  With a fourth stream and two scratch sets, K1 of block l runs on that
+    // stream as soon as the forwards of block l-2 have released its scratch set, i.e. under the
+    // forwards of block l-1 (K1 is bound by the vector ALU and HBM, the forwards by the matrix cores).
+    if (c->overlap_k1) HIPCHK(c, hipEventRecord(c->ev_embed, c->sc));
     for (int l = 0; l < g.n_layers; ++l) {
-        if (c->resident) {
-            zo2_status s = block_forward(c, l, c->slots + (size_t)l * c->bucket_bytes, batch, seq, seed, eps, nullptr);
+        const int sl = c->resident ? l : l % c->n_slots;
+        char* bucket = c->slots + (size_t)sl * c->bucket_bytes;
+        const int sb = l & 1;
+        c->wp = c->wps[sb];
+        c->wm = c->wms[sb];
+        if (c->overlap_k1) {
+            if (l >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
+            if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
+            { zo2_status s = k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, true, seed, eps, c->sk); if (s != ZO2_OK) return s; }
+            HIPCHK(c, hipEventRecord(c->ev_k1done[sb], c->sk));
+            if (!c->resident) HIPCHK(c, hipEventRecord(c->ev_k1[sl], c->sk));
+            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_k1done[sb], 0));
+            zo2_status s = block_forward(c, l, bucket, batch, seq, seed, eps, nullptr, true);
             if (s != ZO2_OK) return s;
+            HIPCHK(c, hipEventRecord(c->ev_fwd_done[sb], c->sc));
         } else {
-            const int sl = l % c->n_slots;
-            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));                 // C(W_i) after U(W_i)
-            zo2_status s = block_forward(c, l, c->slots + (size_t)sl * c->bucket_bytes, batch, seq, seed, eps, c->ev_k1[sl]);
+            if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
+            zo2_status s = block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
             if (s != ZO2_OK) return s;
-            s = enqueue_offload(c, l, upd);                                        // O(W_i) after its update
+        }
+        if (!c->resident) {
+            zo2_status s = enqueue_offload(c, l, upd);                             // O(W_i) after its update
             if (s != ZO2_OK) return s;
             if (next_upload < g.n_layers) {                                        // U(W_{i+n}) into the slot O(W_i) frees
                 s = enqueue_upload(c, next_upload++);
@@ -742,9 +791,22 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     const size_t boff = (size_t)c->fln_off_b * c->csz;
     OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, 2 * T, T, d, g.ln_eps, c->sc));
     {
-        zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps)
-                                      : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps);
+        const int sb = g.n_layers & 1;
+        c->wp = c->wps[sb];
+        c->wm = c->wms[sb];
+        hipStream_t st = c->sc;
+        if (c->overlap_k1) {      // the vocabulary matrix is swept under the last block's forwards
+            st = c->sk;
+            HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_embed, 0));                  // the gather read the table before its update
+            if (g.n_layers >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
+        }
+        zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps, st)
+                                      : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps, st);
         if (s != ZO2_OK) return s;
+        if (c->overlap_k1) {
+            HIPCHK(c, hipEventRecord(c->ev_k1done[sb], c->sk));
+            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_k1done[sb], 0));
+        }
     }
     const int R = c->logit_rows;
     for (int r0 = 0; r0 < T; r0 += R) {
@@ -767,6 +829,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
     if (c->stat_o) HIPCHK(c, hipEventRecord(c->ev_o1, c->so));
     HIPCHK(c, hipStreamSynchronize(c->sc));
+    if (c->overlap_k1) HIPCHK(c, hipStreamSynchronize(c->sk));
     if (!c->resident) {
         HIPCHK(c, hipStreamSynchronize(c->su));
         HIPCHK(c, hipStreamSynchronize(c->so));

@@ -93,6 +93,32 @@ def test_streamed_equals_resident_bitwise():
     ctx_r.close(); ctx_s.close()
 
 
+def test_k1_on_its_own_stream_changes_nothing():
+    """The optional fourth stream (K1 of block l+1 under the forwards of block l, two scratch sets) is a pure
+    scheduling change: identical bits, resident and streamed."""
+    b = _b()
+    cfg = si.tiny_config(n_layers=5, d_model=64, n_heads=4, d_ffn=128, vocab=211, max_pos=40)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 2, 17, seed=12)
+    lab = si.next_token_labels(tok)
+    runs = {}
+    for name, overlap, streamed in (("plain", False, False), ("overlap", True, False), ("overlap_streamed", True, True)):
+        ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20, overlap_k1=overlap)
+        r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
+        if streamed:
+            ctx.set_resident_budget(ctx.plan()["bytes_used"] - 2 * ctx.offs[16] * 4)
+        r += [ctx.step(tok, lab, 6 + j, 1e-3, 1e-3) for j in range(3)]
+        if streamed:
+            assert not ctx.plan()["resident"]
+        ctx.flush(); ctx.sync_to_host()
+        runs[name] = ([tuple(map(float, x)) for x in r], ctx.parameters())
+        ctx.close()
+    for name in ("overlap", "overlap_streamed"):
+        assert runs[name][0] == runs["plain"][0], name
+        for n in runs["plain"][1]:
+            assert np.array_equal(runs[name][1][n], runs["plain"][1][n]), (name, n)
+
+
 def test_zero_lr_leaves_parameters_and_sign_flip_swaps_losses():
     b = _b()
     cfg = si.tiny_config(n_layers=2, d_model=32, n_heads=4, d_ffn=64, vocab=97, max_pos=24)

@@ -186,6 +186,45 @@ def test_low_precision_steps_track_oracle(wire, compute):
     ctx.close()
 
 
+@pytest.mark.parametrize("wire,scale", [("fp8_e4m3", 64.0), ("fp8_e5m2", 1.0)])
+def test_fp8_wire_streamed_steps_track_oracle(wire, scale):
+    """AMP mode with an 8-bit transfer format (Sec. 5.5): parameters live on the host and in the slots as fp8
+    codes (per-tensor power-of-two scale), are decoded to float32 inside K1 for the update, re-encoded, and
+    the forwards run in bf16.  Streamed through 3 slots.  Losses against the oracle with the same storage rule."""
+    b = _b()
+    cfg = si.tiny_config(n_layers=4, d_model=64, n_heads=4, d_ffn=128, vocab=211, max_pos=40)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 3, 23, seed=12)
+    lab = si.next_token_labels(tok)
+    shape = opt_model.OptShape(**cfg)
+    names = [n for n, _, _ in opt_model.tensor_table(shape)]
+    scales = {n: scale for n in names}
+    Po = {n: (codec.round_to(P[n].astype(np.float64) * scale, wire).astype(np.float64) / scale).astype(np.float32) for n in names}
+    oz = zo_step.Zo2Blockwise(shape, Po, store=wire, compute="bf16", scales=scales)
+    ctx = b.Zo2Context(cfg, P, wire=wire, compute="bf16", arena_bytes=64 << 20, scales=np.full(len(names), scale, np.float32))
+    P0 = {n: a.copy() for n, a in Po.items()}
+    ro, rg = [], []
+    for j in range(3):
+        ro.append(oz.step(tok, lab, 42 + j, 1e-3, 5e-3))         # large enough that some fp8 codes change
+        rg.append(ctx.step(tok, lab, 42 + j, 1e-3, 5e-3))
+        if j == 0:
+            ctx.set_resident_budget(ctx.plan()["bytes_used"] - ctx.offs[16])     # 3 of 4 blocks fit: streamed from now on
+    assert not ctx.plan()["resident"]
+    for a, g in zip(ro, rg):
+        print(a, g)
+        assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
+        assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
+    oz.flush(); ctx.flush(); ctx.sync_to_host()
+    Pg = ctx.parameters()
+    changed = 0
+    for n in names:
+        # every stored value is an fp8 code of the format
+        assert np.array_equal(codec.round_to(Pg[n].astype(np.float64) * scale, wire).astype(np.float32) / np.float32(scale), Pg[n]), n
+        changed += int(np.sum(Pg[n] != P0[n]))
+    assert changed > 0
+    ctx.close()
+
+
 def _config1():
     cfg = si.opt_config("opt-125m")
     P = si.make_weights(cfg, seed=1)

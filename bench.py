@@ -108,18 +108,31 @@ def main():
     for j in range(args.warmup):
         ctx.step(tok, lab, SEED0 + j, EPS, LR)
     plan = ctx.plan()
+
+    # timed region: exactly K steps, nothing else on the GPU
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(args.steps):
+        ctx.step(tok, lab, SEED0 + args.warmup + j, EPS, LR)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / args.steps * 1e3
+
+    # second pass over the same K steps with a pair of HIP events around every GEMM / K1 / attention launch on the
+    # library's compute stream.  Kept out of the timed region: each event costs about 5 us of idle GPU between two
+    # kernels (about 250 of them per step, +6 % step time), the kernels themselves run as in the timed region.
     ctx.set_profiling(("gemm", "k1", "attn"))
     acc = {k: [0.0, 0] for k in ctx.KERNEL_CLASSES}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for j in range(args.steps):
-        ctx.step(tok, lab, SEED0 + args.warmup + j, EPS, LR)
+        ctx.step(tok, lab, SEED0 + args.warmup + args.steps + j, EPS, LR)
         for k, (ms, n) in ctx.kernel_times().items():
             acc[k][0] += ms
             acc[k][1] += n
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_step = dt / args.steps * 1e3
+    ms_step_profiled = (time.perf_counter() - t0) / args.steps * 1e3
+    ctx.set_profiling(())
 
     gemm_ms, gemm_n = acc["gemm"]
     k1_ms, k1_n = acc["k1"]
@@ -148,7 +161,9 @@ def main():
                         "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated, offline)",
                         "algorithmic_bytes_per_launch": k1_bytes / k1_n if k1_n else None,
                         "launches_per_step": k1_n / args.steps, "ms_per_step": k1_ms / args.steps},
-        "kernel_ms_per_step": {"gemm": gemm_ms / args.steps, "k1": k1_ms / args.steps, "attention": att_ms / args.steps},
+        "kernel_ms_per_step": {"gemm": gemm_ms / args.steps, "k1": k1_ms / args.steps, "attention": att_ms / args.steps,
+                               "note": "from a second pass of the same number of steps with HIP events around every launch",
+                               "ms_per_step_with_events": ms_step_profiled},
     }
     ctx.close()
     del ctx

@@ -154,8 +154,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         uint4 fa[2][4], fb[2][4];
         // One "group" = the four MFMAs of X row-block i at k-step buffer `buf`, preceded by the two
         // LDS reads that fetch row-block i of both operands for the next k-step into buffer `nbuf`,
-        // and optionally two direct-to-LDS loads of the next k-slab.  A scheduling barrier after
+        // and optionally two direct-to-LDS loads of a later k-slab.  A scheduling barrier after
         // every group keeps memory instructions spread evenly under the MFMAs instead of bunched.
+        // (Issuing the reads one group earlier was tried: no gain.)
         auto mgroup = [&](int i, int buf, int nbuf, bool do_read, const char* sa, const char* sb, bool do_dma, int dma_stage, int dma_k0, int dma_t) {
             if (do_dma) {
                 const uint32_t so = dma_stage * kStageBytes;
@@ -254,6 +255,60 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         // once per lane) and a store covers complete cache lines.
         const T* __restrict__ bias = reinterpret_cast<const T*>(p.bias);
         OutT* __restrict__ Y = reinterpret_cast<OutT*>(p.Y);
+        if constexpr (sizeof(OutT) == 2) {
+            // 16-bit output without residual (QKV, FC1): finish the values in registers (the 16 bias
+            // vectors a lane needs are fetched together up front), park them in LDS as 16-bit values,
+            // two 32-row passes in flight (double-buffered region), and store 16 bytes per lane.
+            constexpr int ROWH = 128 * 2 + 16;                     // padded 16-bit row
+            char* reg = smem + kStageBytes + wave * kEpiRegion;
+            const float lower = a.relu ? 0.f : -INFINITY;
+            const float sc = p.out_scale;
+            float bvv[4][4][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * 128 + j * 32 + 8 * q + 4 * kh;
+                    Vec<T, 4> b4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) b4.v[e] = Fmt<T>::store(0.f);
+                    if (bias && n < a.N) b4 = load_vec<T, 4>(bias + n);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) bvv[j][q][e] = Fmt<T>::load(b4.v[e]) * sc;      // (acc + b) s = acc s + b s: one FMA per value
+                }
+            const int rr = lane >> 4, ch = lane & 15;              // 4 rows x 16 pieces of 8 elements per store
+            const int n = n0 + wn * 128 + ch * 8;
+            const bool n_ok = n < a.N;                             // N % 8 == 0 is required for this path
+            const bool interior = (m0 + kBM <= a.M) && (n0 + kBN <= a.N);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                char* buf = reg + (i & 1) * (32 * ROWH);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        Vec<OutT, 4> ov;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            ov.v[e] = Fmt<OutT>::store(fmaxf(__builtin_fmaf(acc[i][j][4 * q + e], sc, bvv[j][q][e]), lower));
+                        store_vec<OutT, 4>(reinterpret_cast<OutT*>(buf + r * ROWH) + j * 32 + 8 * q + 4 * kh, ov);
+                    }
+                __builtin_amdgcn_wave_barrier();
+                uint4 v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v8[u] = *reinterpret_cast<const uint4*>(buf + (4 * u + rr) * ROWH + ch * 16);
+                const int mf = m0 + wm * 128 + i * 32 + rr;
+                OutT* yp = Y + (size_t)mf * a.ldy + n;
+                if (interior) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) *reinterpret_cast<uint4*>(yp + (size_t)(4 * u) * a.ldy) = v8[u];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (n_ok && mf + 4 * u < a.M) *reinterpret_cast<uint4*>(yp + (size_t)(4 * u) * a.ldy) = v8[u];
+                }
+            }
+        } else {
         constexpr int ROWB = 128 * 4 + 16;                         // padded float32 row of the wave's sub-tile
         {
             char* reg = smem + kStageBytes + wave * kEpiRegion;
@@ -264,7 +319,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             if (bias && n_ok) {
                 const Vec<T, 4> b4 = load_vec<T, 4>(bias + n);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) bv[e] = Fmt<T>::load(b4.v[e]);
+                for (int e = 0; e < 4; ++e) bv[e] = Fmt<T>::load(b4.v[e]) * p.out_scale;      // (acc + b) s = acc s + b s
             }
             const float lower = a.relu ? 0.f : -INFINITY;
             const float sc = p.out_scale;
@@ -300,8 +355,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                     }
 #pragma unroll
                     for (int u = 0; u < 16; ++u) {
-                        float y0 = fmaxf((v4[u].x + bv[0]) * sc, lower), y1 = fmaxf((v4[u].y + bv[1]) * sc, lower);
-                        float y2 = fmaxf((v4[u].z + bv[2]) * sc, lower), y3 = fmaxf((v4[u].w + bv[3]) * sc, lower);
+                        float y0 = fmaxf(__builtin_fmaf(v4[u].x, sc, bv[0]), lower), y1 = fmaxf(__builtin_fmaf(v4[u].y, sc, bv[1]), lower);
+                        float y2 = fmaxf(__builtin_fmaf(v4[u].z, sc, bv[2]), lower), y3 = fmaxf(__builtin_fmaf(v4[u].w, sc, bv[3]), lower);
                         if (RES) { y0 += rv[u].x; y1 += rv[u].y; y2 += rv[u].z; y3 += rv[u].w; }
                         Vec<OutT, 4> ov;
                         ov.v[0] = Fmt<OutT>::store(y0); ov.v[1] = Fmt<OutT>::store(y1);
@@ -317,6 +372,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 if (p.residual) run_passes(std::true_type{}, std::true_type{});
                 else run_passes(std::true_type{}, std::false_type{});
             }
+        }
         }
         TSTAMP();
         if (!have_next) break;
@@ -358,10 +414,11 @@ static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
 bool gemm256_applicable(const GemmArgs& a, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16)) return false;
     if (a.K % 64 != 0 || a.M < 256 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
+    if (!a.out_f32 && (a.N % 8 != 0 || a.ldy % 8 != 0)) return false;
     const size_t tsz = 2;
     for (int i = 0; i < a.nprob; ++i) {
         if (((uintptr_t)a.p[i].Y & 15) != 0) return false;
-        if (a.p[i].residual && ((uintptr_t)a.p[i].residual & 15) != 0) return false;
+        if (a.p[i].residual && (((uintptr_t)a.p[i].residual & 15) != 0 || !a.out_f32)) return false;
         if (a.p[i].bias && ((uintptr_t)a.p[i].bias & (4 * tsz - 1)) != 0) return false;
     }
     return true;

@@ -160,6 +160,11 @@ enum { ZO2_KC_K1 = 0,     /* fused update + perturb                        */
 zo2_status zo2_set_profiling(zo2_ctx* ctx, uint32_t class_mask);
 zo2_status zo2_get_kernel_times(const zo2_ctx* ctx, float ms[ZO2_KERNEL_CLASSES], int32_t launches[ZO2_KERNEL_CLASSES]);
 
+/* Test aid for the block scheduler (Alg. 3): before every block's work on stream `which`
+ * (0 compute, 1 upload, 2 offload) an idle kernel of the given duration (<= 100 ms) is enqueued.  With the
+ * dependency rules of Sec. 5.2 in place no choice of delays can change any result. */
+zo2_status zo2_debug_set_stream_delay(zo2_ctx* ctx, int32_t which, uint32_t microseconds);
+
 const char* zo2_last_error(const zo2_ctx* ctx);
 void zo2_destroy(zo2_ctx* ctx);
 

@@ -122,6 +122,8 @@ struct zo2_ctx {
     uint64_t bytes_up, bytes_down;
     float ms_c, ms_u, ms_o;
 
+    uint32_t debug_delay_us[3];         // test aid: idle time inserted before each block's work on compute / upload / offload
+
     // optional per-kernel-class timing with events on the compute stream
     uint32_t prof_mask;
     std::vector<hipEvent_t> prof_ev;    // pairs (begin, end)
@@ -210,6 +212,21 @@ static void prof_collect(zo2_ctx* c) {   // after the compute stream has been sy
         }                                                                    \
         if (s__ != ZO2_OK) return fail(c, s__, "%s", zo2_op_last_error());   \
     } while (0)
+
+// Test aid for the scheduler: a kernel that idles for a bounded time on one stream, so that a test can make
+// any of the three streams arbitrarily slow; with correct event dependencies the results cannot change.
+__global__ void delay_kernel(unsigned long long ticks_100mhz) {
+    const unsigned long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks_100mhz) { __builtin_amdgcn_s_sleep(32); }
+}
+static zo2_status debug_delay(zo2_ctx* c, int which, hipStream_t st) {
+    const uint32_t us = c->debug_delay_us[which];
+    if (us == 0) return ZO2_OK;
+    hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(1), 0, st, (unsigned long long)us * 100ull);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, ZO2_EHIP, "delay kernel: %s", hipGetErrorString(e));
+    return ZO2_OK;
+}
 
 static inline uint32_t block_tid(int l, int k) { return (uint32_t)(2 + 16 * l + k); }
 static inline uint32_t fln_tid(const zo2_ctx* c) { return (uint32_t)(2 + 16 * c->cfg.n_layers); }
@@ -313,6 +330,7 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->bytes_up = c->bytes_down = 0;
     c->ms_c = c->ms_u = c->ms_o = 0.f;
     c->bytes_used = 0;
+    c->debug_delay_us[0] = c->debug_delay_us[1] = c->debug_delay_us[2] = 0;
     c->prof_mask = 0;
     prof_reset(c);
     c->n_slots = 0;
@@ -531,6 +549,12 @@ extern "C" zo2_status zo2_get_kernel_times(const zo2_ctx* c, float ms[ZO2_KERNEL
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_debug_set_stream_delay(zo2_ctx* c, int32_t which, uint32_t microseconds) {
+    if (!c || which < 0 || which > 2 || microseconds > 100000u) return ZO2_EINVAL;
+    c->debug_delay_us[which] = microseconds;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_step_stats(const zo2_ctx* c, float* ms_c, float* ms_u, float* ms_o, uint64_t* up, uint64_t* down) {
     if (!c) return ZO2_EINVAL;
     if (ms_c) *ms_c = c->ms_c;
@@ -666,6 +690,7 @@ static zo2_status enqueue_upload(zo2_ctx* c, int l) {
     const int s = l % c->n_slots;
     if (c->ev_free_valid[s]) HIPCHK(c, hipStreamWaitEvent(c->su, c->ev_free[s], 0));
     if (!c->stat_u) { HIPCHK(c, hipEventRecord(c->ev_u0, c->su)); c->stat_u = true; }
+    { zo2_status ds = debug_delay(c, 1, c->su); if (ds != ZO2_OK) return ds; }
     HIPCHK(c, hipMemcpyAsync(c->slots + (size_t)s * c->bucket_bytes, c->host_bucket[l], c->bucket_bytes, hipMemcpyHostToDevice, c->su));
     HIPCHK(c, hipEventRecord(c->ev_up[s], c->su));
     c->bytes_up += c->bucket_bytes;
@@ -679,6 +704,7 @@ static zo2_status enqueue_offload(zo2_ctx* c, int l, bool changed) {
     if (changed) {
         HIPCHK(c, hipStreamWaitEvent(c->so, c->ev_k1[s], 0));
         if (!c->stat_o) { HIPCHK(c, hipEventRecord(c->ev_o0, c->so)); c->stat_o = true; }
+        { zo2_status ds = debug_delay(c, 2, c->so); if (ds != ZO2_OK) return ds; }
         HIPCHK(c, hipMemcpyAsync(c->host_bucket[l], c->slots + (size_t)s * c->bucket_bytes, c->bucket_bytes, hipMemcpyDeviceToHost, c->so));
         HIPCHK(c, hipEventRecord(c->ev_free[s], c->so));
         c->bytes_down += c->bucket_bytes;
@@ -764,6 +790,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
             HIPCHK(c, hipEventRecord(c->ev_fwd_done[sb], c->sc));
         } else {
             if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
+            { zo2_status ds = debug_delay(c, 0, c->sc); if (ds != ZO2_OK) return ds; }
             zo2_status s = block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
             if (s != ZO2_OK) return s;
         }

@@ -93,6 +93,33 @@ def test_streamed_equals_resident_bitwise():
     ctx_r.close(); ctx_s.close()
 
 
+@pytest.mark.parametrize("slow", ["compute", "upload", "offload"])
+def test_scheduler_dependencies_hold_under_adversarial_delays(slow):
+    """Alg. 3 / Sec. 5.2: offload after the block's update, compute after its upload, upload into a slot only after
+    its previous occupant has left.  Making one of the three streams much slower than the others (an idle kernel
+    before each of its block operations) reorders everything that is not held by an event; results must not move."""
+    b = _b()
+    cfg = si.tiny_config(n_layers=9, d_model=64, n_heads=4, d_ffn=128, vocab=211, max_pos=40)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 2, 17, seed=12)
+    lab = si.next_token_labels(tok)
+    runs = []
+    for delayed in (False, True):
+        ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+        r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
+        ctx.set_resident_budget(ctx.plan()["bytes_used"] - 6 * ctx.offs[16] * 4)      # 3 slots for 9 blocks
+        if delayed:
+            ctx.debug_set_stream_delay(slow, 300)
+        r += [ctx.step(tok, lab, 6 + j, 1e-3, 1e-3) for j in range(3)]
+        assert ctx.plan()["n_slots"] == 3 and not ctx.plan()["resident"]
+        ctx.flush(); ctx.sync_to_host()
+        runs.append(([tuple(map(float, x)) for x in r], ctx.parameters()))
+        ctx.close()
+    assert runs[0][0] == runs[1][0]
+    for n in runs[0][1]:
+        assert np.array_equal(runs[0][1][n], runs[1][1][n]), n
+
+
 def test_k1_on_its_own_stream_changes_nothing():
     """The optional fourth stream (K1 of block l+1 under the forwards of block l, two scratch sets) is a pure
     scheduling change: identical bits, resident and streamed."""

@@ -12,14 +12,23 @@ struct GemmProblem {
     void* Y;                // [M, ldy] compute dtype or float32
     float out_scale;        // multiplies (acc + bias); 1/sqrt(d_head) for the query projection
     int32_t pad_;
+    // cross-entropy mode (GemmArgs::ce_mode): nothing is stored to Y; per row and per 64-column span the
+    // kernel writes max and sum(exp(y - max)), and the logit of the row's label.  The partial arrays are
+    // span-major: span s of row m sits at [s * part_ld + m], s < 4 * ceil(N / 256).  No bias, relu, residual.
+    const int32_t* labels;  // [M] device, -100 = ignored (partials are still written)
+    float* part_max;        // [4 * ceil(N / 256), part_ld]
+    float* part_sum;        // [4 * ceil(N / 256), part_ld]
+    float* label_logit;     // [M]
 };
 
 struct GemmArgs {
     static constexpr int kMaxProblems = 6;
     int32_t M, N, K;
     int64_t ldx, ldw, ldy;
+    int64_t part_ld;        // cross-entropy mode: elements between consecutive spans of the partial arrays (>= M)
     int32_t relu;
     int32_t out_f32;        // Y is float32 instead of the compute dtype
+    int32_t ce_mode;        // 1: LM-head + cross-entropy partials instead of an output matrix (256 x 256 kernel only)
     int32_t nprob;          // problems of identical shape, one per grid.z (the +/- streams, q/k/v)
     GemmProblem p[kMaxProblems];
 };

@@ -223,7 +223,7 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
     ZO2_OP_CHECK(a.ldx % 8 == 0 && a.ldw % 8 == 0, ZO2_EINVAL, "gemm: ldx / ldw must be multiples of 8");
     ZO2_OP_CHECK(a.nprob >= 1 && a.nprob <= GemmArgs::kMaxProblems, ZO2_EINVAL, "gemm: %d problems", a.nprob);
     for (int i = 0; i < a.nprob; ++i) {
-        ZO2_OP_CHECK(a.p[i].X && a.p[i].W && a.p[i].Y, ZO2_EINVAL, "gemm: NULL operand in problem %d", i);
+        ZO2_OP_CHECK(a.p[i].X && a.p[i].W && (a.p[i].Y || a.ce_mode), ZO2_EINVAL, "gemm: NULL operand in problem %d", i);
         ZO2_OP_CHECK(((uintptr_t)a.p[i].X & 15) == 0 && ((uintptr_t)a.p[i].W & 15) == 0, ZO2_EINVAL,
                      "gemm: operands must be 16-byte aligned");
     }
@@ -235,6 +235,7 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
         return ZO2_OK;
     }
     if (gemm256_applicable(a, dtype)) return gemm_launch_256(a, dtype, st);
+    ZO2_OP_CHECK(!a.ce_mode, ZO2_EINVAL, "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 64 == 0, M, N >= 256)");
     if (dtype == ZO2_BF16) return launch_mfma<bf16_t>(a, st);
     if (dtype == ZO2_F16) return launch_mfma<f16_t>(a, st);
     set_op_error("gemm: dtype %d is not a compute dtype", dtype);

@@ -358,14 +358,68 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                         float y0 = fmaxf(__builtin_fmaf(v4[u].x, sc, bv[0]), lower), y1 = fmaxf(__builtin_fmaf(v4[u].y, sc, bv[1]), lower);
                         float y2 = fmaxf(__builtin_fmaf(v4[u].z, sc, bv[2]), lower), y3 = fmaxf(__builtin_fmaf(v4[u].w, sc, bv[3]), lower);
                         if (RES) { y0 += rv[u].x; y1 += rv[u].y; y2 += rv[u].z; y3 += rv[u].w; }
-                        Vec<OutT, 4> ov;
-                        ov.v[0] = Fmt<OutT>::store(y0); ov.v[1] = Fmt<OutT>::store(y1);
-                        ov.v[2] = Fmt<OutT>::store(y2); ov.v[3] = Fmt<OutT>::store(y3);
-                        if (!MASKED || (n_ok && mf + 2 * u < a.M)) store_vec<OutT, 4>(Y + off0 + u * row_step, ov);
+                        {
+                            Vec<OutT, 4> ov;
+                            ov.v[0] = Fmt<OutT>::store(y0); ov.v[1] = Fmt<OutT>::store(y1);
+                            ov.v[2] = Fmt<OutT>::store(y2); ov.v[3] = Fmt<OutT>::store(y3);
+                            if (!MASKED || (n_ok && mf + 2 * u < a.M)) store_vec<OutT, 4>(Y + off0 + u * row_step, ov);
+                        }
                     }
                 }
             };
-            if (interior) {
+            // Cross-entropy mode (LM head): instead of storing logits, a lane owns one row of the pass and a
+            // 64-column span of it, and reduces that span to max and sum(exp(y - max)) in registers: no
+            // cross-lane traffic, and the partials of 32 consecutive rows leave as one 128-byte store.
+            auto run_ce = [&](auto masked_c) {
+                constexpr bool MASKED = decltype(masked_c)::value;
+                constexpr float kL2e = 1.4426950408889634f;
+                const int crow = lane & 31, chalf = lane >> 5;
+                const int ncol0 = n0 + wn * 128 + chalf * 64;
+                const size_t span = (size_t)(4 * (n0 / kBN) + 2 * wn + chalf) * (size_t)a.part_ld;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (i) __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float4 w4 = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                            *reinterpret_cast<float4*>(reg + r * ROWB + (j * 32 + 8 * q + 4 * kh) * 4) = w4;
+                        }
+                    __builtin_amdgcn_wave_barrier();
+                    const int row = m0 + wm * 128 + i * 32 + crow;
+                    const bool row_ok = !MASKED || row < a.M;
+                    const char* rp = reg + crow * ROWB + chalf * 256;
+                    const int lab = p.labels[MASKED ? min(row, a.M - 1) : row];
+                    float4 v4[16];
+#pragma unroll
+                    for (int t = 0; t < 16; ++t) v4[t] = *reinterpret_cast<const float4*>(rp + t * 16);
+                    const int dl = lab - ncol0;
+                    if (row_ok && dl >= 0 && dl < 64) p.label_logit[row] = *reinterpret_cast<const float*>(rp + dl * 4) * sc;
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int t = 0; t < 16; ++t) {
+                        v4[t].x *= sc; v4[t].y *= sc; v4[t].z *= sc; v4[t].w *= sc;
+                        if (MASKED && ncol0 + 4 * t >= a.N) v4[t] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);   // N % 4 == 0
+                        mx = fmaxf(mx, fmaxf(fmaxf(v4[t].x, v4[t].y), fmaxf(v4[t].z, v4[t].w)));
+                    }
+                    const float mb = mx == -INFINITY ? 0.f : mx;        // a fully masked span sums to 0
+                    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                    for (int t = 0; t < 16; ++t) {
+                        s0 += __builtin_amdgcn_exp2f((v4[t].x - mb) * kL2e) + __builtin_amdgcn_exp2f((v4[t].y - mb) * kL2e);
+                        s1 += __builtin_amdgcn_exp2f((v4[t].z - mb) * kL2e) + __builtin_amdgcn_exp2f((v4[t].w - mb) * kL2e);
+                    }
+                    if (row_ok) {
+                        p.part_max[span + row] = mx;
+                        p.part_sum[span + row] = s0 + s1;
+                    }
+                }
+            };
+            if (a.ce_mode) {
+                if (interior) run_ce(std::false_type{});
+                else run_ce(std::true_type{});
+            } else if (interior) {
                 if (p.residual) run_passes(std::false_type{}, std::true_type{});
                 else run_passes(std::false_type{}, std::false_type{});
             } else {
@@ -415,8 +469,15 @@ bool gemm256_applicable(const GemmArgs& a, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16)) return false;
     if (a.K % 64 != 0 || a.M < 256 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
     if (!a.out_f32 && (a.N % 8 != 0 || a.ldy % 8 != 0)) return false;
+    if (a.ce_mode && !a.out_f32) return false;
     const size_t tsz = 2;
     for (int i = 0; i < a.nprob; ++i) {
+        if (a.ce_mode) {
+            if (!a.p[i].labels || !a.p[i].part_max || !a.p[i].part_sum || !a.p[i].label_logit || a.p[i].residual || a.p[i].bias ||
+                a.relu || a.part_ld < a.M)
+                return false;
+            continue;
+        }
         if (((uintptr_t)a.p[i].Y & 15) != 0) return false;
         if (a.p[i].residual && (((uintptr_t)a.p[i].residual & 15) != 0 || !a.out_f32)) return false;
         if (a.p[i].bias && ((uintptr_t)a.p[i].bias & (4 * tsz - 1)) != 0) return false;

@@ -26,6 +26,9 @@ zo2_status embed_gather(const EmbedArgs& a, int wire_dtype, int compute_dtype, b
 // rows of logits -> row_loss[row0 + r]; the label of stacked row i is labels[i % label_period]
 zo2_status cross_entropy_rows(const float* logits, int64_t ld, const int32_t* labels, int rows, int row0, int label_period,
                               int vocab, float* row_loss, hipStream_t st);
+// span-major (max, sum exp) partials written by the LM-head kernel's cross-entropy mode -> row_loss[row0 + r]
+zo2_status ce_combine(const float* part_max, const float* part_sum, const float* label_logit, const int32_t* labels, int rows,
+                      int n_parts, int64_t part_ld, int row0, int label_period, float* row_loss, hipStream_t st);
 // result[0..3] = l+, l-, g, number of counted labels; *c_pending = lr * g
 zo2_status loss_epilogue(const float* row_loss, const int32_t* labels, int T, float eps, float lr, float* result,
                          float* c_pending, hipStream_t st);

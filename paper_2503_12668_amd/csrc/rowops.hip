@@ -278,6 +278,59 @@ zo2_status cross_entropy_rows(const float* logits, int64_t ld, const int32_t* la
     return ZO2_OK;
 }
 
+// ------------------------------------------------------------------ combine the LM-head kernel's cross-entropy partials
+// Row r has n_parts pairs (m_i, s_i), span-major ([i * part_ld + r]), with s_i = sum over a 64-column span of
+// exp(y - m_i); then logsumexp = M + log(sum_i s_i exp(m_i - M)), M = max_i m_i.
+__global__ __launch_bounds__(256) void ce_combine_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum,
+                                                         const float* __restrict__ label_logit, const int32_t* __restrict__ labels,
+                                                         int rows, int n_parts, int64_t part_ld, int row0, int label_period,
+                                                         float* __restrict__ row_loss) {
+    // 64 rows per block; the 4 wavefronts split the spans, so every load is 64 consecutive floats
+    __shared__ float sh_m[4][64];
+    __shared__ double sh_s[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + lane;
+    const int rc = r < rows ? r : rows - 1;
+    float m = -INFINITY;
+    double s = 0.0;
+    for (int i = w; i < n_parts; i += 4) {
+        const float mi = part_max[(size_t)i * part_ld + rc];
+        const float si = part_sum[(size_t)i * part_ld + rc];
+        if (mi == -INFINITY) continue;               // span entirely past the last column
+        if (mi > m) {
+            s = s * (double)expf(m - mi) + (double)si;      // expf(-inf) = 0 on the first span
+            m = mi;
+        } else {
+            s += (double)si * (double)expf(mi - m);
+        }
+    }
+    sh_m[w][lane] = m;
+    sh_s[w][lane] = s;
+    __syncthreads();
+    if (w != 0 || r >= rows) return;
+    const int lab = labels[(row0 + r) % label_period];
+    if (lab < 0) {
+        row_loss[row0 + r] = 0.f;
+        return;
+    }
+    float mm = fmaxf(fmaxf(sh_m[0][lane], sh_m[1][lane]), fmaxf(sh_m[2][lane], sh_m[3][lane]));
+    double ss = 0.0;
+    for (int k = 0; k < 4; ++k)
+        if (sh_m[k][lane] != -INFINITY) ss += sh_s[k][lane] * (double)expf(sh_m[k][lane] - mm);
+    row_loss[row0 + r] = (float)(log(ss) + (double)mm - (double)label_logit[r]);
+}
+
+zo2_status ce_combine(const float* part_max, const float* part_sum, const float* label_logit, const int32_t* labels, int rows,
+                      int n_parts, int64_t part_ld, int row0, int label_period, float* row_loss, hipStream_t st) {
+    if (rows == 0) return ZO2_OK;
+    ZO2_OP_CHECK(part_max && part_sum && label_logit && labels && row_loss && n_parts > 0 && label_period > 0 && part_ld >= rows,
+                 ZO2_EINVAL, "ce_combine: bad argument");
+    hipLaunchKernelGGL(ce_combine_kernel, dim3((rows + 63) / 64), dim3(256), 0, st, part_max, part_sum, label_logit, labels, rows, n_parts,
+                       part_ld, row0, label_period, row_loss);
+    ZO2_HIP_LAUNCH_CHECK();
+    return ZO2_OK;
+}
+
 // ------------------------------------------------------------------ scalar epilogue (Eq. 2)
 // l+ = mean of row_loss[0..T) over non-ignored labels, l- of row_loss[T..2T);
 // g = (l+ - l-) / (2 eps); the pending step c = lr * g stays in device memory.

@@ -10,6 +10,7 @@
 // update of iteration j-1 is applied when the block is visited in iteration j (Sec. 5.4).
 #include <math.h>
 #include <stdarg.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -104,6 +105,9 @@ struct zo2_ctx {
     size_t att_ws_bytes;
     float* logits;
     int logit_rows;                     // rows per sign per chunk
+    bool fused_ce;                      // LM head writes cross-entropy partials instead of logits
+    float *ce_pmax, *ce_psum, *ce_lab;  // [4 ceil(V/256), 2T] x 2 and [2T]
+    int ce_parts;
     float* row_loss;
     int32_t *d_tokens, *d_labels;
     size_t bytes_used;
@@ -425,6 +429,10 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const size_t budget = c->budget;
     const size_t rows2 = 2 * (size_t)T;
     // logits chunk: up to 1/8 of the budget, at least 128 rows per sign
+    // (ZO2_DISABLE_FUSED_CE=1 keeps the materialised-logits path, for A/B measurements)
+    const bool fused_ce = (g.compute_dtype != ZO2_F32) && T >= 256 && V >= 256 && (d % 64 == 0) && (V % 4 == 0) &&
+                          getenv("ZO2_DISABLE_FUSED_CE") == nullptr;
+    const size_t ce_parts = 4 * ((V + 255) / 256);
     size_t lrows = budget / 8 / (V * 4) / 2;
     lrows = lrows / 128 * 128;
     if (lrows < 128) lrows = 128;
@@ -435,7 +443,8 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
                  o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
                  o_aws = sz(att_ws),
-                 o_logits = sz(2 * lrows * V * 4), o_rl = sz(rows2 * 4), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
+                 o_logits = sz(fused_ce ? 0 : 2 * lrows * V * 4), o_rl = sz(rows2 * 4),
+                 o_cpm = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cps = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cl = sz(fused_ce ? rows2 * 4 : 0), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
                  o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
     const size_t act_bytes = act;
 
@@ -487,6 +496,8 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     c->mid = a0 + o_mid; c->att_ws = a0 + o_aws; c->att_ws_bytes = att_ws; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
     c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
     c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
+    c->fused_ce = fused_ce; c->ce_parts = (int)ce_parts;
+    c->ce_pmax = (float*)(a0 + o_cpm); c->ce_psum = (float*)(a0 + o_cps); c->ce_lab = (float*)(a0 + o_cl);
     off += act_bytes;
     c->bytes_used = off;
     c->logit_rows = (int)lrows;
@@ -835,6 +846,21 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
             HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_k1done[sb], 0));
         }
     }
+    if (c->fused_ce) {
+        // logits are never written: the GEMM epilogue reduces each 64-column span to (max, sum exp) and picks the label's logit
+        GemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.M = T; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2; ga.ce_mode = 1; ga.part_ld = 2 * (int64_t)T;
+        for (int s = 0; s < 2; ++s) {
+            GemmProblem& p = ga.p[s];
+            p.X = c->x + (size_t)s * T * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr; p.Y = nullptr;
+            p.out_scale = 1.0f; p.labels = c->d_labels;
+            p.part_max = c->ce_pmax + (size_t)s * T; p.part_sum = c->ce_psum + (size_t)s * T;
+            p.label_logit = c->ce_lab + (size_t)s * T;
+        }
+        OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+        OPK(c, ZO2_KC_CE, ce_combine(c->ce_pmax, c->ce_psum, c->ce_lab, c->d_labels, 2 * T, c->ce_parts, 2 * (int64_t)T, 0, T, c->row_loss, c->sc));
+    } else {
     const int R = c->logit_rows;
     for (int r0 = 0; r0 < T; r0 += R) {
         const int rows = std::min(R, T - r0);
@@ -849,6 +875,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
         for (int s = 0; s < 2; ++s)
             OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
+    }
     }
     OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, c->d_state + 4, c->d_state, c->sc));
     HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));

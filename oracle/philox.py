@@ -8,7 +8,9 @@ z[p, e], so any block can regenerate its z at any time, in any order.
 
 Generator: Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel
 random numbers: as easy as 1, 2, 3", SC'11).  Gaussian map: Box-Muller on
-24-bit uniforms, evaluated in float64 and rounded once to float32.
+16-bit uniforms (one 32-bit word per pair of elements), evaluated in float64
+and rounded once to float32.  The paper fixes only that z is standard normal
+and reproducible from the seed (Alg. 1, Sec. 5.1); this map is a choice.
 """
 import os
 from concurrent.futures import ThreadPoolExecutor
@@ -48,10 +50,10 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 
 def random_words(seed, tensor_id, e0, n):
-    """The 32 random bits of elements e0 .. e0+n-1 of tensor `tensor_id` at step
-    seed `seed`.  Element e uses Philox call q = e >> 2 with
-    counter (lo32(q), hi32(q), tensor_id, 0), key (lo32(seed), hi32(seed)),
-    and takes output word e & 3."""
+    """Words e0 .. e0+n-1 of the random stream of tensor `tensor_id` at step seed
+    `seed`.  Word j is output j & 3 of Philox call q = j >> 2 with
+    counter (lo32(q), hi32(q), tensor_id, 0), key (lo32(seed), hi32(seed)).
+    Elements 2j and 2j+1 of the tensor are drawn from word j (see gaussian)."""
     seed = int(seed)
     e = np.arange(int(e0), int(e0) + int(n), dtype=np.uint64)
     q = e >> np.uint64(2)
@@ -62,7 +64,7 @@ def random_words(seed, tensor_id, e0, n):
     return w[inv, (e & np.uint64(3)).astype(np.int64)]
 
 
-_CHUNK = 1 << 20      # elements per piece; a multiple of 4 so pieces start on a Philox call
+_CHUNK = 1 << 20      # elements per piece; a multiple of 8 so pieces start on a Philox call
 
 
 def gaussian(seed, tensor_id, e0, n):
@@ -83,27 +85,26 @@ def gaussian(seed, tensor_id, e0, n):
 def _gaussian_piece(seed, tensor_id, e0, n):
     """z for elements e0 .. e0+n-1 of a tensor, float32.
 
-    Per Philox call the words (x0, x1) and (x2, x3) feed one Box-Muller pair
-    each: u1 = ((xa >> 8) + 1) / 2^24 in (0, 1], u2 = (xb >> 8) / 2^24 in [0, 1),
-    rho = sqrt(-2 ln u1); elements 4q, 4q+1 = rho cos(2 pi u2), rho sin(2 pi u2)
-    from (x0, x1) and 4q+2, 4q+3 likewise from (x2, x3)."""
+    Philox call q covers elements 8q .. 8q+7; its output word i (0..3) feeds one
+    Box-Muller pair: u1 = ((x >> 16) + 1) / 2^16 in (0, 1], u2 = (x & 0xffff) / 2^16
+    in [0, 1), rho = sqrt(-2 ln u1); elements 8q+2i, 8q+2i+1 = rho cos(2 pi u2),
+    rho sin(2 pi u2).  |z| <= sqrt(32 ln 2) = 4.71."""
     seed = int(seed)
     e0 = int(e0)
     n = int(n)
-    q_lo = e0 >> 2
-    q_hi = (e0 + n + 3) >> 2
+    q_lo = e0 >> 3
+    q_hi = (e0 + n + 7) >> 3
     q = np.arange(q_lo, q_hi, dtype=np.uint64)
     x = philox4x32_10(q & _MASK, q >> _S32, np.uint64(tensor_id), np.uint64(0),
                       seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
-    out = np.empty((q.size, 4), dtype=np.float64)
-    for pair in (0, 1):
-        xa = x[2 * pair].astype(np.float64)
-        xb = x[2 * pair + 1].astype(np.float64)
-        u1 = (np.floor(xa / 256.0) + 1.0) / 16777216.0
-        u2 = np.floor(xb / 256.0) / 16777216.0
+    out = np.empty((q.size, 8), dtype=np.float64)
+    for i in range(4):
+        xi = x[i].astype(np.uint64)
+        u1 = ((xi >> np.uint64(16)).astype(np.float64) + 1.0) / 65536.0
+        u2 = (xi & np.uint64(0xFFFF)).astype(np.float64) / 65536.0
         rho = np.sqrt(-2.0 * np.log(u1))
-        out[:, 2 * pair] = rho * np.cos(2.0 * np.pi * u2)
-        out[:, 2 * pair + 1] = rho * np.sin(2.0 * np.pi * u2)
+        out[:, 2 * i] = rho * np.cos(2.0 * np.pi * u2)
+        out[:, 2 * i + 1] = rho * np.sin(2.0 * np.pi * u2)
     flat = out.reshape(-1)
-    lo = e0 - 4 * q_lo
+    lo = e0 - 8 * q_lo
     return flat[lo:lo + n].astype(np.float32)

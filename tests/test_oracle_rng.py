@@ -37,8 +37,8 @@ def test_philox_vectorised_matches_scalar():
 
 
 def test_word_addressing():
-    """Element e takes word e&3 of call e>>2 with counter (lo(q), hi(q), tensor, 0) and
-    key (lo(seed), hi(seed)); the 64-bit element index and seed really use both halves."""
+    """Stream word j is output j&3 of call j>>2 with counter (lo(q), hi(q), tensor, 0) and
+    key (lo(seed), hi(seed)); the 64-bit word index and seed really use both halves."""
     seed = (0xABCDEF01 << 32) | 0x13572468
     e0 = (1 << 34) + 6
     w = philox.random_words(seed, 77, e0, 9)
@@ -64,19 +64,21 @@ def test_gaussian_window_invariance():
 
 
 def test_gaussian_box_muller_structure():
-    """Elements (4q, 4q+1) share a radius rho = sqrt(-2 ln u1) taken from word 0 and an
-    angle from word 1; (4q+2, 4q+3) use words 2 and 3."""
-    w = philox.random_words(9, 4, 0, 4096).astype(np.float64).reshape(-1, 4)
-    z = philox.gaussian(9, 4, 0, 4096).astype(np.float64).reshape(-1, 4)
-    for a in (0, 2):
-        u1 = (np.floor(w[:, a] / 256) + 1) / 2 ** 24
-        u2 = np.floor(w[:, a + 1] / 256) / 2 ** 24
-        r2 = z[:, a] ** 2 + z[:, a + 1] ** 2
-        assert np.allclose(r2, -2 * np.log(u1), rtol=1e-5, atol=1e-6)
-        ang = np.mod(np.arctan2(z[:, a + 1], z[:, a]) / (2 * np.pi), 1.0)
-        ok = r2 > 1e-3
-        d = np.abs(ang - u2)[ok]
-        assert np.all(np.minimum(d, 1 - d) < 1e-5)
+    """Elements (2j, 2j+1) come from stream word j: they share the radius
+    rho = sqrt(-2 ln u1) set by the word's high half and the angle set by its low half."""
+    w = philox.random_words(9, 4, 0, 2048).astype(np.int64)
+    z = philox.gaussian(9, 4, 0, 4096).astype(np.float64).reshape(-1, 2)
+    u1 = ((w >> 16) + 1) / 2.0 ** 16
+    u2 = (w & 0xFFFF) / 2.0 ** 16
+    r2 = z[:, 0] ** 2 + z[:, 1] ** 2
+    assert np.allclose(r2, -2 * np.log(u1), rtol=1e-5, atol=1e-6)
+    ang = np.mod(np.arctan2(z[:, 1], z[:, 0]) / (2 * np.pi), 1.0)
+    ok = r2 > 1e-3
+    d = np.abs(ang - u2)[ok]
+    assert np.all(np.minimum(d, 1 - d) < 1e-5)
+    # a window that starts in the middle of a Philox call (element 8q + 5) lines up with the same words
+    z5 = philox.gaussian(9, 4, 8 * 37 + 5, 3).astype(np.float64)
+    assert np.array_equal(z5, z.reshape(-1)[8 * 37 + 5: 8 * 37 + 8])
 
 
 def test_gaussian_distribution():
@@ -86,7 +88,8 @@ def test_gaussian_distribution():
     assert abs(z.var() - 1) < 4 * np.sqrt(2 / n)
     assert abs(stats.skew(z)) < 0.02 and abs(stats.kurtosis(z)) < 0.03
     assert stats.kstest(z, "norm").pvalue > 1e-3
-    assert np.abs(z).max() <= np.sqrt(-2 * np.log(2.0 ** -24)) + 1e-6      # 5.768
+    assert np.abs(z).max() <= np.sqrt(-2 * np.log(2.0 ** -16)) + 1e-6      # 4.710
+    assert np.abs(z).max() > 4.0                                           # the tail is there up to the cut
     # no linear correlation between neighbours, tensors, seeds (consecutive steps)
     z_t = philox.gaussian(42, 3, 0, n).astype(np.float64)
     z_s = philox.gaussian(43, 2, 0, n).astype(np.float64)

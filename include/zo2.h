@@ -71,9 +71,10 @@ typedef struct {
  *     ln1.w ln1.b q.w q.b k.w k.b v.w v.b o.w o.b ln2.w ln2.b fc1.w fc1.b fc2.w fc2.b;
  *   2 + 16 L, 3 + 16 L: final_ln.w, final_ln.b;  4 + 16 L: lm_head.w (only if untied).
  * z of element e of tensor p at step seed s is a pure function of (s, p, e): Philox4x32-10
- * with key (lo32 s, hi32 s) and counter (lo32 q, hi32 q, p, 0), q = e >> 2, output word e & 3;
- * words (0,1) and (2,3) feed one Box-Muller pair each with 24-bit uniforms.  This replaces
- * the saved / restored generator states of Alg. 2 (Sec. 5.1). */
+ * with key (lo32 s, hi32 s) and counter (lo32 q, hi32 q, p, 0), q = e >> 3; output word
+ * (e >> 1) & 3 feeds the Box-Muller pair of elements (e & ~1, e | 1): its high 16 bits give
+ * the radius, its low 16 bits the angle (cosine for the even element, sine for the odd one).
+ * This replaces the saved / restored generator states of Alg. 2 (Sec. 5.1). */
 #define ZO2_BLOCK_TENSORS 16
 
 /* A block's 16 tensors are packed into one contiguous "bucket" (Sec. 5.3): tensor k starts
@@ -174,11 +175,12 @@ void zo2_destroy(zo2_ctx* ctx);
 
 const char* zo2_op_last_error(void);
 
-/* The 32 random bits of elements e0 .. e0+n-1 of tensor `tensor_id` at `seed` (test hook for
- * the bit-exactness of the stream).  out: device uint32[n]. */
+/* Words e0 .. e0+n-1 of the random stream of tensor `tensor_id` at `seed`: word j is output
+ * j & 3 of Philox call j >> 2; elements 2j and 2j+1 are drawn from it (test hook for the
+ * bit-exactness of the stream).  out: device uint32[n]. */
 zo2_status zo2_op_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, uint32_t* out, void* stream);
 
-/* z of the same elements as float32.  out: device float[n]. */
+/* z of elements e0 .. e0+n-1 of the tensor as float32.  out: device float[n]. */
 zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint64_t n, float* out, void* stream);
 
 /* Fused regenerate + update + perturb (Alg. 2 DualForward lines "update", "perturb";

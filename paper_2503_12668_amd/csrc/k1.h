@@ -11,8 +11,7 @@ struct K1Seg {
     uint64_t n;           // elements
     uint32_t tensor_id;   // selects the random stream
     float scale;          // wire scale of the tensor (8-bit formats), else 1
-    uint32_t first_chunk; // filled in by k1_launch
-    uint32_t pad_;
+    uint32_t pad_[2];
 };
 
 struct K1Args {
@@ -27,6 +26,7 @@ struct K1Args {
     float eps;
     const float* c_ptr;   // device scalar holding eta_prev * g_prev (stays on the GPU between steps)
     PhiloxKeys k_prev, k_cur;
+    uint32_t first_chunk[kMaxSeg];   // filled in by k1_launch: first workgroup of each segment (0xffffffff past nseg)
     K1Seg seg[kMaxSeg];
 };
 

@@ -20,26 +20,81 @@ static constexpr int kPerLane = 8;
 static constexpr int kIters = 4;
 static constexpr int kChunk = kThreads * kPerLane * kIters;   // 8192 elements per workgroup
 
+// The arithmetic of one group of 8 consecutive elements (one Philox call q per random stream): tv holds
+// theta on entry and theta' on return.
+template <typename W, typename C, bool UPDATE, bool PERTURB>
+__device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, uint64_t q, float c, float eps, float scale,
+                                         float inv_scale, Vec<W, kPerLane>& tv, Vec<C, kPerLane>& p, Vec<C, kPerLane>& m) {
+    constexpr bool kScaled = (Fmt<W>::kBytes == 1);
+    float th[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        th[j] = Fmt<W>::load(tv.v[j]);
+        if (kScaled) th[j] *= inv_scale;
+    }
+    if (UPDATE) {
+        float zp[kPerLane];
+        gaussian8(a.k_prev, tensor_id, q, zp);
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const float t = __builtin_fmaf(-c, zp[j], th[j]);
+            tv.v[j] = Fmt<W>::store(kScaled ? t * scale : t);
+            th[j] = Fmt<W>::load(tv.v[j]);
+            if (kScaled) th[j] *= inv_scale;
+        }
+    }
+    if (PERTURB) {
+        float z[kPerLane];
+        gaussian8(a.k_cur, tensor_id, q, z);
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
+            m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
+        }
+    }
+}
+
 template <typename W, typename C, bool UPDATE, bool PERTURB>
 __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
-    // which tensor does this workgroup work on (wave-uniform search)
+    // which tensor does this workgroup work on: first_chunk[] ascends (0xffffffff past the last segment),
+    // so the segment index is the number of entries at or below this workgroup's index
     int s = 0;
-#pragma unroll 1
-    for (int i = 1; i < a.nseg; ++i)
-        if (blockIdx.x >= a.seg[i].first_chunk) s = i;
+#pragma unroll
+    for (int i = 1; i < K1Args::kMaxSeg; ++i) s += (blockIdx.x >= a.first_chunk[i]) ? 1 : 0;
     const K1Seg sg = a.seg[s];
-    const uint64_t chunk0 = (uint64_t)(blockIdx.x - sg.first_chunk) * kChunk;
+    const uint64_t chunk0 = (uint64_t)(blockIdx.x - a.first_chunk[s]) * kChunk;
     W* __restrict__ theta = reinterpret_cast<W*>(a.theta) + sg.off;
     C* __restrict__ wp = PERTURB ? reinterpret_cast<C*>(a.w_plus) + (sg.off - a.w_off0) : nullptr;
     C* __restrict__ wm = PERTURB ? reinterpret_cast<C*>(a.w_minus) + (sg.off - a.w_off0) : nullptr;
     const float c = UPDATE ? (a.c_ptr ? *a.c_ptr : a.c_imm) : 0.f;
     const float eps = a.eps;
     const float scale = sg.scale, inv_scale = 1.0f / sg.scale;
-    constexpr bool kScaled = (Fmt<W>::kBytes == 1);
+    constexpr int kStride = kThreads * kPerLane;
 
+    if (chunk0 + kChunk <= sg.n) {
+        // whole chunk inside the tensor (all but the last workgroup of a segment): every load is in
+        // flight before the first group is computed, and nothing is masked
+        const uint64_t i0 = chunk0 + (uint64_t)threadIdx.x * kPerLane;
+        Vec<W, kPerLane> tv[kIters];
 #pragma unroll
+        for (int it = 0; it < kIters; ++it) tv[it] = load_vec<W, kPerLane>(theta + i0 + (uint64_t)it * kStride);
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const uint64_t i = i0 + (uint64_t)it * kStride;
+            Vec<C, kPerLane> p, m;
+            k1_group<W, C, UPDATE, PERTURB>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
+            if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
+            if (PERTURB) {
+                store_vec<C, kPerLane>(wp + i, p);
+                store_vec<C, kPerLane>(wm + i, m);
+            }
+        }
+        return;
+    }
+    // last chunk of a segment: ragged end, element-wise masking
+#pragma unroll 1
     for (int it = 0; it < kIters; ++it) {
-        const uint64_t i0 = chunk0 + (uint64_t)it * (kThreads * kPerLane) + (uint64_t)threadIdx.x * kPerLane;
+        const uint64_t i0 = chunk0 + (uint64_t)it * kStride + (uint64_t)threadIdx.x * kPerLane;
         if (i0 >= sg.n) break;
         const int valid = (sg.n - i0 >= (uint64_t)kPerLane) ? kPerLane : (int)(sg.n - i0);
         Vec<W, kPerLane> tv;
@@ -49,50 +104,21 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j) tv.v[j] = (j < valid) ? theta[i0 + j] : Fmt<W>::store(0.f);
         }
-        float th[kPerLane];
-#pragma unroll
-        for (int j = 0; j < kPerLane; ++j) {
-            th[j] = Fmt<W>::load(tv.v[j]);
-            if (kScaled) th[j] *= inv_scale;
-        }
-        const uint64_t q = (sg.e0 + i0) >> 2;
-        if (UPDATE) {
-            float zp[kPerLane];
-            gaussian4(a.k_prev, sg.tensor_id, q, zp);
-            gaussian4(a.k_prev, sg.tensor_id, q + 1, zp + 4);
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                const float t = __builtin_fmaf(-c, zp[j], th[j]);
-                tv.v[j] = Fmt<W>::store(kScaled ? t * scale : t);
-                th[j] = Fmt<W>::load(tv.v[j]);
-                if (kScaled) th[j] *= inv_scale;
-            }
-            if (valid == kPerLane) {
-                store_vec<W, kPerLane>(theta + i0, tv);
-            } else {
-#pragma unroll
-                for (int j = 0; j < kPerLane; ++j)
-                    if (j < valid) theta[i0 + j] = tv.v[j];
-            }
-        }
-        if (PERTURB) {
-            float z[kPerLane];
-            gaussian4(a.k_cur, sg.tensor_id, q, z);
-            gaussian4(a.k_cur, sg.tensor_id, q + 1, z + 4);
-            Vec<C, kPerLane> p, m;
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
-                m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
-            }
-            if (valid == kPerLane) {
+        Vec<C, kPerLane> p, m;
+        k1_group<W, C, UPDATE, PERTURB>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
+        if (valid == kPerLane) {
+            if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
+            if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i0, p);
                 store_vec<C, kPerLane>(wm + i0, m);
-            } else {
-#pragma unroll
-                for (int j = 0; j < kPerLane; ++j)
-                    if (j < valid) { wp[i0 + j] = p.v[j]; wm[i0 + j] = m.v[j]; }
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j)
+                if (j < valid) {
+                    if (UPDATE) theta[i0 + j] = tv.v[j];
+                    if (PERTURB) { wp[i0 + j] = p.v[j]; wm[i0 + j] = m.v[j]; }
+                }
         }
     }
 }
@@ -116,11 +142,12 @@ zo2_status k1_launch(K1Args& a, int wire_dtype, int compute_dtype, bool update, 
         ZO2_OP_CHECK((a.seg[i].e0 & 7) == 0 && (a.seg[i].off & 7) == 0, ZO2_EINVAL,
                      "k1: segment %d not aligned to 8 elements", i);
         ZO2_OP_CHECK(a.seg[i].scale > 0.f, ZO2_EINVAL, "k1: segment %d has scale %g", i, (double)a.seg[i].scale);
-        a.seg[i].first_chunk = chunks;
+        a.first_chunk[i] = chunks;
         const uint64_t nc = (a.seg[i].n + kChunk - 1) / kChunk;
         ZO2_OP_CHECK(chunks + nc < 0x7fffffffull, ZO2_EINVAL, "k1: too many chunks");
         chunks += (uint32_t)nc;
     }
+    for (int i = a.nseg; i < K1Args::kMaxSeg; ++i) a.first_chunk[i] = 0xffffffffu;
     a.total_chunks = chunks;
     if (chunks == 0 || (!update && !perturb)) return ZO2_OK;
     ZO2_OP_CHECK(a.theta != nullptr, ZO2_EINVAL, "k1: theta is NULL");

@@ -1,6 +1,6 @@
 // Counter-based random direction z (replaces the saved generator states of Alg. 2, Sec. 5.1):
-// Philox4x32-10 keyed by the step seed, counter = (element index / 4, tensor id), followed by
-// Box-Muller on 24-bit uniforms.  z[p, e] is a pure function of (seed, p, e).
+// Philox4x32-10 keyed by the step seed, counter = (element index / 8, tensor id), followed by
+// Box-Muller on 16-bit uniforms (each 32-bit output word yields one pair of elements).  z[p, e] is a pure function of (seed, p, e).
 #pragma once
 #include "common.h"
 
@@ -39,13 +39,13 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// One Box-Muller pair from two words: u1 = ((xa >> 8) + 1) / 2^24 in (0, 1],
-// u2 = (xb >> 8) / 2^24 in [0, 1); (rho cos 2 pi u2, rho sin 2 pi u2), rho = sqrt(-2 ln u1).
+// One Box-Muller pair from one word: u1 = ((x >> 16) + 1) / 2^16 in (0, 1],
+// u2 = (x & 0xffff) / 2^16 in [0, 1); (rho cos 2 pi u2, rho sin 2 pi u2), rho = sqrt(-2 ln u1) <= 4.71.
 // u1 and u2 are exact in fp32.  The hardware log2 / sqrt are 1-ulp operations; the
 // hardware sin / cos take their argument in revolutions, which u2 already is.
-__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& za, float& zb) {
-    const float u1 = (float)((xa >> 8) + 1u) * 5.9604644775390625e-08f;
-    const float u2 = (float)(xb >> 8) * 5.9604644775390625e-08f;
+__device__ __forceinline__ void box_muller(uint32_t x, float& za, float& zb) {
+    const float u1 = (float)((x >> 16) + 1u) * 1.52587890625e-05f;
+    const float u2 = (float)(x & 0xffffu) * 1.52587890625e-05f;
     // -2 ln u1 = (-2 ln 2) log2 u1
     const float t = -1.3862943611198906f * __builtin_amdgcn_logf(u1);
     const float rho = __builtin_amdgcn_sqrtf(t);
@@ -53,12 +53,22 @@ __device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& za, 
     zb = rho * __builtin_amdgcn_sinf(u2);
 }
 
-// z of elements 4q .. 4q+3 of tensor `tensor_id`.
-__device__ __forceinline__ void gaussian4(const PhiloxKeys& k, uint32_t tensor_id, uint64_t q, float z[4]) {
+// z of elements 8q .. 8q+7 of tensor `tensor_id`: one Philox call, output word i gives elements 8q+2i, 8q+2i+1.
+__device__ __forceinline__ void gaussian8(const PhiloxKeys& k, uint32_t tensor_id, uint64_t q, float z[8]) {
     uint32_t w[4];
     philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, 0u, k, w);
-    box_muller(w[0], w[1], z[0], z[1]);
-    box_muller(w[2], w[3], z[2], z[3]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) box_muller(w[i], z[2 * i], z[2 * i + 1]);
+}
+
+// z of elements e .. e+3, e a multiple of 4 (half of a Philox call).
+__device__ __forceinline__ void gaussian4(const PhiloxKeys& k, uint32_t tensor_id, uint64_t e, float z[4]) {
+    const uint64_t q = e >> 3;
+    uint32_t w[4];
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, 0u, k, w);
+    const bool hi = (e & 4) != 0;
+    box_muller(hi ? w[2] : w[0], z[0], z[1]);
+    box_muller(hi ? w[3] : w[1], z[2], z[3]);
 }
 
 }  // namespace zo2

@@ -57,7 +57,7 @@ __global__ void gaussian_kernel(PhiloxKeys k, uint32_t tensor_id, uint64_t e0, u
     if (i >= n) return;
     const uint64_t e = e0 + i;
     float z[4];
-    gaussian4(k, tensor_id, e >> 2, z);
+    gaussian4(k, tensor_id, e & ~(uint64_t)3, z);
     const uint32_t r = (uint32_t)(e & 3);
     out[i] = r == 0 ? z[0] : r == 1 ? z[1] : r == 2 ? z[2] : z[3];
 }
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
             if (kScaled) th[i] *= inv_scale;
         }
         if (UPDATE) {
-            gaussian4(a.k_prev, (uint32_t)which, e >> 2, z);
+            gaussian4(a.k_prev, (uint32_t)which, e, z);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float u = __builtin_fmaf(-c, z[i], th[i]);
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
                 if (kScaled) th[i] *= inv_scale;
             }
         }
-        gaussian4(a.k_cur, (uint32_t)which, e >> 2, z);
+        gaussian4(a.k_cur, (uint32_t)which, e, z);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             hp[i] += Fmt<C>::load(Fmt<C>::store(__builtin_fmaf(a.eps, z[i], th[i])));

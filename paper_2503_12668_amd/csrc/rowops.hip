@@ -119,41 +119,121 @@ zo2_status convert(const void* src, int sdt, float sscale, void* dst, int ddt, f
 }
 
 // ------------------------------------------------------------------ LayerNorm
-// One 256-thread workgroup per row; the row (<= 48 KB) stays in cache across the passes.
-template <typename C>
+// One 256-thread workgroup per row.  Rows of up to 12288 elements are read once and held in
+// registers for the mean, the centred variance and the output; longer rows are re-read from cache.
+template <typename C, bool CACHED>
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, const C* __restrict__ w, const C* __restrict__ b,
                                                         const C* __restrict__ w2, const C* __restrict__ b2, C* __restrict__ y,
                                                         int rows_first, int d, float eps) {
+    constexpr int kMaxVec = 12;                     // float4 per lane held in registers
     __shared__ float sh[4];
     const int r = blockIdx.x;
-    const float* xr = x + (size_t)r * d;
+    const float4* xr = reinterpret_cast<const float4*>(x + (size_t)r * d);
     const C* ww = r < rows_first ? w : w2;
     const C* bb = r < rows_first ? b : b2;
     const int nv = d >> 2;
+    float4 v[kMaxVec];
     float s = 0.f;
-    for (int i = threadIdx.x; i < nv; i += 256) {
-        const float4 v = reinterpret_cast<const float4*>(xr)[i];
-        s += (v.x + v.y) + (v.z + v.w);
+    if (CACHED) {
+#pragma unroll
+        for (int k = 0; k < kMaxVec; ++k) {
+            const int i = threadIdx.x + 256 * k;
+            v[k] = i < nv ? xr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < kMaxVec; ++k) s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+    } else {
+        for (int i = threadIdx.x; i < nv; i += 256) {
+            const float4 t = xr[i];
+            s += (t.x + t.y) + (t.z + t.w);
+        }
     }
     const float mean = block_sum(s, sh) / (float)d;
     float q = 0.f;
-    for (int i = threadIdx.x; i < nv; i += 256) {
-        const float4 v = reinterpret_cast<const float4*>(xr)[i];
-        const float a0 = v.x - mean, a1 = v.y - mean, a2 = v.z - mean, a3 = v.w - mean;
-        q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    if (CACHED) {
+#pragma unroll
+        for (int k = 0; k < kMaxVec; ++k) {
+            if (threadIdx.x + 256 * k < nv) {
+                const float a0 = v[k].x - mean, a1 = v[k].y - mean, a2 = v[k].z - mean, a3 = v[k].w - mean;
+                q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < nv; i += 256) {
+            const float4 t = xr[i];
+            const float a0 = t.x - mean, a1 = t.y - mean, a2 = t.z - mean, a3 = t.w - mean;
+            q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
     }
     const float var = block_sum(q, sh) / (float)d;
     const float rstd = 1.0f / sqrtf(var + eps);
     C* yr = y + (size_t)r * d;
-    for (int i = threadIdx.x; i < nv; i += 256) {
-        const float4 v = reinterpret_cast<const float4*>(xr)[i];
+    auto emit = [&](int i, const float4& t) {
         const Vec<C, 4> wv = load_vec<C, 4>(ww + 4 * i), bv = load_vec<C, 4>(bb + 4 * i);
         Vec<C, 4> o;
-        o.v[0] = Fmt<C>::store((v.x - mean) * rstd * Fmt<C>::load(wv.v[0]) + Fmt<C>::load(bv.v[0]));
-        o.v[1] = Fmt<C>::store((v.y - mean) * rstd * Fmt<C>::load(wv.v[1]) + Fmt<C>::load(bv.v[1]));
-        o.v[2] = Fmt<C>::store((v.z - mean) * rstd * Fmt<C>::load(wv.v[2]) + Fmt<C>::load(bv.v[2]));
-        o.v[3] = Fmt<C>::store((v.w - mean) * rstd * Fmt<C>::load(wv.v[3]) + Fmt<C>::load(bv.v[3]));
+        o.v[0] = Fmt<C>::store((t.x - mean) * rstd * Fmt<C>::load(wv.v[0]) + Fmt<C>::load(bv.v[0]));
+        o.v[1] = Fmt<C>::store((t.y - mean) * rstd * Fmt<C>::load(wv.v[1]) + Fmt<C>::load(bv.v[1]));
+        o.v[2] = Fmt<C>::store((t.z - mean) * rstd * Fmt<C>::load(wv.v[2]) + Fmt<C>::load(bv.v[2]));
+        o.v[3] = Fmt<C>::store((t.w - mean) * rstd * Fmt<C>::load(wv.v[3]) + Fmt<C>::load(bv.v[3]));
         store_vec<C, 4>(yr + 4 * i, o);
+    };
+    if (CACHED) {
+#pragma unroll
+        for (int k = 0; k < kMaxVec; ++k) {
+            const int i = threadIdx.x + 256 * k;
+            if (i < nv) emit(i, v[k]);
+        }
+    } else {
+        for (int i = threadIdx.x; i < nv; i += 256) emit(i, xr[i]);
+    }
+}
+
+// One wavefront per row (rows of up to 4 * 64 * KV elements): the row lives in the wave's registers and
+// both reductions are cross-lane only, so the four waves of a workgroup never wait for each other.
+template <typename C, int KV>
+__global__ __launch_bounds__(256) void layernorm_wave_kernel(const float* __restrict__ x, const C* __restrict__ w, const C* __restrict__ b,
+                                                             const C* __restrict__ w2, const C* __restrict__ b2, C* __restrict__ y,
+                                                             int rows, int rows_first, int d, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const float4* xr = reinterpret_cast<const float4*>(x + (size_t)r * d);
+    const C* ww = r < rows_first ? w : w2;
+    const C* bb = r < rows_first ? b : b2;
+    const int nv = d >> 2;
+    float4 v[KV];
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        const int i = lane + 64 * k;
+        v[k] = i < nv ? xr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < KV; ++k) s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        if (lane + 64 * k < nv) {
+            const float a0 = v[k].x - mean, a1 = v[k].y - mean, a2 = v[k].z - mean, a3 = v[k].w - mean;
+            q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+    }
+    const float var = wave_sum(q) / (float)d;
+    const float rstd = 1.0f / sqrtf(var + eps);
+    C* yr = y + (size_t)r * d;
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+        const int i = lane + 64 * k;
+        if (i < nv) {
+            const Vec<C, 4> wv = load_vec<C, 4>(ww + 4 * i), bv = load_vec<C, 4>(bb + 4 * i);
+            Vec<C, 4> o;
+            o.v[0] = Fmt<C>::store((v[k].x - mean) * rstd * Fmt<C>::load(wv.v[0]) + Fmt<C>::load(bv.v[0]));
+            o.v[1] = Fmt<C>::store((v[k].y - mean) * rstd * Fmt<C>::load(wv.v[1]) + Fmt<C>::load(bv.v[1]));
+            o.v[2] = Fmt<C>::store((v[k].z - mean) * rstd * Fmt<C>::load(wv.v[2]) + Fmt<C>::load(bv.v[2]));
+            o.v[3] = Fmt<C>::store((v[k].w - mean) * rstd * Fmt<C>::load(wv.v[3]) + Fmt<C>::load(bv.v[3]));
+            store_vec<C, 4>(yr + 4 * i, o);
+        }
     }
 }
 
@@ -164,8 +244,18 @@ zo2_status layernorm(int dtype, const float* x, const void* w, const void* b, co
     ZO2_OP_CHECK(x && w && b && y, ZO2_EINVAL, "layernorm: NULL buffer");
     ZO2_OP_CHECK(rows_first >= rows || (w2 && b2), ZO2_EINVAL, "layernorm: second gain / bias missing");
     ZO2_DISPATCH_COMPUTE(dtype, C, {
-        hipLaunchKernelGGL((layernorm_kernel<C>), dim3(rows), dim3(256), 0, st, x, (const C*)w, (const C*)b,
-                           (const C*)w2, (const C*)b2, (C*)y, rows_first, d, eps);
+        if (d <= 8 * 64 * 4)
+            hipLaunchKernelGGL((layernorm_wave_kernel<C, 8>), dim3((rows + 3) / 4), dim3(256), 0, st, x, (const C*)w, (const C*)b,
+                               (const C*)w2, (const C*)b2, (C*)y, rows, rows_first, d, eps);
+        else if (d <= 20 * 64 * 4)
+            hipLaunchKernelGGL((layernorm_wave_kernel<C, 20>), dim3((rows + 3) / 4), dim3(256), 0, st, x, (const C*)w, (const C*)b,
+                               (const C*)w2, (const C*)b2, (C*)y, rows, rows_first, d, eps);
+        else if (d <= 12 * 256 * 4)
+            hipLaunchKernelGGL((layernorm_kernel<C, true>), dim3(rows), dim3(256), 0, st, x, (const C*)w, (const C*)b,
+                               (const C*)w2, (const C*)b2, (C*)y, rows_first, d, eps);
+        else
+            hipLaunchKernelGGL((layernorm_kernel<C, false>), dim3(rows), dim3(256), 0, st, x, (const C*)w, (const C*)b,
+                               (const C*)w2, (const C*)b2, (C*)y, rows_first, d, eps);
     });
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
@@ -285,38 +375,43 @@ __global__ __launch_bounds__(256) void ce_combine_kernel(const float* __restrict
                                                          const float* __restrict__ label_logit, const int32_t* __restrict__ labels,
                                                          int rows, int n_parts, int64_t part_ld, int row0, int label_period,
                                                          float* __restrict__ row_loss) {
-    // 64 rows per block; the 4 wavefronts split the spans, so every load is 64 consecutive floats
-    __shared__ float sh_m[4][64];
-    __shared__ double sh_s[4][64];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int r = blockIdx.x * 64 + lane;
+    // 32 rows per block; 8 groups of lanes split the spans, so every load is 32 consecutive floats.
+    // Two sweeps (max, then sum) keep the loads independent of each other.
+    constexpr int kRows = 32, kGroups = 8;
+    __shared__ float sh_m[kGroups][kRows];
+    __shared__ double sh_s[kGroups][kRows];
+    const int lr = threadIdx.x & (kRows - 1), grp = threadIdx.x / kRows;
+    const int r = blockIdx.x * kRows + lr;
     const int rc = r < rows ? r : rows - 1;
+    const float* pm = part_max + rc;
+    const float* ps = part_sum + rc;
     float m = -INFINITY;
+#pragma unroll 4
+    for (int i = grp; i < n_parts; i += kGroups) m = fmaxf(m, pm[(size_t)i * part_ld]);
     double s = 0.0;
-    for (int i = w; i < n_parts; i += 4) {
-        const float mi = part_max[(size_t)i * part_ld + rc];
-        const float si = part_sum[(size_t)i * part_ld + rc];
-        if (mi == -INFINITY) continue;               // span entirely past the last column
-        if (mi > m) {
-            s = s * (double)expf(m - mi) + (double)si;      // expf(-inf) = 0 on the first span
-            m = mi;
-        } else {
-            s += (double)si * (double)expf(mi - m);
+    if (m != -INFINITY) {
+#pragma unroll 4
+        for (int i = grp; i < n_parts; i += kGroups) {
+            const float mi = pm[(size_t)i * part_ld];
+            s += (double)(ps[(size_t)i * part_ld] * expf(mi - m));     // a span past the last column has sum 0 and exp(-inf) = 0
         }
     }
-    sh_m[w][lane] = m;
-    sh_s[w][lane] = s;
+    sh_m[grp][lr] = m;
+    sh_s[grp][lr] = s;
     __syncthreads();
-    if (w != 0 || r >= rows) return;
+    if (grp != 0 || r >= rows) return;
     const int lab = labels[(row0 + r) % label_period];
     if (lab < 0) {
         row_loss[row0 + r] = 0.f;
         return;
     }
-    float mm = fmaxf(fmaxf(sh_m[0][lane], sh_m[1][lane]), fmaxf(sh_m[2][lane], sh_m[3][lane]));
+    float mm = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kGroups; ++k) mm = fmaxf(mm, sh_m[k][lr]);
     double ss = 0.0;
-    for (int k = 0; k < 4; ++k)
-        if (sh_m[k][lane] != -INFINITY) ss += sh_s[k][lane] * (double)expf(sh_m[k][lane] - mm);
+#pragma unroll
+    for (int k = 0; k < kGroups; ++k)
+        if (sh_m[k][lr] != -INFINITY) ss += sh_s[k][lr] * (double)expf(sh_m[k][lr] - mm);
     row_loss[row0 + r] = (float)(log(ss) + (double)mm - (double)label_logit[r]);
 }
 
@@ -325,7 +420,7 @@ zo2_status ce_combine(const float* part_max, const float* part_sum, const float*
     if (rows == 0) return ZO2_OK;
     ZO2_OP_CHECK(part_max && part_sum && label_logit && labels && row_loss && n_parts > 0 && label_period > 0 && part_ld >= rows,
                  ZO2_EINVAL, "ce_combine: bad argument");
-    hipLaunchKernelGGL(ce_combine_kernel, dim3((rows + 63) / 64), dim3(256), 0, st, part_max, part_sum, label_logit, labels, rows, n_parts,
+    hipLaunchKernelGGL(ce_combine_kernel, dim3((rows + 31) / 32), dim3(256), 0, st, part_max, part_sum, label_logit, labels, rows, n_parts,
                        part_ld, row0, label_period, row_loss);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;

@@ -75,7 +75,7 @@ def test_attention_against_float64(dt, n_seq, seq, H, dh, ws):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,d", [(5, 32), (64, 768), (9, 2048), (3, 12288)])
+@pytest.mark.parametrize("rows,d", [(5, 32), (64, 768), (9, 2048), (6, 5120), (3, 12288), (2, 16384)])
 def test_layernorm_two_parameter_sets(dt, rows, d):
     b = _b()
     g = torch.Generator().manual_seed(d)

@@ -78,8 +78,7 @@ def lib():
         "zo2_op_update_perturb": (i32, [vp, i32, vp, vp, i32, u32, u64, u64, i32, u64, f32, u64, f32, f32, vp]),
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
-        "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, vp, C.c_size_t, i32, i32, i32, i32, i64, vp]),
-        "zo2_op_attention_workspace_bytes": (C.c_size_t, [i32, i32, i32, i32, i32]),
+        "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i32, vp]),
         "zo2_op_layernorm": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
         "zo2_op_cross_entropy_rows": (i32, [vp, i64, vp, i32, i32, vp, vp]),
     }
@@ -94,7 +93,7 @@ def lib():
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
-            "zo2_op_attention", "zo2_op_attention_workspace_bytes", "zo2_op_layernorm", "zo2_op_cross_entropy_rows"]
+            "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows"]
 
 
 def _op_check(st):
@@ -176,15 +175,10 @@ def op_gemm(X, W, bias=None, residual=None, out_dtype=None, out_scale=1.0, relu=
     return Y
 
 
-def op_attention(q, k, v, n_seq, seq, n_heads, d_head, use_workspace=True, stream=None):
+def op_attention(q, k, v, n_seq, seq, n_heads, d_head, vector_kernel=False, stream=None):
     out = torch.empty_like(q)
-    ws, nb = None, 0
-    if use_workspace:
-        nb = lib().zo2_op_attention_workspace_bytes(_dt(q), n_seq, seq, n_heads, d_head)
-        if nb:
-            ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
-    _op_check(lib().zo2_op_attention(_dt(q), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ws), nb, n_seq, seq, n_heads, d_head,
-                                     q.stride(0), _stream_ptr(stream)))
+    _op_check(lib().zo2_op_attention(_dt(q), _ptr(q), _ptr(k), _ptr(v), _ptr(out), n_seq, seq, n_heads, d_head,
+                                     q.stride(0), 1 if vector_kernel else 0, _stream_ptr(stream)))
     return out
 
 

@@ -5,11 +5,9 @@
 namespace zo2 {
 
 // q, k, v, out: [n_seq * seq, ld] of `dtype`; head h occupies columns h*d_head..; q pre-scaled.
-// workspace: device scratch for the transposed values used by the MFMA path (bf16 / fp16 with
-// d_head 64 or 128); attention_workspace_bytes gives its size (0 = the path does not apply).
-// Without a large enough workspace the vector-ALU kernel runs instead.
-zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out, void* workspace, size_t workspace_bytes,
-                            int n_seq, int seq, int n_heads, int d_head, int64_t ld, hipStream_t st);
-size_t attention_workspace_bytes(int dtype, int n_seq, int seq, int n_heads, int d_head);
+// bf16 / fp16 with d_head 64 or 128 run on the matrix cores unless vector_kernel != 0; everything else
+// (and float32) runs on the float32 vector-ALU kernel.
+zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out, int n_seq, int seq, int n_heads,
+                            int d_head, int64_t ld, int vector_kernel, hipStream_t st);
 
 }  // namespace zo2

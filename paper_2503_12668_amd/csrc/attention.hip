@@ -105,24 +105,24 @@ __global__ __launch_bounds__(64) void attention_valu_kernel(const T* __restrict_
 
 // ---------------------------------------------------------------------------------------
 // MFMA kernel (bf16 / fp16, d_head 64 or 128).  One wavefront owns 32 queries and walks the
-// keys in tiles of 32; everything lives in registers, operands come straight from global
-// memory (L2) as 16-byte loads, no LDS.
+// keys in tiles of 32 staged through LDS.
 //
 //   S^T = K Q^T   (32 keys x 32 queries)   A operand: K rows, B operand: Q rows
-//   O^T += V^T P^T (d_head x 32 queries)   A operand: V^T rows (needs V transposed: `vt`),
+//   O^T += V^T P^T (d_head x 32 queries)   A operand: V^T rows, read out of the key-major V
+//                                           tile with the transposing LDS read,
 //                                           B operand: P^T taken directly from the S^T
 //                                           accumulator registers.
 // In the 32x32 accumulator layout a lane holds one query column and 16 key rows
 // rho = 8 (v/4) + 4 kh + v%4.  As a B operand of the second product a lane must supply 8
 // consecutive contraction slots 8 kh .. 8 kh + 7 per 16-slot step.  Both fit together if
 // accumulator row rho carries key pi(rho), pi swapping the bits "kh" and "v/4 & 1" inside each
-// 16-block: then registers v = 8 s .. 8 s + 7 are keys 16 s + 8 kh .. + 7, which is also a
-// single 16-byte run of a V^T row.  pi is applied for free when choosing which K row a lane
-// loads.
+// 16-block: then registers v = 8 s .. 8 s + 7 are keys 16 s + 8 kh .. + 7, the same run of keys
+// a lane holds of its V^T row.  pi is applied for free when choosing which K row a lane loads.
 // ---------------------------------------------------------------------------------------
 typedef __bf16 att_bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 att_f16x8 __attribute__((ext_vector_type(8)));
 typedef float att_f32x16 __attribute__((ext_vector_type(16)));
+typedef short att_i16x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct AttMfma;
 template <> struct AttMfma<bf16_t> {
@@ -136,26 +136,6 @@ template <> struct AttMfma<f16_t> {
     }
 };
 
-// v [n_seq * seq, ld] -> vt [n_seq][ld_cols = n_heads * d_head][seq_pad], zero beyond seq
-template <typename T>
-__global__ __launch_bounds__(256) void transpose_v_kernel(const T* __restrict__ v, T* __restrict__ vt, int seq, int seq_pad,
-                                                          int cols, int64_t ld) {
-    __shared__ T tile[32][33];
-    const int t0 = blockIdx.x * 32, c0 = blockIdx.y * 32, sq = blockIdx.z;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int t = t0 + ty + 8 * i, c = c0 + tx;
-        tile[ty + 8 * i][tx] = (t < seq && c < cols) ? v[((size_t)sq * seq + t) * ld + c] : Fmt<T>::store(0.f);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = c0 + ty + 8 * i, t = t0 + tx;
-        if (c < cols && t < seq_pad) vt[((size_t)sq * cols + c) * seq_pad + t] = tile[tx][ty + 8 * i];
-    }
-}
-
 // direct-to-LDS load of 16 bytes per lane (lane i lands at lds_base + 16 i)
 __device__ __forceinline__ void att_load_to_lds(const void* gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
@@ -164,16 +144,19 @@ __device__ __forceinline__ void att_load_to_lds(const void* gptr, uint32_t lds_b
 // One workgroup = 128 queries of one (sequence, head); wavefront w owns queries 32 w .. 32 w + 31.
 // Key tiles of 32 keys are brought into LDS once per workgroup (direct-to-LDS loads, two buffers,
 // one barrier per tile) and shared by the four wavefronts; a wavefront skips the tiles past its
-// diagonal.  K tile: 32 rows of d_head elements, 16-byte chunks XOR-swizzled by (row & 7).
-// V^T tile: d_head rows of 32 keys (64 bytes), chunks swizzled by ((row >> 1) & 3).
+// diagonal.  K and V tiles: 32 rows of d_head elements, 16-byte chunks XOR-swizzled by (row & 7).
+// The transposing 8-byte LDS read works on groups of 16 lanes: lane 4 j + g of a group supplies the
+// address of 4 consecutive elements, and lane 4 g + c receives element c of lanes g, 4 + g, 8 + g, 12 + g.
+// Pointing lane 4 j + g at V[key0 + j][m0 + 4 g ..] therefore hands lane i the keys key0 .. key0 + 3 of
+// column m0 + i: four consecutive contraction slots of its V^T row.
 template <typename T, int DH>
-__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vt,
-                                                                 T* __restrict__ out, int seq, int seq_pad, int cols, int64_t ld) {
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+                                                                 T* __restrict__ out, int seq, int64_t ld) {
     constexpr int KS = DH / 16;          // contraction steps of the first product
     constexpr int DT = DH / 32;          // 32-row tiles of O^T
     constexpr int KCH = DH / 8;          // 16-byte chunks per K row
-    constexpr int KTILE = 32 * DH * 2, VTILE = DH * 64, BUF = KTILE + VTILE;
-    constexpr int KINSTR = KTILE / 1024 / 4, VINSTR = VTILE / 1024 / 4;   // direct-to-LDS loads per wavefront per tile
+    constexpr int KTILE = 32 * DH * 2, BUF = 2 * KTILE;                   // K tile, then V tile
+    constexpr int KINSTR = KTILE / 1024 / 4;                              // direct-to-LDS loads per wavefront per tile and operand
     __shared__ __attribute__((aligned(1024))) char lds[2 * BUF];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -203,7 +186,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
     const int wg_last_q = min(blockIdx.x * 128 + 127, seq - 1);
     const int wg_last_tile = wg_last_q >> 5;
     const int my_last_tile = q0 >> 5;
-    const T* vt_head = vt + ((size_t)sq * cols + (size_t)head * DH) * seq_pad;
+    // transposing read: lane = 16 g16 + a; the group covers columns 16 (g16 & 1) .. + 15 and keys 8 (g16 >> 1) + 4 h + (a >> 2)
+    const int g16 = lane >> 4, a16 = lane & 15;
 
     auto issue_tile = [&](int tile, int buf) {
         const int j0 = tile * 32;
@@ -212,14 +196,9 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
             const int inst = wave * KINSTR + x;
             const int row = inst * (512 / DH) + lane / KCH;
             const int chunk = (lane % KCH) ^ (row & 7);
-            att_load_to_lds(k + base + (size_t)min(j0 + row, seq - 1) * ld + chunk * 8, lds0 + buf * BUF + inst * 1024);
-        }
-#pragma unroll
-        for (int x = 0; x < VINSTR; ++x) {                   // V^T rows: 16 rows of 64 bytes per instruction
-            const int inst = wave * VINSTR + x;
-            const int row = inst * 16 + (lane >> 2);
-            const int chunk = (lane & 3) ^ ((row >> 1) & 3);
-            att_load_to_lds(vt_head + (size_t)row * seq_pad + j0 + chunk * 8, lds0 + buf * BUF + KTILE + inst * 1024);
+            const size_t g = base + (size_t)min(j0 + row, seq - 1) * ld + chunk * 8;   // rows past the end repeat the last one (masked keys)
+            att_load_to_lds(k + g, lds0 + buf * BUF + inst * 1024);
+            att_load_to_lds(v + g, lds0 + buf * BUF + KTILE + inst * 1024);
         }
     };
     auto process_tile = [&](int tile, int buf) {
@@ -233,8 +212,16 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
         for (int d = 0; d < DT; ++d)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
-                const int row = d * 32 + r;
-                vf[d][s2] = *reinterpret_cast<const uint4*>(vb + row * 64 + (((2 * s2 + kh) ^ ((row >> 1) & 3)) * 16));
+                att_i16x4 half[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int key = 16 * s2 + 8 * (g16 >> 1) + 4 * h + (a16 >> 2);
+                    const int chunk = 4 * d + 2 * (g16 & 1) + ((a16 & 3) >> 1);
+                    const char* src = vb + key * (DH * 2) + ((chunk ^ (key & 7)) * 16) + 8 * (a16 & 1);
+                    half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) att_i16x4*)src);
+                }
+                vf[d][s2] = make_uint4(__builtin_bit_cast(uint2, half[0]).x, __builtin_bit_cast(uint2, half[0]).y,
+                                       __builtin_bit_cast(uint2, half[1]).x, __builtin_bit_cast(uint2, half[1]).y);
             }
         // ---- S^T = K Q^T
         att_f32x16 st;
@@ -306,21 +293,13 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
 }
 
 template <typename T>
-static zo2_status launch_mfma_att(const T* q, const T* k, const T* v, T* out, T* vt, int n_seq, int seq, int n_heads, int d_head,
+static zo2_status launch_mfma_att(const T* q, const T* k, const T* v, T* out, int n_seq, int seq, int n_heads, int d_head,
                                   int64_t ld, hipStream_t st) {
-    const int seq_pad = (seq + 31) / 32 * 32, cols = n_heads * d_head;
-    hipLaunchKernelGGL((transpose_v_kernel<T>), dim3(seq_pad / 32, (cols + 31) / 32, n_seq), dim3(256), 0, st, v, vt, seq, seq_pad, cols, ld);
-    ZO2_HIP_LAUNCH_CHECK();
     const dim3 grid((seq + 127) / 128, n_heads, n_seq), block(256);
-    if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, vt, out, seq, seq_pad, cols, ld);
-    else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, vt, out, seq, seq_pad, cols, ld);
+    if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, v, out, seq, ld);
+    else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, v, out, seq, ld);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
-}
-
-size_t attention_workspace_bytes(int dtype, int n_seq, int seq, int n_heads, int d_head) {
-    if (dtype == ZO2_F32 || !(d_head == 64 || d_head == 128)) return 0;
-    return (size_t)n_seq * n_heads * d_head * ((seq + 31) / 32 * 32) * 2;
 }
 
 template <typename T>
@@ -340,20 +319,18 @@ static zo2_status launch_valu(const T* q, const T* k, const T* v, T* out, int n_
     return ZO2_OK;
 }
 
-zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out, void* workspace, size_t workspace_bytes,
-                            int n_seq, int seq, int n_heads, int d_head, int64_t ld, hipStream_t st) {
+zo2_status attention_launch(int dtype, const void* q, const void* k, const void* v, void* out, int n_seq, int seq, int n_heads,
+                            int d_head, int64_t ld, int vector_kernel, hipStream_t st) {
     if (n_seq == 0 || seq == 0) return ZO2_OK;
     ZO2_OP_CHECK(n_seq > 0 && seq > 0 && n_heads > 0 && d_head > 0, ZO2_EINVAL, "attention: bad shape");
     ZO2_OP_CHECK(q && k && v && out, ZO2_EINVAL, "attention: NULL buffer");
     ZO2_OP_CHECK(ld >= (int64_t)n_heads * d_head && ld % 8 == 0, ZO2_EINVAL, "attention: bad leading dimension");
     ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535, ZO2_EINVAL, "attention: grid too large");
-    const size_t need = attention_workspace_bytes(dtype, n_seq, seq, n_heads, d_head);
-    if (need != 0 && workspace != nullptr && workspace_bytes >= need && ((uintptr_t)workspace & 15) == 0) {
+    if (!vector_kernel && dtype != ZO2_F32 && (d_head == 64 || d_head == 128)) {
+        ZO2_OP_CHECK((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0, ZO2_EINVAL, "attention: operands must be 16-byte aligned");
         if (dtype == ZO2_BF16)
-            return launch_mfma_att<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, (bf16_t*)workspace,
-                                           n_seq, seq, n_heads, d_head, ld, st);
-        return launch_mfma_att<f16_t>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, (f16_t*)out, (f16_t*)workspace,
-                                      n_seq, seq, n_heads, d_head, ld, st);
+            return launch_mfma_att<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, n_seq, seq, n_heads, d_head, ld, st);
+        return launch_mfma_att<f16_t>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, (f16_t*)out, n_seq, seq, n_heads, d_head, ld, st);
     }
     ZO2_DISPATCH_COMPUTE(dtype, T, {
         return launch_valu<T>((const T*)q, (const T*)k, (const T*)v, (T*)out, n_seq, seq, n_heads, d_head, ld, st);

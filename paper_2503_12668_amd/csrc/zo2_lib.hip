@@ -101,8 +101,7 @@ struct zo2_ctx {
     int64_t scratch_elems;
     char *fln_wp, *fln_wm;
     float* h;
-    char *x, *qb, *kb, *vb, *ctxb, *mid, *att_ws;
-    size_t att_ws_bytes;
+    char *x, *qb, *kb, *vb, *ctxb, *mid;
     float* logits;
     int logit_rows;                     // rows per sign per chunk
     bool fused_ce;                      // LM head writes cross-entropy partials instead of logits
@@ -437,12 +436,10 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     lrows = lrows / 128 * 128;
     if (lrows < 128) lrows = 128;
     if (lrows > (size_t)T) lrows = T;
-    const size_t att_ws = attention_workspace_bytes(g.compute_dtype, 2 * batch, seq, g.n_heads, g.d_model / g.n_heads);
     size_t act = 0;
     auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
     const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
                  o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
-                 o_aws = sz(att_ws),
                  o_logits = sz(fused_ce ? 0 : 2 * lrows * V * 4), o_rl = sz(rows2 * 4),
                  o_cpm = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cps = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cl = sz(fused_ce ? rows2 * 4 : 0), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
                  o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
@@ -493,7 +490,7 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     c->overlap_k1 = two_sets;
     char* a0 = base + off;
     c->h = (float*)(a0 + o_h); c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
-    c->mid = a0 + o_mid; c->att_ws = a0 + o_aws; c->att_ws_bytes = att_ws; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
+    c->mid = a0 + o_mid; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
     c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
     c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
     c->fused_ce = fused_ce; c->ce_parts = (int)ce_parts;
@@ -657,7 +654,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
             p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
         }
     OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, c->att_ws, c->att_ws_bytes, 2 * batch, seq, g.n_heads, dh, d, c->sc));
+    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, 0, c->sc));
     { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
     w = view(1);
     memset(&ga, 0, sizeof(ga));
@@ -1002,14 +999,9 @@ extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K
     return gemm_launch(a, dtype, as_stream(stream));
 }
 
-extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, void* workspace,
-                                       size_t workspace_bytes, int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head, int64_t ld,
-                                       void* stream) {
-    return attention_launch(dtype, q, k, v, out, workspace, workspace_bytes, n_seq, seq, n_heads, d_head, ld, as_stream(stream));
-}
-
-extern "C" size_t zo2_op_attention_workspace_bytes(int32_t dtype, int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head) {
-    return attention_workspace_bytes(dtype, n_seq, seq, n_heads, d_head);
+extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, int32_t n_seq,
+                                       int32_t seq, int32_t n_heads, int32_t d_head, int64_t ld, int32_t vector_kernel, void* stream) {
+    return attention_launch(dtype, q, k, v, out, n_seq, seq, n_heads, d_head, ld, vector_kernel, as_stream(stream));
 }
 
 extern "C" zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2, void* y,

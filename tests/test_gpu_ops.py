@@ -62,13 +62,13 @@ def _attention_ref(q, k, v, n_seq, seq, H, dh):
 @pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("n_seq,seq,H,dh", [(2, 11, 4, 8), (3, 64, 2, 64), (2, 130, 3, 32), (1, 257, 2, 128), (4, 1, 2, 16),
                                            (2, 256, 3, 64), (2, 23, 2, 64), (1, 300, 2, 128), (3, 33, 1, 128)])
-@pytest.mark.parametrize("ws", [True, False])
-def test_attention_against_float64(dt, n_seq, seq, H, dh, ws):
+@pytest.mark.parametrize("vector_kernel", [False, True])
+def test_attention_against_float64(dt, n_seq, seq, H, dh, vector_kernel):
     b = _b()
     g = torch.Generator().manual_seed(seq * 7 + dh)
     mk = lambda s: (torch.randn(n_seq * seq, H * dh, generator=g) * s).to(TD[dt])
     q, k, v = mk(0.3), mk(1.0), mk(1.0)
-    out = b.op_attention(q.cuda(), k.cuda(), v.cuda(), n_seq, seq, H, dh, use_workspace=ws)
+    out = b.op_attention(q.cuda(), k.cuda(), v.cuda(), n_seq, seq, H, dh, vector_kernel=vector_kernel)
     ref = _attention_ref(q, k, v, n_seq, seq, H, dh)
     tol = 2e-6 if dt == "f32" else 1.5e-2
     assert (out.double().cpu() - ref).abs().max() <= tol * max(1.0, ref.abs().max())

@@ -135,6 +135,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #ifdef ZO2_GEMM_EXP_TIMING
     unsigned long long* tlog = (unsigned long long*)a.p[GemmArgs::kMaxProblems - 1].residual;
     int tcount = 0;
+    unsigned long long wait_vm = 0, wait_lds = 0, wait_bar = 0;
 #define TSTAMP() do { if (blockIdx.x == 0 && threadIdx.x == 0 && tcount < 60) tlog[tcount++] = __builtin_amdgcn_s_memtime(); } while (0)
 #else
 #define TSTAMP() do { } while (0)
@@ -154,23 +155,31 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         uint4 fa[2][4], fb[2][4];
         // One "group" = the four MFMAs of X row-block i at k-step buffer `buf`, preceded by the two
         // LDS reads that fetch row-block i of both operands for the next k-step into buffer `nbuf`,
-        // and optionally two direct-to-LDS loads of a later k-slab.  A scheduling barrier after
-        // every group keeps memory instructions spread evenly under the MFMAs instead of bunched.
-        // (Issuing the reads one group earlier was tried: no gain.)
+        // and optionally two direct-to-LDS loads of a later k-slab.
+        // (Issuing the reads one group earlier, or the W fragments before the X fragments, was tried: no gain.)
         auto mgroup = [&](int i, int buf, int nbuf, bool do_read, const char* sa, const char* sb, bool do_dma, int dma_stage, int dma_k0, int dma_t) {
-            if (do_dma) {
-                const uint32_t so = dma_stage * kStageBytes;
-                load_to_lds(base_x + dma_k0, pa[dma_t], ld_a + so + dma_t * 1024);
-                load_to_lds(base_w + dma_k0, pb[dma_t], ld_b + so + dma_t * 1024);
-            }
+            // With one wavefront per SIMD every instruction takes an issue slot of this wavefront, and only about
+            // seven fit under one MFMA: the memory instructions are dealt out one piece per MFMA (scheduling
+            // barriers pin them there) instead of standing together between two groups.
+            const uint32_t so = dma_stage * kStageBytes;
+            acc[i][0] = Mfma32<T>::run(fb[buf][0], fa[buf][i], acc[i][0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_dma) load_to_lds(base_x + dma_k0, pa[dma_t], ld_a + so + dma_t * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[i][1] = Mfma32<T>::run(fb[buf][1], fa[buf][i], acc[i][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_dma) load_to_lds(base_w + dma_k0, pb[dma_t], ld_b + so + dma_t * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[i][2] = Mfma32<T>::run(fb[buf][2], fa[buf][i], acc[i][2]);
+            __builtin_amdgcn_sched_barrier(0);
 #ifndef ZO2_GEMM_EXP_NOREAD
             if (do_read) {
                 fa[nbuf][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
                 fb[nbuf][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
             }
 #endif
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(fb[buf][j], fa[buf][i], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[i][3] = Mfma32<T>::run(fb[buf][3], fa[buf][i], acc[i][3]);
             __builtin_amdgcn_sched_barrier(0);
         };
 
@@ -211,8 +220,19 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[3], base_b + koff[3], false, 0, 0, 0);
             // one barrier per slab: publishes slab kt+1 (every wavefront waited for its own loads)
             // and retires stage cur (every wavefront has its last fragments in registers)
+#ifdef ZO2_GEMM_EXP_TIMING
+            const unsigned long long w0 = __builtin_amdgcn_s_memtime();
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const unsigned long long w1 = __builtin_amdgcn_s_memtime();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            const unsigned long long w2 = __builtin_amdgcn_s_memtime();
+            __syncthreads();
+            const unsigned long long w3 = __builtin_amdgcn_s_memtime();
+            wait_vm += w1 - w0; wait_lds += w2 - w1; wait_bar += w3 - w2;
+#else
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __syncthreads();
+#endif
             const char* next_a = smem + (cur ^ 1) * kStageBytes + fr_a + koff[0];
             const char* next_b = smem + (cur ^ 1) * kStageBytes + fr_b + koff[0];
 #pragma unroll
@@ -232,6 +252,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         if (nk > 1) slab_iter(nk - 2, std::true_type{}, std::false_type{});
         slab_iter(nk - 1, std::false_type{}, std::false_type{});
         TSTAMP();
+#ifdef ZO2_GEMM_EXP_TIMING
+        if (blockIdx.x == 0 && threadIdx.x == 0) { tlog[60] = wait_vm; tlog[61] = wait_lds; tlog[62] = wait_bar; }
+#endif
 
         // Both stages are free now (all fragment reads are behind the last barrier).  Start the
         // next tile's k-slab 0 into stage 0 so that its latency hides under this tile's epilogue,

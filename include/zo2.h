@@ -4,8 +4,8 @@
  *
  * Two layers of entry points:
  *
- *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_flush /
- *      zo2_sync_to_host / zo2_destroy.  One call of zo2_step is one iteration of the paper's
+ *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_flush / zo2_eval /
+ *      zo2_get_pending / zo2_set_pending / zo2_sync_to_host / zo2_destroy.  One call of zo2_step is one iteration of the paper's
  *      Alg. 2: for every module (embedding, decoder blocks, LM head) apply the update left
  *      pending by the previous iteration, perturb by +eps z and -eps z, run both forwards,
  *      and form the projected gradient g (Eq. 2).  Blocks that do not fit the HBM budget
@@ -134,6 +134,22 @@ zo2_status zo2_step(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, 
 /* Apply the pending update to every parameter now (Alg. 2 leaves the last g unapplied). */
 zo2_status zo2_flush(zo2_ctx* ctx);
 
+/* Loss of the current parameters on a batch with a single, unperturbed forward pass over the same
+ * block walk as zo2_step (the evaluation regime of the paper's Limitation section: one forward per
+ * block, so a streamed block's copy time is hidden by half the compute).  A pending update is applied
+ * to each module on the way, exactly as zo2_step would (Sec. 5.4), so *loss = L(theta_up_to_date)
+ * and nothing is pending afterwards; training continued after the call gives the same results as
+ * without it.  Streamed blocks are written back only if an update was pending.  tokens, labels as
+ * for zo2_step.  *loss is written on ZO2_OK (it may be non-finite). */
+zo2_status zo2_eval(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq, float* loss);
+
+/* The deferred update as data (Sec. 5.4): *has_pending, and if set the seed whose z it uses and
+ * *step = eta * g.  With the parameters in the host buffers (zo2_sync_to_host) this is the complete
+ * training state: a context created from those buffers and given the same triple with
+ * zo2_set_pending continues bit-identically.  zo2_set_pending replaces whatever was pending. */
+zo2_status zo2_get_pending(zo2_ctx* ctx, int32_t* has_pending, uint64_t* seed, float* step);
+zo2_status zo2_set_pending(zo2_ctx* ctx, int32_t has_pending, uint64_t seed, float step);
+
 /* Copy device-resident parameters (embeddings, final LayerNorm, LM head, and the blocks when
  * all are resident) back into the caller's host buffers.  Does not flush. */
 zo2_status zo2_sync_to_host(zo2_ctx* ctx);
@@ -189,7 +205,8 @@ zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint6
  *   w_plus  = store_compute( fma(+eps, z, theta') ),  w_minus = store_compute( fma(-eps, z, theta') )
  * theta: n elements of wire dtype, element i being element e0 + i of the tensor; e0 and
  * every pointer must be aligned to 8 elements.  theta is rewritten in place; w_plus /
- * w_minus (compute dtype, n elements) may both be NULL for an update-only pass.
+ * w_minus (compute dtype, n elements) may both be NULL for an update-only pass, or w_minus
+ * alone for a pass that writes only w_plus; with eps = 0 no z is drawn and w_plus = theta'.
  * scale: the tensor's wire scale (1 unless an 8-bit format uses one). */
 zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
                                  uint32_t tensor_id, uint64_t e0, uint64_t n,

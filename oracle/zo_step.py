@@ -171,3 +171,11 @@ class Zo2Blockwise:
         for names in opt_model.modules(self.cfg):
             self._update_module(names)
         self.pending = None
+
+    def eval_loss(self, tokens, labels):
+        """L(theta; B) with one unperturbed forward (the single-forward evaluation regime of the paper's
+        Limitation section).  The deferred update (Sec. 5.4) belongs to theta already, so it is applied
+        first; the forward then sees the parameters in the compute format, as the dual forward does."""
+        self.flush()
+        W = {n: _store(a, self.compute) for n, a in self.P.items()}
+        return np.float32(opt_model.loss(self.cfg, W, tokens, labels))

@@ -64,6 +64,9 @@ def lib():
         "zo2_set_resident_budget": (i32, [vp, C.c_size_t]),
         "zo2_step": (i32, [vp, vp, vp, i32, i32, u64, f32, f32, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]),
         "zo2_flush": (i32, [vp]),
+        "zo2_eval": (i32, [vp, vp, vp, i32, i32, C.POINTER(f32)]),
+        "zo2_get_pending": (i32, [vp, C.POINTER(i32), C.POINTER(u64), C.POINTER(f32)]),
+        "zo2_set_pending": (i32, [vp, i32, u64, f32]),
         "zo2_sync_to_host": (i32, [vp]),
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
@@ -90,7 +93,7 @@ def lib():
     return L
 
 
-EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush",
+EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows"]
@@ -309,6 +312,23 @@ class Zo2Context:
 
     def flush(self):
         self._check(lib().zo2_flush(self.handle))
+
+    def eval(self, tokens, labels):
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        lab = np.ascontiguousarray(labels, dtype=np.int32)
+        assert tok.shape == lab.shape and tok.ndim == 2
+        loss = C.c_float()
+        self._check(lib().zo2_eval(self.handle, tok.ctypes.data, lab.ctypes.data, tok.shape[0], tok.shape[1], C.byref(loss)))
+        return np.float32(loss.value)
+
+    def pending(self):
+        """(has_pending, seed, eta * g) of the deferred update."""
+        has, seed, step = C.c_int32(), C.c_uint64(), C.c_float()
+        self._check(lib().zo2_get_pending(self.handle, C.byref(has), C.byref(seed), C.byref(step)))
+        return bool(has.value), int(seed.value), np.float32(step.value)
+
+    def set_pending(self, has_pending, seed=0, step=0.0):
+        self._check(lib().zo2_set_pending(self.handle, 1 if has_pending else 0, int(seed), float(step)))
 
     def sync_to_host(self):
         self._check(lib().zo2_sync_to_host(self.handle))

@@ -18,7 +18,7 @@ struct K1Args {
     static constexpr int kMaxSeg = 16;
     void* theta;          // wire dtype; rewritten in place when an update is pending
     void* w_plus;         // compute dtype, addressed as w_plus[off - w_off0 + i]
-    void* w_minus;
+    void* w_minus;        // may be nullptr: only W+ is written (single forward)
     int64_t w_off0;       // element offset (in theta's numbering) that maps to w_plus[0]
     int32_t nseg;
     uint32_t total_chunks;

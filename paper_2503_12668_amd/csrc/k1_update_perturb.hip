@@ -44,12 +44,17 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
         }
     }
     if (PERTURB) {
-        float z[kPerLane];
-        gaussian8(a.k_cur, tensor_id, q, z);
+        if (eps == 0.f) {                      // evaluation: W+ = theta' in the compute format, no draw needed
 #pragma unroll
-        for (int j = 0; j < kPerLane; ++j) {
-            p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
-            m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
+            for (int j = 0; j < kPerLane; ++j) p.v[j] = m.v[j] = Fmt<C>::store(th[j]);
+        } else {
+            float z[kPerLane];
+            gaussian8(a.k_cur, tensor_id, q, z);
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
+                m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
+            }
         }
     }
 }
@@ -65,7 +70,8 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
     const uint64_t chunk0 = (uint64_t)(blockIdx.x - a.first_chunk[s]) * kChunk;
     W* __restrict__ theta = reinterpret_cast<W*>(a.theta) + sg.off;
     C* __restrict__ wp = PERTURB ? reinterpret_cast<C*>(a.w_plus) + (sg.off - a.w_off0) : nullptr;
-    C* __restrict__ wm = PERTURB ? reinterpret_cast<C*>(a.w_minus) + (sg.off - a.w_off0) : nullptr;
+    const bool has_m = PERTURB && a.w_minus != nullptr;            // a single forward needs W+ only
+    C* __restrict__ wm = has_m ? reinterpret_cast<C*>(a.w_minus) + (sg.off - a.w_off0) : nullptr;
     const float c = UPDATE ? (a.c_ptr ? *a.c_ptr : a.c_imm) : 0.f;
     const float eps = a.eps;
     const float scale = sg.scale, inv_scale = 1.0f / sg.scale;
@@ -86,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
             if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i, p);
-                store_vec<C, kPerLane>(wm + i, m);
+                if (has_m) store_vec<C, kPerLane>(wm + i, m);
             }
         }
         return;
@@ -110,14 +116,14 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
             if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i0, p);
-                store_vec<C, kPerLane>(wm + i0, m);
+                if (has_m) store_vec<C, kPerLane>(wm + i0, m);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j)
                 if (j < valid) {
                     if (UPDATE) theta[i0 + j] = tv.v[j];
-                    if (PERTURB) { wp[i0 + j] = p.v[j]; wm[i0 + j] = m.v[j]; }
+                    if (PERTURB) { wp[i0 + j] = p.v[j]; if (has_m) wm[i0 + j] = m.v[j]; }
                 }
         }
     }
@@ -151,7 +157,7 @@ zo2_status k1_launch(K1Args& a, int wire_dtype, int compute_dtype, bool update, 
     a.total_chunks = chunks;
     if (chunks == 0 || (!update && !perturb)) return ZO2_OK;
     ZO2_OP_CHECK(a.theta != nullptr, ZO2_EINVAL, "k1: theta is NULL");
-    ZO2_OP_CHECK(!perturb || (a.w_plus && a.w_minus), ZO2_EINVAL, "k1: W+/W- missing");
+    ZO2_OP_CHECK(!perturb || a.w_plus, ZO2_EINVAL, "k1: W+ missing");
     ZO2_DISPATCH_WIRE(wire_dtype, W, {
         ZO2_DISPATCH_COMPUTE(compute_dtype, C, { return launch_wc<W, C>(a, update, perturb, st); });
     });

@@ -18,6 +18,7 @@ struct EmbedArgs {
     float* h;                // out: float32 [2 T, d]; rows 0..T-1 the "+" stream, T..2T-1 the "-" stream
     int32_t T, seq, d, pos_offset;
     float eps, scale_tok, scale_pos;
+    int32_t single;          // 1: only the "+" rows are produced (single forward; eps is 0 then)
     const float* c_ptr;      // device scalar eta_prev * g_prev
     PhiloxKeys k_prev, k_cur;
 };
@@ -29,8 +30,9 @@ zo2_status cross_entropy_rows(const float* logits, int64_t ld, const int32_t* la
 // span-major (max, sum exp) partials written by the LM-head kernel's cross-entropy mode -> row_loss[row0 + r]
 zo2_status ce_combine(const float* part_max, const float* part_sum, const float* label_logit, const int32_t* labels, int rows,
                       int n_parts, int64_t part_ld, int row0, int label_period, float* row_loss, hipStream_t st);
-// result[0..3] = l+, l-, g, number of counted labels; *c_pending = lr * g
-zo2_status loss_epilogue(const float* row_loss, const int32_t* labels, int T, float eps, float lr, float* result,
+// result[0..3] = l+, l-, g, number of counted labels; *c_pending = lr * g.  ns = 1 (single forward): only rows 0..T-1
+// exist, result = (l, l, 0, count) and c_pending is left alone
+zo2_status loss_epilogue(const float* row_loss, const int32_t* labels, int T, float eps, float lr, int ns, float* result,
                          float* c_pending, hipStream_t st);
 
 }  // namespace zo2

@@ -297,6 +297,11 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
                 if (kScaled) th[i] *= inv_scale;
             }
         }
+        if (a.single) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hp[i] += Fmt<C>::load(Fmt<C>::store(th[i]));
+            continue;
+        }
         gaussian4(a.k_cur, (uint32_t)which, e, z);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -305,8 +310,9 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
         }
     }
     float* op = a.h + (size_t)t * a.d + j;
-    float* om = a.h + ((size_t)a.T + t) * a.d + j;
     *reinterpret_cast<float4*>(op) = make_float4(hp[0], hp[1], hp[2], hp[3]);
+    if (a.single) return;
+    float* om = a.h + ((size_t)a.T + t) * a.d + j;
     *reinterpret_cast<float4*>(om) = make_float4(hm[0], hm[1], hm[2], hm[3]);
 }
 
@@ -430,13 +436,14 @@ zo2_status ce_combine(const float* part_max, const float* part_sum, const float*
 // l+ = mean of row_loss[0..T) over non-ignored labels, l- of row_loss[T..2T);
 // g = (l+ - l-) / (2 eps); the pending step c = lr * g stays in device memory.
 __global__ __launch_bounds__(256) void loss_epilogue_kernel(const float* __restrict__ row_loss, const int32_t* __restrict__ labels,
-                                                            int T, float eps, float lr, float* __restrict__ result, float* __restrict__ c_pending) {
+                                                            int T, float eps, float lr, int ns, float* __restrict__ result,
+                                                            float* __restrict__ c_pending) {
     __shared__ double shd[4];
     double sp = 0.0, sm = 0.0, cnt = 0.0;
     for (int i = threadIdx.x; i < T; i += 256) {
         if (labels[i] >= 0) {
             sp += (double)row_loss[i];
-            sm += (double)row_loss[T + i];
+            if (ns == 2) sm += (double)row_loss[T + i];
             cnt += 1.0;
         }
     }
@@ -444,19 +451,19 @@ __global__ __launch_bounds__(256) void loss_epilogue_kernel(const float* __restr
     sm = block_sum(sm, shd);
     cnt = block_sum(cnt, shd);
     if (threadIdx.x == 0) {
-        const float lp = (float)(sp / cnt), lm = (float)(sm / cnt);
-        const float g = (lp - lm) / (2.0f * eps);
+        const float lp = (float)(sp / cnt), lm = ns == 2 ? (float)(sm / cnt) : lp;
+        const float g = ns == 2 ? (lp - lm) / (2.0f * eps) : 0.f;
         result[0] = lp;
         result[1] = lm;
         result[2] = g;
         result[3] = (float)cnt;
-        *c_pending = lr * g;
+        if (ns == 2) *c_pending = lr * g;
     }
 }
 
-zo2_status loss_epilogue(const float* row_loss, const int32_t* labels, int T, float eps, float lr, float* result,
+zo2_status loss_epilogue(const float* row_loss, const int32_t* labels, int T, float eps, float lr, int ns, float* result,
                          float* c_pending, hipStream_t st) {
-    hipLaunchKernelGGL(loss_epilogue_kernel, dim3(1), dim3(256), 0, st, row_loss, labels, T, eps, lr, result, c_pending);
+    hipLaunchKernelGGL(loss_epilogue_kernel, dim3(1), dim3(256), 0, st, row_loss, labels, T, eps, lr, ns, result, c_pending);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
 }

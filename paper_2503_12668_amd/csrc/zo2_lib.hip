@@ -105,6 +105,7 @@ struct zo2_ctx {
     float* logits;
     int logit_rows;                     // rows per sign per chunk
     bool fused_ce;                      // LM head writes cross-entropy partials instead of logits
+    int ns;                              // perturbation streams of the pass in progress: 2 (step) or 1 (evaluation)
     float *ce_pmax, *ce_psum, *ce_lab;  // [4 ceil(V/256), 2T] x 2 and [2T]
     int ce_parts;
     float* row_loss;
@@ -286,6 +287,7 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
         if (!w->block_bucket[l]) { set_op_error("zo2_init: block_bucket[%d] is NULL", l); return ZO2_EINVAL; }
 
     zo2_ctx* c = new (std::nothrow) zo2_ctx();
+    if (c) c->ns = 2;
     if (!c) { set_op_error("zo2_init: out of host memory"); return ZO2_ENOMEM; }
     c->cfg = *cfg;
     c->dev = *dev;
@@ -589,7 +591,7 @@ static zo2_status k1_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, bo
     if (!st) st = c->sc;
     K1Args a;
     k1_common(c, a, seed, eps);
-    a.theta = theta; a.w_plus = wp; a.w_minus = wm; a.w_off0 = 0; a.nseg = 1;
+    a.theta = theta; a.w_plus = wp; a.w_minus = c->ns == 2 ? wm : nullptr; a.w_off0 = 0; a.nseg = 1;
     a.seg[0].off = 0; a.seg[0].e0 = 0; a.seg[0].n = (uint64_t)n; a.seg[0].tensor_id = tid; a.seg[0].scale = c->scales[tid];
     OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, st));
     return ZO2_OK;
@@ -601,7 +603,7 @@ static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool
     if (!st) st = c->sc;
     K1Args a;
     k1_common(c, a, seed, eps);
-    a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->wm; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
+    a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->ns == 2 ? c->wm : nullptr; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
     for (int k = t0; k < t1; ++k) {
         K1Seg& s = a.seg[k - t0];
         s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
@@ -626,6 +628,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     const size_t cs = c->csz;
     const size_t half_d = (size_t)T * d * cs, half_f = (size_t)T * f * cs;
     const bool f32 = dt == ZO2_F32;
+    const int ns = c->ns;                 // 2: both perturbation streams (rows 0..T-1 and T..2T-1); 1: a single forward
     auto phase = [&](int p) -> zo2_status {
         if (k1_enqueued) return ZO2_OK;
         if (c->phased) return k1_block(c, l, bucket, kPhase[p], kPhase[p + 1], true, seed, eps);
@@ -639,11 +642,11 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
     if (!c->phased && k1_done && !k1_enqueued) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     PhaseView w = view(0);
-    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, ns * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
-    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = f32; ga.nprob = 6;
+    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = f32; ga.nprob = 3 * ns;
     char* outs[3] = {c->qb, c->kb, c->vb};
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < ns; ++s)
         for (int t = 0; t < 3; ++t) {
             GemmProblem& p = ga.p[s * 3 + t];
             p.X = c->x + s * half_d;
@@ -654,12 +657,12 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
             p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
         }
     OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, 0, c->sc));
+    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, ns * batch, seq, g.n_heads, dh, d, 0, c->sc));
     { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
     w = view(1);
     memset(&ga, 0, sizeof(ga));
-    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
-    for (int s = 0; s < 2; ++s) {
+    ga.M = T; ga.N = d; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;
+    for (int s = 0; s < ns; ++s) {
         GemmProblem& p = ga.p[s];
         p.X = c->ctxb + s * half_d; p.W = s ? w.M(8) : w.P(8); p.bias = s ? w.M(9) : w.P(9);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
@@ -669,10 +672,10 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     // ---- FFN half: h += FC2(ReLU(FC1(LN2(h))))
     { zo2_status s = phase(2); if (s != ZO2_OK) return s; }
     w = view(2);
-    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(10), w.P(11), w.M(10), w.M(11), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(10), w.P(11), w.M(10), w.M(11), c->x, ns * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
-    ga.M = T; ga.N = f; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = f; ga.relu = 1; ga.out_f32 = f32; ga.nprob = 2;
-    for (int s = 0; s < 2; ++s) {
+    ga.M = T; ga.N = f; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = f; ga.relu = 1; ga.out_f32 = f32; ga.nprob = ns;
+    for (int s = 0; s < ns; ++s) {
         GemmProblem& p = ga.p[s];
         p.X = c->x + s * half_d; p.W = s ? w.M(12) : w.P(12); p.bias = s ? w.M(13) : w.P(13);
         p.residual = nullptr; p.Y = c->mid + s * half_f; p.out_scale = 1.0f;
@@ -682,8 +685,8 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     if (c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     w = view(3);
     memset(&ga, 0, sizeof(ga));
-    ga.M = T; ga.N = d; ga.K = f; ga.ldx = f; ga.ldw = f; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
-    for (int s = 0; s < 2; ++s) {
+    ga.M = T; ga.N = d; ga.K = f; ga.ldx = f; ga.ldw = f; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;
+    for (int s = 0; s < ns; ++s) {
         GemmProblem& p = ga.p[s];
         p.X = c->mid + s * half_f; p.W = s ? w.M(14) : w.P(14); p.bias = s ? w.M(15) : w.P(15);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
@@ -724,20 +727,19 @@ static zo2_status enqueue_offload(zo2_ctx* c, int l, bool changed) {
     return ZO2_OK;
 }
 
-// ---------------------------------------------------------------------------------- step
-extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
-                               uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* gout) {
-    if (!c) return ZO2_EINVAL;
-    if (c->dead) return ZO2_ESTATE;
+// ---------------------------------------------------------------------------------- one pass over the model
+// ns = 2: Alg. 2's iteration (update, perturb both ways, dual forward, g).  ns = 1: the same walk with a
+// single unperturbed forward (evaluation): the pending update is still applied on the way, W+ = theta'.
+static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                             uint64_t seed, float eps, float lr, int ns) {
     const zo2_config& g = c->cfg;
-    if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step: NULL argument");
-    if (batch <= 0 || seq <= 0 || seq > g.max_pos) return fail(c, ZO2_EINVAL, "zo2_step: batch %d, seq %d (max_pos %d)", batch, seq, g.max_pos);
-    if ((int64_t)batch * seq > (1 << 24)) return fail(c, ZO2_EINVAL, "zo2_step: too many tokens");
-    if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step: eps must be non-zero and finite, lr finite");
+    if (batch <= 0 || seq <= 0 || seq > g.max_pos) return fail(c, ZO2_EINVAL, "%s: batch %d, seq %d (max_pos %d)", who, batch, seq, g.max_pos);
+    if ((int64_t)batch * seq > (1 << 24)) return fail(c, ZO2_EINVAL, "%s: too many tokens", who);
+    c->ns = ns;
     const int T = batch * seq;
     for (int i = 0; i < T; ++i) {
-        if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, ZO2_EINVAL, "zo2_step: token %d at %d outside [0, %d)", tokens[i], i, g.vocab);
-        if (labels[i] != -100 && (labels[i] < 0 || labels[i] >= g.vocab)) return fail(c, ZO2_EINVAL, "zo2_step: label %d at %d invalid", labels[i], i);
+        if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, ZO2_EINVAL, "%s: token %d at %d outside [0, %d)", who, tokens[i], i, g.vocab);
+        if (labels[i] != -100 && (labels[i] < 0 || labels[i] >= g.vocab)) return fail(c, ZO2_EINVAL, "%s: label %d at %d invalid", who, labels[i], i);
     }
     if (!c->planned || c->need_plan || c->plan_T != T || c->plan_seq != seq) {
         zo2_status s = plan(c, T, batch, seq);
@@ -767,7 +769,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     EmbedArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.tok_emb = c->d_tok; ea.pos_emb = c->d_pos; ea.tokens = c->d_tokens; ea.h = c->h;
-    ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps;
+    ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps; ea.single = ns == 1;
     ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = c->d_state;
     ea.k_prev = philox_keys(c->seed_prev); ea.k_cur = philox_keys(seed);
     OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
@@ -816,7 +818,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     {
         K1Args a;
         k1_common(c, a, seed, eps);
-        a.theta = c->d_fln; a.w_plus = c->fln_wp; a.w_minus = c->fln_wm; a.w_off0 = 0; a.nseg = 2;
+        a.theta = c->d_fln; a.w_plus = c->fln_wp; a.w_minus = ns == 2 ? c->fln_wm : nullptr; a.w_off0 = 0; a.nseg = 2;
         for (int k = 0; k < 2; ++k) {
             a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)d;
             a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
@@ -824,7 +826,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, dt, upd, true, c->sc));
     }
     const size_t boff = (size_t)c->fln_off_b * c->csz;
-    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, ns * T, T, d, g.ln_eps, c->sc));
     {
         const int sb = g.n_layers & 1;
         c->wp = c->wps[sb];
@@ -847,8 +849,8 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
         // logits are never written: the GEMM epilogue reduces each 64-column span to (max, sum exp) and picks the label's logit
         GemmArgs ga;
         memset(&ga, 0, sizeof(ga));
-        ga.M = T; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2; ga.ce_mode = 1; ga.part_ld = 2 * (int64_t)T;
-        for (int s = 0; s < 2; ++s) {
+        ga.M = T; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns; ga.ce_mode = 1; ga.part_ld = 2 * (int64_t)T;
+        for (int s = 0; s < ns; ++s) {
             GemmProblem& p = ga.p[s];
             p.X = c->x + (size_t)s * T * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr; p.Y = nullptr;
             p.out_scale = 1.0f; p.labels = c->d_labels;
@@ -856,25 +858,25 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
             p.label_logit = c->ce_lab + (size_t)s * T;
         }
         OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-        OPK(c, ZO2_KC_CE, ce_combine(c->ce_pmax, c->ce_psum, c->ce_lab, c->d_labels, 2 * T, c->ce_parts, 2 * (int64_t)T, 0, T, c->row_loss, c->sc));
+        OPK(c, ZO2_KC_CE, ce_combine(c->ce_pmax, c->ce_psum, c->ce_lab, c->d_labels, ns * T, c->ce_parts, 2 * (int64_t)T, 0, T, c->row_loss, c->sc));
     } else {
     const int R = c->logit_rows;
     for (int r0 = 0; r0 < T; r0 += R) {
         const int rows = std::min(R, T - r0);
         GemmArgs ga;
         memset(&ga, 0, sizeof(ga));
-        ga.M = rows; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = 2;
-        for (int s = 0; s < 2; ++s) {
+        ga.M = rows; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;
+        for (int s = 0; s < ns; ++s) {
             GemmProblem& p = ga.p[s];
             p.X = c->x + ((size_t)s * T + r0) * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr;
             p.Y = c->logits + (size_t)s * R * g.vocab; p.out_scale = 1.0f;
         }
         OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-        for (int s = 0; s < 2; ++s)
+        for (int s = 0; s < ns; ++s)
             OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
     }
     }
-    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, c->d_state + 4, c->d_state, c->sc));
+    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, c->d_state, c->sc));
     HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
     if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
@@ -891,15 +893,74 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     if (c->stat_u) hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
     if (c->stat_o) hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
 
+    if (ns == 1) {
+        c->has_pending = false;   // the pending update has been applied to every module on the way
+        return ZO2_OK;
+    }
     c->has_pending = true;
     c->seed_prev = seed;
-    *loss_plus = c->h_result[0];
-    *loss_minus = c->h_result[1];
-    *gout = c->h_result[2];
     if (!isfinite(c->h_result[0]) || !isfinite(c->h_result[1]) || !isfinite(c->h_result[2])) {
         c->has_pending = false;   // a non-finite g must never reach the parameters: this iteration's update is dropped
-        return fail(c, ZO2_ENONFINITE, "zo2_step: non-finite loss (l+ %g, l- %g)", (double)c->h_result[0], (double)c->h_result[1]);
+        return fail(c, ZO2_ENONFINITE, "%s: non-finite loss (l+ %g, l- %g)", who, (double)c->h_result[0], (double)c->h_result[1]);
     }
+    return ZO2_OK;
+}
+
+// ---------------------------------------------------------------------------------- step
+extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                               uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* gout) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step: NULL argument");
+    if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step: eps must be non-zero and finite, lr finite");
+    const zo2_status s = model_pass(c, "zo2_step", tokens, labels, batch, seq, seed, eps, lr, 2);
+    if (s == ZO2_OK || s == ZO2_ENONFINITE) {
+        *loss_plus = c->h_result[0];
+        *loss_minus = c->h_result[1];
+        *gout = c->h_result[2];
+    }
+    return s;
+}
+
+// ---------------------------------------------------------------------------------- evaluation (single forward)
+extern "C" zo2_status zo2_eval(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq, float* loss) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!tokens || !labels || !loss) return fail(c, ZO2_EINVAL, "zo2_eval: NULL argument");
+    const zo2_status s = model_pass(c, "zo2_eval", tokens, labels, batch, seq, 0, 0.f, 0.f, 1);
+    if (s == ZO2_OK) *loss = c->h_result[0];
+    return s;
+}
+
+// ---------------------------------------------------------------------------------- the deferred update as data
+// What Sec. 5.4 carries from one iteration to the next: (seed, c = eta * g).  Together with the parameters
+// (zo2_sync_to_host) this is the whole training state, so it is what a checkpoint has to hold.
+extern "C" zo2_status zo2_get_pending(zo2_ctx* c, int32_t* has_pending, uint64_t* seed, float* step) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!has_pending || !seed || !step) return fail(c, ZO2_EINVAL, "zo2_get_pending: NULL argument");
+    *has_pending = c->has_pending ? 1 : 0;
+    *seed = c->has_pending ? c->seed_prev : 0;
+    *step = 0.f;
+    if (c->has_pending) {
+        HIPCHK(c, hipMemcpyAsync(c->h_result + 8, c->d_state, sizeof(float), hipMemcpyDeviceToHost, c->sc));
+        HIPCHK(c, hipStreamSynchronize(c->sc));
+        *step = c->h_result[8];
+    }
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_set_pending(zo2_ctx* c, int32_t has_pending, uint64_t seed, float step) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (has_pending && !isfinite(step)) return fail(c, ZO2_EINVAL, "zo2_set_pending: step must be finite");
+    if (has_pending) {
+        c->h_result[8] = step;
+        HIPCHK(c, hipMemcpyAsync(c->d_state, c->h_result + 8, sizeof(float), hipMemcpyHostToDevice, c->sc));
+        HIPCHK(c, hipStreamSynchronize(c->sc));
+    }
+    c->has_pending = has_pending != 0;
+    c->seed_prev = seed;
     return ZO2_OK;
 }
 
@@ -972,7 +1033,7 @@ extern "C" zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, voi
     if (n == 0) return ZO2_OK;
     const size_t ws = zo2_dtype_size(wire_dtype), cs = zo2_dtype_size(compute_dtype);
     ZO2_OP_CHECK(ws != 0 && cs != 0, ZO2_EINVAL, "update_perturb: unknown dtype");
-    ZO2_OP_CHECK((w_plus == nullptr) == (w_minus == nullptr), ZO2_EINVAL, "update_perturb: give both W+ and W- or neither");
+    ZO2_OP_CHECK(w_plus != nullptr || w_minus == nullptr, ZO2_EINVAL, "update_perturb: W- without W+");
     ZO2_OP_CHECK(((uintptr_t)theta % (8 * ws)) == 0 && ((uintptr_t)w_plus % (8 * cs)) == 0 && ((uintptr_t)w_minus % (8 * cs)) == 0,
                  ZO2_EINVAL, "update_perturb: pointers must be aligned to 8 elements");
     K1Args a;

@@ -141,3 +141,24 @@ def test_convert_matches_oracle_codec():
     b.op_convert(src, dst, 1.0, 64.0)
     want = codec.encode(x.astype(np.float64) * 64.0, "fp8_e4m3")
     assert np.array_equal(dst.view(torch.uint8).cpu().numpy(), want)
+
+
+def test_w_plus_only_and_zero_eps():
+    """The single-forward pass writes W+ alone; with eps = 0 it is theta' in the compute format."""
+    b = _b()
+    n = 2 * 8192 + 77
+    raw = (np.random.default_rng(5).standard_normal(n) * 0.02).astype(np.float32)
+    t1, t2, t3 = (torch.from_numpy(raw.copy()).cuda() for _ in range(3))
+    wp1 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    wm1 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    wp2 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    b.op_update_perturb(t1, wp1, wm1, 9, 64, True, 41, 2e-3, 42, 1e-3)
+    b.op_update_perturb(t2, wp2, None, 9, 64, True, 41, 2e-3, 42, 1e-3)
+    torch.cuda.synchronize()
+    assert torch.equal(wp1, wp2) and torch.equal(t1, t2)
+    wp3 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    b.op_update_perturb(t3, wp3, None, 9, 64, True, 41, 2e-3, 42, 0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(t3, t1) and torch.equal(wp3, t3.to(torch.bfloat16))
+    with pytest.raises(b.Zo2Error):
+        b.op_update_perturb(t3, None, wm1, 9, 64, True, 41, 2e-3, 42, 1e-3)       # W- without W+

@@ -100,6 +100,32 @@ def test_blockwise_deferred_equals_whole_model(tied):
         assert np.array_equal(Pa[n], Pb[n]), n
 
 
+def test_eval_loss_is_the_loss_of_the_updated_parameters():
+    """The single-forward evaluation sees theta with the deferred update applied: it equals the loss of
+    Alg. 1's theta_{j+1} (whole-model form), it is the eps -> 0 limit of (l+ + l-) / 2 of a step taken from
+    there (the odd terms cancel), and it leaves nothing pending."""
+    cfg, s, P, tok, lab = _setup()
+    tok2 = si.make_tokens(cfg["vocab"], 2, 11, seed=9)
+    lab2 = si.next_token_labels(tok2)
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    zo = zo_step.Zo2Blockwise(s, Pb)
+    for j in range(3):
+        zo_step.step_whole(s, Pa, tok, lab, 100 + j, 1e-3, 2e-3)
+        zo.step(tok, lab, 100 + j, 1e-3, 2e-3)
+    ev = zo.eval_loss(tok2, lab2)
+    assert zo.pending is None
+    assert float(ev) == float(np.float32(opt_model.loss(s, Pa, tok2, lab2)))       # Alg. 1's parameters, same loss
+    gaps = []
+    for eps in (2e-3, 1e-3):
+        lp, lm, _ = zo_step.step_whole(s, copy.deepcopy(Pa), tok2, lab2, 7, eps, 0.0)
+        gaps.append(abs(0.5 * (float(lp) + float(lm)) - float(ev)))
+    assert gaps[0] < 1e-4 * float(ev) and gaps[1] < gaps[0]          # shrinks with eps (ReLU kinks keep it from a clean eps^2)
+    # training continued after an evaluation is the training without it
+    a = zo_step.step_whole(s, Pa, tok, lab, 200, 1e-3, 1e-3)
+    b = zo.step(tok, lab, 200, 1e-3, 1e-3)
+    assert tuple(map(float, a)) == tuple(map(float, b))
+
+
 def test_zero_learning_rate_and_sign_symmetry():
     cfg, s, P, tok, lab = _setup()
     P0 = copy.deepcopy(P)

@@ -84,6 +84,8 @@ def lib():
         "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i32, vp]),
         "zo2_op_layernorm": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
         "zo2_op_cross_entropy_rows": (i32, [vp, i64, vp, i32, i32, vp, vp]),
+        "zo2_op_lm_head_ce": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, C.c_size_t, vp]),
+        "zo2_op_lm_head_ce_workspace_bytes": (C.c_size_t, [i32, i32]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(L, name)
@@ -96,7 +98,8 @@ def lib():
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
-            "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows"]
+            "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
+            "zo2_op_lm_head_ce_workspace_bytes"]
 
 
 def _op_check(st):
@@ -200,6 +203,17 @@ def op_cross_entropy_rows(logits, labels, vocab=None, stream=None):
     out = torch.empty(rows, dtype=torch.float32, device="cuda")
     _op_check(lib().zo2_op_cross_entropy_rows(_ptr(logits), logits.stride(0), _ptr(labels), rows, vocab, _ptr(out),
                                               _stream_ptr(stream)))
+    return out
+
+
+def op_lm_head_ce(X, W, labels, stream=None):
+    M, K = X.shape
+    N = W.shape[0]
+    nb = lib().zo2_op_lm_head_ce_workspace_bytes(M, N)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    out = torch.empty(M, dtype=torch.float32, device="cuda")
+    _op_check(lib().zo2_op_lm_head_ce(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(labels), _ptr(out),
+                                      _ptr(ws), nb, _stream_ptr(stream)))
     return out
 
 

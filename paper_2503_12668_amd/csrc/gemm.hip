@@ -227,6 +227,10 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
         ZO2_OP_CHECK(((uintptr_t)a.p[i].X & 15) == 0 && ((uintptr_t)a.p[i].W & 15) == 0, ZO2_EINVAL,
                      "gemm: operands must be 16-byte aligned");
     }
+    // cross-entropy mode has no output matrix (Y may be NULL): only the 256 x 256 kernel implements it, so every
+    // other path must be refused before anything is launched
+    ZO2_OP_CHECK(!a.ce_mode || (dtype != ZO2_F32 && gemm256_applicable(a, dtype)), ZO2_EINVAL,
+                 "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 64 == 0, M, N >= 256, N %% 4 == 0)");
     if (dtype == ZO2_F32) {
         ZO2_OP_CHECK(a.out_f32, ZO2_EINVAL, "gemm: the float32 kernel writes float32 output");
         const unsigned tiles = (unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64));
@@ -235,7 +239,6 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
         return ZO2_OK;
     }
     if (gemm256_applicable(a, dtype)) return gemm_launch_256(a, dtype, st);
-    ZO2_OP_CHECK(!a.ce_mode, ZO2_EINVAL, "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 64 == 0, M, N >= 256)");
     if (dtype == ZO2_BF16) return launch_mfma<bf16_t>(a, st);
     if (dtype == ZO2_F16) return launch_mfma<f16_t>(a, st);
     set_op_error("gemm: dtype %d is not a compute dtype", dtype);

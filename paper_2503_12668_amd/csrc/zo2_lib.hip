@@ -1074,3 +1074,33 @@ extern "C" zo2_status zo2_op_cross_entropy_rows(const float* logits, int64_t ld,
                                                 float* row_loss, void* stream) {
     return cross_entropy_rows(logits, ld, labels, rows, 0, rows > 0 ? rows : 1, vocab, row_loss, as_stream(stream));
 }
+
+extern "C" size_t zo2_op_lm_head_ce_workspace_bytes(int32_t M, int32_t N) {
+    if (M <= 0 || N <= 0) return 0;
+    const size_t parts = 4 * (((size_t)N + 255) / 256);
+    return (2 * parts + 1) * (size_t)M * sizeof(float);
+}
+
+extern "C" zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W,
+                                        int64_t ldw, const int32_t* labels, float* row_loss, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+    if (M == 0) return ZO2_OK;
+    ZO2_OP_CHECK(X && W && labels && row_loss && workspace, ZO2_EINVAL, "lm_head_ce: NULL argument");
+    ZO2_OP_CHECK(dtype == ZO2_BF16 || dtype == ZO2_F16, ZO2_EINVAL, "lm_head_ce: dtype must be BF16 or F16");
+    ZO2_OP_CHECK(M >= 256 && N >= 256 && K > 0 && K % 64 == 0 && N % 4 == 0, ZO2_EINVAL,
+                 "lm_head_ce: needs M, N >= 256, K %% 64 == 0, N %% 4 == 0 (got %d x %d x %d)", M, N, K);
+    ZO2_OP_CHECK(((uintptr_t)workspace & 255) == 0 && workspace_bytes >= zo2_op_lm_head_ce_workspace_bytes(M, N) && M > 0 && N > 0,
+                 ZO2_EINVAL, "lm_head_ce: workspace too small or not 256-byte aligned");
+    const int parts = 4 * ((N + 255) / 256);
+    float* pmax = (float*)workspace;
+    float* psum = pmax + (size_t)parts * M;
+    float* lab = psum + (size_t)parts * M;
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.M = M; ga.N = N; ga.K = K; ga.ldx = ldx; ga.ldw = ldw; ga.ldy = N; ga.out_f32 = 1; ga.nprob = 1; ga.ce_mode = 1; ga.part_ld = M;
+    ga.p[0].X = X; ga.p[0].W = W; ga.p[0].out_scale = 1.0f; ga.p[0].labels = labels;
+    ga.p[0].part_max = pmax; ga.p[0].part_sum = psum; ga.p[0].label_logit = lab;
+    const zo2_status s = gemm_launch(ga, dtype, as_stream(stream));
+    if (s != ZO2_OK) return s;
+    return ce_combine(pmax, psum, lab, labels, M, parts, M, 0, M, row_loss, as_stream(stream));
+}

@@ -100,6 +100,34 @@ def test_attention_full_size_sampled_heads():
         assert (out[rs, cs].double() - ref).abs().max() <= 1.5e-2 * max(1.0, float(ref.abs().max()))
 
 
+def test_lm_head_cross_entropy_sampled_rows_at_bench_shape():
+    """The LM head of the benchmark (4096 x 50272 x 2048, bf16, ragged last tile: 50272 = 196 * 256 + 96) with the
+    cross-entropy taken in the GEMM epilogue: every row's loss against float64 on sampled rows, ignored labels,
+    labels in the first / last column and in the ragged tile."""
+    b = _b()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    X = torch.randn(T, D, device="cuda", generator=g).to(torch.bfloat16)
+    W = (torch.randn(V, D, device="cuda", generator=g) * 0.05).to(torch.bfloat16)
+    lab = torch.randint(0, V, (T,), device="cuda", generator=g, dtype=torch.int32)
+    lab[5] = -100
+    lab[6], lab[7], lab[8], lab[9] = 0, V - 1, 196 * 256, 196 * 256 + 95
+    out = b.op_lm_head_ce(X, W, lab)
+    torch.cuda.synchronize()
+    assert float(out[5]) == 0.0
+    rows = torch.cat([torch.arange(0, 16, device="cuda"), torch.randint(0, T, (48,), device="cuda", generator=g),
+                      torch.arange(T - 8, T, device="cuda")])
+    logits = X[rows].double() @ W.double().T
+    ref = torch.logsumexp(logits, -1) - logits.gather(1, lab[rows].clamp(min=0).long()[:, None])[:, 0]
+    ref[lab[rows] < 0] = 0.0
+    err = (out[rows].double() - ref).abs().max()
+    print("max |row loss - float64|", float(err), flush=True)
+    assert err <= 2e-3 * max(1.0, float(ref.abs().max()))        # float32 accumulation over K = 2048 of bf16 products
+    # same rows through the unfused path (float32 logits, then row-wise cross-entropy): agreement to float32 rounding
+    lg = b.op_gemm(X[:512].contiguous(), W, out_dtype=b.F32)
+    unfused = b.op_cross_entropy_rows(lg, lab[:512].contiguous())
+    assert (out[:512] - unfused).abs().max() <= 2e-5 * max(1.0, float(unfused.abs().max()))
+
+
 @pytest.mark.timeout(600)
 def test_one_block_model_at_full_width_and_batch_matches_oracle():
     """OPT-1.3B width, vocabulary and batch 16 x 256 with a single decoder block: two whole steps (the second

@@ -101,3 +101,22 @@ def test_cross_entropy_rows(rows, V):
     ref = torch.logsumexp(lg.double(), -1) - lg.double().gather(1, lab.clamp(min=0).long()[:, None])[:, 0]
     ref[rows // 2] = 0.0
     assert (out.double().cpu() - ref).abs().max() <= 2e-6 * ref.abs().max()
+
+
+def test_lm_head_ce_small_and_bad_shapes():
+    b = _b()
+    g = torch.Generator().manual_seed(1)
+    M, N, K = 300, 520, 128                                  # ragged in both directions, several spans per row
+    X = (torch.randn(M, K, generator=g)).to(torch.float16)
+    W = (torch.randn(N, K, generator=g) * 0.2).to(torch.float16)
+    lab = torch.randint(0, N, (M,), generator=g, dtype=torch.int32)
+    lab[0] = -100
+    out = b.op_lm_head_ce(X.cuda(), W.cuda(), lab.cuda()).cpu()
+    logits = X.double() @ W.double().T
+    ref = torch.logsumexp(logits, -1) - logits.gather(1, lab.clamp(min=0).long()[:, None])[:, 0]
+    ref[0] = 0.0
+    assert (out.double() - ref).abs().max() <= 2e-3 * max(1.0, float(ref.abs().max()))
+    with pytest.raises(b.Zo2Error):
+        b.op_lm_head_ce(X[:100].cuda(), W.cuda(), lab[:100].cuda())          # fewer than 256 rows
+    with pytest.raises(b.Zo2Error):
+        b.op_lm_head_ce(X.float().cuda(), W.float().cuda(), lab.cuda())      # float32 has no fused path

@@ -229,8 +229,8 @@ zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K,
 
 /* Causal multi-head self-attention.  q, k, v, out: [n_seq * seq, ld] of `dtype`, head h in
  * columns h*d_head .. (h+1)*d_head-1; q already carries the 1/sqrt(d_head) factor.
- * out[i] = softmax_{j <= i}(q_i . k_j) v_j within each sequence.  d_head in {8,16,32,64,128}.
- * bf16 / fp16 with d_head 64 or 128 run on the matrix cores (operands 16-byte aligned) unless
+ * out[i] = softmax_{j <= i}(q_i . k_j) v_j within each sequence.  d_head in {8,16,32,64,80,128}.
+ * bf16 / fp16 with d_head 64, 80 or 128 run on the matrix cores (operands 16-byte aligned) unless
  * vector_kernel != 0; everything else, and F32, runs on a float32 vector kernel. */
 zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                             int32_t n_seq, int32_t seq, int32_t n_heads, int32_t d_head, int64_t ld,

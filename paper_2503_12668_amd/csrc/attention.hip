@@ -104,7 +104,7 @@ __global__ __launch_bounds__(64) void attention_valu_kernel(const T* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
-// MFMA kernel (bf16 / fp16, d_head 64 or 128).  One wavefront owns 32 queries and walks the
+// MFMA kernel (bf16 / fp16, d_head 64, 80 or 128).  One wavefront owns 32 queries and walks the
 // keys in tiles of 32 staged through LDS.
 //
 //   S^T = K Q^T   (32 keys x 32 queries)   A operand: K rows, B operand: Q rows
@@ -153,9 +153,11 @@ template <typename T, int DH>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                                                                  T* __restrict__ out, int seq, int64_t ld) {
     constexpr int KS = DH / 16;          // contraction steps of the first product
-    constexpr int DT = DH / 32;          // 32-row tiles of O^T
-    constexpr int KCH = DH / 8;          // 16-byte chunks per K row
-    constexpr int KTILE = 32 * DH * 2, BUF = 2 * KTILE;                   // K tile, then V tile
+    constexpr int DT = (DH + 31) / 32;   // 32-row tiles of O^T (rows past DH are computed on padding and dropped)
+    constexpr int DHP = DH <= 64 ? 64 : 128;   // LDS row pitch in elements: a power of two, so that the swizzle stays inside the row
+    constexpr int KCH = DHP / 8;         // 16-byte chunk positions per LDS row
+    constexpr int GCH = DH / 8;          // 16-byte chunks per row in memory
+    constexpr int KTILE = 32 * DHP * 2, BUF = 2 * KTILE;                  // K tile, then V tile
     constexpr int KINSTR = KTILE / 1024 / 4;                              // direct-to-LDS loads per wavefront per tile and operand
     __shared__ __attribute__((aligned(1024))) char lds[2 * BUF];
     const int lane = threadIdx.x & 63;
@@ -194,8 +196,9 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
 #pragma unroll
         for (int x = 0; x < KINSTR; ++x) {                   // K rows: 1024 / (2 DH) rows per instruction
             const int inst = wave * KINSTR + x;
-            const int row = inst * (512 / DH) + lane / KCH;
-            const int chunk = (lane % KCH) ^ (row & 7);
+            const int row = inst * (512 / DHP) + lane / KCH;
+            int chunk = (lane % KCH) ^ (row & 7);
+            if (GCH < KCH && chunk >= GCH) chunk &= 7;       // padding positions of a row repeat a real chunk (finite, never used in a kept result)
             const size_t g = base + (size_t)min(j0 + row, seq - 1) * ld + chunk * 8;   // rows past the end repeat the last one (masked keys)
             att_load_to_lds(k + g, lds0 + buf * BUF + inst * 1024);
             att_load_to_lds(v + g, lds0 + buf * BUF + KTILE + inst * 1024);
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
         const char* vb = kb + KTILE;
         uint4 kf[KS], vf[DT][2];
 #pragma unroll
-        for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kb + pr * (DH * 2) + (((2 * c + kh) ^ (pr & 7)) * 16));
+        for (int c = 0; c < KS; ++c) kf[c] = *reinterpret_cast<const uint4*>(kb + pr * (DHP * 2) + (((2 * c + kh) ^ (pr & 7)) * 16));
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
                 for (int h = 0; h < 2; ++h) {
                     const int key = 16 * s2 + 8 * (g16 >> 1) + 4 * h + (a16 >> 2);
                     const int chunk = 4 * d + 2 * (g16 & 1) + ((a16 & 3) >> 1);
-                    const char* src = vb + key * (DH * 2) + ((chunk ^ (key & 7)) * 16) + 8 * (a16 & 1);
+                    const char* src = vb + key * (DHP * 2) + ((chunk ^ (key & 7)) * 16) + 8 * (a16 & 1);
                     half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) att_i16x4*)src);
                 }
                 vf[d][s2] = make_uint4(__builtin_bit_cast(uint2, half[0]).x, __builtin_bit_cast(uint2, half[0]).y,
@@ -284,6 +287,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
         for (int d = 0; d < DT; ++d)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
+                if (d * 32 + 8 * g >= DH) continue;          // rows of the last O^T tile that lie past d_head
                 Vec<T, 4> ov;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ov.v[e] = Fmt<T>::store(o[d][4 * g + e] * inv);
@@ -297,6 +301,7 @@ static zo2_status launch_mfma_att(const T* q, const T* k, const T* v, T* out, in
                                   int64_t ld, hipStream_t st) {
     const dim3 grid((seq + 127) / 128, n_heads, n_seq), block(256);
     if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, v, out, seq, ld);
+    else if (d_head == 80) hipLaunchKernelGGL((attention_mfma_kernel<T, 80>), grid, block, 0, st, q, k, v, out, seq, ld);
     else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, v, out, seq, ld);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
@@ -309,10 +314,10 @@ static zo2_status launch_valu(const T* q, const T* k, const T* v, T* out, int n_
     switch (d_head) {
 #define ZO2_ATT_CASE(D) \
     case D: hipLaunchKernelGGL((attention_valu_kernel<T, D>), grid, block, 0, st, q, k, v, out, seq, ld); break;
-        ZO2_ATT_CASE(8) ZO2_ATT_CASE(16) ZO2_ATT_CASE(32) ZO2_ATT_CASE(64) ZO2_ATT_CASE(128)
+        ZO2_ATT_CASE(8) ZO2_ATT_CASE(16) ZO2_ATT_CASE(32) ZO2_ATT_CASE(64) ZO2_ATT_CASE(80) ZO2_ATT_CASE(128)
 #undef ZO2_ATT_CASE
         default:
-            set_op_error("attention: d_head %d not supported (8, 16, 32, 64, 128)", d_head);
+            set_op_error("attention: d_head %d not supported (8, 16, 32, 64, 80, 128)", d_head);
             return ZO2_EINVAL;
     }
     ZO2_HIP_LAUNCH_CHECK();
@@ -326,7 +331,7 @@ zo2_status attention_launch(int dtype, const void* q, const void* k, const void*
     ZO2_OP_CHECK(q && k && v && out, ZO2_EINVAL, "attention: NULL buffer");
     ZO2_OP_CHECK(ld >= (int64_t)n_heads * d_head && ld % 8 == 0, ZO2_EINVAL, "attention: bad leading dimension");
     ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535, ZO2_EINVAL, "attention: grid too large");
-    if (!vector_kernel && dtype != ZO2_F32 && (d_head == 64 || d_head == 128)) {
+    if (!vector_kernel && dtype != ZO2_F32 && (d_head == 64 || d_head == 80 || d_head == 128)) {
         ZO2_OP_CHECK((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0, ZO2_EINVAL, "attention: operands must be 16-byte aligned");
         if (dtype == ZO2_BF16)
             return launch_mfma_att<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, n_seq, seq, n_heads, d_head, ld, st);

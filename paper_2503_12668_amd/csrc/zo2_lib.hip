@@ -42,7 +42,7 @@ static bool config_ok(const zo2_config* c, char* why, size_t n) {
     if (c->d_model % 8 || c->d_ffn % 8) BAD("d_model (%d) and d_ffn (%d) must be multiples of 8", c->d_model, c->d_ffn);
     if (c->d_model % c->n_heads) BAD("n_heads %d does not divide d_model %d", c->n_heads, c->d_model);
     const int dh = c->d_model / c->n_heads;
-    if (!(dh == 8 || dh == 16 || dh == 32 || dh == 64 || dh == 128)) BAD("head dimension %d not in {8,16,32,64,128}", dh);
+    if (!(dh == 8 || dh == 16 || dh == 32 || dh == 64 || dh == 80 || dh == 128)) BAD("head dimension %d not in {8,16,32,64,80,128}", dh);
     if (zo2_dtype_size(c->wire_dtype) == 0) BAD("unknown wire dtype %d", c->wire_dtype);
     if (!(c->compute_dtype == ZO2_F32 || c->compute_dtype == ZO2_BF16 || c->compute_dtype == ZO2_F16))
         BAD("compute dtype %d is not F32, BF16 or F16", c->compute_dtype);

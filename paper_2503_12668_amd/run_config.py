@@ -55,6 +55,7 @@ def main():
     from paper_2503_12668_amd import binding
 
     cfg = si.opt_config(args.model, n_layers=args.layers)
+    cfg["max_pos"] = max(cfg["max_pos"], args.seq)        # sequence sweeps beyond 2048 extend the position table
     L = cfg["n_layers"]
     tok = si.make_tokens(cfg["vocab"], args.batch, args.seq, seed=2, dist="zipf")
     lab = si.next_token_labels(tok)

@@ -147,3 +147,24 @@ def test_one_block_model_at_full_width_and_batch_matches_oracle():
         assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
         assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
     ctx.close()
+
+
+@pytest.mark.parametrize("n_seq,seq,heads,dh", [(2, 2048, 4, 128), (2, 2048, 4, 80), (1, 8192, 2, 64)])
+def test_attention_long_sequences_sampled_queries(n_seq, seq, heads, dh):
+    """Sequence lengths of the paper's main setting (2048: OPT-2.7B's d_head 80, the d_head 128 of 6.7B-175B) and of
+    its longest sweep point (8192): sampled query rows against float64 softmax(q K^T) V."""
+    b = _b()
+    g = torch.Generator(device="cuda").manual_seed(seq + dh)
+    mk = lambda s: (torch.randn(n_seq * seq, heads * dh, device="cuda", generator=g) * s).to(torch.bfloat16)
+    q, k, v = mk(0.2), mk(1.0), mk(1.0)
+    out = b.op_attention(q, k, v, n_seq, seq, heads, dh)
+    torch.cuda.synchronize()
+    for sq, hd in ((0, 0), (n_seq - 1, heads - 1)):
+        cs = slice(hd * dh, (hd + 1) * dh)
+        rows = torch.tensor([0, 1, 31, 32, 127, 128, seq // 2 - 1, seq // 2, seq - 129, seq - 2, seq - 1], device="cuda")
+        kk, vv = k[sq * seq:(sq + 1) * seq, cs].double(), v[sq * seq:(sq + 1) * seq, cs].double()
+        s_ = q[sq * seq + rows][:, cs].double() @ kk.T
+        s_ = s_.masked_fill(torch.arange(seq, device="cuda")[None, :] > rows[:, None], float("-inf"))
+        ref = torch.softmax(s_, -1) @ vv
+        got = out[sq * seq + rows][:, cs].double()
+        assert (got - ref).abs().max() <= 1.5e-2 * max(1.0, float(ref.abs().max()))

@@ -61,7 +61,7 @@ def _attention_ref(q, k, v, n_seq, seq, H, dh):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("n_seq,seq,H,dh", [(2, 11, 4, 8), (3, 64, 2, 64), (2, 130, 3, 32), (1, 257, 2, 128), (4, 1, 2, 16),
-                                           (2, 256, 3, 64), (2, 23, 2, 64), (1, 300, 2, 128), (3, 33, 1, 128)])
+                                           (2, 256, 3, 64), (2, 23, 2, 64), (1, 300, 2, 128), (3, 33, 1, 128), (2, 200, 3, 80), (1, 31, 2, 80)])
 @pytest.mark.parametrize("vector_kernel", [False, True])
 def test_attention_against_float64(dt, n_seq, seq, H, dh, vector_kernel):
     b = _b()

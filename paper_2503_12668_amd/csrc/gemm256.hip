@@ -33,9 +33,10 @@ template <> struct Mfma32<f16_t> {
     }
 };
 
-#ifndef ZO2_GEMM_SWZ_SHIFT
-#define ZO2_GEMM_SWZ_SHIFT 0
-#endif
+// Measurement hooks for a stand-alone timing harness (never defined in the library build):
+//   ZO2_GEMM_EXP_TIMING  cycle-counter stamps at tile start / end of main loop / end of epilogue, and the cycles
+//                        spent at the k-slab barrier, written through problem slot 5's residual pointer;
+//   ZO2_GEMM_EXP_NODMA   no direct-to-LDS loads after a tile's first slab;  ZO2_GEMM_EXP_NOREAD  no LDS fragment reads.
 static constexpr int kBM = 256, kBN = 256, kBK = 64;
 static constexpr int kStageBytes = (kBM + kBN) * kBK * 2;      // 65536
 static constexpr int kEpiRegion = 24576;                       // per-wave output staging above stage 0
@@ -53,7 +54,7 @@ __device__ __forceinline__ void load_to_lds(const void* sbase, uint32_t voff, ui
 }
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row
-__device__ __forceinline__ int swz(int row) { return (row >> ZO2_GEMM_SWZ_SHIFT) & 7; }
+__device__ __forceinline__ int swz(int row) { return row & 7; }
 
 // Where virtual tile id `vid` (0 .. ntiles * nprob - 1) lives: problem, tile row, tile column.
 // Tiles of one problem are walked in groups of 8 rows of the tile grid (column-major inside a

@@ -182,6 +182,13 @@ zo2_status zo2_get_kernel_times(const zo2_ctx* ctx, float ms[ZO2_KERNEL_CLASSES]
  * dependency rules of Sec. 5.2 in place no choice of delays can change any result. */
 zo2_status zo2_debug_set_stream_delay(zo2_ctx* ctx, int32_t which, uint32_t microseconds);
 
+/* Ablation switch for the dynamic scheduler (Sec. 5.2; the paper's reverse ablation, Table 4, "no
+ * scheduler overlap"): with enabled = 0 a streamed block's upload, compute and offload run strictly
+ * one after the other (the host waits in between), and the next block's upload starts only then.
+ * Results do not change.  Default: enabled; ignored while zo2_device.stream_k1 is in use.  The table's "no efficient update" column needs no
+ * switch: call zo2_flush after every zo2_step (each block then travels twice per iteration). */
+zo2_status zo2_set_stream_overlap(zo2_ctx* ctx, int32_t enabled);
+
 const char* zo2_last_error(const zo2_ctx* ctx);
 void zo2_destroy(zo2_ctx* ctx);
 

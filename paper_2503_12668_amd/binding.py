@@ -71,6 +71,7 @@ def lib():
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
+        "zo2_set_stream_overlap": (i32, [vp, i32]),
         "zo2_get_kernel_times": (i32, [vp, C.POINTER(f32), C.POINTER(i32)]),
         "zo2_debug_set_stream_delay": (i32, [vp, i32, u32]),
         "zo2_last_error": (C.c_char_p, [vp]),
@@ -96,7 +97,7 @@ def lib():
 
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes"]
@@ -357,6 +358,9 @@ class Zo2Context:
         u, d = C.c_uint64(), C.c_uint64()
         self._check(lib().zo2_get_step_stats(self.handle, C.byref(a), C.byref(b), C.byref(c_), C.byref(u), C.byref(d)))
         return dict(ms_compute=a.value, ms_upload=b.value, ms_offload=c_.value, bytes_up=u.value, bytes_down=d.value)
+
+    def set_stream_overlap(self, enabled):
+        self._check(lib().zo2_set_stream_overlap(self.handle, 1 if enabled else 0))
 
     def debug_set_stream_delay(self, which, microseconds):
         self._check(lib().zo2_debug_set_stream_delay(self.handle, {"compute": 0, "upload": 1, "offload": 2}[which], int(microseconds)))

@@ -105,6 +105,7 @@ struct zo2_ctx {
     float* logits;
     int logit_rows;                     // rows per sign per chunk
     bool fused_ce;                      // LM head writes cross-entropy partials instead of logits
+    bool serial_streams;                 // ablation: upload, compute and offload of a block run one after the other
     int ns;                              // perturbation streams of the pass in progress: 2 (step) or 1 (evaluation)
     float *ce_pmax, *ce_psum, *ce_lab;  // [4 ceil(V/256), 2T] x 2 and [2T]
     int ce_parts;
@@ -565,6 +566,13 @@ extern "C" zo2_status zo2_debug_set_stream_delay(zo2_ctx* c, int32_t which, uint
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_set_stream_overlap(zo2_ctx* c, int32_t enabled) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    c->serial_streams = enabled == 0;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_step_stats(const zo2_ctx* c, float* ms_c, float* ms_u, float* ms_o, uint64_t* up, uint64_t* down) {
     if (!c) return ZO2_EINVAL;
     if (ms_c) *ms_c = c->ms_c;
@@ -759,7 +767,8 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
 
     // U(W_1..): prefetch as many blocks as there are slots; overlaps the embedding
     int next_upload = 0;
-    if (!c->resident)
+    const bool serial = c->serial_streams && !c->overlap_k1;   // the ablation is defined for the three-stream schedule
+    if (!c->resident && !serial)
         for (; next_upload < c->n_slots && next_upload < g.n_layers; ++next_upload) {
             zo2_status s = enqueue_upload(c, next_upload);
             if (s != ZO2_OK) return s;
@@ -799,12 +808,22 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             if (s != ZO2_OK) return s;
             HIPCHK(c, hipEventRecord(c->ev_fwd_done[sb], c->sc));
         } else {
+            if (!c->resident && serial) {      // ablation of Sec. 5.2: nothing overlaps, U(W_i) starts when O(W_{i-1}) is done
+                zo2_status us = enqueue_upload(c, next_upload++);
+                if (us != ZO2_OK) return us;
+                HIPCHK(c, hipStreamSynchronize(c->su));
+            }
             if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
             { zo2_status ds = debug_delay(c, 0, c->sc); if (ds != ZO2_OK) return ds; }
             zo2_status s = block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
             if (s != ZO2_OK) return s;
         }
-        if (!c->resident) {
+        if (!c->resident && serial) {
+            HIPCHK(c, hipStreamSynchronize(c->sc));
+            zo2_status s = enqueue_offload(c, l, upd);
+            if (s != ZO2_OK) return s;
+            HIPCHK(c, hipStreamSynchronize(c->so));
+        } else if (!c->resident) {
             zo2_status s = enqueue_offload(c, l, upd);                             // O(W_i) after its update
             if (s != ZO2_OK) return s;
             if (next_upload < g.n_layers) {                                        // U(W_{i+n}) into the slot O(W_i) frees

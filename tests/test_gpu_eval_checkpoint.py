@@ -155,3 +155,29 @@ def test_checkpoint_resume_is_bit_identical():
     with pytest.raises(b.Zo2Error):
         ctx_d.set_pending(True, 1, float("nan"))
     ctx_d.close()
+
+
+def test_ablation_switches_change_time_not_results():
+    """Table 4's reverse ablation as switches: no stream overlap (zo2_set_stream_overlap(0)) and no deferred update
+    (zo2_flush after every step) leave every loss and parameter bit-identical."""
+    b = _b()
+    cfg, P, tok, lab, _, _ = _setup(n_layers=7)
+    runs = []
+    for mode in ("full", "serial", "flush_each_step"):
+        ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+        r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
+        ctx.set_resident_budget(ctx.plan()["bytes_used"] - 4 * ctx.offs[16] * 4)      # 3 slots for 7 blocks
+        if mode == "serial":
+            ctx.set_stream_overlap(False)
+        for j in range(1, 4):
+            if mode == "flush_each_step":
+                ctx.flush()
+            r.append(ctx.step(tok, lab, 5 + j, 1e-3, 1e-3))
+        assert not ctx.plan()["resident"]
+        ctx.flush(); ctx.sync_to_host()
+        runs.append((r, ctx.parameters()))
+        ctx.close()
+    for other in runs[1:]:
+        assert [tuple(map(float, x)) for x in runs[0][0]] == [tuple(map(float, x)) for x in other[0]]
+        for n in runs[0][1]:
+            assert np.array_equal(runs[0][1][n], other[1][n]), n

@@ -334,3 +334,32 @@ def test_streamed_equals_resident_at_13b_block_shape():
     for a, c in zip(params["resident"], params["streamed"]):
         assert torch.equal(a, c)
     assert all(np.isfinite(x).all() for x in np.array(res["resident"]))
+
+
+def test_degenerate_batches():
+    """One token, the longest allowed sequence, several very short sequences; a batch with every label ignored has
+    no loss (0 / 0): the step reports it and leaves nothing pending."""
+    b = _b()
+    cfg = si.tiny_config(n_layers=2, d_model=64, n_heads=4, d_ffn=128, vocab=211, max_pos=40)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    for (B, S) in ((1, 1), (1, 40), (5, 3)):
+        tok = si.make_tokens(cfg["vocab"], B, S, seed=12)
+        lab = si.next_token_labels(tok)
+        if S == 1:
+            lab[:] = tok                        # a single position: give it a label that counts
+        oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), copy.deepcopy(P))
+        ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+        for j in range(2):
+            a, g = oz.step(tok, lab, 42 + j, 1e-3, 1e-4), ctx.step(tok, lab, 42 + j, 1e-3, 1e-4)
+            assert abs(float(g[0]) - float(a[0])) <= 1e-5 * abs(float(a[0])), (B, S, j)
+            assert abs(float(g[1]) - float(a[1])) <= 1e-5 * abs(float(a[1])), (B, S, j)
+        assert abs(float(ctx.eval(tok, lab)) - float(oz.eval_loss(tok, lab))) <= 1e-5 * 6.0
+        ctx.close()
+    tok = si.make_tokens(cfg["vocab"], 2, 5, seed=12)
+    ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+    with pytest.raises(b.Zo2Error) as e:
+        ctx.step(tok, np.full_like(tok, -100), 1, 1e-3, 1e-4)
+    assert e.value.status == 6 and not ctx.pending()[0]
+    r = ctx.step(tok, si.next_token_labels(tok), 2, 1e-3, 1e-4)            # the context is still usable
+    assert np.isfinite(float(r[0]))
+    ctx.close()

@@ -182,6 +182,16 @@ zo2_status zo2_get_kernel_times(const zo2_ctx* ctx, float ms[ZO2_KERNEL_CLASSES]
  * dependency rules of Sec. 5.2 in place no choice of delays can change any result. */
 zo2_status zo2_debug_set_stream_delay(zo2_ctx* ctx, int32_t which, uint32_t microseconds);
 
+/* Rounding of the updated parameters into a low-bit wire format (Sec. 5.5 leaves it open; default 0 = to
+ * nearest, ties to even, which is what a plain cast does).  With stochastic != 0, theta' = theta - eta g z is
+ * stored as one of its two neighbours in the format, the one further from zero with probability
+ * (|x| - lo) / (hi - lo): realised as r16 < 65536 (|x| - lo) / (hi - lo) with 16 bits r16 per element from the
+ * same Philox4x32-10 stream as z_prev but with the last counter word set to 1 (call e >> 3, low / high half of
+ * output word (e >> 1) & 3 for even / odd e).  Values beyond the largest finite value saturate.  A master copy
+ * in bf16 / fp16 / fp8 then follows updates far below its spacing in expectation; with rounding to nearest
+ * such updates are lost.  No effect on a float32 wire.  Takes effect at the next update. */
+zo2_status zo2_set_wire_rounding(zo2_ctx* ctx, int32_t stochastic);
+
 /* Ablation switch for the dynamic scheduler (Sec. 5.2; the paper's reverse ablation, Table 4, "no
  * scheduler overlap"): with enabled = 0 a streamed block's upload, compute and offload run strictly
  * one after the other (the host waits in between), and the next block's upload starts only then.
@@ -214,11 +224,12 @@ zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint6
  * every pointer must be aligned to 8 elements.  theta is rewritten in place; w_plus /
  * w_minus (compute dtype, n elements) may both be NULL for an update-only pass, or w_minus
  * alone for a pass that writes only w_plus; with eps = 0 no z is drawn and w_plus = theta'.
- * scale: the tensor's wire scale (1 unless an 8-bit format uses one). */
+ * scale: the tensor's wire scale (1 unless an 8-bit format uses one).  stochastic_rounding != 0 stores theta'
+ * as zo2_set_wire_rounding describes. */
 zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
                                  uint32_t tensor_id, uint64_t e0, uint64_t n,
                                  int32_t has_pending, uint64_t seed_prev, float c,
-                                 uint64_t seed, float eps, float scale, void* stream);
+                                 uint64_t seed, float eps, float scale, int32_t stochastic_rounding, void* stream);
 
 /* Low-bit pack / unpack (Sec. 5.5): convert n elements between two storage formats,
  * dst = store_dst(load_src(src) / scale_src * scale_dst). */

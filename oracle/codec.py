@@ -17,6 +17,12 @@ going to the code with an even mantissa; magnitudes beyond the largest finite
 value saturate to it in the 8-bit formats and follow IEEE (round to infinity)
 in the 16-bit ones.  It is a search over the table of all codes, not a bit
 trick.
+
+round_stochastic() is the rounding that lets a low-bit master copy move by steps
+far below its spacing (the paper rounds to nearest, which returns theta unchanged
+when eta * g * z is under half a unit in the last place; Sec. 5.5 leaves the
+rounding open): x goes to one of the two representable values around it, to the
+upper one with probability (|x| - lo) / (hi - lo).
 """
 import numpy as np
 
@@ -95,3 +101,24 @@ def round_to(x, fmt):
     if fmt == "f32":
         return np.asarray(x, dtype=np.float64).astype(np.float32)
     return decode(encode(x, fmt), fmt).astype(np.float32)
+
+
+def round_stochastic(x, fmt, r16):
+    """x rounded to one of its two neighbours lo <= |x| <= hi in the format (sign kept), returned as
+    float32: the one further from zero is taken iff r16 < 65536 * (|x| - lo) / (hi - lo), r16 being a
+    uniform integer in [0, 65536).  The expectation over r16 is x to within (hi - lo) / 65536.
+    Magnitudes beyond the largest finite value go to it (all formats saturate here); NaN stays NaN;
+    a representable x is returned unchanged for every r16."""
+    if fmt == "f32":
+        return np.asarray(x, dtype=np.float64).astype(np.float32)
+    x = np.asarray(x, dtype=np.float64)
+    r16 = np.asarray(r16).astype(np.float64)
+    _, vals = _finite_table(fmt)
+    a = np.abs(x)
+    lo = np.clip(np.searchsorted(vals, a, side="right") - 1, 0, len(vals) - 1)     # vals[lo] <= a
+    hi = np.minimum(lo + 1, len(vals) - 1)
+    gap = vals[hi] - vals[lo]
+    frac = np.where(gap > 0, (np.minimum(a, vals[hi]) - vals[lo]) / np.where(gap > 0, gap, 1.0), 0.0)
+    v = np.where(r16 < frac * 65536.0, vals[hi], vals[lo])
+    v = np.where(np.isnan(x), np.nan, np.copysign(v, x))
+    return v.astype(np.float32)

@@ -108,3 +108,18 @@ def _gaussian_piece(seed, tensor_id, e0, n):
     flat = out.reshape(-1)
     lo = e0 - 8 * q_lo
     return flat[lo:lo + n].astype(np.float32)
+
+
+def rounding_bits(seed, tensor_id, e0, n):
+    """16 uniform bits per element e0 .. e0+n-1 for the stochastic rounding of an update that uses the
+    direction of step seed `seed`: a second stream of the same generator, told apart from the one z is
+    drawn from by the last counter word (1 instead of 0).  Call q = e >> 3 covers 8 elements; element e
+    takes the low (e even) or high (e odd) half of output word (e >> 1) & 3."""
+    seed = int(seed)
+    e = np.arange(int(e0), int(e0) + int(n), dtype=np.uint64)
+    q = e >> np.uint64(3)
+    qs, inv = np.unique(q, return_inverse=True)
+    w = philox4x32_10(qs & _MASK, qs >> _S32, np.uint64(tensor_id), np.uint64(1),
+                      seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    w = np.stack(w, axis=1).astype(np.uint64)[inv, ((e >> np.uint64(1)) & np.uint64(3)).astype(np.int64)]
+    return ((w >> (np.uint64(16) * (e & np.uint64(1)))) & np.uint64(0xFFFF)).astype(np.uint16)

@@ -33,13 +33,18 @@ def _fma32(a, b, c):
     return (np.float64(a) * np.asarray(b, dtype=np.float64) + np.asarray(c, dtype=np.float64)).astype(np.float32)
 
 
-def _store(x, fmt, scale=1.0):
-    """Round float32 x to the parameter storage format (value returned as float32)."""
+def _store(x, fmt, scale=1.0, r16=None):
+    """Round float32 x to the parameter storage format (value returned as float32): to nearest, or -
+    given 16 random bits per element - stochastically.  The scaled value is formed in float32."""
     if fmt == "f32":
         return np.asarray(x, dtype=np.float32)
+    xs = np.asarray(x, dtype=np.float32)
     if scale != 1.0:
-        return (codec.round_to(np.float64(x) * scale, fmt).astype(np.float64) / scale).astype(np.float32)
-    return codec.round_to(x, fmt)
+        xs = (xs * np.float32(scale)).astype(np.float32) if r16 is not None else np.float64(x) * scale
+    q = codec.round_to(xs, fmt) if r16 is None else codec.round_stochastic(xs, fmt, r16)
+    if scale != 1.0:
+        return (q.astype(np.float64) / scale).astype(np.float32)
+    return q
 
 
 def z_of(shape_cfg, seed, names=None):
@@ -107,12 +112,13 @@ class Zo2Blockwise:
     visited in iteration j (Sec. 5.4).  `pending` = (g, seed, lr) of the last
     iteration, or None."""
 
-    def __init__(self, cfg, P, store="f32", compute="f32", scales=None):
+    def __init__(self, cfg, P, store="f32", compute="f32", scales=None, rounding="nearest"):
         self.cfg = cfg
         self.P = P
         self.store = store
         self.compute = compute
         self.scales = scales or {}
+        self.rounding = rounding            # of the stored theta': "nearest" (the paper's cast) or "stochastic"
         self.pending = None
         self.ids = {name: tid for name, tid, _ in opt_model.tensor_table(cfg)}
 
@@ -126,7 +132,10 @@ class Zo2Blockwise:
         g, seed, lr = self.pending
         c = np.float32(np.float32(lr) * np.float32(g))
         for n in names:
-            self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0))
+            r16 = None
+            if self.rounding == "stochastic" and self.store != "f32":
+                r16 = philox.rounding_bits(seed, self.ids[n], 0, self.P[n].size).reshape(self.P[n].shape)
+            self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0), r16)
 
     def _perturbed_pair(self, names, seed, eps):
         """(W+, W-) of a module: z drawn once, used with both signs (Eq. 2)."""

@@ -72,6 +72,7 @@ def lib():
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
         "zo2_set_stream_overlap": (i32, [vp, i32]),
+        "zo2_set_wire_rounding": (i32, [vp, i32]),
         "zo2_get_kernel_times": (i32, [vp, C.POINTER(f32), C.POINTER(i32)]),
         "zo2_debug_set_stream_delay": (i32, [vp, i32, u32]),
         "zo2_last_error": (C.c_char_p, [vp]),
@@ -79,7 +80,7 @@ def lib():
         "zo2_op_last_error": (C.c_char_p, []),
         "zo2_op_philox_words": (i32, [u64, u32, u64, u64, vp, vp]),
         "zo2_op_gaussian": (i32, [u64, u32, u64, u64, vp, vp]),
-        "zo2_op_update_perturb": (i32, [vp, i32, vp, vp, i32, u32, u64, u64, i32, u64, f32, u64, f32, f32, vp]),
+        "zo2_op_update_perturb": (i32, [vp, i32, vp, vp, i32, u32, u64, u64, i32, u64, f32, u64, f32, f32, i32, vp]),
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
         "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i32, vp]),
@@ -97,7 +98,7 @@ def lib():
 
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes"]
@@ -157,12 +158,13 @@ def op_gaussian(seed, tensor_id, e0, n, stream=None):
 
 
 def op_update_perturb(theta, w_plus, w_minus, tensor_id, e0, has_pending, seed_prev, c, seed, eps, scale=1.0,
-                      compute_dtype=None, n=None, stream=None):
+                      compute_dtype=None, n=None, stochastic=False, stream=None):
     """theta: device tensor in wire dtype (rewritten in place); w_plus / w_minus: device tensors or None."""
     n = theta.numel() if n is None else n
     cdt = _dt(w_plus) if w_plus is not None else (compute_dtype if compute_dtype is not None else F32)
     _op_check(lib().zo2_op_update_perturb(_ptr(theta), _dt(theta), _ptr(w_plus), _ptr(w_minus), cdt, tensor_id, e0, n,
-                                          1 if has_pending else 0, seed_prev, c, seed, eps, scale, _stream_ptr(stream)))
+                                          1 if has_pending else 0, seed_prev, c, seed, eps, scale, 1 if stochastic else 0,
+                                          _stream_ptr(stream)))
 
 
 def op_convert(src, dst, src_scale=1.0, dst_scale=1.0, stream=None):
@@ -358,6 +360,9 @@ class Zo2Context:
         u, d = C.c_uint64(), C.c_uint64()
         self._check(lib().zo2_get_step_stats(self.handle, C.byref(a), C.byref(b), C.byref(c_), C.byref(u), C.byref(d)))
         return dict(ms_compute=a.value, ms_upload=b.value, ms_offload=c_.value, bytes_up=u.value, bytes_down=d.value)
+
+    def set_wire_rounding(self, stochastic):
+        self._check(lib().zo2_set_wire_rounding(self.handle, 1 if stochastic else 0))
 
     def set_stream_overlap(self, enabled):
         self._check(lib().zo2_set_stream_overlap(self.handle, 1 if enabled else 0))

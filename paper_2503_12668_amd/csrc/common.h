@@ -110,6 +110,62 @@ template <> struct Fmt<fp8_e5m2_t> {
     }
 };
 
+// ---------------------------------------------------------------- stochastic rounding to a storage format
+// Bit pattern of a stored element as an integer and back; kSign is the sign bit, kMaxMag the largest finite
+// magnitude pattern.  In all these formats the magnitude patterns are ordered like the magnitudes.
+template <typename T> struct FmtBits;
+template <> struct FmtBits<bf16_t> {
+    static constexpr uint32_t kSign = 0x8000u, kMaxMag = 0x7f7fu;
+    static __device__ __forceinline__ uint32_t get(bf16_t v) { return __builtin_bit_cast(uint16_t, v); }
+    static __device__ __forceinline__ bf16_t make(uint32_t b) { return __builtin_bit_cast(bf16_t, (uint16_t)b); }
+};
+template <> struct FmtBits<f16_t> {
+    static constexpr uint32_t kSign = 0x8000u, kMaxMag = 0x7bffu;
+    static __device__ __forceinline__ uint32_t get(f16_t v) { return __builtin_bit_cast(uint16_t, v); }
+    static __device__ __forceinline__ f16_t make(uint32_t b) { return __builtin_bit_cast(f16_t, (uint16_t)b); }
+};
+template <> struct FmtBits<fp8_e4m3_t> {
+    static constexpr uint32_t kSign = 0x80u, kMaxMag = 0x7eu;
+    static __device__ __forceinline__ uint32_t get(fp8_e4m3_t v) { return v.v; }
+    static __device__ __forceinline__ fp8_e4m3_t make(uint32_t b) { return fp8_e4m3_t{(uint8_t)b}; }
+};
+template <> struct FmtBits<fp8_e5m2_t> {
+    static constexpr uint32_t kSign = 0x80u, kMaxMag = 0x7bu;
+    static __device__ __forceinline__ uint32_t get(fp8_e5m2_t v) { return v.v; }
+    static __device__ __forceinline__ fp8_e5m2_t make(uint32_t b) { return fp8_e5m2_t{(uint8_t)b}; }
+};
+
+// x goes to one of its two neighbours lo <= |x| <= hi in format T (sign kept): to hi iff
+// r16 < 65536 (|x| - lo) / (hi - lo), r16 uniform in [0, 65536).  hi - lo is a power of two and |x| - lo is
+// exact in float32, so the comparison is exact.  Beyond the largest finite value: that value.  NaN: NaN.
+template <typename T>
+__device__ __forceinline__ T store_stochastic(float x, uint32_t r16) {
+    const T n = Fmt<T>::store(x);                                   // nearest: never more than one step from lo
+    const uint32_t nb = FmtBits<T>::get(n);
+    const uint32_t sign = nb & FmtBits<T>::kSign, mag = nb & (FmtBits<T>::kSign - 1u);
+    const float ax = __builtin_fabsf(x);
+    if (!(ax == ax)) return n;
+    uint32_t lo = mag;
+    if (mag > FmtBits<T>::kMaxMag) lo = FmtBits<T>::kMaxMag;         // rounded to infinity: saturate instead
+    else if (__builtin_fabsf(Fmt<T>::load(n)) > ax) lo = mag - 1u;  // nearest rounded away from zero
+    if (lo >= FmtBits<T>::kMaxMag) return FmtBits<T>::make(sign | FmtBits<T>::kMaxMag);
+    const float vlo = Fmt<T>::load(FmtBits<T>::make(lo)), vhi = Fmt<T>::load(FmtBits<T>::make(lo + 1u));
+    const float frac = (ax - vlo) / (vhi - vlo);
+    return FmtBits<T>::make(sign | (lo + ((float)r16 < frac * 65536.0f ? 1u : 0u)));
+}
+template <>
+__device__ __forceinline__ float store_stochastic<float>(float x, uint32_t) { return x; }
+// bfloat16 keeps the upper half of the float32 pattern, so the dropped half is 65536 times the fraction itself:
+// "r16 < fraction" is a carry out of (dropped half + 65535 - r16).
+template <>
+__device__ __forceinline__ bf16_t store_stochastic<bf16_t>(float x, uint32_t r16) {
+    const uint32_t u = f2u(x), a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return Fmt<bf16_t>::store(x);
+    uint32_t m = (a + (0xffffu - r16)) & 0xffff0000u;
+    m = m > 0x7f7f0000u ? 0x7f7f0000u : m;
+    return FmtBits<bf16_t>::make(((u >> 31) << 15) | (m >> 16));
+}
+
 // A group of N elements moved with one (or two) wide memory operations.
 template <typename T, int N>
 struct alignas(sizeof(T) * N) Vec {

@@ -23,6 +23,7 @@ struct K1Args {
     int32_t nseg;
     uint32_t total_chunks;
     float c_imm;          // eta_prev * g_prev, used when c_ptr == nullptr
+    int32_t stochastic;   // 1: theta' is stored with stochastic rounding (low-bit wire formats), 0: to nearest
     float eps;
     const float* c_ptr;   // device scalar holding eta_prev * g_prev (stays on the GPU between steps)
     PhiloxKeys k_prev, k_cur;

@@ -35,10 +35,14 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
     if (UPDATE) {
         float zp[kPerLane];
         gaussian8(a.k_prev, tensor_id, q, zp);
+        uint32_t rw[4] = {0u, 0u, 0u, 0u};
+        const bool sr = Fmt<W>::kBytes < 4 && a.stochastic != 0;
+        if (sr) rounding_words(a.k_prev, tensor_id, q, rw);
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
             const float t = __builtin_fmaf(-c, zp[j], th[j]);
-            tv.v[j] = Fmt<W>::store(kScaled ? t * scale : t);
+            const float ts = kScaled ? t * scale : t;
+            tv.v[j] = sr ? store_stochastic<W>(ts, rounding_bits_of(rw, j)) : Fmt<W>::store(ts);
             th[j] = Fmt<W>::load(tv.v[j]);
             if (kScaled) th[j] *= inv_scale;
         }

@@ -71,4 +71,12 @@ __device__ __forceinline__ void gaussian4(const PhiloxKeys& k, uint32_t tensor_i
     box_muller(hi ? w[3] : w[1], z[2], z[3]);
 }
 
+// 16 rounding bits for each of the elements 8q .. 8q+7 (stochastic rounding of the stored theta'): a second
+// stream of the same generator, told apart by the last counter word (1; z uses 0).  Element 8q + j takes the
+// low (j even) or high (j odd) half of output word j >> 1.
+__device__ __forceinline__ void rounding_words(const PhiloxKeys& k, uint32_t tensor_id, uint64_t q, uint32_t w[4]) {
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, 1u, k, w);
+}
+__device__ __forceinline__ uint32_t rounding_bits_of(const uint32_t w[4], int j) { return (w[j >> 1] >> (16 * (j & 1))) & 0xffffu; }
+
 }  // namespace zo2

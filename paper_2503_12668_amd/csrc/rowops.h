@@ -19,6 +19,7 @@ struct EmbedArgs {
     int32_t T, seq, d, pos_offset;
     float eps, scale_tok, scale_pos;
     int32_t single;          // 1: only the "+" rows are produced (single forward; eps is 0 then)
+    int32_t stochastic;      // 1: the pending update is stored with stochastic rounding, as K1 will do for the table
     const float* c_ptr;      // device scalar eta_prev * g_prev
     PhiloxKeys k_prev, k_cur;
 };

@@ -290,10 +290,17 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
         }
         if (UPDATE) {
             gaussian4(a.k_prev, (uint32_t)which, e, z);
+            uint32_t rw[4] = {0u, 0u, 0u, 0u};
+            const bool sr = Fmt<W>::kBytes < 4 && a.stochastic != 0;
+            if (sr) rounding_words(a.k_prev, (uint32_t)which, e >> 3, rw);
+            // this group of 4 is the lower or the upper half of its Philox call: rounding words 0, 1 or 2, 3
+            const uint32_t r2[2] = {(e & 4) ? rw[2] : rw[0], (e & 4) ? rw[3] : rw[1]};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float u = __builtin_fmaf(-c, z[i], th[i]);
-                th[i] = Fmt<W>::load(Fmt<W>::store(kScaled ? u * scale : u));
+                const float us = kScaled ? u * scale : u;
+                const uint32_t r16 = (r2[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+                th[i] = Fmt<W>::load(sr ? store_stochastic<W>(us, r16) : Fmt<W>::store(us));
                 if (kScaled) th[i] *= inv_scale;
             }
         }

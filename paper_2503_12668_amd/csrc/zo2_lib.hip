@@ -105,6 +105,7 @@ struct zo2_ctx {
     float* logits;
     int logit_rows;                     // rows per sign per chunk
     bool fused_ce;                      // LM head writes cross-entropy partials instead of logits
+    bool stochastic;                     // theta' is stored with stochastic rounding (low-bit wire formats)
     bool serial_streams;                 // ablation: upload, compute and offload of a block run one after the other
     int ns;                              // perturbation streams of the pass in progress: 2 (step) or 1 (evaluation)
     float *ce_pmax, *ce_psum, *ce_lab;  // [4 ceil(V/256), 2T] x 2 and [2T]
@@ -566,6 +567,13 @@ extern "C" zo2_status zo2_debug_set_stream_delay(zo2_ctx* c, int32_t which, uint
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_set_wire_rounding(zo2_ctx* c, int32_t stochastic) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    c->stochastic = stochastic != 0;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_set_stream_overlap(zo2_ctx* c, int32_t enabled) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
@@ -588,6 +596,7 @@ static void k1_common(const zo2_ctx* c, K1Args& a, uint64_t seed, float eps) {
     memset(&a, 0, sizeof(a));
     a.c_ptr = c->d_state;
     a.c_imm = 0.f;
+    a.stochastic = c->stochastic ? 1 : 0;
     a.eps = eps;
     a.k_prev = philox_keys(c->seed_prev);
     a.k_cur = philox_keys(seed);
@@ -778,7 +787,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     EmbedArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.tok_emb = c->d_tok; ea.pos_emb = c->d_pos; ea.tokens = c->d_tokens; ea.h = c->h;
-    ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps; ea.single = ns == 1;
+    ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps; ea.single = ns == 1; ea.stochastic = c->stochastic ? 1 : 0;
     ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = c->d_state;
     ea.k_prev = philox_keys(c->seed_prev); ea.k_cur = philox_keys(seed);
     OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
@@ -1048,7 +1057,7 @@ extern "C" zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_
 
 extern "C" zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
                                             uint32_t tensor_id, uint64_t e0, uint64_t n, int32_t has_pending, uint64_t seed_prev,
-                                            float cval, uint64_t seed, float eps, float scale, void* stream) {
+                                            float cval, uint64_t seed, float eps, float scale, int32_t stochastic, void* stream) {
     if (n == 0) return ZO2_OK;
     const size_t ws = zo2_dtype_size(wire_dtype), cs = zo2_dtype_size(compute_dtype);
     ZO2_OP_CHECK(ws != 0 && cs != 0, ZO2_EINVAL, "update_perturb: unknown dtype");
@@ -1058,7 +1067,7 @@ extern "C" zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, voi
     K1Args a;
     memset(&a, 0, sizeof(a));
     a.theta = theta; a.w_plus = w_plus; a.w_minus = w_minus; a.w_off0 = 0; a.nseg = 1;
-    a.c_imm = cval; a.c_ptr = nullptr; a.eps = eps;
+    a.c_imm = cval; a.c_ptr = nullptr; a.eps = eps; a.stochastic = stochastic != 0;
     a.k_prev = philox_keys(seed_prev); a.k_cur = philox_keys(seed);
     a.seg[0].off = 0; a.seg[0].e0 = e0; a.seg[0].n = n; a.seg[0].tensor_id = tensor_id; a.seg[0].scale = scale;
     return k1_launch(a, wire_dtype, compute_dtype, has_pending != 0, w_plus != nullptr, as_stream(stream));

@@ -162,3 +162,32 @@ def test_w_plus_only_and_zero_eps():
     assert torch.equal(t3, t1) and torch.equal(wp3, t3.to(torch.bfloat16))
     with pytest.raises(b.Zo2Error):
         b.op_update_perturb(t3, None, wm1, 9, 64, True, 41, 2e-3, 42, 1e-3)       # W- without W+
+
+
+@pytest.mark.parametrize("wire,scale", [("bf16", 1.0), ("f16", 1.0), ("fp8_e4m3", 64.0), ("fp8_e5m2", 1.0)])
+def test_update_with_stochastic_rounding_matches_oracle(wire, scale):
+    """theta' stored with stochastic rounding: same neighbour as the oracle wherever z's 4e-6 tolerance cannot move
+    the decision, one code apart otherwise; and the codes differ from round-to-nearest in a good share of elements."""
+    b = _b()
+    rng = np.random.default_rng(8)
+    n, e0, tid = 2 * 8192 + 1000 + 3, 8 * 555, 21
+    raw = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    theta0 = (codec.round_to(raw.astype(np.float64) * scale, wire) / np.float32(scale)).astype(np.float32)
+    c = np.float32(2.5e-4)
+    from oracle.zo_step import _fma32, _store
+    r16 = philox.rounding_bits(41, tid, e0, n)
+    want = _store(_fma32(np.float32(-c), philox.gaussian(41, tid, e0, n), theta0), wire, scale, r16)
+    nearest = _store(_fma32(np.float32(-c), philox.gaussian(41, tid, e0, n), theta0), wire, scale)
+    t_dev = (torch.from_numpy(theta0) * scale).to(WIRE[wire]).cuda()
+    b.op_update_perturb(t_dev, None, None, tid, e0, True, 41, float(c), 0, 0.0, scale=scale, stochastic=True)
+    torch.cuda.synchronize()
+    got = t_dev.float().cpu().numpy() / np.float32(scale)
+    same = got == want
+    print(wire, "identical", same.mean(), "differs from nearest", (want != nearest).mean())
+    assert same.mean() > 0.995
+    step = np.abs(codec.round_to(np.abs(want) * 1.01 + 1e-30, wire) - codec.round_to(np.abs(want) * 0.99, wire)).astype(np.float64)
+    step = np.maximum(step, {"f16": 2.0 ** -24, "fp8_e4m3": 2.0 ** -9, "fp8_e5m2": 2.0 ** -16}.get(wire, 1e-12)) / scale
+    assert np.all(np.abs(got.astype(np.float64) - want) <= step * 1.01 + 1e-12)
+    assert (want != nearest).mean() > 0.05
+    # the stored values are representable: rounding them again changes nothing
+    assert np.array_equal(codec.round_to(got.astype(np.float64) * scale, wire) / np.float32(scale), got)

@@ -81,3 +81,54 @@ def test_overflow_rules_and_idempotence():
     for fmt in ("bf16", "f16", "fp8_e4m3", "fp8_e5m2"):
         once = codec.round_to(x, fmt)
         assert np.array_equal(codec.round_to(once, fmt), once)
+
+
+TD = {"bf16": torch.bfloat16, "f16": torch.float16, "fp8_e4m3": torch.float8_e4m3fn, "fp8_e5m2": torch.float8_e5m2}
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16", "fp8_e4m3", "fp8_e5m2"])
+def test_stochastic_rounding_brackets_and_is_unbiased(fmt):
+    """Every outcome is one of the two representable neighbours of x (found with torch's CPU cast and its bit
+    pattern, not with the oracle's table), the largest r16 truncates toward zero, a representable x never moves, and the
+    mean over all 65536 values of r16 is x to within gap / 65536."""
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(40) * 0.3).astype(np.float32)
+    x[:4] = [0.0, -0.0, 1.0, -0.375]                                          # representable in every format
+    # neighbours from torch: nearest value, then step one code towards / away from zero
+    t = torch.from_numpy(x).to(TD[fmt])
+    bits = t.view(torch.uint8 if fmt.startswith("fp8") else torch.int16).to(torch.int32)
+    mag = bits & (0x7F if fmt.startswith("fp8") else 0x7FFF)
+    near = t.to(torch.float32).abs().numpy().astype(np.float64)
+    def val(m):
+        m = m.to(torch.uint8 if fmt.startswith("fp8") else torch.int16)
+        return m.view(TD[fmt]).to(torch.float32).numpy().astype(np.float64)
+    a = np.abs(x).astype(np.float64)
+    lo = np.where(near > a, val(torch.clamp(mag - 1, min=0)), near)
+    hi = np.where(near > a, near, np.where(near == a, near, val(mag + 1)))
+    r_all = np.arange(65536)
+    for i in range(x.size):
+        out = codec.round_stochastic(np.full(65536, x[i], dtype=np.float32), fmt, r_all).astype(np.float64)
+        assert set(np.unique(np.abs(out))) <= {lo[i], hi[i]}, (fmt, x[i])
+        assert np.all(np.signbit(out) == np.signbit(x[i])) or a[i] == 0
+        if hi[i] > lo[i] and (a[i] - lo[i]) / (hi[i] - lo[i]) <= 65535 / 65536:
+            assert abs(out[65535]) == lo[i]                                    # largest r16: toward zero
+        assert abs(out.mean() - x[i]) <= (hi[i] - lo[i]) / 65536 + 1e-300
+        if lo[i] == hi[i]:
+            assert np.all(out == x[i])
+    # saturation and NaN
+    big = np.finfo(np.float32).max                                            # above every format's largest finite value
+    _, vals = codec._finite_table(fmt)
+    assert float(codec.round_stochastic(big, fmt, 65535)) == float(np.float32(vals[-1]))
+    assert np.isnan(codec.round_stochastic(np.float32("nan"), fmt, 7))
+
+
+def test_stochastic_rounding_bf16_is_the_add_and_truncate_rule():
+    """For bfloat16 the dropped 16 bits of the float32 pattern are the fraction itself: rounding up iff
+    r16 < fraction is adding (65535 - r16) to the pattern and cutting the low half off."""
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal(5000) * 0.05).astype(np.float32)
+    r16 = rng.integers(0, 65536, size=x.size)
+    bits = x.view(np.uint32).astype(np.uint64)
+    want = (((bits + (65535 - r16).astype(np.uint64)) & np.uint64(0xFFFF0000)).astype(np.uint32)).view(np.float32)
+    got = codec.round_stochastic(x, "bf16", r16)
+    assert np.array_equal(got, want)

@@ -98,3 +98,20 @@ def test_gaussian_distribution():
     assert abs(np.mean(z[0::4] * z[2::4])) < lim * 2
     assert abs(np.mean(z * z_t)) < lim
     assert abs(np.mean(z * z_s)) < lim
+
+
+def test_rounding_bits_are_a_separate_uniform_stream():
+    """The 16-bit rounding draws come from the same generator with the last counter word set to 1: halves of the
+    words of call e >> 3, uniform, window-invariant, and unrelated to the words z is drawn from."""
+    seed, tid = 1234567, 9
+    r = philox.rounding_bits(seed, tid, 0, 1 << 16).astype(np.int64)
+    for e in (0, 1, 6, 7, 8, 13, 4095):
+        q = e >> 3
+        x = philox.philox4x32_10(q, 0, tid, 1, seed & 0xFFFFFFFF, seed >> 32)
+        w = int(np.asarray(x[(e >> 1) & 3]).reshape(-1)[0])
+        assert int(r[e]) == (w >> (16 * (e & 1))) & 0xFFFF
+    assert np.array_equal(r[100:177], philox.rounding_bits(seed, tid, 100, 77))
+    assert abs(r.mean() / 65535 - 0.5) < 4 / np.sqrt(12 * r.size)
+    assert stats.kstest(r / 65536.0, "uniform").pvalue > 1e-3
+    zw = philox.random_words(seed, tid, 0, 1 << 15).astype(np.int64)             # the stream z uses (counter word 0)
+    assert abs(np.corrcoef(r[0::2], zw & 0xFFFF)[0, 1]) < 5 / np.sqrt(zw.size)

@@ -165,3 +165,36 @@ def test_low_bit_storage_step_keeps_parameters_representable():
         assert np.array_equal(Pa[n], Pb[n])
         assert np.array_equal(codec.round_to(Pa[n], "bf16"), Pa[n])
     assert any(not np.array_equal(Pa[n], P[n]) for n in P)
+
+
+def test_stochastic_rounding_lets_a_bf16_master_follow_small_updates():
+    """With round-to-nearest a bfloat16 master ignores an update far below half its spacing (the situation at the
+    paper's lr = 1e-7); with stochastic rounding the stored parameters follow the float32 trajectory on average."""
+    from oracle import codec
+    cfg, s, P, tok, lab = _setup()
+    P16 = {n: codec.round_to(a, "bf16") for n, a in P.items()}
+    runs = {}
+    for mode in ("nearest", "stochastic"):
+        zo = zo_step.Zo2Blockwise(s, copy.deepcopy(P16), store="bf16", compute="bf16", rounding=mode)
+        for j in range(6):
+            zo.step(tok, lab, 300 + j, 1e-3, 2e-6)
+        zo.flush()
+        runs[mode] = zo.P
+    ref = zo_step.Zo2Blockwise(s, copy.deepcopy(P16), store="f32", compute="bf16")
+    for j in range(6):
+        ref.step(tok, lab, 300 + j, 1e-3, 2e-6)
+    ref.flush()
+    n = "blocks.0.fc1.w"
+    moved = ref.P[n] - P16[n]                                   # the float32 master's total displacement
+    sp = np.spacing(np.abs(P16[n]).astype(np.float32)).astype(np.float64) * 65536                  # bfloat16 spacing at each element
+    assert np.median(np.abs(moved) / sp) < 0.1                  # typical displacement: far below one bf16 step
+    d_near = runs["nearest"][n] - P16[n]
+    d_sr = runs["stochastic"][n] - P16[n]
+    print(np.count_nonzero(d_near), np.count_nonzero(d_sr), d_near.size)
+    assert np.count_nonzero(d_near) < 0.03 * d_near.size       # nearest: only elements close to zero (fine spacing) move
+    assert np.count_nonzero(d_sr) > 0
+    # summed over many elements, the stochastic master's displacement tracks the float32 one (unbiased)
+    proj = lambda d: float(np.sum(d.astype(np.float64) * np.sign(moved)))
+    print(proj(d_sr), proj(d_near), proj(moved))
+    assert abs(proj(d_sr) - proj(moved)) < 0.5 * proj(moved)
+    assert proj(d_near) < 0.1 * proj(moved)

@@ -22,7 +22,7 @@ static constexpr int kChunk = kThreads * kPerLane * kIters;   // 8192 elements p
 
 // The arithmetic of one group of 8 consecutive elements (one Philox call q per random stream): tv holds
 // theta on entry and theta' on return.
-template <typename W, typename C, bool UPDATE, bool PERTURB>
+template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR>
 __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, uint64_t q, float c, float eps, float scale,
                                          float inv_scale, Vec<W, kPerLane>& tv, Vec<C, kPerLane>& p, Vec<C, kPerLane>& m) {
     constexpr bool kScaled = (Fmt<W>::kBytes == 1);
@@ -36,7 +36,7 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
         float zp[kPerLane];
         gaussian8(a.k_prev, tensor_id, q, zp);
         uint32_t rw[4] = {0u, 0u, 0u, 0u};
-        const bool sr = Fmt<W>::kBytes < 4 && a.stochastic != 0;
+        constexpr bool sr = SR && Fmt<W>::kBytes < 4;
         if (sr) rounding_words(a.k_prev, tensor_id, q, rw);
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -63,7 +63,7 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
     }
 }
 
-template <typename W, typename C, bool UPDATE, bool PERTURB>
+template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR>
 __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
     // which tensor does this workgroup work on: first_chunk[] ascends (0xffffffff past the last segment),
     // so the segment index is the number of entries at or below this workgroup's index
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
         for (int it = 0; it < kIters; ++it) {
             const uint64_t i = i0 + (uint64_t)it * kStride;
             Vec<C, kPerLane> p, m;
-            k1_group<W, C, UPDATE, PERTURB>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
+            k1_group<W, C, UPDATE, PERTURB, SR>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
             if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i, p);
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
             for (int j = 0; j < kPerLane; ++j) tv.v[j] = (j < valid) ? theta[i0 + j] : Fmt<W>::store(0.f);
         }
         Vec<C, kPerLane> p, m;
-        k1_group<W, C, UPDATE, PERTURB>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
+        k1_group<W, C, UPDATE, PERTURB, SR>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
         if (valid == kPerLane) {
             if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
             if (PERTURB) {
@@ -136,9 +136,12 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
 template <typename W, typename C>
 static zo2_status launch_wc(const K1Args& a, bool update, bool perturb, hipStream_t st) {
     const dim3 grid(a.total_chunks), block(kThreads);
-    if (update && perturb) hipLaunchKernelGGL((k1_kernel<W, C, true, true>), grid, block, 0, st, a);
-    else if (update) hipLaunchKernelGGL((k1_kernel<W, C, true, false>), grid, block, 0, st, a);
-    else if (perturb) hipLaunchKernelGGL((k1_kernel<W, C, false, true>), grid, block, 0, st, a);
+    const bool sr = update && a.stochastic != 0 && sizeof(W) < 4;      // stochastic rounding only concerns a low-bit theta'
+    if (update && perturb && sr) hipLaunchKernelGGL((k1_kernel<W, C, true, true, true>), grid, block, 0, st, a);
+    else if (update && perturb) hipLaunchKernelGGL((k1_kernel<W, C, true, true, false>), grid, block, 0, st, a);
+    else if (update && sr) hipLaunchKernelGGL((k1_kernel<W, C, true, false, true>), grid, block, 0, st, a);
+    else if (update) hipLaunchKernelGGL((k1_kernel<W, C, true, false, false>), grid, block, 0, st, a);
+    else if (perturb) hipLaunchKernelGGL((k1_kernel<W, C, false, true, false>), grid, block, 0, st, a);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
 }

@@ -149,7 +149,7 @@ def main():
                                f"ffn {cfg['d_ffn']}, vocab {cfg['vocab']}), bf16 weights resident in HBM, batch {BATCH} x seq {SEQ}, "
                                f"Zipf(1.1) tokens, eps {EPS}, lr {LR}",
                    "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"]},
-        "roofline": {"kernel": "gemm_mfma_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
+        "roofline": {"kernel": "gemm_mfma256_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
                      "achieved": tflops, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_MFMA,
                      "traffic": (PMC_GEMM_BYTES_PER_STEP / (gemm_n / args.steps)) if (gemm_n and args.layers is None) else None,
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, calibrated, offline)",

@@ -331,8 +331,12 @@ zo2_status attention_launch(int dtype, const void* q, const void* k, const void*
     ZO2_OP_CHECK(q && k && v && out, ZO2_EINVAL, "attention: NULL buffer");
     ZO2_OP_CHECK(ld >= (int64_t)n_heads * d_head && ld % 8 == 0, ZO2_EINVAL, "attention: bad leading dimension");
     ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535, ZO2_EINVAL, "attention: grid too large");
+    {   // every kernel moves groups of 8 elements
+        const uintptr_t align = 8 * (uintptr_t)zo2_dtype_size(dtype);
+        ZO2_OP_CHECK(align != 0 && ((uintptr_t)q % align) == 0 && ((uintptr_t)k % align) == 0 && ((uintptr_t)v % align) == 0 &&
+                     ((uintptr_t)out % align) == 0, ZO2_EINVAL, "attention: unknown dtype, or operands not aligned to 8 elements");
+    }
     if (!vector_kernel && dtype != ZO2_F32 && (d_head == 64 || d_head == 80 || d_head == 128)) {
-        ZO2_OP_CHECK((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) == 0, ZO2_EINVAL, "attention: operands must be 16-byte aligned");
         if (dtype == ZO2_BF16)
             return launch_mfma_att<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, n_seq, seq, n_heads, d_head, ld, st);
         return launch_mfma_att<f16_t>((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, (f16_t*)out, n_seq, seq, n_heads, d_head, ld, st);

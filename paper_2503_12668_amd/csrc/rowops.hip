@@ -243,6 +243,11 @@ zo2_status layernorm(int dtype, const float* x, const void* w, const void* b, co
     ZO2_OP_CHECK(rows > 0 && d > 0 && d % 4 == 0, ZO2_EINVAL, "layernorm: rows %d, d %d (d must be a multiple of 4)", rows, d);
     ZO2_OP_CHECK(x && w && b && y, ZO2_EINVAL, "layernorm: NULL buffer");
     ZO2_OP_CHECK(rows_first >= rows || (w2 && b2), ZO2_EINVAL, "layernorm: second gain / bias missing");
+    {   // rows are moved in groups of 4 elements
+        const uintptr_t ca = 4 * (uintptr_t)zo2_dtype_size(dtype);
+        ZO2_OP_CHECK(ca != 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % ca) == 0 && ((uintptr_t)w % ca) == 0 && ((uintptr_t)b % ca) == 0 &&
+                     ((uintptr_t)w2 % ca) == 0 && ((uintptr_t)b2 % ca) == 0, ZO2_EINVAL, "layernorm: unknown dtype, or buffers not aligned to 4 elements");
+    }
     ZO2_DISPATCH_COMPUTE(dtype, C, {
         if (d <= 8 * 64 * 4)
             hipLaunchKernelGGL((layernorm_wave_kernel<C, 8>), dim3((rows + 3) / 4), dim3(256), 0, st, x, (const C*)w, (const C*)b,

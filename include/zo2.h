@@ -270,7 +270,7 @@ zo2_status zo2_op_cross_entropy_rows(const float* logits, int64_t ld, const int3
  * W [N, ldw] (row n = vocabulary entry n) of `dtype` (BF16 or F16),
  *   row_loss[r] = logsumexp_n(X[r, :] . W[n, :]) - X[r, :] . W[labels[r], :],   0 if labels[r] = -100.
  * The GEMM epilogue reduces every 64-column span of a row to (max, sum exp) in float32; a second
- * kernel merges the spans.  Needs M, N >= 256, K % 64 == 0, N % 4 == 0, 16-byte aligned operands
+ * kernel merges the spans.  Needs M, N >= 256, K % 128 == 0, N % 4 == 0, 16-byte aligned operands
  * (ZO2_EINVAL otherwise) and a 256-byte aligned device workspace of at least
  * zo2_op_lm_head_ce_workspace_bytes(M, N) bytes.  labels: device int32 [M]; row_loss: device float [M]. */
 zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx,

@@ -230,7 +230,7 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
     // cross-entropy mode has no output matrix (Y may be NULL): only the 256 x 256 kernel implements it, so every
     // other path must be refused before anything is launched
     ZO2_OP_CHECK(!a.ce_mode || (dtype != ZO2_F32 && gemm256_applicable(a, dtype)), ZO2_EINVAL,
-                 "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 64 == 0, M, N >= 256, N %% 4 == 0)");
+                 "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 128 == 0, M, N >= 256, N %% 4 == 0)");
     if (dtype == ZO2_F32) {
         ZO2_OP_CHECK(a.out_f32, ZO2_EINVAL, "gemm: the float32 kernel writes float32 output");
         const unsigned tiles = (unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64));

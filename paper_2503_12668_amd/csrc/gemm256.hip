@@ -1,6 +1,8 @@
 // Large-tile MFMA GEMM for the big projections: 256 x 256 x 64 block tile, four wavefronts
-// (2 x 2), each owning 128 x 128 = 4 x 4 MFMA tiles of 32 x 32 with float32 accumulators in
-// the accumulation registers.  One workgroup per compute unit.
+// (2 x 2), each owning 128 x 128 = 8 x 8 MFMA tiles of 16 x 16 (v_mfma_f32_16x16x32) with float32
+// accumulators in the accumulation registers.  One workgroup per compute unit.  (Under this kernel's
+// full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip sustains a higher clock with
+// the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster in an MFMA-only loop.)
 //
 // Data path: global memory -> LDS with the direct-to-LDS loads of gfx950 (16 bytes per
 // lane, no staging through vector registers), two LDS stages of 64 KB, 128-bit LDS reads
@@ -9,7 +11,7 @@
 // at LDS offset 16 i, the swizzle is applied on the global side: lane i fetches the chunk that
 // belongs at position i.
 //
-// Requires K % 64 == 0, N % 4 == 0, ldy % 4 == 0 and 16-byte aligned Y / residual (gemm256_applicable);
+// Requires K % 128 == 0 (an even number of k-slabs), N % 4 == 0, ldy % 4 == 0 and 16-byte aligned Y / residual (gemm256_applicable);
 // M and N are otherwise arbitrary (rows are clamped on load, masked on store).
 #include <type_traits>
 
@@ -19,24 +21,26 @@ namespace zo2 {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-template <typename T> struct Mfma32;
-template <> struct Mfma32<bf16_t> {
-    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+// D[16 x 16] += A[16 x 32] B[32 x 16]: lane l supplies row (l & 15), k = 8 (l >> 4) .. + 7 of both operands and
+// receives D[4 (l >> 4) + e][l & 15], e = 0..3.  Written as inline assembly with the accumulator tied to an
+// accumulation-register tuple ("+a"): left to the register allocator, some of the 64 accumulator tuples end up in
+// ordinary vector registers and are copied back and forth on every k-slab.  The compiler does not see an MFMA
+// here, so the kernel itself keeps the required distance between the last MFMA and the first read of a result.
+template <typename T> struct Mfma16;
+template <> struct Mfma16<bf16_t> {
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x4_t& c) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
     }
 };
-template <> struct Mfma32<f16_t> {
-    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+template <> struct Mfma16<f16_t> {
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x4_t& c) {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
     }
 };
 
-// Measurement hooks for a stand-alone timing harness (never defined in the library build):
-//   ZO2_GEMM_EXP_TIMING  cycle-counter stamps at tile start / end of main loop / end of epilogue, and the cycles
-//                        spent at the k-slab barrier, written through problem slot 5's residual pointer;
-//   ZO2_GEMM_EXP_NODMA   no direct-to-LDS loads after a tile's first slab;  ZO2_GEMM_EXP_NOREAD  no LDS fragment reads.
 static constexpr int kBM = 256, kBN = 256, kBK = 64;
 static constexpr int kStageBytes = (kBM + kBN) * kBK * 2;      // 65536
 static constexpr int kEpiRegion = 24576;                       // per-wave output staging above stage 0
@@ -51,6 +55,27 @@ __device__ __forceinline__ const void* uniform_ptr(const void* p) {   // pin a w
 }
 __device__ __forceinline__ void load_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+
+// The same load split into its pieces, for the main loop: there every instruction of a wavefront competes with its
+// MFMAs for issue slots, so the LDS destination register is stepped with one scalar add (instead of being recomputed
+// and moved), and the MFMA issued between the write of m0 and the load takes the place of the wait state they need.
+__device__ __forceinline__ void m0_set(uint32_t lds_base) { asm volatile("s_mov_b32 m0, %0" : : "s"(lds_base) : "memory"); }
+template <uint32_t DELTA>
+__device__ __forceinline__ void m0_step() { asm volatile("s_add_u32 m0, m0, %0" : : "i"(DELTA) : "memory", "scc"); }
+// `lanes` (wave-uniform: all ones or zero) is the execution mask of the load: zero turns it into a no-op without a
+// branch, so that the compiler sees straight-line code and keeps one register assignment for the accumulators over the
+// whole k loop (see Mfma16).  The k loop runs with all 64 lanes active, which is what the mask is restored to.
+__device__ __forceinline__ void load_to_lds_at_m0_masked(const void* sbase, uint32_t voff, uint64_t lanes) {
+    asm volatile("s_mov_b64 exec, %2\n\tglobal_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1" : : "v"(voff), "s"(sbase), "s"(lanes) : "memory");
+}
+
+// The lane index, derived anew from the execution mask (all 64 lanes active) through an operand the compiler cannot
+// see through: values computed from it cannot be hoisted out of the loop that contains the call.
+__device__ __forceinline__ int fresh_lane_id() {
+    uint32_t ones = 0xffffffffu;
+    asm volatile("" : "+s"(ones));
+    return (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
 }
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row
@@ -86,18 +111,28 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     const int G = gridDim.x;
     const int slot = (G % 8 == 0) ? (int)((blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane_id = tid & 63, lane = lane_id;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, r = lane & 31, kh = lane >> 5;
-    const int lrow = lane >> 3;
+    const int wm = wave >> 1, wn = wave & 1, r = lane & 15, kg = lane >> 4;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
     const uint32_t ld_a = lds0 + wave * 8192, ld_b = lds0 + 32768 + wave * 8192;
-    // fragment read plan: row (w*128 + i*32 + r), chunk (2 ks + kh) ^ swz(row); swz(row) = swz(r)
+    // fragment read plan: row (w*128 + i*16 + r), chunk (4 ks + kg) ^ swz(row); swz(row) = swz(r); two k-steps of 32 per slab
     const uint32_t fr_a = (wm * 128 + r) * 128, fr_b = 32768 + (wn * 128 + r) * 128;
-    uint32_t koff[4];
+    uint32_t koff[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[ks] = (uint32_t)(((ks * 2 + kh) ^ swz(r)) * 16);
+    for (int ks = 0; ks < 2; ++ks) koff[ks] = (uint32_t)(((ks * 4 + kg) ^ swz(r)) * 16);
+    // where this lane's X / W fragments of k-step ks sit in stage st: fixed for the whole kernel, so that the
+    // k-slab loop (unrolled by two, one copy per stage) contains no address arithmetic at all
+    const char* frag_x[2][2];
+    const char* frag_w[2][2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            frag_x[st][ks] = smem + st * kStageBytes + fr_a + koff[ks];
+            frag_w[st][ks] = smem + st * kStageBytes + fr_b + koff[ks];
+        }
     const int nk = a.K / kBK;
 
     // loader plan: per stage each wavefront brings 64 rows of A and 64 rows of B, 8 rows per
@@ -108,6 +143,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     const T* base_w;
     auto plan_loads = [&](const TileCoord& tc) {
         const GemmProblem& pp = a.p[tc.prob];
+        // (a freshly derived lane index: this arithmetic is redone per tile instead of being kept in registers, or
+        // spilled, across the k loop)
+        const int lane = fresh_lane_id();
+        const int lrow = lane >> 3;
         base_x = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.X) + (size_t)tc.m0 * a.ldx));
         base_w = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.W) + (size_t)tc.n0 * a.ldw));
         const int mrem = a.M - 1 - tc.m0, nrem = a.N - 1 - tc.n0;
@@ -133,129 +172,106 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     plan_loads(tc);
     issue_slab0();
 
-#ifdef ZO2_GEMM_EXP_TIMING
-    unsigned long long* tlog = (unsigned long long*)a.p[GemmArgs::kMaxProblems - 1].residual;
-    int tcount = 0;
-    unsigned long long wait_vm = 0, wait_lds = 0, wait_bar = 0;
-#define TSTAMP() do { if (blockIdx.x == 0 && threadIdx.x == 0 && tcount < 60) tlog[tcount++] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define TSTAMP() do { } while (0)
-#endif
     for (;;) {
-        TSTAMP();
-        // acc[i][j]: X rows (m) i-th 32-block, W rows (n) j-th 32-block.  The W fragment is the
-        // MFMA "A" operand, so a lane ends up with one m (= r) and runs of 4 consecutive n.
-        f32x16_t acc[4][4];
+        // acc[i][j]: X rows (m) i-th 16-block, W rows (n) j-th 16-block.  The W fragment is the
+        // MFMA "A" operand, so a lane ends up with one m (= r) and a run of 4 consecutive n (4 kg ..).
+        f32x4_t acc[8][8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int j = 0; j < 8; ++j)
+                acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        uint4 fa[2][4], fb[2][4];
-        // One "group" = the four MFMAs of X row-block i at k-step buffer `buf`, preceded by the two
-        // LDS reads that fetch row-block i of both operands for the next k-step into buffer `nbuf`,
-        // and optionally two direct-to-LDS loads of a later k-slab.
-        // (Issuing the reads one group earlier, or the W fragments before the X fragments, was tried: no gain.)
-        auto mgroup = [&](int i, int buf, int nbuf, bool do_read, const char* sa, const char* sb, bool do_dma, int dma_stage, int dma_k0, int dma_t) {
-            // With one wavefront per SIMD every instruction takes an issue slot of this wavefront, and only about
-            // seven fit under one MFMA: the memory instructions are dealt out one piece per MFMA (scheduling
-            // barriers pin them there) instead of standing together between two groups.
-            const uint32_t so = dma_stage * kStageBytes;
-            acc[i][0] = Mfma32<T>::run(fb[buf][0], fa[buf][i], acc[i][0]);
+        uint4 fa[8], fb[2][8];      // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
+        // One "group" = the eight MFMAs of X row-block i at k-step buffer `buf`, with the two LDS reads
+        // that fetch row-block i of both operands for the next k-step into buffer `nbuf` and optionally
+        // two direct-to-LDS loads of a later k-slab dealt out between them.  With one wavefront per SIMD
+        // every instruction takes an issue slot of this wavefront and only about three fit under one
+        // 16-cycle MFMA: scheduling barriers pin one piece of memory work behind each of the first MFMAs.
+        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool do_dma, uint64_t dma_lanes, int dma_stage, int dma_k0) {
+            // do_dma: direct-to-LDS loads of rows 8 i .. 8 i + 7 (of this wavefront's 64) of both operands of a later
+            // slab; their LDS destinations follow each other as X_0, W_0, X_1, W_1, ...: + 32768, - 31744, + 32768 ...
+            Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) load_to_lds(base_x + dma_k0, pa[dma_t], ld_a + so + dma_t * 1024);
+            if (do_dma) { if (i == 0) m0_set(ld_a + dma_stage * kStageBytes); else m0_step<0xffff8400u>(); }
             __builtin_amdgcn_sched_barrier(0);
-            acc[i][1] = Mfma32<T>::run(fb[buf][1], fa[buf][i], acc[i][1]);
+            Mfma16<T>::run(fb[buf][1], fa[i], acc[i][1]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) load_to_lds(base_w + dma_k0, pb[dma_t], ld_b + so + dma_t * 1024);
+            if (do_dma) load_to_lds_at_m0_masked(base_x + dma_k0, pa[i], dma_lanes);
             __builtin_amdgcn_sched_barrier(0);
-            acc[i][2] = Mfma32<T>::run(fb[buf][2], fa[buf][i], acc[i][2]);
+            Mfma16<T>::run(fb[buf][2], fa[i], acc[i][2]);
             __builtin_amdgcn_sched_barrier(0);
-#ifndef ZO2_GEMM_EXP_NOREAD
-            if (do_read) {
-                fa[nbuf][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
-                fb[nbuf][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
-            }
-#endif
+            if (do_dma) m0_step<0x8000u>();
             __builtin_amdgcn_sched_barrier(0);
-            acc[i][3] = Mfma32<T>::run(fb[buf][3], fa[buf][i], acc[i][3]);
+            Mfma16<T>::run(fb[buf][3], fa[i], acc[i][3]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i], dma_lanes);
+            __builtin_amdgcn_sched_barrier(0);
+            Mfma16<T>::run(fb[buf][4], fa[i], acc[i][4]);
+            __builtin_amdgcn_sched_barrier(0);
+            fb[nbuf][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
+            __builtin_amdgcn_sched_barrier(0);
+            Mfma16<T>::run(fb[buf][5], fa[i], acc[i][5]);
+            Mfma16<T>::run(fb[buf][6], fa[i], acc[i][6]);
+            Mfma16<T>::run(fb[buf][7], fa[i], acc[i][7]);
+            __builtin_amdgcn_sched_barrier(0);
+            fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);      // this group's X fragment is free now
             __builtin_amdgcn_sched_barrier(0);
         };
 
         // k-slab 0 of this tile is in flight into stage 0 (issued before the loop or under the
         // previous tile's epilogue): wait, publish, read the first fragments
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // (as a builtin, not an assembly statement: the compiler's own wait-count bookkeeping must learn that no
+        // load of the previous tile's epilogue is outstanding any more, or it protects the first register the k loop
+        // overwrites with a vmcnt(0) of its own - which there also waits for the loads issued one k-step earlier)
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), other counters untouched
+        asm volatile("" ::: "memory");
         __syncthreads();
         {
-            const char* sa = smem + fr_a + koff[0];
-            const char* sb = smem + fr_b + koff[0];
+            const char* sa = frag_x[0][0];
+            const char* sb = frag_w[0][0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                fa[0][i] = *reinterpret_cast<const uint4*>(sa + i * 4096);
-                fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 4096);
+            for (int i = 0; i < 8; ++i) {
+                fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);
+                fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
             }
         }
-        // Direct-to-LDS loads of slab kt+1 are split in two halves: row-blocks t = 0..3 are issued
-        // under k-step 3 of slab kt-1 (right after the barrier that retired their stage), t = 4..7
-        // under k-step 0 of slab kt; they then have k-steps 1 and 2 to land before the barrier.
-        // NEXT1: slab kt+1 exists (second half of its loads; its first fragments are read under
-        // k-step 3); NEXT2: slab kt+2 exists (first half of its loads).  Compile-time so that no
-        // group carries a branch.
-        auto slab_iter = [&](int kt, auto next1_c, auto next2_c) {
-            constexpr bool next1 = decltype(next1_c)::value, next2 = decltype(next2_c)::value;
-#ifdef ZO2_GEMM_EXP_NODMA
-            constexpr bool dma1 = false, dma2 = false;
-#else
-            constexpr bool dma1 = next1, dma2 = next2;
-#endif
-            const int cur = kt & 1;
-            const char* base_a = smem + cur * kStageBytes + fr_a;
-            const char* base_b = smem + cur * kStageBytes + fr_b;
+        // A slab is two k-steps of 32.  Under k-step 0 the fragments of k-step 1 are read; then one barrier
+        // (publishes slab kt+1: every wavefront waited for its own loads; retires stage cur: every wavefront
+        // has its last fragments in registers); under k-step 1 the first fragments of slab kt+1 are read and
+        // all direct-to-LDS loads of slab kt+2 are issued into the retired stage, so that they have k-step 0
+        // of the next slab to land.  Every slab runs the same instructions: where slab kt+2 does not exist the
+        // loads run with an empty execution mask (more_slabs == 0), and where slab kt+1 does not exist
+        // the fragment reads fetch bytes nobody uses.  A separate copy of the loop body for the last slabs
+        // would invite the compiler to give the accumulators another register assignment there and to move
+        // them between MFMAs that it does not know to be MFMAs.
+        auto slab_iter = [&](int kt, auto stage_c, uint64_t more_slabs) {
+            constexpr int cur = decltype(stage_c)::value;          // kt & 1
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[1], base_b + koff[1], dma1, cur ^ 1, (kt + 1) * kBK, 4 + i);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, true, base_a + koff[2], base_b + koff[2], false, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 0, 1, true, base_a + koff[3], base_b + koff[3], false, 0, 0, 0);
-            // one barrier per slab: publishes slab kt+1 (every wavefront waited for its own loads)
-            // and retires stage cur (every wavefront has its last fragments in registers)
-#ifdef ZO2_GEMM_EXP_TIMING
-            const unsigned long long w0 = __builtin_amdgcn_s_memtime();
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            const unsigned long long w1 = __builtin_amdgcn_s_memtime();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            const unsigned long long w2 = __builtin_amdgcn_s_memtime();
-            __syncthreads();
-            const unsigned long long w3 = __builtin_amdgcn_s_memtime();
-            wait_vm += w1 - w0; wait_lds += w2 - w1; wait_bar += w3 - w2;
-#else
+            for (int i = 0; i < 8; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0ull, 0, 0);
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __syncthreads();
-#endif
-            const char* next_a = smem + (cur ^ 1) * kStageBytes + fr_a + koff[0];
-            const char* next_b = smem + (cur ^ 1) * kStageBytes + fr_b + koff[0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mgroup(i, 1, 0, next1, next_a, next_b, dma2, cur, (kt + 2) * kBK, i);
+            for (int i = 0; i < 8; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, more_slabs, cur, (kt + 2) * kBK);
         };
-#ifndef ZO2_GEMM_EXP_NODMA
-        if (nk > 1) {                    // first half of slab 1 (stage 1 is free once the barrier above is passed)
+        {                                // slab 1 (stage 1 is free once the barrier above is passed)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < 8; ++t) {
                 load_to_lds(base_x + kBK, pa[t], ld_a + kStageBytes + t * 1024);
                 load_to_lds(base_w + kBK, pb[t], ld_b + kStageBytes + t * 1024);
             }
         }
-#endif
-        TSTAMP();
-        for (int kt = 0; kt + 2 < nk; ++kt) slab_iter(kt, std::true_type{}, std::true_type{});
-        if (nk > 1) slab_iter(nk - 2, std::true_type{}, std::false_type{});
-        slab_iter(nk - 1, std::false_type{}, std::false_type{});
-        TSTAMP();
-#ifdef ZO2_GEMM_EXP_TIMING
-        if (blockIdx.x == 0 && threadIdx.x == 0) { tlog[60] = wait_vm; tlog[61] = wait_lds; tlog[62] = wait_bar; }
-#endif
+        // nk is even (K % 128 == 0): slabs alternate between the two stages, two per trip
+        using St0 = std::integral_constant<int, 0>;
+        using St1 = std::integral_constant<int, 1>;
+        for (int kt = 0; kt < nk; kt += 2) {
+            const uint32_t m32 = __builtin_amdgcn_readfirstlane(kt + 2 < nk ? 0xffffffffu : 0u);
+            const uint64_t more = ((uint64_t)m32 << 32) | m32;
+            slab_iter(kt, St0{}, more);
+            slab_iter(kt + 1, St1{}, more);
+        }
+        // the last MFMAs' results must have left the pipeline before the epilogue reads them (see Mfma16)
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
         // Both stages are free now (all fragment reads are behind the last barrier).  Start the
         // next tile's k-slab 0 into stage 0 so that its latency hides under this tile's epilogue,
@@ -271,7 +287,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         }
         vid = next_vid;
 
-        // ---- epilogue.  For tile (i, j) a lane holds row m = r and columns 8 q + 4 kh + (0..3).
+        // ---- epilogue.  For MFMA tile (i, j) a lane holds row m = 16 i + r and columns 16 j + 4 kg + (0..3).
         // Writing that straight to memory would touch 32 different cache lines per store with 8-16
         // bytes each; instead every wavefront parks its sub-tile, 32 rows at a time and still in
         // float32, in its own LDS region and reads it back so that a lane owns 4 consecutive
@@ -279,27 +295,29 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         // once per lane) and a store covers complete cache lines.
         const T* __restrict__ bias = reinterpret_cast<const T*>(p.bias);
         OutT* __restrict__ Y = reinterpret_cast<OutT*>(p.Y);
+        // the epilogue's many per-lane offsets derive from the lane index; recomputing them per tile (see plan_loads)
+        // keeps them out of the k loop's register budget
+        const int lane = fresh_lane_id();
+        const int r = lane & 15, kg = lane >> 4;
         if constexpr (sizeof(OutT) == 2) {
-            // 16-bit output without residual (QKV, FC1): finish the values in registers (the 16 bias
+            // 16-bit output without residual (QKV, FC1): finish the values in registers (the 8 bias
             // vectors a lane needs are fetched together up front), park them in LDS as 16-bit values,
             // two 32-row passes in flight (double-buffered region), and store 16 bytes per lane.
             constexpr int ROWH = 128 * 2 + 16;                     // padded 16-bit row
             char* reg = smem + kStageBytes + wave * kEpiRegion;
-            const float lower = a.relu ? 0.f : -INFINITY;
+            const float lower = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(a.relu ? 0u : 0xff800000u));   // 0 or -inf, in a scalar register
             const float sc = p.out_scale;
-            float bvv[4][4][4];
+            float bvv[8][4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 8; ++j) {
+                const int n = n0 + wn * 128 + j * 16 + 4 * kg;
+                Vec<T, 4> b4;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + wn * 128 + j * 32 + 8 * q + 4 * kh;
-                    Vec<T, 4> b4;
+                for (int e = 0; e < 4; ++e) b4.v[e] = Fmt<T>::store(0.f);
+                if (bias && n < a.N) b4 = load_vec<T, 4>(bias + n);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) b4.v[e] = Fmt<T>::store(0.f);
-                    if (bias && n < a.N) b4 = load_vec<T, 4>(bias + n);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) bvv[j][q][e] = Fmt<T>::load(b4.v[e]) * sc;      // (acc + b) s = acc s + b s: one FMA per value
-                }
+                for (int e = 0; e < 4; ++e) bvv[j][e] = Fmt<T>::load(b4.v[e]) * sc;      // (acc + b) s = acc s + b s: one FMA per value
+            }
             const int rr = lane >> 4, ch = lane & 15;              // 4 rows x 16 pieces of 8 elements per store
             const int n = n0 + wn * 128 + ch * 8;
             const bool n_ok = n < a.N;                             // N % 8 == 0 is required for this path
@@ -308,14 +326,14 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             for (int i = 0; i < 4; ++i) {
                 char* buf = reg + (i & 1) * (32 * ROWH);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int mb = 0; mb < 2; ++mb)                 // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
+                    for (int j = 0; j < 8; ++j) {
                         Vec<OutT, 4> ov;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            ov.v[e] = Fmt<OutT>::store(fmaxf(__builtin_fmaf(acc[i][j][4 * q + e], sc, bvv[j][q][e]), lower));
-                        store_vec<OutT, 4>(reinterpret_cast<OutT*>(buf + r * ROWH) + j * 32 + 8 * q + 4 * kh, ov);
+                            ov.v[e] = Fmt<OutT>::store(fmaxf(__builtin_fmaf(acc[2 * i + mb][j][e], sc, bvv[j][e]), lower));
+                        store_vec<OutT, 4>(reinterpret_cast<OutT*>(buf + (mb * 16 + r) * ROWH) + j * 16 + 4 * kg, ov);
                     }
                 __builtin_amdgcn_wave_barrier();
                 uint4 v8[8];
@@ -345,7 +363,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) bv[e] = Fmt<T>::load(b4.v[e]) * p.out_scale;      // (acc + b) s = acc s + b s
             }
-            const float lower = a.relu ? 0.f : -INFINITY;
+            const float lower = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(a.relu ? 0u : 0xff800000u));   // 0 or -inf, in a scalar register
             const float sc = p.out_scale;
             // interior tiles (the common case) run without any masking; the residual branch is
             // taken once per tile, not per store
@@ -357,11 +375,11 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 for (int i = 0; i < 4; ++i) {
                     if (i) __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            float4 w4 = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                            *reinterpret_cast<float4*>(reg + r * ROWB + (j * 32 + 8 * q + 4 * kh) * 4) = w4;
+                        for (int j = 0; j < 8; ++j) {
+                            const f32x4_t t4 = acc[2 * i + mb][j];
+                            *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
                     const int mf = m0 + wm * 128 + i * 32 + rr;                 // row of u = 0; u adds 2 rows
@@ -404,11 +422,11 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 for (int i = 0; i < 4; ++i) {
                     if (i) __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            float4 w4 = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                            *reinterpret_cast<float4*>(reg + r * ROWB + (j * 32 + 8 * q + 4 * kh) * 4) = w4;
+                        for (int j = 0; j < 8; ++j) {
+                            const f32x4_t t4 = acc[2 * i + mb][j];
+                            *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
                     const int row = m0 + wm * 128 + i * 32 + crow;
@@ -452,7 +470,6 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             }
         }
         }
-        TSTAMP();
         if (!have_next) break;
         // the epilogue's LDS reads must be done in every wavefront before stage 1 is loaded again;
         // the barrier at the top of the loop (after the wait for slab 0) provides that
@@ -491,7 +508,7 @@ static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
 
 bool gemm256_applicable(const GemmArgs& a, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16)) return false;
-    if (a.K % 64 != 0 || a.M < 256 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
+    if (a.K % 128 != 0 || a.M < 256 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
     if (!a.out_f32 && (a.N % 8 != 0 || a.ldy % 8 != 0)) return false;
     if (a.ce_mode && !a.out_f32) return false;
     const size_t tsz = 2;

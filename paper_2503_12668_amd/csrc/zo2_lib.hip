@@ -433,7 +433,7 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const size_t rows2 = 2 * (size_t)T;
     // logits chunk: up to 1/8 of the budget, at least 128 rows per sign
     // (ZO2_DISABLE_FUSED_CE=1 keeps the materialised-logits path, for A/B measurements)
-    const bool fused_ce = (g.compute_dtype != ZO2_F32) && T >= 256 && V >= 256 && (d % 64 == 0) && (V % 4 == 0) &&
+    const bool fused_ce = (g.compute_dtype != ZO2_F32) && T >= 256 && V >= 256 && (d % 128 == 0) && (V % 4 == 0) &&
                           getenv("ZO2_DISABLE_FUSED_CE") == nullptr;
     const size_t ce_parts = 4 * ((V + 255) / 256);
     size_t lrows = budget / 8 / (V * 4) / 2;
@@ -1115,8 +1115,8 @@ extern "C" zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int
     if (M == 0) return ZO2_OK;
     ZO2_OP_CHECK(X && W && labels && row_loss && workspace, ZO2_EINVAL, "lm_head_ce: NULL argument");
     ZO2_OP_CHECK(dtype == ZO2_BF16 || dtype == ZO2_F16, ZO2_EINVAL, "lm_head_ce: dtype must be BF16 or F16");
-    ZO2_OP_CHECK(M >= 256 && N >= 256 && K > 0 && K % 64 == 0 && N % 4 == 0, ZO2_EINVAL,
-                 "lm_head_ce: needs M, N >= 256, K %% 64 == 0, N %% 4 == 0 (got %d x %d x %d)", M, N, K);
+    ZO2_OP_CHECK(M >= 256 && N >= 256 && K > 0 && K % 128 == 0 && N % 4 == 0, ZO2_EINVAL,
+                 "lm_head_ce: needs M, N >= 256, K %% 128 == 0, N %% 4 == 0 (got %d x %d x %d)", M, N, K);
     ZO2_OP_CHECK(((uintptr_t)workspace & 255) == 0 && workspace_bytes >= zo2_op_lm_head_ce_workspace_bytes(M, N) && M > 0 && N > 0,
                  ZO2_EINVAL, "lm_head_ce: workspace too small or not 256-byte aligned");
     const int parts = 4 * ((N + 255) / 256);

@@ -35,7 +35,7 @@ struct GemmArgs {
 
 // Y = act((X W^T + bias) * out_scale) + residual for every problem; float32 accumulation.
 zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st);
-// the 256 x 256 x 64 kernel (bf16 / fp16, K % 64 == 0); gemm_launch picks it for large problems
+// the 256 x 256 x 64 kernel (bf16 / fp16, K % 128 == 0); gemm_launch picks it for large problems
 zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st);
 bool gemm256_applicable(const GemmArgs& a, int dtype);
 

@@ -23,8 +23,8 @@ PEAK_BF16_MFMA = 2500.0      # TFLOP/s, dense
 PEAK_HBM = 8000.0            # GB/s
 # HBM bytes per step from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE) over this same command, scaled by
 # a 1 GiB copy through the same counters (profiles/step_opt1.3b_bf16_resident_hbm_traffic.md); not measured live
-PMC_GEMM_BYTES_PER_STEP = 43.9e9      # over the 97 GEMM launches of a step
-PMC_K1_BYTES_PER_STEP = 10.52e9       # over the 27 K1 launches of a step
+PMC_GEMM_BYTES_PER_STEP = 44.0e9      # over the 97 GEMM launches of a step
+PMC_K1_BYTES_PER_STEP = 11.02e9       # over the 27 K1 launches of a step
 
 
 def gemm_flops_per_step(cfg, T):

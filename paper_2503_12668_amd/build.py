@@ -1,6 +1,7 @@
 """Build libzo2.so (HIP, gfx950) in-tree with hipcc.  Cross-compiles without a GPU."""
 import glob
 import os
+import re
 import subprocess
 import sys
 
@@ -18,6 +19,58 @@ def _needs_build(obj, src, deps):
         return True
     t = os.path.getmtime(obj)
     return any(os.path.getmtime(p) > t for p in [src] + deps)
+
+
+# csrc/gemm256.hip issues its MFMAs from inline assembly (to pin the accumulators to accumulation registers), so the
+# compiler neither knows that they are MFMAs nor inserts the wait states an MFMA result needs before another kind of
+# instruction may touch it.  The kernel keeps that distance itself; this scan of the generated assembly fails the build
+# if a compiler-generated access to an accumulation register ever lands closer than kMfmaDistance instructions behind
+# an MFMA (each instruction is at least one wait state; s_nop N counts N + 1).
+kMfmaDistance = 20
+_ACC_REG = re.compile(r"\ba(\d+|\[\d+:\d+\])")
+
+
+def scan_mfma_hazards(asm_text):
+    """Returns a list of (kernel, line number, instruction, distance) for every accumulation-register access that
+    follows an MFMA too closely in program order."""
+    bad, kernel, dist = [], None, 10 ** 9
+    for n, line in enumerate(asm_text.splitlines(), 1):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            kernel, dist = m.group(1), 10 ** 9
+            continue
+        ins = line.split(";")[0].strip()
+        if not ins or ins.startswith(".") or ins.endswith(":"):
+            continue
+        op = ins.split()[0]
+        if op.startswith("v_mfma"):
+            dist = 0
+            continue
+        if op == "s_nop":
+            dist += int(ins.split()[1], 0) + 1
+            continue
+        if dist < kMfmaDistance and ("accvgpr" in op or _ACC_REG.search(ins)):
+            bad.append((kernel, n, ins, dist))
+        dist += 1
+    return bad
+
+
+def _check_gemm256(hipcc, src, bdir, verbose):
+    asm = os.path.join(bdir, "gemm256.s")
+    cmd = [hipcc] + [f for f in HIPCC_FLAGS if f != "-fPIC"] + ["--offload-device-only", "-S", src, "-o", asm]
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    with open(asm) as f:
+        text = f.read()
+    if "v_mfma" not in text:
+        raise RuntimeError("gemm256: no MFMA in the generated assembly - the hazard scan is looking at the wrong file")
+    bad = scan_mfma_hazards(text)
+    if bad:
+        head = "\n".join("  %s line %d: %s (%d behind an MFMA)" % b for b in bad[:8])
+        raise RuntimeError("gemm256: %d accumulation-register accesses too close behind an inline-assembly MFMA:\n%s" % (len(bad), head))
+    if verbose:
+        print("[build] gemm256 MFMA hazard scan: clean", flush=True)
 
 
 def build(force=False, verbose=True):
@@ -46,6 +99,9 @@ def build(force=False, verbose=True):
             print(out)
     if not ok:
         raise RuntimeError("hipcc failed")
+    g256 = os.path.join(CSRC, "gemm256.hip")
+    if any(src == g256 for src, _ in procs):
+        _check_gemm256(hipcc, g256, bdir, verbose)
     if force or procs or not os.path.exists(LIB):
         cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
         if verbose:

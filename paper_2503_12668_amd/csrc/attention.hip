@@ -151,7 +151,7 @@ __device__ __forceinline__ void att_load_to_lds(const void* gptr, uint32_t lds_b
 // column m0 + i: four consecutive contraction slots of its V^T row.
 template <typename T, int DH>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
-                                                                 T* __restrict__ out, int seq, int64_t ld) {
+                                                                 T* __restrict__ out, int seq, int64_t ld, int n_heads, int n_pairs) {
     constexpr int KS = DH / 16;          // contraction steps of the first product
     constexpr int DT = (DH + 31) / 32;   // 32-row tiles of O^T (rows past DH are computed on padding and dropped)
     constexpr int DHP = DH <= 64 ? 64 : 128;   // LDS row pitch in elements: a power of two, so that the swizzle stays inside the row
@@ -163,8 +163,16 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, kh = lane >> 5;
-    const int head = blockIdx.y, sq = blockIdx.z;
-    const int q0 = blockIdx.x * 128 + wave * 32;
+    // Workgroup id -> (block of 128 queries, head, sequence).  The query blocks of one (sequence, head) read the same
+    // keys and values; consecutive workgroup ids go to different XCDs, each with its own L2, so those blocks get ids that
+    // are congruent mod 8 and adjacent in their XCD's order.  Late query blocks (more keys under the causal mask) first.
+    const int nqb = (seq + 127) >> 7;
+    const int slot = blockIdx.x >> 3;
+    const int qb = nqb - 1 - slot % nqb;
+    const int pair = (slot / nqb) * 8 + (int)(blockIdx.x & 7);
+    if (pair >= n_pairs) return;                             // padding of the last group of 8 (whole workgroup)
+    const int head = pair % n_heads, sq = pair / n_heads;
+    const int q0 = qb * 128 + wave * 32;
     const bool active = q0 < seq;                            // inactive wavefronts still load and synchronise
     const size_t base = (size_t)sq * seq * ld + (size_t)head * DH;
     const int qi = q0 + r;                                   // this lane's query
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
     constexpr float kLog2e = 1.4426950408889634f;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
-    const int wg_last_q = min(blockIdx.x * 128 + 127, seq - 1);
+    const int wg_last_q = min(qb * 128 + 127, seq - 1);
     const int wg_last_tile = wg_last_q >> 5;
     const int my_last_tile = q0 >> 5;
     // transposing read: lane = 16 g16 + a; the group covers columns 16 (g16 & 1) .. + 15 and keys 8 (g16 >> 1) + 4 h + (a >> 2)
@@ -299,10 +307,11 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
 template <typename T>
 static zo2_status launch_mfma_att(const T* q, const T* k, const T* v, T* out, int n_seq, int seq, int n_heads, int d_head,
                                   int64_t ld, hipStream_t st) {
-    const dim3 grid((seq + 127) / 128, n_heads, n_seq), block(256);
-    if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, v, out, seq, ld);
-    else if (d_head == 80) hipLaunchKernelGGL((attention_mfma_kernel<T, 80>), grid, block, 0, st, q, k, v, out, seq, ld);
-    else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, v, out, seq, ld);
+    const int n_pairs = n_heads * n_seq, nqb = (seq + 127) / 128;
+    const dim3 grid((unsigned)(8 * nqb) * (unsigned)((n_pairs + 7) / 8)), block(256);
+    if (d_head == 64) hipLaunchKernelGGL((attention_mfma_kernel<T, 64>), grid, block, 0, st, q, k, v, out, seq, ld, n_heads, n_pairs);
+    else if (d_head == 80) hipLaunchKernelGGL((attention_mfma_kernel<T, 80>), grid, block, 0, st, q, k, v, out, seq, ld, n_heads, n_pairs);
+    else hipLaunchKernelGGL((attention_mfma_kernel<T, 128>), grid, block, 0, st, q, k, v, out, seq, ld, n_heads, n_pairs);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
 }
@@ -330,7 +339,8 @@ zo2_status attention_launch(int dtype, const void* q, const void* k, const void*
     ZO2_OP_CHECK(n_seq > 0 && seq > 0 && n_heads > 0 && d_head > 0, ZO2_EINVAL, "attention: bad shape");
     ZO2_OP_CHECK(q && k && v && out, ZO2_EINVAL, "attention: NULL buffer");
     ZO2_OP_CHECK(ld >= (int64_t)n_heads * d_head && ld % 8 == 0, ZO2_EINVAL, "attention: bad leading dimension");
-    ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535, ZO2_EINVAL, "attention: grid too large");
+    ZO2_OP_CHECK(n_seq <= 65535 && n_heads <= 65535 && (int64_t)n_seq * n_heads * ((seq + 127) / 128 + 1) < (int64_t)1 << 30, ZO2_EINVAL,
+                 "attention: grid too large");
     {   // every kernel moves groups of 8 elements
         const uintptr_t align = 8 * (uintptr_t)zo2_dtype_size(dtype);
         ZO2_OP_CHECK(align != 0 && ((uintptr_t)q % align) == 0 && ((uintptr_t)k % align) == 0 && ((uintptr_t)v % align) == 0 &&

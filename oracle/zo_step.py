@@ -12,6 +12,12 @@ Three forms of the same step, all on float32 parameters:
                  update left pending by the previous iteration (its g, its seed,
                  its learning rate), then is perturbed both ways and run on the
                  two activation streams.  The last g stays pending until flush().
+  step_whole_multi / Zo2Blockwise.step_extra
+                 the same estimator averaged over q directions (Sec. 3 notes that the
+                 framework carries over to other ZO estimators; this is the q-sample
+                 form of Eq. 1-2): g_i from direction z_i, i = 0..q-1, all at the same
+                 parameters and batch, then theta <- theta - sum_i eta_i g_i z_i
+                 (eta_i = eta / q for the average), applied in the order i = 0, 1, ...
 
 Arithmetic shared by the last two ("canonical"): one fused multiply-add per
 element, a*b+c evaluated exactly and rounded once to float32; then, if the
@@ -106,6 +112,30 @@ def step_whole(cfg, P, tokens, labels, seed, eps, lr, store="f32", compute="f32"
     return lp, lm, g
 
 
+def step_whole_multi(cfg, P, tokens, labels, seeds, eps, lrs, store="f32", compute="f32", scales=None):
+    """q directions at the same parameters (Eq. 2 once per seed), then the q updates of Eq. 3 one after the
+    other in the order of `seeds`, each with canonical arithmetic.  lrs[i] belongs to seeds[i].  P modified in
+    place.  Returns a list of (l+, l-, g)."""
+    scales = scales or {}
+    eps32 = np.float32(eps)
+    out = []
+    for seed in seeds:
+        z = z_of(cfg, seed)
+        Wp = {n: _store(_fma32(eps32, z[n], P[n]), compute) for n in P}
+        lp = np.float32(opt_model.loss(cfg, Wp, tokens, labels))
+        del Wp
+        Wm = {n: _store(_fma32(-eps32, z[n], P[n]), compute) for n in P}
+        lm = np.float32(opt_model.loss(cfg, Wm, tokens, labels))
+        del Wm
+        out.append((lp, lm, projected_gradient(lp, lm, eps)))
+    for (lp, lm, g), seed, lr in zip(out, seeds, lrs):
+        z = z_of(cfg, seed)
+        c = np.float32(np.float32(lr) * g)
+        for n in P:
+            P[n] = _store(_fma32(-c, z[n], P[n]), store, scales.get(n, 1.0))
+    return out
+
+
 # --------------------------------------------------------------------------- Alg. 2 + deferred update
 class Zo2Blockwise:
     """Alg. 2 with the update of iteration j-1 applied when each module is
@@ -120,6 +150,7 @@ class Zo2Blockwise:
         self.scales = scales or {}
         self.rounding = rounding            # of the stored theta': "nearest" (the paper's cast) or "stochastic"
         self.pending = None
+        self.extra = []
         self.ids = {name: tid for name, tid, _ in opt_model.tensor_table(cfg)}
 
     def _z(self, name, seed):
@@ -129,13 +160,13 @@ class Zo2Blockwise:
     def _update_module(self, names):
         if self.pending is None:
             return
-        g, seed, lr = self.pending
-        c = np.float32(np.float32(lr) * np.float32(g))
-        for n in names:
-            r16 = None
-            if self.rounding == "stochastic" and self.store != "f32":
-                r16 = philox.rounding_bits(seed, self.ids[n], 0, self.P[n].size).reshape(self.P[n].shape)
-            self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0), r16)
+        for g, seed, lr in [self.pending] + self.extra:
+            c = np.float32(np.float32(lr) * np.float32(g))
+            for n in names:
+                r16 = None
+                if self.rounding == "stochastic" and self.store != "f32":
+                    r16 = philox.rounding_bits(seed, self.ids[n], 0, self.P[n].size).reshape(self.P[n].shape)
+                self.P[n] = _store(_fma32(-c, self._z(n, seed), self.P[n]), self.store, self.scales.get(n, 1.0), r16)
 
     def _perturbed_pair(self, names, seed, eps):
         """(W+, W-) of a module: z drawn once, used with both signs (Eq. 2)."""
@@ -146,23 +177,27 @@ class Zo2Blockwise:
             Wm[n] = _store(_fma32(-np.float32(eps), z, self.P[n]), self.compute)
         return Wp, Wm
 
-    def step(self, tokens, labels, seed, eps, lr):
+    def _walk(self, tokens, labels, seed, eps, update):
+        """One pass of Alg. 2 over the modules; `update`: apply what is pending to each module first."""
         cfg = self.cfg
         mods = opt_model.modules(cfg)
         # Embedding
-        self._update_module(mods[0])
+        if update:
+            self._update_module(mods[0])
         W = self._perturbed_pair(mods[0], seed, eps)
         emb_W = W
         acts = [opt_model.embed(cfg, W[k], tokens) for k in (0, 1)]
         # transformer blocks
         for l in range(cfg.n_layers):
             names = mods[1 + l]
-            self._update_module(names)
+            if update:
+                self._update_module(names)
             W = self._perturbed_pair(names, seed, eps)
             acts = [opt_model.block_forward(cfg, W[k], l, acts[k]) for k in (0, 1)]
         # LM head (its tied weight was already updated with the embedding module)
         names = mods[-1]
-        self._update_module(names)
+        if update:
+            self._update_module(names)
         W = self._perturbed_pair(names, seed, eps)
         losses = []
         for k in (0, 1):
@@ -171,15 +206,29 @@ class Zo2Blockwise:
                 Wk["tok_emb"] = emb_W[k]["tok_emb"]
             lg = opt_model.head_logits(cfg, Wk, acts[k])
             losses.append(np.float32(opt_model.cross_entropy(lg, labels)))
-        g = projected_gradient(losses[0], losses[1], eps)
+        return losses[0], losses[1], projected_gradient(losses[0], losses[1], eps)
+
+    def step(self, tokens, labels, seed, eps, lr):
+        lp, lm, g = self._walk(tokens, labels, seed, eps, update=True)
         self.pending = (g, seed, lr)
-        return losses[0], losses[1], g
+        self.extra = []
+        return lp, lm, g
+
+    def step_extra(self, tokens, labels, seed, eps, lr):
+        """A further direction at the parameters the last step() left (its own update and the extras so far
+        stay pending, nothing is applied): its (g, seed, lr) joins them."""
+        if self.pending is None:
+            raise ValueError("step_extra needs a step() before it")
+        lp, lm, g = self._walk(tokens, labels, seed, eps, update=False)
+        self.extra.append((g, seed, lr))
+        return lp, lm, g
 
     def flush(self):
         """Apply the update still pending after the last iteration."""
         for names in opt_model.modules(self.cfg):
             self._update_module(names)
         self.pending = None
+        self.extra = []
 
     def eval_loss(self, tokens, labels):
         """L(theta; B) with one unperturbed forward (the single-forward evaluation regime of the paper's

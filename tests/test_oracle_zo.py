@@ -198,3 +198,63 @@ def test_stochastic_rounding_lets_a_bf16_master_follow_small_updates():
     print(proj(d_sr), proj(d_near), proj(moved))
     assert abs(proj(d_sr) - proj(moved)) < 0.5 * proj(moved)
     assert proj(d_near) < 0.1 * proj(moved)
+
+
+# --------------------------------------------------------------------------- q directions per update
+def test_one_direction_of_the_multi_form_is_the_plain_step():
+    cfg, s, P, tok, lab = _setup()
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    a = zo_step.step_whole(s, Pa, tok, lab, 42, 1e-3, 1e-3)
+    b = zo_step.step_whole_multi(s, Pb, tok, lab, [42], 1e-3, [1e-3])
+    assert tuple(map(float, a)) == tuple(map(float, b[0]))
+    for n in P:
+        assert np.array_equal(Pa[n], Pb[n]), n
+
+
+@pytest.mark.parametrize("tied", [True, False])
+def test_blockwise_with_extra_directions_equals_whole_model(tied):
+    """All directions of a round are evaluated at the same parameters (none of the round's own updates is visible
+    to them), and the deferred, module-by-module application reproduces the whole-model form bit for bit."""
+    cfg, s, P, tok, lab = _setup(tied=tied)
+    Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
+    zo = zo_step.Zo2Blockwise(s, Pb)
+    for j in range(3):
+        seeds = [1000 + 10 * j + i for i in range(3)]
+        lrs = [1e-3 * (j + 1) / 3, 2e-3 / 3, 5e-4]             # every direction carries its own eta
+        a = zo_step.step_whole_multi(s, Pa, tok, lab, seeds, 1e-3, lrs)
+        b = [zo.step(tok, lab, seeds[0], 1e-3, lrs[0])]
+        b += [zo.step_extra(tok, lab, seeds[i], 1e-3, lrs[i]) for i in (1, 2)]
+        assert [tuple(map(float, x)) for x in a] == [tuple(map(float, x)) for x in b], j
+        # the directions of one round see the same parameters: l+ and l- differ only through z
+        assert len({float(x[0]) for x in a}) == 3
+    zo.flush()
+    for n in P:
+        assert np.array_equal(Pa[n], Pb[n]), n
+    with pytest.raises(ValueError):
+        zo_step.Zo2Blockwise(s, copy.deepcopy(P)).step_extra(tok, lab, 1, 1e-3, 1e-3)
+
+
+def test_average_over_directions_estimates_the_gradient():
+    """E[g z] = grad L (Eq. 1-2): the average over q directions has projection (ghat . G) / |G|^2 -> 1 with relative
+    spread sqrt(2 / q), and its cosine with G grows like sqrt(q / (q + d)); one direction alone is almost orthogonal."""
+    cfg, s, P, tok, lab = _setup()
+    for l in range(cfg["n_layers"]):                       # keep L smooth along every direction (see the first test)
+        P[f"blocks.{l}.fc1.b"] = P[f"blocks.{l}.fc1.b"] + np.float32(4.0)
+    _, G = hf_param_grads(cfg, P, tok, lab)
+    gnorm2 = sum(float(np.sum(G[n] ** 2)) for n in P)
+    d = sum(P[n].size for n in P)
+
+    def estimate(q, seed0):
+        Pq = copy.deepcopy(P)
+        eta = 1e-3
+        zo_step.step_whole_multi(s, Pq, tok, lab, list(range(seed0, seed0 + q)), 1e-3, [eta / q] * q)
+        gh = {n: (P[n].astype(np.float64) - Pq[n].astype(np.float64)) / eta for n in P}
+        dot = sum(float(np.sum(gh[n] * G[n])) for n in P)
+        return dot / gnorm2, dot / np.sqrt(gnorm2 * sum(float(np.sum(gh[n] ** 2)) for n in P))
+
+    q = 200
+    proj, cos = estimate(q, 5000)
+    assert abs(proj - 1.0) < 3.5 * np.sqrt(2.0 / q), proj
+    assert 0.5 * np.sqrt(q / (q + d)) < cos < 2.0 * np.sqrt(q / (q + d)), (cos, d)
+    _, cos1 = estimate(1, 7000)
+    assert 0.0 <= cos1 < 0.4 * cos

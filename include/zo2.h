@@ -4,7 +4,7 @@
  *
  * Two layers of entry points:
  *
- *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_flush / zo2_eval /
+ *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_step_extra / zo2_flush / zo2_eval /
  *      zo2_get_pending / zo2_set_pending / zo2_sync_to_host / zo2_destroy.  One call of zo2_step is one iteration of the paper's
  *      Alg. 2: for every module (embedding, decoder blocks, LM head) apply the update left
  *      pending by the previous iteration, perturb by +eps z and -eps z, run both forwards,
@@ -131,6 +131,20 @@ zo2_status zo2_set_resident_budget(zo2_ctx* ctx, size_t hbm_bytes);
 zo2_status zo2_step(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
                     uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* g);
 
+/* One more direction of the current round: the q-direction form of the randomized gradient estimate (Sec. 3:
+ * the framework carries over to other ZO estimators; this one averages Eq. 2 over q directions z_0 .. z_q-1
+ * drawn at the same parameters).  A round is zo2_step(seed_0, lr_0) followed by q - 1 calls of
+ * zo2_step_extra(seed_i, lr_i) on the same batch (lr_i = eta / q for the plain average).  The call perturbs
+ * the parameters as zo2_step left them -- none of the round's own updates is visible to it -- runs the same
+ * dual forward, and defers its update eta_i g_i z_i with the others; nothing is applied, and streamed blocks
+ * are uploaded but not written back.  The next zo2_step, zo2_eval or zo2_flush applies the round's updates to
+ * each module in the order i = 0 .. q - 1 (the first q - 1 as update-only sweeps while the module is on the
+ * device, the last one fused with the next perturbation as usual).  At most 16 directions per round
+ * (ZO2_ESTATE beyond, and without a zo2_step before).  Arguments, outputs and ZO2_ENONFINITE as for zo2_step;
+ * a non-finite direction is dropped from the round. */
+zo2_status zo2_step_extra(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                          uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* g);
+
 /* Apply the pending update to every parameter now (Alg. 2 leaves the last g unapplied). */
 zo2_status zo2_flush(zo2_ctx* ctx);
 
@@ -149,6 +163,13 @@ zo2_status zo2_eval(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, 
  * zo2_set_pending continues bit-identically.  zo2_set_pending replaces whatever was pending. */
 zo2_status zo2_get_pending(zo2_ctx* ctx, int32_t* has_pending, uint64_t* seed, float* step);
 zo2_status zo2_set_pending(zo2_ctx* ctx, int32_t has_pending, uint64_t seed, float step);
+
+/* The same for a round of several directions (zo2_step_extra): how many updates are deferred, update i
+ * (0 <= i < count, in the order of application), and appending one to those already deferred.
+ * zo2_get_pending answers ZO2_ESTATE while more than one is deferred. */
+zo2_status zo2_pending_count(zo2_ctx* ctx, int32_t* count);
+zo2_status zo2_get_pending_at(zo2_ctx* ctx, int32_t i, uint64_t* seed, float* step);
+zo2_status zo2_add_pending(zo2_ctx* ctx, uint64_t seed, float step);
 
 /* Copy device-resident parameters (embeddings, final LayerNorm, LM head, and the blocks when
  * all are resident) back into the caller's host buffers.  Does not flush. */

@@ -63,10 +63,14 @@ def lib():
         "zo2_init": (i32, [C.POINTER(vp), C.POINTER(Config), C.POINTER(HostWeights), C.POINTER(Device)]),
         "zo2_set_resident_budget": (i32, [vp, C.c_size_t]),
         "zo2_step": (i32, [vp, vp, vp, i32, i32, u64, f32, f32, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]),
+        "zo2_step_extra": (i32, [vp, vp, vp, i32, i32, u64, f32, f32, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]),
         "zo2_flush": (i32, [vp]),
         "zo2_eval": (i32, [vp, vp, vp, i32, i32, C.POINTER(f32)]),
         "zo2_get_pending": (i32, [vp, C.POINTER(i32), C.POINTER(u64), C.POINTER(f32)]),
         "zo2_set_pending": (i32, [vp, i32, u64, f32]),
+        "zo2_pending_count": (i32, [vp, C.POINTER(i32)]),
+        "zo2_get_pending_at": (i32, [vp, i32, C.POINTER(u64), C.POINTER(f32)]),
+        "zo2_add_pending": (i32, [vp, u64, f32]),
         "zo2_sync_to_host": (i32, [vp]),
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
@@ -97,7 +101,8 @@ def lib():
     return L
 
 
-EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
+EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
+            "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
@@ -327,6 +332,17 @@ class Zo2Context:
                     allow=(6,) if allow_nonfinite else ())
         return np.float32(lp.value), np.float32(lm.value), np.float32(g.value)
 
+    def step_extra(self, tokens, labels, seed, eps, lr, allow_nonfinite=False):
+        """One more direction of the current round (after step): same parameters, its update deferred with the others."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        lab = np.ascontiguousarray(labels, dtype=np.int32)
+        assert tok.shape == lab.shape and tok.ndim == 2
+        lp, lm, g = C.c_float(), C.c_float(), C.c_float()
+        self._check(lib().zo2_step_extra(self.handle, tok.ctypes.data, lab.ctypes.data, tok.shape[0], tok.shape[1], int(seed),
+                                         float(eps), float(lr), C.byref(lp), C.byref(lm), C.byref(g)),
+                    allow=(6,) if allow_nonfinite else ())
+        return np.float32(lp.value), np.float32(lm.value), np.float32(g.value)
+
     def flush(self):
         self._check(lib().zo2_flush(self.handle))
 
@@ -346,6 +362,22 @@ class Zo2Context:
 
     def set_pending(self, has_pending, seed=0, step=0.0):
         self._check(lib().zo2_set_pending(self.handle, 1 if has_pending else 0, int(seed), float(step)))
+
+    def pending_list(self):
+        """[(seed, eta * g), ...] of all deferred updates, in the order of application."""
+        n = C.c_int32()
+        self._check(lib().zo2_pending_count(self.handle, C.byref(n)))
+        out = []
+        for i in range(n.value):
+            seed, step = C.c_uint64(), C.c_float()
+            self._check(lib().zo2_get_pending_at(self.handle, i, C.byref(seed), C.byref(step)))
+            out.append((int(seed.value), np.float32(step.value)))
+        return out
+
+    def set_pending_list(self, items):
+        self.set_pending(False)
+        for seed, step in items:
+            self._check(lib().zo2_add_pending(self.handle, int(seed), float(step)))
 
     def sync_to_host(self):
         self._check(lib().zo2_sync_to_host(self.handle))

@@ -84,7 +84,7 @@ struct zo2_ctx {
 
     // persistent device region
     char *d_tok, *d_pos, *d_fln, *d_lm;
-    float* d_state;                     // [0] c_pending, [4..7] result
+    float* d_state;                     // [4..7] result of a pass, [16 + k] coefficient eta g of deferred update k
     size_t persistent_bytes;
 
     // plan (depends on budget and batch x seq)
@@ -115,9 +115,12 @@ struct zo2_ctx {
     size_t bytes_used;
     bool blocks_on_device;
 
-    // pending update (Sec. 5.4)
-    bool has_pending;
-    uint64_t seed_prev;
+    // deferred updates (Sec. 5.4): none, one (the paper's case), or the directions of one round of the q-direction
+    // estimator (zo2_step_extra), in the order in which they are applied.  Coefficient k sits at d_state[16 + k].
+    static constexpr int kMaxPending = 16;
+    int n_pend;
+    uint64_t pend_seed[kMaxPending];
+    bool apply_now;                      // the pass in progress applies them (false: a further direction at unchanged parameters)
 
     // streams / events
     hipStream_t sc, su, so;
@@ -329,8 +332,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->planned = false;
     c->need_plan = false;
     c->blocks_on_device = false;
-    c->has_pending = false;
-    c->seed_prev = 0;
+    c->n_pend = 0;
+    c->apply_now = true;
     c->h_ids = nullptr;
     c->h_ids_cap = 0;
     c->h_result = nullptr;
@@ -592,40 +595,80 @@ extern "C" zo2_status zo2_get_step_stats(const zo2_ctx* c, float* ms_c, float* m
 }
 
 // ---------------------------------------------------------------------------------- K1 helpers
-static void k1_common(const zo2_ctx* c, K1Args& a, uint64_t seed, float eps) {
+static inline float* coef_slot(const zo2_ctx* c, int k) { return c->d_state + 16 + k; }
+// does the fused sweep (update + perturb) of the pass in progress carry an update?  It carries the last deferred one;
+// the earlier ones of a round of several directions are applied by update-only sweeps in front of it.
+static inline bool fused_update(const zo2_ctx* c) { return c->apply_now && c->n_pend > 0; }
+
+// pend: index of the deferred update this sweep applies; -1 = the last one (the fused sweep's)
+static void k1_common(const zo2_ctx* c, K1Args& a, uint64_t seed, float eps, int pend = -1) {
     memset(&a, 0, sizeof(a));
-    a.c_ptr = c->d_state;
+    const int k = pend >= 0 ? pend : (c->n_pend > 0 ? c->n_pend - 1 : 0);
+    a.c_ptr = coef_slot(c, k);
     a.c_imm = 0.f;
     a.stochastic = c->stochastic ? 1 : 0;
     a.eps = eps;
-    a.k_prev = philox_keys(c->seed_prev);
+    a.k_prev = philox_keys(c->n_pend > 0 ? c->pend_seed[k] : 0);
     a.k_cur = philox_keys(seed);
 }
 
 // one whole tensor held contiguously at `theta`
 static zo2_status k1_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, bool perturb, void* wp, void* wm,
-                            uint64_t seed, float eps, hipStream_t st = nullptr) {
+                            uint64_t seed, float eps, hipStream_t st = nullptr, int pend = -1) {
     if (!st) st = c->sc;
     K1Args a;
-    k1_common(c, a, seed, eps);
+    k1_common(c, a, seed, eps, pend);
     a.theta = theta; a.w_plus = wp; a.w_minus = c->ns == 2 ? wm : nullptr; a.w_off0 = 0; a.nseg = 1;
     a.seg[0].off = 0; a.seg[0].e0 = 0; a.seg[0].n = (uint64_t)n; a.seg[0].tensor_id = tid; a.seg[0].scale = c->scales[tid];
-    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, st));
+    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, pend >= 0 || fused_update(c), perturb, st));
     return ZO2_OK;
 }
 
 // tensors [t0, t1) of block l whose bucket sits at `bucket`; W+- go to the scratch, tensor t0 at its start
 static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool perturb, uint64_t seed, float eps,
-                           hipStream_t st = nullptr) {
+                           hipStream_t st = nullptr, int pend = -1) {
     if (!st) st = c->sc;
     K1Args a;
-    k1_common(c, a, seed, eps);
+    k1_common(c, a, seed, eps, pend);
     a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->ns == 2 ? c->wm : nullptr; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
     for (int k = t0; k < t1; ++k) {
         K1Seg& s = a.seg[k - t0];
         s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
     }
-    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, c->has_pending, perturb, st));
+    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, pend >= 0 || fused_update(c), perturb, st));
+    return ZO2_OK;
+}
+
+// the final LayerNorm's two vectors
+static zo2_status k1_final_ln(zo2_ctx* c, bool perturb, uint64_t seed, float eps, int pend = -1) {
+    K1Args a;
+    k1_common(c, a, seed, eps, pend);
+    a.theta = c->d_fln; a.w_off0 = 0; a.nseg = 2;
+    if (perturb) { a.w_plus = c->fln_wp; a.w_minus = c->ns == 2 ? c->fln_wm : nullptr; }
+    for (int k = 0; k < 2; ++k) {
+        a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)c->cfg.d_model;
+        a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
+    }
+    OPK(c, ZO2_KC_K1, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, pend >= 0 || fused_update(c), perturb, c->sc));
+    return ZO2_OK;
+}
+
+// Deferred updates 0 .. n_pend - 2 of a module, in order, as update-only sweeps: after a round of several directions
+// they precede the fused sweep, which applies the last one together with the new perturbation.
+static zo2_status earlier_updates_tensor(zo2_ctx* c, void* theta, int64_t n, uint32_t tid, hipStream_t st = nullptr) {
+    if (!c->apply_now) return ZO2_OK;
+    for (int k = 0; k + 1 < c->n_pend; ++k) {
+        zo2_status s = k1_tensor(c, theta, n, tid, false, nullptr, nullptr, 0, 0.f, st, k);
+        if (s != ZO2_OK) return s;
+    }
+    return ZO2_OK;
+}
+static zo2_status earlier_updates_block(zo2_ctx* c, int l, char* bucket, hipStream_t st = nullptr) {
+    if (!c->apply_now) return ZO2_OK;
+    for (int k = 0; k + 1 < c->n_pend; ++k) {
+        zo2_status s = k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f, st, k);
+        if (s != ZO2_OK) return s;
+    }
     return ZO2_OK;
 }
 
@@ -656,6 +699,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     GemmArgs ga;
 
     // ---- attention half: h += O(Attn(LN1(h)))
+    if (!k1_enqueued) { zo2_status s = earlier_updates_block(c, l, bucket); if (s != ZO2_OK) return s; }
     { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
     if (!c->phased && k1_done && !k1_enqueued) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     PhaseView w = view(0);
@@ -747,8 +791,10 @@ static zo2_status enqueue_offload(zo2_ctx* c, int l, bool changed) {
 // ---------------------------------------------------------------------------------- one pass over the model
 // ns = 2: Alg. 2's iteration (update, perturb both ways, dual forward, g).  ns = 1: the same walk with a
 // single unperturbed forward (evaluation): the pending update is still applied on the way, W+ = theta'.
+// extra: a further direction of the current round (ns = 2): nothing deferred is applied, the parameters stay as
+// they are, and the pass's own (seed, eta g) joins the deferred updates instead of replacing them.
 static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
-                             uint64_t seed, float eps, float lr, int ns) {
+                             uint64_t seed, float eps, float lr, int ns, bool extra = false) {
     const zo2_config& g = c->cfg;
     if (batch <= 0 || seq <= 0 || seq > g.max_pos) return fail(c, ZO2_EINVAL, "%s: batch %d, seq %d (max_pos %d)", who, batch, seq, g.max_pos);
     if ((int64_t)batch * seq > (1 << 24)) return fail(c, ZO2_EINVAL, "%s: too many tokens", who);
@@ -763,7 +809,8 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         if (s != ZO2_OK) return s;
     }
     const int d = g.d_model, dt = g.compute_dtype;
-    const bool upd = c->has_pending;
+    c->apply_now = !extra;
+    const bool upd = fused_update(c);
     c->bytes_up = c->bytes_down = 0;
     c->stat_u = c->stat_o = false;
     prof_reset(c);
@@ -784,12 +831,17 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         }
 
     // DualForward(Embedding)
+    {   // earlier directions of the last round: the tables first, the gather then sees them
+        zo2_status s = earlier_updates_tensor(c, c->d_tok, c->tok_elems, 0);
+        if (s == ZO2_OK) s = earlier_updates_tensor(c, c->d_pos, c->pos_elems, 1);
+        if (s != ZO2_OK) return s;
+    }
     EmbedArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.tok_emb = c->d_tok; ea.pos_emb = c->d_pos; ea.tokens = c->d_tokens; ea.h = c->h;
     ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps; ea.single = ns == 1; ea.stochastic = c->stochastic ? 1 : 0;
-    ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = c->d_state;
-    ea.k_prev = philox_keys(c->seed_prev); ea.k_cur = philox_keys(seed);
+    ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = coef_slot(c, c->n_pend > 0 ? c->n_pend - 1 : 0);
+    ea.k_prev = philox_keys(c->n_pend > 0 ? c->pend_seed[c->n_pend - 1] : 0); ea.k_cur = philox_keys(seed);
     OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
     if (upd) {
         { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
@@ -809,6 +861,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         if (c->overlap_k1) {
             if (l >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
             if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
+            { zo2_status s = earlier_updates_block(c, l, bucket, c->sk); if (s != ZO2_OK) return s; }
             { zo2_status s = k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, true, seed, eps, c->sk); if (s != ZO2_OK) return s; }
             HIPCHK(c, hipEventRecord(c->ev_k1done[sb], c->sk));
             if (!c->resident) HIPCHK(c, hipEventRecord(c->ev_k1[sl], c->sk));
@@ -843,16 +896,9 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     }
 
     // DualForward(LM head): final LayerNorm, (tied) vocabulary matrix, loss
-    {
-        K1Args a;
-        k1_common(c, a, seed, eps);
-        a.theta = c->d_fln; a.w_plus = c->fln_wp; a.w_minus = ns == 2 ? c->fln_wm : nullptr; a.w_off0 = 0; a.nseg = 2;
-        for (int k = 0; k < 2; ++k) {
-            a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)d;
-            a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
-        }
-        OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, dt, upd, true, c->sc));
-    }
+    if (c->apply_now)
+        for (int k = 0; k + 1 < c->n_pend; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
+    { zo2_status s = k1_final_ln(c, true, seed, eps); if (s != ZO2_OK) return s; }
     const size_t boff = (size_t)c->fln_off_b * c->csz;
     OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, ns * T, T, d, g.ln_eps, c->sc));
     {
@@ -865,6 +911,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_embed, 0));                  // the gather read the table before its update
             if (g.n_layers >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
         }
+        if (!g.tied_lm_head) { zo2_status es = earlier_updates_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), st); if (es != ZO2_OK) return es; }
         zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps, st)
                                       : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps, st);
         if (s != ZO2_OK) return s;
@@ -904,7 +951,9 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
     }
     }
-    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, c->d_state, c->sc));
+    // eta g of this pass: deferred update 0 of a new round (every older one has been applied on the way), or one more of
+    // the current round
+    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : 0), c->sc));
     HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
     if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
@@ -921,16 +970,20 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     if (c->stat_u) hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
     if (c->stat_o) hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
 
+    c->apply_now = true;
     if (ns == 1) {
-        c->has_pending = false;   // the pending update has been applied to every module on the way
+        c->n_pend = 0;            // the pending updates have been applied to every module on the way
         return ZO2_OK;
     }
-    c->has_pending = true;
-    c->seed_prev = seed;
-    if (!isfinite(c->h_result[0]) || !isfinite(c->h_result[1]) || !isfinite(c->h_result[2])) {
-        c->has_pending = false;   // a non-finite g must never reach the parameters: this iteration's update is dropped
-        return fail(c, ZO2_ENONFINITE, "%s: non-finite loss (l+ %g, l- %g)", who, (double)c->h_result[0], (double)c->h_result[1]);
+    const bool finite = isfinite(c->h_result[0]) && isfinite(c->h_result[1]) && isfinite(c->h_result[2]);
+    if (extra) {
+        if (finite) c->pend_seed[c->n_pend++] = seed;
+    } else {
+        c->n_pend = finite ? 1 : 0;
+        c->pend_seed[0] = seed;
     }
+    // a non-finite g must never reach the parameters: this direction's update is dropped
+    if (!finite) return fail(c, ZO2_ENONFINITE, "%s: non-finite loss (l+ %g, l- %g)", who, (double)c->h_result[0], (double)c->h_result[1]);
     return ZO2_OK;
 }
 
@@ -942,6 +995,25 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step: NULL argument");
     if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step: eps must be non-zero and finite, lr finite");
     const zo2_status s = model_pass(c, "zo2_step", tokens, labels, batch, seq, seed, eps, lr, 2);
+    if (s == ZO2_OK || s == ZO2_ENONFINITE) {
+        *loss_plus = c->h_result[0];
+        *loss_minus = c->h_result[1];
+        *gout = c->h_result[2];
+    }
+    return s;
+}
+
+// A further direction of the current round (q-direction form of the estimator): same parameters, same arithmetic,
+// nothing applied; its update joins the deferred ones.
+extern "C" zo2_status zo2_step_extra(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                                     uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* gout) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step_extra: NULL argument");
+    if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step_extra: eps must be non-zero and finite, lr finite");
+    if (c->n_pend < 1) return fail(c, ZO2_ESTATE, "zo2_step_extra: no round in progress (call zo2_step first)");
+    if (c->n_pend >= zo2_ctx::kMaxPending) return fail(c, ZO2_ESTATE, "zo2_step_extra: at most %d directions per round", zo2_ctx::kMaxPending);
+    const zo2_status s = model_pass(c, "zo2_step_extra", tokens, labels, batch, seq, seed, eps, lr, 2, true);
     if (s == ZO2_OK || s == ZO2_ENONFINITE) {
         *loss_plus = c->h_result[0];
         *loss_minus = c->h_result[1];
@@ -963,44 +1035,68 @@ extern "C" zo2_status zo2_eval(zo2_ctx* c, const int32_t* tokens, const int32_t*
 // ---------------------------------------------------------------------------------- the deferred update as data
 // What Sec. 5.4 carries from one iteration to the next: (seed, c = eta * g).  Together with the parameters
 // (zo2_sync_to_host) this is the whole training state, so it is what a checkpoint has to hold.
+extern "C" zo2_status zo2_pending_count(zo2_ctx* c, int32_t* n) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!n) return fail(c, ZO2_EINVAL, "zo2_pending_count: NULL argument");
+    *n = c->n_pend;
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_pending_at(zo2_ctx* c, int32_t i, uint64_t* seed, float* step) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!seed || !step) return fail(c, ZO2_EINVAL, "zo2_get_pending_at: NULL argument");
+    if (i < 0 || i >= c->n_pend) return fail(c, ZO2_EINVAL, "zo2_get_pending_at: index %d of %d", i, c->n_pend);
+    HIPCHK(c, hipMemcpyAsync(c->h_result + 8, coef_slot(c, i), sizeof(float), hipMemcpyDeviceToHost, c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    *seed = c->pend_seed[i];
+    *step = c->h_result[8];
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_add_pending(zo2_ctx* c, uint64_t seed, float step) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!isfinite(step)) return fail(c, ZO2_EINVAL, "zo2_add_pending: step must be finite");
+    if (c->n_pend >= zo2_ctx::kMaxPending) return fail(c, ZO2_ESTATE, "zo2_add_pending: at most %d deferred updates", zo2_ctx::kMaxPending);
+    c->h_result[8] = step;
+    HIPCHK(c, hipMemcpyAsync(coef_slot(c, c->n_pend), c->h_result + 8, sizeof(float), hipMemcpyHostToDevice, c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    c->pend_seed[c->n_pend++] = seed;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_pending(zo2_ctx* c, int32_t* has_pending, uint64_t* seed, float* step) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
     if (!has_pending || !seed || !step) return fail(c, ZO2_EINVAL, "zo2_get_pending: NULL argument");
-    *has_pending = c->has_pending ? 1 : 0;
-    *seed = c->has_pending ? c->seed_prev : 0;
+    if (c->n_pend > 1) return fail(c, ZO2_ESTATE, "zo2_get_pending: %d updates are deferred; read them with zo2_get_pending_at", c->n_pend);
+    *has_pending = c->n_pend;
+    *seed = 0;
     *step = 0.f;
-    if (c->has_pending) {
-        HIPCHK(c, hipMemcpyAsync(c->h_result + 8, c->d_state, sizeof(float), hipMemcpyDeviceToHost, c->sc));
-        HIPCHK(c, hipStreamSynchronize(c->sc));
-        *step = c->h_result[8];
-    }
-    return ZO2_OK;
+    return c->n_pend ? zo2_get_pending_at(c, 0, seed, step) : ZO2_OK;
 }
 
 extern "C" zo2_status zo2_set_pending(zo2_ctx* c, int32_t has_pending, uint64_t seed, float step) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
     if (has_pending && !isfinite(step)) return fail(c, ZO2_EINVAL, "zo2_set_pending: step must be finite");
-    if (has_pending) {
-        c->h_result[8] = step;
-        HIPCHK(c, hipMemcpyAsync(c->d_state, c->h_result + 8, sizeof(float), hipMemcpyHostToDevice, c->sc));
-        HIPCHK(c, hipStreamSynchronize(c->sc));
-    }
-    c->has_pending = has_pending != 0;
-    c->seed_prev = seed;
-    return ZO2_OK;
+    c->n_pend = 0;
+    return has_pending ? zo2_add_pending(c, seed, step) : ZO2_OK;
 }
 
 // ---------------------------------------------------------------------------------- flush
 extern "C" zo2_status zo2_flush(zo2_ctx* c) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
-    if (!c->has_pending) return ZO2_OK;
+    if (c->n_pend == 0) return ZO2_OK;
     const zo2_config& g = c->cfg;
     if (!c->planned) return fail(c, ZO2_EINVAL, "zo2_flush: nothing to flush");
-    { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
-    { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
+    c->apply_now = true;
+    const int np = c->n_pend;       // every module takes all deferred updates, in order, while it is on the device
+    for (int k = 0; k < np; ++k) { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, 0, 0.f, nullptr, k); if (s != ZO2_OK) return s; }
+    for (int k = 0; k < np; ++k) { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, 0, 0.f, nullptr, k); if (s != ZO2_OK) return s; }
     c->bytes_up = c->bytes_down = 0;
     c->stat_u = c->stat_o = true;   // no span statistics for a flush
     int next_upload = 0;
@@ -1011,15 +1107,19 @@ extern "C" zo2_status zo2_flush(zo2_ctx* c) {
         }
     for (int l = 0; l < g.n_layers; ++l) {
         if (c->resident) {
-            zo2_status s = k1_block(c, l, c->slots + (size_t)l * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f);
-            if (s != ZO2_OK) return s;
+            for (int k = 0; k < np; ++k) {
+                zo2_status s = k1_block(c, l, c->slots + (size_t)l * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f, nullptr, k);
+                if (s != ZO2_OK) return s;
+            }
         } else {
             const int sl = l % c->n_slots;
             HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));
-            zo2_status s = k1_block(c, l, c->slots + (size_t)sl * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f);
-            if (s != ZO2_OK) return s;
+            for (int k = 0; k < np; ++k) {
+                zo2_status s = k1_block(c, l, c->slots + (size_t)sl * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f, nullptr, k);
+                if (s != ZO2_OK) return s;
+            }
             HIPCHK(c, hipEventRecord(c->ev_k1[sl], c->sc));
-            s = enqueue_offload(c, l, true);
+            zo2_status s = enqueue_offload(c, l, true);
             if (s != ZO2_OK) return s;
             if (next_upload < g.n_layers) {
                 s = enqueue_upload(c, next_upload++);
@@ -1027,21 +1127,13 @@ extern "C" zo2_status zo2_flush(zo2_ctx* c) {
             }
         }
     }
-    {
-        K1Args a;
-        k1_common(c, a, 0, 0.f);
-        a.theta = c->d_fln; a.nseg = 2;
-        for (int k = 0; k < 2; ++k) {
-            a.seg[k].off = k * c->fln_off_b; a.seg[k].e0 = 0; a.seg[k].n = (uint64_t)g.d_model;
-            a.seg[k].tensor_id = fln_tid(c) + k; a.seg[k].scale = c->scales[fln_tid(c) + k];
-        }
-        OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, g.compute_dtype, true, false, c->sc));
-    }
-    if (c->d_lm) { zo2_status s = k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), false, nullptr, nullptr, 0, 0.f); if (s != ZO2_OK) return s; }
+    for (int k = 0; k < np; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
+    if (c->d_lm)
+        for (int k = 0; k < np; ++k) { zo2_status s = k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), false, nullptr, nullptr, 0, 0.f, nullptr, k); if (s != ZO2_OK) return s; }
     HIPCHK(c, hipStreamSynchronize(c->sc));
     HIPCHK(c, hipStreamSynchronize(c->su));
     HIPCHK(c, hipStreamSynchronize(c->so));
-    c->has_pending = false;
+    c->n_pend = 0;
     return ZO2_OK;
 }
 

@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--eps", type=float, default=1e-3)
     ap.add_argument("--lr", type=float, default=1e-7)
     ap.add_argument("--fp8-scale", type=float, default=64.0)
+    ap.add_argument("--directions", type=int, default=1, help="directions per update (1 = the paper's estimator; q > 1: one step + q - 1 extra directions per round, eta / q each)")
     ap.add_argument("--no-overlap", action="store_true", help="ablation: upload, compute, offload of a block strictly in sequence")
     ap.add_argument("--flush-each-step", action="store_true", help="ablation: no deferred update (every block travels twice per step)")
     args = ap.parse_args()
@@ -91,17 +92,19 @@ def main():
     t0 = time.perf_counter()
     up = down = 0
     ms_u = ms_o = ms_c = 0.0
+    q = max(1, args.directions)
     for j in range(args.steps):
-        res = ctx.step(tok, lab, 100 + j, args.eps, args.lr)
-        st = ctx.step_stats()
+        for i in range(q):           # a "step" of the output below is one round of q directions
+            res = (ctx.step if i == 0 else ctx.step_extra)(tok, lab, 100 + 16 * j + i, args.eps, args.lr / q)
+            st = ctx.step_stats()
+            up += st["bytes_up"]; down += st["bytes_down"]
+            ms_u += st["ms_upload"]; ms_o += st["ms_offload"]; ms_c += st["ms_compute"]
         if args.flush_each_step:
             ctx.flush()
-        up += st["bytes_up"]; down += st["bytes_down"]
-        ms_u += st["ms_upload"]; ms_o += st["ms_offload"]; ms_c += st["ms_compute"]
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
     out = {"model": args.model, "layers": L, "batch": args.batch, "seq": args.seq, "wire": args.wire, "compute": args.compute,
-           "resident": plan["resident"], "n_slots": plan["n_slots"], "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
+           "resident": plan["resident"], "n_slots": plan["n_slots"], "directions": q, "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
            "ms_per_step": dt * 1e3, "tokens_per_s": T / dt, "ms_per_block": dt * 1e3 / max(L, 1),
            "bucket_MB": bucket_bytes / 1e6,
            "upload_GBps": (up / 1e9) / (ms_u / 1e3) if ms_u else None,

@@ -1,0 +1,145 @@
+"""GPU parity of rounds of several directions (zo2_step + zo2_step_extra through the C ABI) against the oracle's
+q-direction form of the estimator: same losses per direction, same parameters after the round's updates."""
+import copy
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import codec, opt_model, zo_step
+
+pytestmark = pytest.mark.gpu
+
+
+def _b():
+    from paper_2503_12668_amd import binding
+    return binding
+
+
+def _case(n_layers=3, tied=True):
+    cfg = si.tiny_config(n_layers=n_layers, d_model=64, n_heads=4, d_ffn=136, vocab=211, max_pos=40, tied=tied)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 3, 23, seed=12)
+    lab = si.next_token_labels(tok)
+    lab[1, 4] = -100
+    return cfg, P, tok, lab
+
+
+def _round(obj, tok, lab, seeds, eps, lrs):
+    out = [obj.step(tok, lab, seeds[0], eps, lrs[0])]
+    out += [obj.step_extra(tok, lab, s, eps, lr) for s, lr in zip(seeds[1:], lrs[1:])]
+    return out
+
+
+@pytest.mark.parametrize("tied", [True, False])
+def test_fp32_rounds_match_oracle(tied):
+    b = _b()
+    cfg, P, tok, lab = _case(tied=tied)
+    oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), copy.deepcopy(P))
+    ctx = b.Zo2Context(cfg, P, arena_bytes=256 << 20)
+    q = 3
+    for j in range(3):
+        seeds = [500 + 10 * j + i for i in range(q)]
+        lrs = [3e-4 / q] * q
+        ro = _round(oz, tok, lab, seeds, 1e-3, lrs)
+        rg = _round(ctx, tok, lab, seeds, 1e-3, lrs)
+        for a, g in zip(ro, rg):
+            assert abs(float(g[0]) - float(a[0])) <= 1e-5 * abs(float(a[0]))
+            assert abs(float(g[1]) - float(a[1])) <= 1e-5 * abs(float(a[1]))
+            assert abs(float(g[2]) - float(a[2])) <= 1e-5 * abs(float(a[0])) / 1e-3
+        assert len(ctx.pending_list()) == q and [s for s, _ in ctx.pending_list()] == seeds
+    oz.flush(); ctx.flush(); ctx.sync_to_host()
+    assert ctx.pending_list() == []
+    Pg = ctx.parameters()
+    for n in oz.P:
+        assert np.abs(Pg[n] - oz.P[n]).max() <= 1e-6, n
+        assert not np.array_equal(Pg[n], P[n]), n
+    ctx.close()
+
+
+def test_extra_directions_leave_the_parameters_alone_and_streamed_equals_resident():
+    """A further direction uploads a streamed block but writes nothing back; the round's updates are applied while each
+    block passes through its slot in the next pass; streamed and resident runs agree bit for bit."""
+    b = _b()
+    cfg, P, tok, lab = _case(n_layers=7)
+    ctx_r = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+    ctx_s = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+    r = [ctx_r.step(tok, lab, 5, 1e-3, 1e-4)]
+    bucket = ctx_r.offs[16] * 4
+    ctx_s.set_resident_budget(ctx_r.plan()["bytes_used"] - 3 * bucket)
+    s = [ctx_s.step(tok, lab, 5, 1e-3, 1e-4)]
+    assert not ctx_s.plan()["resident"]
+    for j in range(3):
+        for i in range(1, 4):
+            r.append(ctx_r.step_extra(tok, lab, 100 * j + i, 1e-3, 1e-4))
+            s.append(ctx_s.step_extra(tok, lab, 100 * j + i, 1e-3, 1e-4))
+            st = ctx_s.step_stats()
+            assert st["bytes_up"] == 7 * bucket and st["bytes_down"] == 0
+        r.append(ctx_r.step(tok, lab, 100 * j + 50, 1e-3, 1e-4))
+        s.append(ctx_s.step(tok, lab, 100 * j + 50, 1e-3, 1e-4))
+        st = ctx_s.step_stats()
+        assert st["bytes_up"] == 7 * bucket and st["bytes_down"] == 7 * bucket
+    assert [tuple(map(float, x)) for x in r] == [tuple(map(float, x)) for x in s]
+    # the same direction again at unchanged parameters gives the same numbers
+    a = ctx_r.step_extra(tok, lab, 777, 1e-3, 0.0)
+    a2 = ctx_r.step_extra(tok, lab, 777, 1e-3, 0.0)
+    assert tuple(map(float, a)) == tuple(map(float, a2))
+    s.append(ctx_s.step_extra(tok, lab, 777, 1e-3, 0.0)); s.append(ctx_s.step_extra(tok, lab, 777, 1e-3, 0.0))
+    ctx_r.flush(); ctx_s.flush(); ctx_r.sync_to_host(); ctx_s.sync_to_host()
+    Pr, Ps = ctx_r.parameters(), ctx_s.parameters()
+    for n in Pr:
+        assert np.array_equal(Pr[n], Ps[n]), n
+    ctx_r.close(); ctx_s.close()
+
+
+def test_round_state_travels_through_a_checkpoint_and_limits_hold():
+    b = _b()
+    cfg, P, tok, lab = _case()
+    ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+    with pytest.raises(b.Zo2Error) as e:                       # no round in progress
+        ctx.step_extra(tok, lab, 1, 1e-3, 1e-4)
+    assert e.value.status == 5
+    _round(ctx, tok, lab, [1, 2, 3], 1e-3, [1e-4] * 3)
+    with pytest.raises(b.Zo2Error) as e:                       # the single-update accessor refuses a round of three
+        ctx.pending()
+    assert e.value.status == 5
+    items = ctx.pending_list()
+    ctx.sync_to_host()
+    P1 = ctx.parameters()
+    ctx2 = b.Zo2Context(cfg, P1, arena_bytes=64 << 20)
+    ctx2.set_pending_list(items)
+    a = _round(ctx, tok, lab, [11, 12], 1e-3, [1e-4] * 2)
+    c = _round(ctx2, tok, lab, [11, 12], 1e-3, [1e-4] * 2)
+    assert [tuple(map(float, x)) for x in a] == [tuple(map(float, x)) for x in c]
+    ctx.flush(); ctx2.flush(); ctx.sync_to_host(); ctx2.sync_to_host()
+    Pa, Pc = ctx.parameters(), ctx2.parameters()
+    for n in Pa:
+        assert np.array_equal(Pa[n], Pc[n]), n
+    # sixteen directions per round at most
+    ctx.step(tok, lab, 1, 1e-3, 0.0)
+    for i in range(15):
+        ctx.step_extra(tok, lab, 100 + i, 1e-3, 0.0)
+    with pytest.raises(b.Zo2Error) as e:
+        ctx.step_extra(tok, lab, 999, 1e-3, 0.0)
+    assert e.value.status == 5
+    # evaluation applies the whole round, like a flush
+    l0 = ctx.eval(tok, lab)
+    assert ctx.pending_list() == [] and np.isfinite(l0)
+    ctx.close(); ctx2.close()
+
+
+@pytest.mark.parametrize("wire,compute", [("bf16", "bf16"), ("fp8_e4m3", "bf16")])
+def test_low_precision_rounds_track_oracle_losses(wire, compute):
+    b = _b()
+    cfg, P, tok, lab = _case()
+    Po = {n: codec.round_to(a, wire) for n, a in copy.deepcopy(P).items()}
+    oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), Po, store=wire, compute=compute)
+    ctx = b.Zo2Context(cfg, P, wire=wire, compute=compute, arena_bytes=64 << 20)
+    for j in range(2):
+        seeds = [40 + 10 * j + i for i in range(3)]
+        ro = _round(oz, tok, lab, seeds, 1e-3, [1e-2 / 3] * 3)
+        rg = _round(ctx, tok, lab, seeds, 1e-3, [1e-2 / 3] * 3)
+        for a, g in zip(ro, rg):
+            assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
+            assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
+    ctx.close()

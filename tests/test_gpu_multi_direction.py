@@ -143,3 +143,23 @@ def test_low_precision_rounds_track_oracle_losses(wire, compute):
             assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
             assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
     ctx.close()
+
+
+def test_training_on_a_fixed_batch_lowers_the_loss_and_more_directions_lower_it_faster():
+    """End to end through the C ABI: 200 updates on one batch.  One direction per update at eta = 1e-3 takes the
+    loss from 5.56 to about 4.84; four directions per update carry a three times larger eta and reach about 4.25
+    (an average over q directions has 1/q of the variance)."""
+    b = _b()
+    cfg, P, tok, lab = _case()
+    final = {}
+    for q, lr in ((1, 1e-3), (4, 3e-3)):
+        ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
+        l0 = float(ctx.eval(tok, lab))
+        for j in range(200):
+            ctx.step(tok, lab, 1000 + 16 * j, 1e-3, lr / q)
+            for i in range(1, q):
+                ctx.step_extra(tok, lab, 1000 + 16 * j + i, 1e-3, lr / q)
+        final[q] = float(ctx.eval(tok, lab))
+        ctx.close()
+    assert final[1] < 0.93 * l0, (l0, final)
+    assert final[4] < 0.85 * l0 and final[4] < final[1] - 0.2, (l0, final)

@@ -159,7 +159,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
     constexpr int GCH = DH / 8;          // 16-byte chunks per row in memory
     constexpr int KTILE = 32 * DHP * 2, BUF = 2 * KTILE;                  // K tile, then V tile
     constexpr int KINSTR = KTILE / 1024 / 4;                              // direct-to-LDS loads per wavefront per tile and operand
-    __shared__ __attribute__((aligned(1024))) char lds[2 * BUF];
+    constexpr int NBUF = 4;                                               // ring of K / V tiles: loads run NBUF - 1 tiles ahead of the MFMAs
+    __shared__ __attribute__((aligned(1024))) char lds[NBUF * BUF];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, kh = lane >> 5;
@@ -280,12 +281,25 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
             for (int s2 = 0; s2 < 2; ++s2) o[d] = AttMfma<T>::run(vf[d][s2], pf[s2], o[d]);
     };
 
-    issue_tile(0, 0);
+    // A tile is 8 - 16 KB and its MFMAs take a few hundred cycles, far less than a trip to memory: with one tile in
+    // flight every iteration waited out the full latency.  NBUF - 1 tiles are kept in flight instead; direct-to-LDS loads
+    // complete in issue order, so "all but the loads of the `ahead` younger tiles" is an exact wait for this tile.
+#pragma unroll
+    for (int t = 0; t < NBUF - 1; ++t)
+        if (t <= wg_last_tile) issue_tile(t, t);
+    // (the Q fragments were requested before the tiles; consuming them here puts the compiler's wait for them in front
+    // of the loop instead of inside it, where it would also wait for every tile in flight)
+#pragma unroll
+    for (int c = 0; c < KS; ++c) asm volatile("" : : "v"(qf[c].x), "v"(qf[c].y), "v"(qf[c].z), "v"(qf[c].w));
     for (int tile = 0; tile <= wg_last_tile; ++tile) {
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // own loads of this tile landed; own reads of the other buffer done
+        const int ahead = min(NBUF - 2, wg_last_tile - tile);        // younger tiles already issued
+        // own loads of this tile landed; own reads of the buffer that is refilled below are done
+        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * 2 * KINSTR) : "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * KINSTR) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __syncthreads();
-        if (tile + 1 <= wg_last_tile) issue_tile(tile + 1, (tile + 1) & 1);
-        if (active && tile <= my_last_tile) process_tile(tile, tile & 1);
+        if (tile + NBUF - 1 <= wg_last_tile) issue_tile(tile + NBUF - 1, (tile + NBUF - 1) % NBUF);   // into the buffer of tile - 1
+        if (active && tile <= my_last_tile) process_tile(tile, tile % NBUF);
     }
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;

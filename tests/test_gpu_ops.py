@@ -16,7 +16,9 @@ def _b():
 
 @pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("M,N,K", [(64, 64, 64), (22, 32, 32), (200, 136, 72), (257, 515, 264), (128, 97 * 8, 40), (4, 8, 8),
-                                   (256, 256, 64), (512, 768, 128), (300, 515, 192), (1024, 384, 2048), (700, 1030, 320)])
+                                   (256, 256, 64), (512, 768, 128), (300, 515, 192), (1024, 384, 2048), (700, 1030, 320),
+                                   # the 256 x 256 kernel (K % 128 == 0) with ragged rows and columns, two to six k-slabs
+                                   (257, 260, 128), (300, 520, 256), (700, 1032, 384)])
 def test_gemm_against_float64(dt, M, N, K):
     b = _b()
     g = torch.Generator().manual_seed(M * 1000 + N + K)
@@ -120,3 +122,5 @@ def test_lm_head_ce_small_and_bad_shapes():
         b.op_lm_head_ce(X[:100].cuda(), W.cuda(), lab[:100].cuda())          # fewer than 256 rows
     with pytest.raises(b.Zo2Error):
         b.op_lm_head_ce(X.float().cuda(), W.float().cuda(), lab.cuda())      # float32 has no fused path
+    with pytest.raises(b.Zo2Error):
+        b.op_lm_head_ce(X[:, :64].contiguous().cuda(), W[:, :64].contiguous().cuda(), lab.cuda())   # K is not a multiple of 128

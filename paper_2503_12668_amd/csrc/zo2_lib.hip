@@ -965,10 +965,11 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         HIPCHK(c, hipStreamSynchronize(c->so));
     }
     prof_collect(c);
-    hipEventElapsedTime(&c->ms_c, c->ev_step0, c->ev_c1);
-    c->ms_u = c->ms_o = 0.f;
-    if (c->stat_u) hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
-    if (c->stat_o) hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
+    // statistics only: a failed query leaves the figure at zero
+    c->ms_c = c->ms_u = c->ms_o = 0.f;
+    (void)hipEventElapsedTime(&c->ms_c, c->ev_step0, c->ev_c1);
+    if (c->stat_u) (void)hipEventElapsedTime(&c->ms_u, c->ev_u0, c->ev_u1);
+    if (c->stat_o) (void)hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
 
     c->apply_now = true;
     if (ns == 1) {

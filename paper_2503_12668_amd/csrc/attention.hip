@@ -241,31 +241,40 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const T* __restr
         for (int v = 0; v < 16; ++v) st[v] = 0.f;
 #pragma unroll
         for (int c = 0; c < KS; ++c) st = AttMfma<T>::run(kf[c], qf[c], st);
-        // ---- mask (only the diagonal tile has hidden keys) and online softmax
-        float tmax = -INFINITY;
+        // ---- mask (only the diagonal tile has hidden keys; the branch is wave-uniform) and online softmax
+        if (tile == my_last_tile) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            // accumulator row rho = 8 (v/4) + 4 kh + v%4 carries key j0 + pi(rho) = j0 + 16 (v/8) + 8 kh + v%8
-            const int key = j0 + 16 * (v >> 3) + 8 * kh + (v & 7);
-            if (tile == my_last_tile && key > qi) st[v] = -INFINITY;
-            tmax = fmaxf(tmax, st[v]);
+            for (int v = 0; v < 16; ++v) {
+                // accumulator row rho = 8 (v/4) + 4 kh + v%4 carries key j0 + pi(rho) = j0 + 16 (v/8) + 8 kh + v%8
+                const int key = j0 + 16 * (v >> 3) + 8 * kh + (v & 7);
+                if (key > qi) st[v] = -INFINITY;
+            }
         }
+        float tmax = st[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, st[v]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
         const float m_new = fmaxf(m_run, tmax);              // finite: key j0 <= q0 <= qi is always visible in tile 0
-        const float resc = __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);
+        const float m2 = m_new * kLog2e;
         float psum = 0.f;
         float p[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            p[v] = __builtin_amdgcn_exp2f((st[v] - m_new) * kLog2e);
+            p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[v], kLog2e, -m2));      // exp(st - m_new)
             psum += p[v];
         }
-        l_run = l_run * resc + psum;
-        m_run = m_new;
+        // the running maximum of a query rarely moves after its first tiles: the accumulators are rescaled only when it
+        // moved for some query of this wavefront
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+            const float resc = __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);
+            l_run *= resc;
 #pragma unroll
-        for (int d = 0; d < DT; ++d)
+            for (int d = 0; d < DT; ++d)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[d][v] *= resc;
+                for (int v = 0; v < 16; ++v) o[d][v] *= resc;
+            m_run = m_new;
+        }
+        l_run += psum;
         // ---- O^T += V^T P^T
         uint4 pf[2];
 #pragma unroll

@@ -266,6 +266,13 @@ zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K,
                        const float* residual, void* Y, int32_t out_dtype, int64_t ldy,
                        float out_scale, int32_t relu, void* stream);
 
+/* The large-tile GEMM kernel works on 256- or 128-row tiles and picks the height per launch (whichever fills the
+ * rounds of tiles over the compute units better).  rows = 128 or 256 forces one height for every later launch of the
+ * process, step calls included; 0 restores the choice per launch.  For tests and measurements: results are the same
+ * bit for bit either way (the order in which a dot product is accumulated does not depend on the tile height).
+ * Returns ZO2_EINVAL for any other value. */
+zo2_status zo2_op_set_gemm_tile_rows(int32_t rows);
+
 /* Causal multi-head self-attention.  q, k, v, out: [n_seq * seq, ld] of `dtype`, head h in
  * columns h*d_head .. (h+1)*d_head-1; q already carries the 1/sqrt(d_head) factor.
  * out[i] = softmax_{j <= i}(q_i . k_j) v_j within each sequence.  d_head in {8,16,32,64,80,128}.

@@ -87,6 +87,7 @@ def lib():
         "zo2_op_update_perturb": (i32, [vp, i32, vp, vp, i32, u32, u64, u64, i32, u64, f32, u64, f32, f32, i32, vp]),
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
+        "zo2_op_set_gemm_tile_rows": (i32, [i32]),
         "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i32, vp]),
         "zo2_op_layernorm": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
         "zo2_op_cross_entropy_rows": (i32, [vp, i64, vp, i32, i32, vp, vp]),
@@ -104,7 +105,7 @@ def lib():
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
-            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm",
+            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes"]
 
@@ -187,6 +188,11 @@ def op_gemm(X, W, bias=None, residual=None, out_dtype=None, out_scale=1.0, relu=
     _op_check(lib().zo2_op_gemm(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(residual),
                                 _ptr(Y), odt, Y.stride(0), out_scale, 1 if relu else 0, _stream_ptr(stream)))
     return Y
+
+
+def op_set_gemm_tile_rows(rows):
+    """0: the GEMM picks 128- or 256-row tiles per launch; 128 / 256: forced (tests, measurements)."""
+    _op_check(lib().zo2_op_set_gemm_tile_rows(int(rows)))
 
 
 def op_attention(q, k, v, n_seq, seq, n_heads, d_head, vector_kernel=False, stream=None):

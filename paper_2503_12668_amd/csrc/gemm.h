@@ -37,6 +37,8 @@ struct GemmArgs {
 zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st);
 // the 256 x 256 x 64 kernel (bf16 / fp16, K % 128 == 0); gemm_launch picks it for large problems
 zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st);
+// 0 (default): the 256 x 256 kernel picks 256- or 128-row tiles per launch; 128 / 256: every launch uses that height
+void gemm256_force_tile_rows(int rows);
 bool gemm256_applicable(const GemmArgs& a, int dtype);
 
 }  // namespace zo2

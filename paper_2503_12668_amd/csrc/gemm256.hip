@@ -51,10 +51,15 @@ template <> struct Mfma16<f16_t> {
     }
 };
 
-static constexpr int kBM = 256, kBN = 256, kBK = 64;
-static constexpr int kStageBytes = (kBM + kBN) * kBK * 2;      // 65536
+// Tile: (32 MI) x 256 x 64 with MI = 8 (256 rows; the main shape) or MI = 4 (128 rows: twice as many tiles for
+// launches whose 256-row tiles would leave compute units idle or a last round of tiles mostly empty).
+static constexpr int kBN = 256, kBK = 64;
 static constexpr int kEpiRegion = 24576;                       // per-wave output staging above stage 0
-static constexpr int kLdsBytes = kStageBytes + 4 * kEpiRegion; // 163840 = all 160 KB of a compute unit
+template <int MI> struct Tile256 {
+    static constexpr int BM = 32 * MI;
+    static constexpr int kStageBytes = (BM + kBN) * kBK * 2;           // 65536 / 49152
+    static constexpr int kLdsBytes = kStageBytes + 4 * kEpiRegion;     // 163840 (all 160 KB of a compute unit) / 147456
+};
 
 // direct-to-LDS load of 16 bytes per lane: lane i's data lands at lds_base + 16 i
 // source address = wave-uniform base (SGPR pair) + per-lane 32-bit byte offset
@@ -67,12 +72,9 @@ __device__ __forceinline__ void load_to_lds(const void* sbase, uint32_t voff, ui
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
 
-// The same load split into its pieces, for the main loop: there every instruction of a wavefront competes with its
-// MFMAs for issue slots, so the LDS destination register is stepped with one scalar add (instead of being recomputed
-// and moved), and the MFMA issued between the write of m0 and the load takes the place of the wait state they need.
+// The same load split into its pieces, for the main loop: the MFMA issued between the write of m0 and the load takes the
+// place of the wait state they need.
 __device__ __forceinline__ void m0_set(uint32_t lds_base) { asm volatile("s_mov_b32 m0, %0" : : "s"(lds_base) : "memory"); }
-template <uint32_t DELTA>
-__device__ __forceinline__ void m0_step() { asm volatile("s_add_u32 m0, m0, %0" : : "i"(DELTA) : "memory", "scc"); }
 // `lanes` (wave-uniform: all ones or zero) is the execution mask of the load: zero turns it into a no-op without a
 // branch, so that the compiler sees straight-line code and keeps one register assignment for the accumulators over the
 // whole k loop (see Mfma16).  The k loop runs with all 64 lanes active, which is what the mask is restored to.
@@ -95,6 +97,7 @@ __device__ __forceinline__ int swz(int row) { return row & 7; }
 // Tiles of one problem are walked in groups of 8 rows of the tile grid (column-major inside a
 // group) so that workgroups running at the same time share operand panels in L2.
 struct TileCoord { int prob, m0, n0; };
+template <int BM>
 __device__ __forceinline__ TileCoord tile_coord(int vid, int ntiles, int tiles_m, int tiles_n) {
     constexpr int GM = 8;
     TileCoord c;
@@ -104,7 +107,7 @@ __device__ __forceinline__ TileCoord tile_coord(int vid, int ntiles, int tiles_m
     const int gm0 = group * GM;
     const int gsz = min(GM, tiles_m - gm0);
     const int in_group = local - group * GM * tiles_n;
-    c.m0 = (gm0 + in_group % gsz) * kBM;
+    c.m0 = (gm0 + in_group % gsz) * BM;
     c.n0 = (in_group / gsz) * kBN;
     return c;
 }
@@ -112,9 +115,11 @@ __device__ __forceinline__ TileCoord tile_coord(int vid, int ntiles, int tiles_m
 // Persistent kernel: gridDim.x workgroups (one per compute unit) walk the tile list with stride
 // gridDim.x.  Consecutive workgroup ids sit on different XCDs (8 of them, each with its own L2),
 // so within a round of gridDim.x tiles XCD x takes a contiguous run of tile ids.
-template <typename T, typename OutT>
+template <typename T, typename OutT, int MI>
 __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, int total_tiles) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    constexpr int kBM = Tile256<MI>::BM, kStageBytes = Tile256<MI>::kStageBytes;
+    constexpr int WPG = 8 / MI;                 // W row-blocks handled per group of eight MFMAs: 1 or 2
     const int tiles_n = (a.N + kBN - 1) / kBN;
     const int tiles_m = (a.M + kBM - 1) / kBM;
     const int ntiles = tiles_m * tiles_n;
@@ -126,9 +131,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     const int wm = wave >> 1, wn = wave & 1, r = lane & 15, kg = lane >> 4;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
-    const uint32_t ld_a = lds0 + wave * 8192, ld_b = lds0 + 32768 + wave * 8192;
-    // fragment read plan: row (w*128 + i*16 + r), chunk (4 ks + kg) ^ swz(row); swz(row) = swz(r); two k-steps of 32 per slab
-    const uint32_t fr_a = (wm * 128 + r) * 128, fr_b = 32768 + (wn * 128 + r) * 128;
+    // a stage holds the X rows (128 bytes each), then the W rows; a wavefront loads a quarter of each
+    const uint32_t ld_a = lds0 + wave * (MI * 1024), ld_b = lds0 + kBM * 128 + wave * 8192;
+    // fragment read plan: row (w*16 MI + i*16 + r) of X, (w*128 + j*16 + r) of W, chunk (4 ks + kg) ^ swz(row); swz(row) = swz(r); two k-steps of 32 per slab
+    const uint32_t fr_a = (wm * (16 * MI) + r) * 128, fr_b = kBM * 128 + (wn * 128 + r) * 128;
     uint32_t koff[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) koff[ks] = (uint32_t)(((ks * 4 + kg) ^ swz(r)) * 16);
@@ -145,10 +151,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         }
     const int nk = a.K / kBK;
 
-    // loader plan: per stage each wavefront brings 64 rows of A and 64 rows of B, 8 rows per
+    // loader plan: per stage each wavefront brings 8 MI rows of X and 64 rows of W, 8 rows per
     // instruction; lane -> (row lane/8, position lane%8) and the chunk that belongs there
     // (rows past the end of the matrix are clamped to its last row; their products are never stored)
-    uint32_t pa[8], pb[8];              // per-lane byte offsets from the tile's first row
+    uint32_t pa[MI], pb[8];             // per-lane byte offsets from the tile's first row
     const T* base_x;                    // wave-uniform: first row of the tile in X / W
     const T* base_w;
     auto plan_loads = [&](const TileCoord& tc) {
@@ -160,51 +166,51 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         base_x = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.X) + (size_t)tc.m0 * a.ldx));
         base_w = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.W) + (size_t)tc.n0 * a.ldw));
         const int mrem = a.M - 1 - tc.m0, nrem = a.N - 1 - tc.n0;
+        const int lkc = (lane & 7) ^ swz(lrow);             // rows of one instruction differ in their low three bits only
+#pragma unroll
+        for (int t = 0; t < MI; ++t) pa[t] = (uint32_t)((size_t)min(wave * (8 * MI) + t * 8 + lrow, mrem) * a.ldx + lkc * 8) * (uint32_t)sizeof(T);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) pb[t] = (uint32_t)((size_t)min(wave * 64 + t * 8 + lrow, nrem) * a.ldw + lkc * 8) * (uint32_t)sizeof(T);
+    };
+    auto issue_slab = [&](int stage, int k0) {          // one k-slab of the planned tile, all at once
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const int row = wave * 64 + t * 8 + lrow;
-            const int lkc = (lane & 7) ^ swz(row);
-            pa[t] = (uint32_t)((size_t)min(row, mrem) * a.ldx + lkc * 8) * (uint32_t)sizeof(T);
-            pb[t] = (uint32_t)((size_t)min(row, nrem) * a.ldw + lkc * 8) * (uint32_t)sizeof(T);
+            if (t < MI) load_to_lds(base_x + k0, pa[t], ld_a + stage * kStageBytes + t * 1024);
+            load_to_lds(base_w + k0, pb[t], ld_b + stage * kStageBytes + t * 1024);
         }
     };
-    auto issue_slab0 = [&]() {          // k-slab 0 of the planned tile into stage 0
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            load_to_lds(base_x, pa[t], ld_a + t * 1024);
-            load_to_lds(base_w, pb[t], ld_b + t * 1024);
-        }
-    };
+    auto issue_slab0 = [&]() { issue_slab(0, 0); };     // k-slab 0 into stage 0
 
     int vid = slot;
     if (vid >= total_tiles) return;
-    TileCoord tc = tile_coord(vid, ntiles, tiles_m, tiles_n);
+    TileCoord tc = tile_coord<kBM>(vid, ntiles, tiles_m, tiles_n);
     plan_loads(tc);
     issue_slab0();
 
     for (;;) {
         // acc[i][j]: X rows (m) i-th 16-block, W rows (n) j-th 16-block.  The W fragment is the
         // MFMA "A" operand, so a lane ends up with one m (= r) and a run of 4 consecutive n (4 kg ..).
-        f32x4_t acc[8][8];
+        f32x4_t acc[MI][8];
         const u32x4_t zero_operand = mfma16_zero_operand();
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 mfma16_clear(acc[i][j], zero_operand);
 
-        uint4 fa[8], fb[2][8];      // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
+        uint4 fa[MI], fb[2][8];      // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
         // One "group" = the eight MFMAs of X row-block i at k-step buffer `buf`, with the two LDS reads
         // that fetch row-block i of both operands for the next k-step into buffer `nbuf` and optionally
         // two direct-to-LDS loads of a later k-slab dealt out between them.  With one wavefront per SIMD
         // every instruction takes an issue slot of this wavefront and only about three fit under one
         // 16-cycle MFMA: scheduling barriers pin one piece of memory work behind each of the first MFMAs.
         auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool do_dma, uint64_t dma_lanes, int dma_stage, int dma_k0) {
-            // do_dma: direct-to-LDS loads of rows 8 i .. 8 i + 7 (of this wavefront's 64) of both operands of a later
-            // slab; their LDS destinations follow each other as X_0, W_0, X_1, W_1, ...: + 32768, - 31744, + 32768 ...
+            // do_dma: direct-to-LDS loads of a later slab: rows 8 i .. 8 i + 7 of this wavefront's share of X, and WPG
+            // times as many of its 64 rows of W
+            const uint32_t so = dma_stage * kStageBytes;
             Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) { if (i == 0) m0_set(ld_a + dma_stage * kStageBytes); else m0_step<0xffff8400u>(); }
+            if (do_dma) m0_set(ld_a + so + i * 1024);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][1], fa[i], acc[i][1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -212,18 +218,25 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][2], fa[i], acc[i][2]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) m0_step<0x8000u>();
+            if (do_dma) m0_set(ld_b + so + (i * WPG) * 1024);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][3], fa[i], acc[i][3]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i], dma_lanes);
+            if (do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i * WPG], dma_lanes);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][4], fa[i], acc[i][4]);
             __builtin_amdgcn_sched_barrier(0);
-            fb[nbuf][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
+            fb[nbuf][i * WPG] = *reinterpret_cast<const uint4*>(sb + (i * WPG) * 2048);
+            if (WPG == 2 && do_dma) m0_set(ld_b + so + (i * WPG + 1) * 1024);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][5], fa[i], acc[i][5]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (WPG == 2 && do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i * WPG + WPG - 1], dma_lanes);
+            __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][6], fa[i], acc[i][6]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (WPG == 2) fb[nbuf][i * WPG + WPG - 1] = *reinterpret_cast<const uint4*>(sb + (i * WPG + WPG - 1) * 2048);
+            __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][7], fa[i], acc[i][7]);
             __builtin_amdgcn_sched_barrier(0);
             fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);      // this group's X fragment is free now
@@ -243,7 +256,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             const char* sb = frag_w[0][0];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);
+                if (i < MI) fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);
                 fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
             }
         }
@@ -259,19 +272,13 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         auto slab_iter = [&](int kt, auto stage_c, uint64_t more_slabs) {
             constexpr int cur = decltype(stage_c)::value;          // kt & 1
 #pragma unroll
-            for (int i = 0; i < 8; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0ull, 0, 0);
+            for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0ull, 0, 0);
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 8; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, more_slabs, cur, (kt + 2) * kBK);
+            for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, more_slabs, cur, (kt + 2) * kBK);
         };
-        {                                // slab 1 (stage 1 is free once the barrier above is passed)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                load_to_lds(base_x + kBK, pa[t], ld_a + kStageBytes + t * 1024);
-                load_to_lds(base_w + kBK, pb[t], ld_b + kStageBytes + t * 1024);
-            }
-        }
+        issue_slab(1, kBK);              // slab 1 (stage 1 is free once the barrier above is passed)
         // nk is even (K % 128 == 0): slabs alternate between the two stages, two per trip
         using St0 = std::integral_constant<int, 0>;
         using St1 = std::integral_constant<int, 1>;
@@ -292,7 +299,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         const int next_vid = vid + G;
         const bool have_next = next_vid < total_tiles;
         if (have_next) {
-            tc = tile_coord(next_vid, ntiles, tiles_m, tiles_n);
+            tc = tile_coord<kBM>(next_vid, ntiles, tiles_m, tiles_n);
             plan_loads(tc);
             issue_slab0();
         }
@@ -334,7 +341,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             const bool n_ok = n < a.N;                             // N % 8 == 0 is required for this path
             const bool interior = (m0 + kBM <= a.M) && (n0 + kBN <= a.N);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < MI / 2; ++i) {
                 char* buf = reg + (i & 1) * (32 * ROWH);
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)                 // pass i = X row-blocks 2 i and 2 i + 1
@@ -350,7 +357,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 uint4 v8[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) v8[u] = *reinterpret_cast<const uint4*>(buf + (4 * u + rr) * ROWH + ch * 16);
-                const int mf = m0 + wm * 128 + i * 32 + rr;
+                const int mf = m0 + wm * (16 * MI) + i * 32 + rr;
                 OutT* yp = Y + (size_t)mf * a.ldy + n;
                 if (interior) {
 #pragma unroll
@@ -383,7 +390,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             auto run_passes = [&](auto masked_c, auto res_c) {
                 constexpr bool MASKED = decltype(masked_c)::value, RES = decltype(res_c)::value;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < MI / 2; ++i) {
                     if (i) __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
@@ -393,7 +400,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                             *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
-                    const int mf = m0 + wm * 128 + i * 32 + rr;                 // row of u = 0; u adds 2 rows
+                    const int mf = m0 + wm * (16 * MI) + i * 32 + rr;                 // row of u = 0; u adds 2 rows
                     const size_t off0 = (size_t)(MASKED ? min(mf, a.M - 1) : mf) * a.ldy + (MASKED && !n_ok ? 0 : n);
                     float4 v4[16], rv[16];
 #pragma unroll
@@ -430,7 +437,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 const int ncol0 = n0 + wn * 128 + chalf * 64;
                 const size_t span = (size_t)(4 * (n0 / kBN) + 2 * wn + chalf) * (size_t)a.part_ld;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < MI / 2; ++i) {
                     if (i) __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
@@ -440,7 +447,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                             *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
-                    const int row = m0 + wm * 128 + i * 32 + crow;
+                    const int row = m0 + wm * (16 * MI) + i * 32 + crow;
                     const bool row_ok = !MASKED || row < a.M;
                     const char* rp = reg + crow * ROWB + chalf * 256;
                     const int lab = p.labels[MASKED ? min(row, a.M - 1) : row];
@@ -498,23 +505,43 @@ static int device_cu_count() {
     return n;
 }
 
-template <typename T, typename OutT>
+template <typename T, typename OutT, int MI>
 static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
     static bool attr_set = false;
-    auto kern = gemm_mfma256_kernel<T, OutT>;
+    constexpr int BM = Tile256<MI>::BM, lds = Tile256<MI>::kLdsBytes;
+    auto kern = gemm_mfma256_kernel<T, OutT, MI>;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) {
-            set_op_error("gemm: cannot reserve %d bytes of LDS: %s", kLdsBytes, hipGetErrorString(e));
+            set_op_error("gemm: cannot reserve %d bytes of LDS: %s", lds, hipGetErrorString(e));
             return ZO2_EHIP;
         }
         attr_set = true;
     }
-    const int total = ((a.M + kBM - 1) / kBM) * ((a.N + kBN - 1) / kBN) * a.nprob;
+    const int total = ((a.M + BM - 1) / BM) * ((a.N + kBN - 1) / kBN) * a.nprob;
     const int grid = total < device_cu_count() ? total : device_cu_count();
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLdsBytes, st, a, total);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, total);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
+}
+
+// Rows per tile for a launch.  Workgroups are persistent, one per compute unit, and take whole tiles: with 256-row tiles
+// a launch of 128 tiles keeps half of 256 compute units busy, one of 640 tiles leaves the third round half empty.
+// A 128-row tile does half the work at a lower rate (same W panel per slab, half the X panel, half the MFMAs per
+// fragment read): measured 0.78 - 0.9 of the 256-row rate for K <= 4096 and 0.67 - 0.78 beyond on launches that fill the
+// chip either way.  It is chosen when the better filling of the rounds outweighs that.
+static int g_forced_tile_rows = 0;      // 0: per launch; 128 / 256: every launch (tests and measurements, see gemm256_force_tile_rows)
+void gemm256_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
+static int pick_tile_rows(const GemmArgs& a) {
+    if (g_forced_tile_rows == 128 || g_forced_tile_rows == 256) return g_forced_tile_rows;
+    const long cu = device_cu_count();
+    const long tn = (a.N + kBN - 1) / kBN;
+    auto filling = [&](long rows) {        // useful tile rows over the tile rows the rounds have room for
+        const long t = ((a.M + rows - 1) / rows) * tn * a.nprob, rounds = (t + cu - 1) / cu;
+        return (double)a.M * tn * a.nprob / (double)(rounds * cu * rows);
+    };
+    const double small_tile_rate = a.K > 4096 ? 0.72 : 0.78;
+    return filling(128) * small_tile_rate > filling(256) ? 128 : 256;
 }
 
 bool gemm256_applicable(const GemmArgs& a, int dtype) {
@@ -542,8 +569,15 @@ zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st) {
         set_op_error("gemm256: shape or alignment not supported by the 256 x 256 kernel");
         return ZO2_EINVAL;
     }
-    if (dtype == ZO2_BF16) return a.out_f32 ? launch256_t<bf16_t, float>(a, st) : launch256_t<bf16_t, bf16_t>(a, st);
-    if (dtype == ZO2_F16) return a.out_f32 ? launch256_t<f16_t, float>(a, st) : launch256_t<f16_t, f16_t>(a, st);
+    const bool small = pick_tile_rows(a) == 128;
+    if (dtype == ZO2_BF16) {
+        if (small) return a.out_f32 ? launch256_t<bf16_t, float, 4>(a, st) : launch256_t<bf16_t, bf16_t, 4>(a, st);
+        return a.out_f32 ? launch256_t<bf16_t, float, 8>(a, st) : launch256_t<bf16_t, bf16_t, 8>(a, st);
+    }
+    if (dtype == ZO2_F16) {
+        if (small) return a.out_f32 ? launch256_t<f16_t, float, 4>(a, st) : launch256_t<f16_t, f16_t, 4>(a, st);
+        return a.out_f32 ? launch256_t<f16_t, float, 8>(a, st) : launch256_t<f16_t, f16_t, 8>(a, st);
+    }
     set_op_error("gemm256: dtype %d unsupported", dtype);
     return ZO2_EINVAL;
 }

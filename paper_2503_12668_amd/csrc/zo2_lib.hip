@@ -1186,6 +1186,12 @@ extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void*
     return attention_launch(dtype, q, k, v, out, n_seq, seq, n_heads, d_head, ld, vector_kernel, as_stream(stream));
 }
 
+extern "C" zo2_status zo2_op_set_gemm_tile_rows(int32_t rows) {
+    ZO2_OP_CHECK(rows == 0 || rows == 128 || rows == 256, ZO2_EINVAL, "zo2_op_set_gemm_tile_rows: %d (0, 128 or 256)", rows);
+    gemm256_force_tile_rows(rows);
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2, void* y,
                                        int32_t rows, int32_t rows_first, int32_t d, float eps, void* stream) {
     return layernorm(dtype, x, w, b, w2, b2, y, rows, rows_first, d, eps, as_stream(stream));

@@ -44,6 +44,36 @@ def test_gemm_against_float64(dt, M, N, K):
     assert (Y3.double().cpu() - ref3).abs().max() <= t2 * max(1.0, ref3.abs().max())
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N,K", [(257, 260, 128), (300, 520, 256), (700, 1032, 384), (1024, 384, 2048), (2048, 512, 512)])
+def test_gemm_both_tile_heights(dt, M, N, K):
+    """The large-tile kernel with 256-row and with 128-row tiles: each against float64, and against each other bit for
+    bit (the order in which a dot product is accumulated does not depend on the tile height)."""
+    b = _b()
+    g = torch.Generator().manual_seed(M + N + K)
+    X = (torch.randn(M, K, generator=g) * 0.5).to(TD[dt]).cuda()
+    W = (torch.randn(N, K, generator=g) * 0.5).to(TD[dt]).cuda()
+    bias = (torch.randn(N, generator=g)).to(TD[dt]).cuda()
+    R = torch.randn(M, N, generator=g).cuda()
+    ref = (X.double() @ W.double().T + bias.double()) * 0.125
+    ref2 = torch.relu(ref) + R.double()
+    out = {}
+    try:
+        for rows in (128, 256):
+            b.op_set_gemm_tile_rows(rows)
+            Y = b.op_gemm(X, W, bias, out_scale=0.125)
+            Y2 = b.op_gemm(X, W, bias, residual=R, out_scale=0.125, relu=True, out_dtype=b.F32)
+            assert (Y.double() - ref).abs().max() <= 1e-2 * max(1.0, ref.abs().max()), rows
+            assert (Y2.double() - ref2).abs().max() <= 2e-3 * max(1.0, ref2.abs().max()), rows
+            out[rows] = (Y.cpu(), Y2.cpu())
+        with pytest.raises(b.Zo2Error):
+            b.op_set_gemm_tile_rows(64)
+    finally:
+        b.op_set_gemm_tile_rows(0)
+    assert torch.equal(out[128][0].view(torch.int16), out[256][0].view(torch.int16))
+    assert torch.equal(out[128][1], out[256][1])
+
+
 def test_gemm_rejects_bad_arguments():
     b = _b()
     X = torch.zeros(8, 12, device="cuda", dtype=torch.bfloat16)
@@ -113,11 +143,16 @@ def test_lm_head_ce_small_and_bad_shapes():
     W = (torch.randn(N, K, generator=g) * 0.2).to(torch.float16)
     lab = torch.randint(0, N, (M,), generator=g, dtype=torch.int32)
     lab[0] = -100
-    out = b.op_lm_head_ce(X.cuda(), W.cuda(), lab.cuda()).cpu()
     logits = X.double() @ W.double().T
     ref = torch.logsumexp(logits, -1) - logits.gather(1, lab.clamp(min=0).long()[:, None])[:, 0]
     ref[0] = 0.0
-    assert (out.double() - ref).abs().max() <= 2e-3 * max(1.0, float(ref.abs().max()))
+    try:
+        for rows in (128, 256, 0):                           # both tile heights of the GEMM, then its own choice
+            b.op_set_gemm_tile_rows(rows)
+            out = b.op_lm_head_ce(X.cuda(), W.cuda(), lab.cuda()).cpu()
+            assert (out.double() - ref).abs().max() <= 2e-3 * max(1.0, float(ref.abs().max())), rows
+    finally:
+        b.op_set_gemm_tile_rows(0)
     with pytest.raises(b.Zo2Error):
         b.op_lm_head_ce(X[:100].cuda(), W.cuda(), lab[:100].cuda())          # fewer than 256 rows
     with pytest.raises(b.Zo2Error):

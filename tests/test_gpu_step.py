@@ -312,11 +312,14 @@ def test_streamed_equals_resident_at_13b_block_shape():
     params = {}
     for mode in ("resident", "streamed"):
         ctx = b.Zo2Context(cfg, run_config.gpu_weight_source(seed=3), wire="bf16", compute="bf16", arena_bytes=12 << 30)
-        r = [ctx.step(tok, lab, 7, 1e-3, 1e-2)]
+        # eta = 2e-4: with g of order 10 the update (~3e-3 z) is far above half a unit of bf16 at |theta| ~ 0.02, so the
+        # stored parameters really change, and small enough for four steps on one batch to stay a training run
+        # (at 1e-2 the loss leaves 12 for 50, 3000, ... and overflows after a few steps)
+        r = [ctx.step(tok, lab, 7, 1e-3, 2e-4)]
         if mode == "streamed":
             ctx.set_resident_budget(ctx.plan()["bytes_used"] - 2 * ctx.offs[16] * 2)
         for j in range(1, 4):
-            r.append(ctx.step(tok, lab, 7 + j, 1e-3, 1e-2))
+            r.append(ctx.step(tok, lab, 7 + j, 1e-3, 2e-4))
         pl, st = ctx.plan(), ctx.step_stats()
         if mode == "streamed":
             assert not pl["resident"] and pl["n_slots"] == 3, pl

@@ -1,11 +1,13 @@
 // Large-tile MFMA GEMM for the big projections: 256 x 256 x 64 block tile, four wavefronts
 // (2 x 2), each owning 128 x 128 = 8 x 8 MFMA tiles of 16 x 16 (v_mfma_f32_16x16x32) with float32
-// accumulators in the accumulation registers.  One workgroup per compute unit.  (Under this kernel's
-// full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip sustains a higher clock with
-// the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster in an MFMA-only loop.)
+// accumulators in the accumulation registers; a second instance with 128-row tiles (wavefronts of 64 x 128)
+// serves launches that 256-row tiles would spread badly over the compute units.  One workgroup per compute
+// unit.  (Under this kernel's full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip
+// sustains a higher clock with the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster
+// in an MFMA-only loop.)
 //
 // Data path: global memory -> LDS with the direct-to-LDS loads of gfx950 (16 bytes per
-// lane, no staging through vector registers), two LDS stages of 64 KB, 128-bit LDS reads
+// lane, no staging through vector registers), two LDS stages, 128-bit LDS reads
 // into MFMA operand registers.  The tile is stored as rows of 8 chunks of 16 bytes with the
 // chunk index XOR-swizzled by (row & 7); because a direct-to-LDS load writes lane i's 16 bytes
 // at LDS offset 16 i, the swizzle is applied on the global side: lane i fetches the chunk that

@@ -61,10 +61,20 @@ def test_k1_full_block_bucket_sampled_windows():
         assert torch.equal(theta[pad], theta0[pad]) and float(wp[pad].float().abs().sum()) == 0.0
 
 
+@pytest.mark.parametrize("tile_rows", [256, 128])
 @pytest.mark.parametrize("M,N,K,out32,res", [(T, 3 * D, D, False, False), (T, D, F, True, True), (T, F, D, False, False), (1024, V, D, True, False)])
-def test_gemm_full_size_sampled_outputs(M, N, K, out32, res):
-    """The large-tile kernel at the benchmark's shapes; 4000 sampled outputs against float64 dot products."""
+def test_gemm_full_size_sampled_outputs(M, N, K, out32, res, tile_rows):
+    """The large-tile kernel at the benchmark's shapes, with either tile height; 4000 sampled outputs against float64
+    dot products."""
     b = _b()
+    b.op_set_gemm_tile_rows(tile_rows)
+    try:
+        _gemm_full_size_case(b, M, N, K, out32, res)
+    finally:
+        b.op_set_gemm_tile_rows(0)
+
+
+def _gemm_full_size_case(b, M, N, K, out32, res):
     g = torch.Generator(device="cuda").manual_seed(M + N)
     X = (torch.randn(M, K, device="cuda", generator=g)).bfloat16()
     W = (torch.randn(N, K, device="cuda", generator=g) * 0.02).bfloat16()

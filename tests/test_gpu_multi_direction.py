@@ -163,3 +163,34 @@ def test_training_on_a_fixed_batch_lowers_the_loss_and_more_directions_lower_it_
         ctx.close()
     assert final[1] < 0.93 * l0, (l0, final)
     assert final[4] < 0.85 * l0 and final[4] < final[1] - 0.2, (l0, final)
+
+
+def test_rounds_with_a_stochastically_rounded_bf16_master():
+    """Every deferred update of a round is stored with its own rounding bits (keyed by its own seed), in the update-only
+    sweeps as in the fused one: with float32 compute nearly every decision is the oracle's; streamed == resident bitwise."""
+    b = _b()
+    cfg, P, tok, lab = _case(n_layers=5)
+    Po = {n: codec.round_to(a, "bf16") for n, a in copy.deepcopy(P).items()}
+    oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), Po, store="bf16", compute="f32", rounding="stochastic")
+    ctx = b.Zo2Context(cfg, P, wire="bf16", compute="f32", arena_bytes=256 << 20)
+    ctx_s = b.Zo2Context(cfg, P, wire="bf16", compute="f32", arena_bytes=256 << 20)
+    ctx.set_wire_rounding(True); ctx_s.set_wire_rounding(True)
+    for j in range(2):
+        seeds, lrs = [70 + 10 * j + i for i in range(3)], [5e-4 / 3] * 3
+        ro, rg, rs = _round(oz, tok, lab, seeds, 1e-3, lrs), _round(ctx, tok, lab, seeds, 1e-3, lrs), _round(ctx_s, tok, lab, seeds, 1e-3, lrs)
+        if j == 0:
+            ctx_s.set_resident_budget(ctx_s.plan()["bytes_used"] - 2 * ctx_s.offs[16] * 2)       # 3 slots for 5 blocks
+            for a, g in zip(ro, rg):
+                assert abs(float(g[0]) - float(a[0])) <= 1e-5 * abs(float(a[0]))
+                assert abs(float(g[1]) - float(a[1])) <= 1e-5 * abs(float(a[1]))
+        assert [tuple(map(float, x)) for x in rg] == [tuple(map(float, x)) for x in rs]
+    assert not ctx_s.plan()["resident"]
+    oz.flush(); ctx.flush(); ctx.sync_to_host(); ctx_s.flush(); ctx_s.sync_to_host()
+    Pg, Ps = ctx.parameters(), ctx_s.parameters()
+    tot = same = 0
+    for n in oz.P:
+        assert np.array_equal(Pg[n], Ps[n]), n
+        tot += oz.P[n].size; same += int(np.sum(Pg[n] == oz.P[n]))
+    print("identical parameters:", same / tot)
+    assert same / tot > 0.98
+    ctx.close(); ctx_s.close()

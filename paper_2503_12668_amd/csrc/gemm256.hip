@@ -40,7 +40,11 @@ template <> struct Mfma16<bf16_t> {
 // c = 0: one MFMA on zero operands with a literal-zero addend clears a tuple in a quarter of the issue time of four
 // register writes (the compiler's own zero-initialisation wrote every accumulation register twice)
 __device__ __forceinline__ u32x4_t mfma16_zero_operand() {
-    u32x4_t z = {0u, 0u, 0u, 0u};
+    // made where it is used, through a statement the compiler cannot move: as a loop-invariant constant it was hoisted out
+    // of the tile loop and, with every register taken in the k loop, spilled to scratch and reloaded per tile
+    uint32_t z0 = 0u;
+    asm volatile("" : "+v"(z0));
+    u32x4_t z = {z0, z0, z0, z0};
     asm volatile("s_nop 4" : "+v"(z));      // wait states between the moves that write z and the first MFMA that reads it
     return z;
 }
@@ -188,6 +192,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     TileCoord tc = tile_coord<kBM>(vid, ntiles, tiles_m, tiles_n);
     plan_loads(tc);
     issue_slab0();
+    issue_slab(1, kBK);                  // before the first tile both stages are free: its second slab travels with the first
+    bool slab1_in_flight = true;
 
     for (;;) {
         // acc[i][j]: X rows (m) i-th 16-block, W rows (n) j-th 16-block.  The W fragment is the
@@ -280,7 +286,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
             for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, more_slabs, cur, (kt + 2) * kBK);
         };
-        issue_slab(1, kBK);              // slab 1 (stage 1 is free once the barrier above is passed)
+        // slab 1 of a later tile: stage 1 held the previous tile's epilogue staging and is free once the barrier above is passed
+        if (!slab1_in_flight) issue_slab(1, kBK);
+        slab1_in_flight = false;
         // nk is even (K % 128 == 0): slabs alternate between the two stages, two per trip
         using St0 = std::integral_constant<int, 0>;
         using St1 = std::integral_constant<int, 1>;

@@ -2,8 +2,11 @@
 
 Three forms of the same step, all on float32 parameters:
 
-  step_literal   Alg. 1 as printed: perturb in place by +eps, by -2 eps, by +eps,
-                 then update, regenerating z from the step seed each time.
+  step_in_place   the in-place form of Eq. 1-3: the parameters themselves are moved to
+                 theta + eps z, then to theta - eps z, then back (three in-place moves
+                 by eps z times +1, -2, +1, each with a separately rounded multiply and
+                 add, z regenerated from the step seed for every move), and only then
+                 updated.  It is what the exact-restore form below is pinned against.
   step_whole     Alg. 1 with the restore made exact: theta is never overwritten
                  by a perturbation; W+ = theta + eps z and W- = theta - eps z are
                  formed as copies (Eq. 2), then theta <- theta - eta g z (Eq. 3).
@@ -41,15 +44,18 @@ def _fma32(a, b, c):
 
 def _store(x, fmt, scale=1.0, r16=None):
     """Round float32 x to the parameter storage format (value returned as float32): to nearest, or -
-    given 16 random bits per element - stochastically.  The scaled value is formed in float32."""
+    given 16 random bits per element - stochastically.  With a per-tensor scale s (8-bit formats,
+    Sec. 5.5) the stored code is that of float32(x * s) and the value read back is float32(code / s):
+    the scaled value is formed in float32, the working precision of the update, for both roundings.
+    For a power-of-two s both operations are exact."""
     if fmt == "f32":
         return np.asarray(x, dtype=np.float32)
     xs = np.asarray(x, dtype=np.float32)
     if scale != 1.0:
-        xs = (xs * np.float32(scale)).astype(np.float32) if r16 is not None else np.float64(x) * scale
+        xs = (xs * np.float32(scale)).astype(np.float32)
     q = codec.round_to(xs, fmt) if r16 is None else codec.round_stochastic(xs, fmt, r16)
     if scale != 1.0:
-        return (q.astype(np.float64) / scale).astype(np.float32)
+        return (q.astype(np.float32) / np.float32(scale)).astype(np.float32)
     return q
 
 
@@ -69,27 +75,29 @@ def projected_gradient(lp, lm, eps):
     return np.float32(np.float32(lp - lm) / np.float32(np.float32(2.0) * np.float32(eps)))
 
 
-# --------------------------------------------------------------------------- Alg. 1, literal
-def step_literal(cfg, P, tokens, labels, seed, eps, lr):
-    """Alg. 1 line by line, float32, each multiply and add rounded separately.
-    P (name -> float32 array) is modified in place.  Returns (l+, l-, g)."""
+# --------------------------------------------------------------------------- Eq. 1-3, in place
+def step_in_place(cfg, P, tokens, labels, seed, eps, lr):
+    """The estimator of Eq. 1-2 evaluated by moving the parameters themselves, then the update of
+    Eq. 3: theta visits theta + eps z and theta - eps z through in-place moves by k eps z, k = +1, -2,
+    +1 (the last one brings it back up to rounding), the loss being taken after the first two.  Every
+    move is a float32 multiply followed by a float32 add, and z is drawn afresh from the step seed for
+    each of them and for the update.  P (name -> float32 array) is modified in place.
+    Returns (l+, l-, g)."""
     eps32 = np.float32(eps)
-
-    def perturb(scale):
-        z = z_of(cfg, seed)                     # "reset RNG with seed s", then draw
+    losses = []
+    for k in (1.0, -2.0, 1.0):
+        z = z_of(cfg, seed)
+        move = np.float32(np.float32(k) * eps32)
         for name in P:
-            P[name] = (P[name] + np.float32(scale) * z[name]).astype(np.float32)
-
-    perturb(eps32)
-    lp = np.float32(opt_model.loss(cfg, P, tokens, labels))
-    perturb(np.float32(-2.0) * eps32)
-    lm = np.float32(opt_model.loss(cfg, P, tokens, labels))
-    perturb(eps32)
+            P[name] = (P[name] + (move * z[name]).astype(np.float32)).astype(np.float32)
+        if len(losses) < 2:
+            losses.append(np.float32(opt_model.loss(cfg, P, tokens, labels)))
+    lp, lm = losses
     g = projected_gradient(lp, lm, eps)
     z = z_of(cfg, seed)
     step = np.float32(np.float32(lr) * g)
     for name in P:
-        P[name] = (P[name] - step * z[name]).astype(np.float32)
+        P[name] = (P[name] - (step * z[name]).astype(np.float32)).astype(np.float32)
     return lp, lm, g
 
 

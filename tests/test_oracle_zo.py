@@ -66,14 +66,14 @@ def test_update_uses_the_same_z_and_sign():
     assert opt_model.loss(s, P, tok, lab) < opt_model.loss(s, P0, tok, lab)
 
 
-def test_literal_sequence_vs_exact_restore():
-    """Alg. 1 as printed (in-place +eps, -2eps, +eps, update) against the canonical
-    copy-based form: same losses up to float32 rounding of the perturbation, and
+def test_in_place_sequence_vs_exact_restore():
+    """Eq. 1-3 evaluated by moving the parameters in place (by eps z times +1, -2, +1, then the update)
+    against the canonical copy-based form: same losses up to float32 rounding of the perturbation, and
     parameters within a few float32 ulps per step."""
     cfg, s, P, tok, lab = _setup()
     Pa, Pb = copy.deepcopy(P), copy.deepcopy(P)
     for j in range(3):
-        la = zo_step.step_literal(s, Pa, tok, lab, 42 + j, 1e-3, 1e-3)
+        la = zo_step.step_in_place(s, Pa, tok, lab, 42 + j, 1e-3, 1e-3)
         lb = zo_step.step_whole(s, Pb, tok, lab, 42 + j, 1e-3, 1e-3)
         assert abs(float(la[0]) - float(lb[0])) < 2e-6 * abs(float(lb[0]))
         assert abs(float(la[1]) - float(lb[1])) < 2e-6 * abs(float(lb[1]))
@@ -165,6 +165,69 @@ def test_low_bit_storage_step_keeps_parameters_representable():
         assert np.array_equal(Pa[n], Pb[n])
         assert np.array_equal(codec.round_to(Pa[n], "bf16"), Pa[n])
     assert any(not np.array_equal(Pa[n], P[n]) for n in P)
+
+
+@pytest.mark.parametrize("fmt,scale", [("fp8_e4m3", 64.0), ("fp8_e5m2", 4.0), ("fp8_e4m3", 48.0), ("fp8_e4m3", 0.5)])
+def test_scaled_8bit_store_against_torch_cpu_casts(fmt, scale):
+    """Sec. 5.5 with a per-tensor scale: the stored code is the 8-bit cast of float32(x s), the value read back is
+    float32(code / s).  Pinned against torch's CPU casts on explicitly scaled inputs (in the format's finite range),
+    for powers of two - where scaling is exact - and for a scale that is not one; and the stochastic rounding
+    lands on one of the two neighbours of the same scaled value."""
+    import torch
+    from oracle import codec
+    tdt = {"fp8_e4m3": torch.float8_e4m3fn, "fp8_e5m2": torch.float8_e5m2}[fmt]
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal(20000) * 0.05).astype(np.float32)
+    x[:6] = [0.0, -0.0, 1e-9, -3e-7, 0.9, -1.3]
+    got = zo_step._store(x, fmt, scale)
+    xs = torch.from_numpy(x) * torch.tensor(scale, dtype=torch.float32)          # float32 product
+    want = (xs.to(tdt).to(torch.float32) / torch.tensor(scale, dtype=torch.float32)).numpy()
+    assert np.array_equal(got, want)
+    # the codes are those of the explicitly scaled input, and unscaled storage is the scale-1 case of the same rule
+    if np.frexp(scale)[0] == 0.5:                  # a power of two: un-scaling is exact, so the codes can be read back
+        assert np.array_equal(codec.round_to(xs.numpy(), fmt), got * np.float32(scale))
+    assert np.array_equal(zo_step._store(x, fmt, 1.0), torch.from_numpy(x).to(tdt).to(torch.float32).numpy())
+    # a scale really changes what survives: small values flush to zero without it
+    tiny = np.full(8, 6e-4, np.float32)
+    assert np.all(zo_step._store(tiny, "fp8_e4m3", 1.0) == 0) and np.all(zo_step._store(tiny, "fp8_e4m3", 64.0) != 0)
+    # stochastic: one of the two neighbours of float32(x s), divided by s; exact values stay
+    r16 = rng.integers(0, 65536, x.size)
+    sr = zo_step._store(x, fmt, scale, r16)
+    xs64 = xs.numpy().astype(np.float64)
+    lo = codec.round_stochastic(xs64, fmt, np.full(x.size, 65536))      # never below the fraction: the lower neighbour
+    hi = codec.round_stochastic(xs64, fmt, np.zeros(x.size))
+    s32 = np.float32(scale)
+    assert np.all((sr == (lo / s32).astype(np.float32)) | (sr == (hi / s32).astype(np.float32)))
+    assert np.all(np.abs(lo) <= np.abs(xs64)) and np.all(np.abs(hi) >= np.abs(xs64))
+    assert 0.2 < np.mean(sr == (hi / s32).astype(np.float32)) < 0.8
+
+
+@pytest.mark.parametrize("rounding", ["nearest", "stochastic"])
+def test_blockwise_equals_whole_model_with_scaled_8bit_storage(rounding):
+    """The deferred, module-by-module form with an 8-bit master and per-tensor scales: same losses as the
+    whole-model form at every iteration and - for round-to-nearest, which the whole-model form implements -
+    the same stored parameters after the flush; every stored value is a code of the format at its tensor's scale."""
+    from oracle import codec
+    cfg, s, P, tok, lab = _setup()
+    names = [n for n, _, _ in opt_model.tensor_table(s)]
+    scales = {n: (64.0 if i % 2 else 16.0) for i, n in enumerate(names)}
+    P8 = {n: zo_step._store(P[n], "fp8_e4m3", scales[n]) for n in names}
+    Pa, Pb = copy.deepcopy(P8), copy.deepcopy(P8)
+    zo = zo_step.Zo2Blockwise(s, Pb, store="fp8_e4m3", compute="bf16", scales=scales, rounding=rounding)
+    for j in range(3):
+        b = zo.step(tok, lab, 60 + j, 1e-3, 2e-2)
+        if rounding == "nearest":
+            a = zo_step.step_whole(s, Pa, tok, lab, 60 + j, 1e-3, 2e-2, store="fp8_e4m3", compute="bf16", scales=scales)
+            assert tuple(map(float, a)) == tuple(map(float, b)), j
+    zo.flush()
+    changed = 0
+    for n in names:
+        sc = np.float32(scales[n])
+        assert np.array_equal(codec.round_to(Pb[n] * sc, "fp8_e4m3") / sc, Pb[n]), n
+        if rounding == "nearest":
+            assert np.array_equal(Pa[n], Pb[n]), n
+        changed += int(np.sum(Pb[n] != P8[n]))
+    assert changed > 0
 
 
 def test_stochastic_rounding_lets_a_bf16_master_follow_small_updates():

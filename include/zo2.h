@@ -5,7 +5,7 @@
  * Two layers of entry points:
  *
  *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_step_extra / zo2_flush / zo2_eval /
- *      zo2_get_pending / zo2_set_pending / zo2_sync_to_host / zo2_destroy.  One call of zo2_step is one iteration of the paper's
+ *      zo2_get_pending / zo2_set_pending / zo2_sync_to_host / zo2_get_plan / zo2_get_scratch_plan / zo2_destroy.  One call of zo2_step is one iteration of the paper's
  *      Alg. 2: for every module (embedding, decoder blocks, LM head) apply the update left
  *      pending by the previous iteration, perturb by +eps z and -eps z, run both forwards,
  *      and form the projected gradient g (Eq. 2).  Blocks that do not fit the HBM budget
@@ -93,8 +93,9 @@ typedef struct {
     void** block_bucket;      /* host array of n_layers host pointers, one bucket each; pinned
                                  memory is needed for the streamed mode to overlap copies          */
     const float* tensor_scale;/* host, one float per tensor id, or NULL (= all 1).  Stored value =
-                                 round(theta * scale); used by the 8-bit wire formats, ignored
-                                 (must be NULL or all 1) otherwise.  Powers of two keep it exact.  */
+                                 round(theta * scale); used by the 8-bit wire formats (Sec. 5.5), must
+                                 be NULL or all 1 otherwise.  Every scale must be a power of two, so
+                                 that scaling and un-scaling are exact (ZO2_EINVAL otherwise).     */
 } zo2_host_weights;
 
 typedef struct {
@@ -179,6 +180,20 @@ zo2_status zo2_sync_to_host(zo2_ctx* ctx);
  * resident, how many arena bytes are in use.  Any pointer may be NULL. */
 zo2_status zo2_get_plan(const zo2_ctx* ctx, int32_t* n_slots, int32_t* resident, size_t* bytes_used);
 
+/* How the W+ / W- scratch of the last plan is organised (Sec. 5.3's reusable block space, applied to the
+ * perturbed copies): *per_group = 0 when it holds a whole block's 16 tensors at once (one update + perturb
+ * sweep per block), 1 when it is sized for the largest of the four tensor groups {ln1, q, k, v} {o} {ln2, fc1}
+ * {fc2} and is refilled by a sweep per group, between the projections (what a tight budget forces for wide
+ * blocks: the two whole-block copies of the OPT-175B shape alone would take 7 GB); *scratch_elems = elements of
+ * one copy; *scratch_sets = 1, or 2 when zo2_device.stream_k1 is in use.  Any pointer may be NULL.  Results do
+ * not depend on the organisation. */
+zo2_status zo2_get_scratch_plan(const zo2_ctx* ctx, int32_t* per_group, int64_t* scratch_elems, int32_t* scratch_sets);
+
+/* mode 1: always organise the scratch per tensor group, whatever the budget would allow; mode 0 (default): the
+ * planner prefers whole-block scratch and falls back to per-group scratch when the budget is too small for
+ * 3 block slots otherwise.  Takes effect at the next step.  ZO2_EINVAL for any other mode. */
+zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t mode);
+
 /* Per-stream busy time of the last step in milliseconds (compute, upload, offload) and the
  * bytes copied each way; for host-link rate reporting.  Any pointer may be NULL. */
 zo2_status zo2_get_step_stats(const zo2_ctx* ctx, float* ms_compute, float* ms_upload, float* ms_offload,
@@ -245,12 +260,21 @@ zo2_status zo2_op_gaussian(uint64_t seed, uint32_t tensor_id, uint64_t e0, uint6
  * every pointer must be aligned to 8 elements.  theta is rewritten in place; w_plus /
  * w_minus (compute dtype, n elements) may both be NULL for an update-only pass, or w_minus
  * alone for a pass that writes only w_plus; with eps = 0 no z is drawn and w_plus = theta'.
- * scale: the tensor's wire scale (1 unless an 8-bit format uses one).  stochastic_rounding != 0 stores theta'
+ * scale: the tensor's wire scale (1 unless an 8-bit format uses one; a power of two).  stochastic_rounding != 0 stores theta'
  * as zo2_set_wire_rounding describes. */
 zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, void* w_plus, void* w_minus, int32_t compute_dtype,
                                  uint32_t tensor_id, uint64_t e0, uint64_t n,
                                  int32_t has_pending, uint64_t seed_prev, float c,
                                  uint64_t seed, float eps, float scale, int32_t stochastic_rounding, void* stream);
+
+/* The same over one whole block bucket (Sec. 5.3) in a single launch, as the step issues it per decoder block:
+ * bucket holds the 16 tensors of block `layer` at the offsets of zo2_block_tensor_offsets(cfg) in cfg->wire_dtype
+ * and is rewritten in place; w_plus / w_minus: buffers of the same element count in cfg->compute_dtype (same
+ * offsets; NULL as above); tensor k draws from random stream 2 + 16 layer + k.  host_scales: 16 floats in host
+ * memory (powers of two) or NULL for all 1.  The padding between tensors is neither read nor written. */
+zo2_status zo2_op_update_perturb_block(const zo2_config* cfg, int32_t layer, void* bucket, void* w_plus, void* w_minus,
+                                       int32_t has_pending, uint64_t seed_prev, float c, uint64_t seed, float eps,
+                                       const float* host_scales, int32_t stochastic_rounding, void* stream);
 
 /* Low-bit pack / unpack (Sec. 5.5): convert n elements between two storage formats,
  * dst = store_dst(load_src(src) / scale_src * scale_dst). */

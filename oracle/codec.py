@@ -24,6 +24,9 @@ when eta * g * z is under half a unit in the last place; Sec. 5.5 leaves the
 rounding open): x goes to one of the two representable values around it, to the
 upper one with probability (|x| - lo) / (hi - lo).
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 _FORMATS = {           # name: (exponent bits, mantissa bits, bias, ieee_specials, code dtype)
@@ -95,15 +98,38 @@ def encode(x, fmt):
     return out.astype(dt)
 
 
+_PIECE = 1 << 20
+
+
+def _piecewise(fn, first, *rest):
+    """fn applied to equal cuts of its (same-shaped) array arguments on a thread pool, results joined: the
+    roundings here act on every element by itself, so the cut changes nothing."""
+    first = np.asarray(first)
+    if first.size <= _PIECE:
+        return fn(first, *rest)
+    flat = [np.asarray(a).reshape(-1) for a in (first,) + rest]
+    cuts = list(range(0, first.size, _PIECE)) + [first.size]
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        parts = list(ex.map(lambda ab: fn(*[a[ab[0]:ab[1]] for a in flat]), zip(cuts[:-1], cuts[1:])))
+    return np.concatenate(parts).reshape(first.shape)
+
+
 def round_to(x, fmt):
     """x rounded to the format and returned as float32 (exactly representable there).
     fmt "f32" rounds float64 to float32."""
     if fmt == "f32":
         return np.asarray(x, dtype=np.float64).astype(np.float32)
-    return decode(encode(x, fmt), fmt).astype(np.float32)
+    return _piecewise(lambda a: decode(encode(a, fmt), fmt).astype(np.float32), x)
 
 
 def round_stochastic(x, fmt, r16):
+    """Element by element (see _round_stochastic_piece); long arrays are cut into pieces."""
+    if fmt == "f32":
+        return np.asarray(x, dtype=np.float64).astype(np.float32)
+    return _piecewise(lambda a, r: _round_stochastic_piece(a, fmt, r), x, np.broadcast_to(np.asarray(r16), np.shape(x)))
+
+
+def _round_stochastic_piece(x, fmt, r16):
     """x rounded to one of its two neighbours lo <= |x| <= hi in the format (sign kept), returned as
     float32: the one further from zero is taken iff r16 < 65536 * (|x| - lo) / (hi - lo), r16 being a
     uniform integer in [0, 65536).  The expectation over r16 is x to within (hi - lo) / 65536.

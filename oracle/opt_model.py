@@ -71,10 +71,32 @@ def _t(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(torch.float64)
 
 
-def _layer_norm(x, w, b, eps):
+def layer_norm(x, w, b, eps):
+    """(x - mean) / sqrt(var + eps) * w + b over the last axis, biased variance."""
     mu = x.mean(dim=-1, keepdim=True)
     var = ((x - mu) ** 2).mean(dim=-1, keepdim=True)      # biased variance
     return (x - mu) / torch.sqrt(var + eps) * w + b
+
+
+def linear(x, w, b=None):
+    """y = x w^T + b for a weight stored [out_features, in_features]."""
+    y = x @ w.T
+    return y if b is None else y + b
+
+
+def causal_attention(q, k, v, n_heads):
+    """softmax_{j <= i}(q_i . k_j) v_j per head; q, k, v [B, S, d] with head h in columns h d_h .. (h+1) d_h - 1;
+    q already carries the 1 / sqrt(d_h) factor."""
+    B, S, d = q.shape
+    dh = d // n_heads
+    q = q.view(B, S, n_heads, dh).transpose(1, 2)
+    k = k.view(B, S, n_heads, dh).transpose(1, 2)
+    v = v.view(B, S, n_heads, dh).transpose(1, 2)
+    sc = q @ k.transpose(-1, -2)                           # [B, H, S, S]
+    future = torch.triu(torch.ones(S, S, dtype=torch.bool), diagonal=1)
+    sc = sc.masked_fill(future, float("-inf"))
+    p = torch.softmax(sc, dim=-1)
+    return (p @ v).transpose(1, 2).reshape(B, S, d)
 
 
 def embed(s, P, tokens):
@@ -88,43 +110,37 @@ def embed(s, P, tokens):
 def block_forward(s, P, l, h):
     """One pre-LN decoder block on h [B, S, d]."""
     g = lambda t: _t(P[f"blocks.{l}.{t}"])
-    B, S, d = h.shape
-    H = s.n_heads
-    dh = d // H
-    x = _layer_norm(h, g("ln1.w"), g("ln1.b"), s.ln_eps)
-    q = (x @ g("q.w").T + g("q.b")) * dh ** -0.5
-    k = x @ g("k.w").T + g("k.b")
-    v = x @ g("v.w").T + g("v.b")
-    q = q.view(B, S, H, dh).transpose(1, 2)
-    k = k.view(B, S, H, dh).transpose(1, 2)
-    v = v.view(B, S, H, dh).transpose(1, 2)
-    sc = q @ k.transpose(-1, -2)                           # [B, H, S, S]
-    future = torch.triu(torch.ones(S, S, dtype=torch.bool), diagonal=1)
-    sc = sc.masked_fill(future, float("-inf"))
-    p = torch.softmax(sc, dim=-1)
-    ctx = (p @ v).transpose(1, 2).reshape(B, S, d)
-    h = h + ctx @ g("o.w").T + g("o.b")
-    x = _layer_norm(h, g("ln2.w"), g("ln2.b"), s.ln_eps)
-    y = torch.relu(x @ g("fc1.w").T + g("fc1.b"))
-    return h + y @ g("fc2.w").T + g("fc2.b")
+    dh = s.d_model // s.n_heads
+    x = layer_norm(h, g("ln1.w"), g("ln1.b"), s.ln_eps)
+    q = linear(x, g("q.w"), g("q.b")) * dh ** -0.5
+    k = linear(x, g("k.w"), g("k.b"))
+    v = linear(x, g("v.w"), g("v.b"))
+    ctx = causal_attention(q, k, v, s.n_heads)
+    h = h + linear(ctx, g("o.w"), g("o.b"))
+    x = layer_norm(h, g("ln2.w"), g("ln2.b"), s.ln_eps)
+    y = torch.relu(linear(x, g("fc1.w"), g("fc1.b")))
+    return h + linear(y, g("fc2.w"), g("fc2.b"))
 
 
 def head_logits(s, P, h):
-    x = _layer_norm(h, _t(P["final_ln.w"]), _t(P["final_ln.b"]), s.ln_eps)
-    w = _t(P["tok_emb"] if s.tied else P["lm_head.w"])
-    return x @ w.T
+    x = layer_norm(h, _t(P["final_ln.w"]), _t(P["final_ln.b"]), s.ln_eps)
+    return linear(x, _t(P["tok_emb"] if s.tied else P["lm_head.w"]))
+
+
+def row_cross_entropy(logits, labels):
+    """Per position: logsumexp(logits) - logits[label]; 0 where the label is -100.  logits [rows, vocab]."""
+    lab = torch.from_numpy(np.asarray(labels, dtype=np.int64)).reshape(-1)
+    keep = lab != -100
+    lse = torch.logsumexp(logits, dim=-1)
+    picked = logits.gather(1, lab.clamp(min=0)[:, None])[:, 0]
+    return torch.where(keep, lse - picked, torch.zeros_like(lse))
 
 
 def cross_entropy(logits, labels):
     """Mean over positions whose label is not -100 of logsumexp(logits) - logits[label]."""
     lab = torch.from_numpy(np.asarray(labels, dtype=np.int64)).reshape(-1)
-    lg = logits.reshape(-1, logits.shape[-1])
-    keep = lab != -100
-    lg = lg[keep]
-    lab = lab[keep]
-    lse = torch.logsumexp(lg, dim=-1)
-    picked = lg.gather(1, lab[:, None])[:, 0]
-    return float((lse - picked).sum() / lab.numel())
+    rows = row_cross_entropy(logits.reshape(-1, logits.shape[-1]), lab)
+    return float(rows.sum() / int((lab != -100).sum()))
 
 
 def logits(s, P, tokens):

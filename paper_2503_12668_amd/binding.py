@@ -73,6 +73,8 @@ def lib():
         "zo2_add_pending": (i32, [vp, u64, f32]),
         "zo2_sync_to_host": (i32, [vp]),
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
+        "zo2_get_scratch_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]),
+        "zo2_set_scratch_plan": (i32, [vp, i32]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
         "zo2_set_stream_overlap": (i32, [vp, i32]),
@@ -85,6 +87,7 @@ def lib():
         "zo2_op_philox_words": (i32, [u64, u32, u64, u64, vp, vp]),
         "zo2_op_gaussian": (i32, [u64, u32, u64, u64, vp, vp]),
         "zo2_op_update_perturb": (i32, [vp, i32, vp, vp, i32, u32, u64, u64, i32, u64, f32, u64, f32, f32, i32, vp]),
+        "zo2_op_update_perturb_block": (i32, [C.POINTER(Config), i32, vp, vp, vp, i32, u64, f32, u64, f32, C.POINTER(f32), i32, vp]),
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
         "zo2_op_set_gemm_tile_rows": (i32, [i32]),
@@ -104,8 +107,8 @@ def lib():
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
-            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes"]
 
@@ -173,6 +176,17 @@ def op_update_perturb(theta, w_plus, w_minus, tensor_id, e0, has_pending, seed_p
                                           _stream_ptr(stream)))
 
 
+def op_update_perturb_block(ccfg, layer, bucket, w_plus, w_minus, has_pending, seed_prev, c, seed, eps, scales=None,
+                            stochastic=False, stream=None):
+    """All 16 tensors of one block bucket in one launch (bucket: device tensor in the wire dtype, rewritten in place)."""
+    sc = None
+    if scales is not None:
+        sc = (C.c_float * 16)(*[float(x) for x in scales])
+    _op_check(lib().zo2_op_update_perturb_block(C.byref(ccfg), layer, _ptr(bucket), _ptr(w_plus), _ptr(w_minus),
+                                                1 if has_pending else 0, seed_prev, c, seed, eps, sc, 1 if stochastic else 0,
+                                                _stream_ptr(stream)))
+
+
 def op_convert(src, dst, src_scale=1.0, dst_scale=1.0, stream=None):
     assert src.numel() == dst.numel()
     _op_check(lib().zo2_op_convert(_ptr(src), _dt(src), src_scale, _ptr(dst), _dt(dst), dst_scale, src.numel(),
@@ -235,18 +249,25 @@ def op_lm_head_ce(X, W, labels, stream=None):
 # training context
 # ------------------------------------------------------------------------------------------------
 def _to_wire(a, wire_id, scale=1.0):
-    """float32 numpy / torch tensor -> torch CPU tensor in the wire dtype (round to nearest even)."""
-    t = torch.from_numpy(np.ascontiguousarray(a)) if isinstance(a, np.ndarray) else a
-    if scale != 1.0:
-        t = t * scale
-    return t.to(TORCH_DTYPE[wire_id])
+    """float32 numpy / torch tensor -> flat torch CPU tensor in the wire dtype, packed by the library's own
+    conversion kernel (zo2_op_convert: round to nearest even, 8-bit formats saturating, stored = theta * scale)."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)) if isinstance(a, np.ndarray) else a
+    t = t.to(device="cuda", dtype=torch.float32).contiguous().reshape(-1)
+    if wire_id == F32:
+        return t.cpu()
+    dst = torch.empty(t.numel(), dtype=TORCH_DTYPE[wire_id], device="cuda")
+    op_convert(t, dst, 1.0, float(scale))
+    return dst.cpu()
 
 
 def _from_wire(t, scale=1.0):
-    out = t.to(torch.float32)
-    if scale != 1.0:
-        out = out / scale
-    return out
+    """flat torch CPU tensor in a wire dtype -> float32 CPU tensor, unpacked by the library (theta = stored / scale)."""
+    if t.dtype == torch.float32:
+        return t.clone()
+    src = t.to("cuda")
+    dst = torch.empty(src.numel(), dtype=torch.float32, device="cuda")
+    op_convert(src, dst, float(scale), 1.0)
+    return dst.cpu()
 
 
 class Zo2Context:
@@ -279,7 +300,7 @@ class Zo2Context:
             return weights(name, shape) if callable(weights) else weights[name]
 
         def fill(dst, a, tid):
-            dst.copy_(_to_wire(a, self.wire_id, float(self.scales[tid])).reshape(-1))
+            dst.copy_(_to_wire(a, self.wire_id, float(self.scales[tid])))
 
         self.h_tok = host(cfg["vocab"] * cfg["d_model"]); fill(self.h_tok, get("tok_emb", (cfg["vocab"], cfg["d_model"])), 0)
         self.h_pos = host((cfg["max_pos"] + cfg["pos_offset"]) * cfg["d_model"]); fill(self.h_pos, get("pos_emb", (cfg["max_pos"] + cfg["pos_offset"], cfg["d_model"])), 1)
@@ -391,7 +412,14 @@ class Zo2Context:
     def plan(self):
         n, r, b = C.c_int32(), C.c_int32(), C.c_size_t()
         self._check(lib().zo2_get_plan(self.handle, C.byref(n), C.byref(r), C.byref(b)))
-        return dict(n_slots=n.value, resident=bool(r.value), bytes_used=b.value)
+        pg, se, ss = C.c_int32(), C.c_int64(), C.c_int32()
+        self._check(lib().zo2_get_scratch_plan(self.handle, C.byref(pg), C.byref(se), C.byref(ss)))
+        return dict(n_slots=n.value, resident=bool(r.value), bytes_used=b.value, per_group_scratch=bool(pg.value),
+                    scratch_elems=se.value, scratch_sets=ss.value)
+
+    def set_scratch_plan(self, per_group):
+        """True: W+ / W- scratch sized for the largest tensor group, refilled per group; False: the planner chooses."""
+        self._check(lib().zo2_set_scratch_plan(self.handle, 1 if per_group else 0))
 
     def step_stats(self):
         a, b, c_ = C.c_float(), C.c_float(), C.c_float()

@@ -10,6 +10,8 @@
 // HBM-streaming kernel: each lane moves groups of 8 consecutive elements with 128-bit
 // accesses (bf16/fp16; two for fp32, one 64-bit for the 8-bit formats), a workgroup owns
 // a contiguous chunk of one tensor, the grid covers up to 16 tensors of a bucket.
+#include <math.h>
+
 #include "k1.h"
 #include "philox.h"
 
@@ -154,7 +156,9 @@ zo2_status k1_launch(K1Args& a, int wire_dtype, int compute_dtype, bool update, 
     for (int i = 0; i < a.nseg; ++i) {
         ZO2_OP_CHECK((a.seg[i].e0 & 7) == 0 && (a.seg[i].off & 7) == 0, ZO2_EINVAL,
                      "k1: segment %d not aligned to 8 elements", i);
-        ZO2_OP_CHECK(a.seg[i].scale > 0.f, ZO2_EINVAL, "k1: segment %d has scale %g", i, (double)a.seg[i].scale);
+        int ex = 0;
+        ZO2_OP_CHECK(a.seg[i].scale > 0.f && isfinite(a.seg[i].scale) && frexpf(a.seg[i].scale, &ex) == 0.5f, ZO2_EINVAL,
+                     "k1: segment %d has scale %g (must be a power of two)", i, (double)a.seg[i].scale);
         a.first_chunk[i] = chunks;
         const uint64_t nc = (a.seg[i].n + kChunk - 1) / kChunk;
         ZO2_OP_CHECK(chunks + nc < 0x7fffffffull, ZO2_EINVAL, "k1: too many chunks");

@@ -91,6 +91,7 @@ struct zo2_ctx {
     bool planned, need_plan;
     int plan_T, plan_seq;
     bool resident, phased;
+    int scratch_plan_forced;            // 0: the planner chooses; 1: one scratch set sized for the largest tensor group
     int n_slots;
     char* slots;
     char *wp, *wm;                      // W+ / W- scratch in use (compute dtype)
@@ -307,8 +308,9 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     if (w->tensor_scale) {
         for (int i = 0; i < c->n_tensors; ++i) {
             const float s = w->tensor_scale[i];
-            if (!(s > 0.f) || !isfinite(s) || (!wire8 && s != 1.0f)) {
-                set_op_error("zo2_init: tensor_scale[%d] = %g is invalid for this wire dtype", i, (double)s);
+            int ex = 0;
+            if (!(s > 0.f) || !isfinite(s) || frexpf(s, &ex) != 0.5f || (!wire8 && s != 1.0f)) {
+                set_op_error("zo2_init: tensor_scale[%d] = %g is invalid for this wire dtype (a power of two; 1 unless the format has 8 bits)", i, (double)s);
                 delete c;
                 return ZO2_EINVAL;
             }
@@ -345,6 +347,9 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     prof_reset(c);
     c->n_slots = 0;
     c->resident = false;
+    c->phased = false;
+    c->scratch_plan_forced = 0;
+    c->scratch_elems = 0;
     *out = c;   // from here on errors are reported through the context
 
     // persistent region: embeddings, final LayerNorm, LM head, state
@@ -434,10 +439,9 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const size_t d = g.d_model, f = g.d_ffn, V = g.vocab;
     const size_t budget = c->budget;
     const size_t rows2 = 2 * (size_t)T;
-    // logits chunk: up to 1/8 of the budget, at least 128 rows per sign
-    // (ZO2_DISABLE_FUSED_CE=1 keeps the materialised-logits path, for A/B measurements)
-    const bool fused_ce = (g.compute_dtype != ZO2_F32) && T >= 256 && V >= 256 && (d % 128 == 0) && (V % 4 == 0) &&
-                          getenv("ZO2_DISABLE_FUSED_CE") == nullptr;
+    // logits chunk (float32 mode and shapes the fused LM-head + cross-entropy kernel does not take): up to 1/8 of the
+    // budget, at least 128 rows per sign
+    const bool fused_ce = (g.compute_dtype != ZO2_F32) && T >= 256 && V >= 256 && (d % 128 == 0) && (V % 4 == 0);
     const size_t ce_parts = 4 * ((V + 255) / 256);
     size_t lrows = budget / 8 / (V * 4) / 2;
     lrows = lrows / 128 * 128;
@@ -460,7 +464,7 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     long slots = 0;
     // preference: two whole-block scratch sets (K1 of the next block overlaps this block's forwards),
     // then one whole-block set, then one set sized for the largest tensor group
-    for (int attempt = (c->sk ? 0 : 1); attempt < 3; ++attempt) {
+    for (int attempt = (c->scratch_plan_forced == 1 ? 2 : (c->sk ? 0 : 1)); attempt < 3; ++attempt) {
         phased = attempt == 2;
         two_sets = attempt == 0;
         scratch = std::max(phased ? phase_max : c->offs[ZO2_BLOCK_TENSORS], head_elems);
@@ -546,6 +550,23 @@ extern "C" zo2_status zo2_get_plan(const zo2_ctx* c, int32_t* n_slots, int32_t* 
     if (n_slots) *n_slots = c->n_slots;
     if (resident) *resident = c->resident ? 1 : 0;
     if (bytes_used) *bytes_used = c->planned ? c->bytes_used : c->persistent_bytes;
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_scratch_plan(const zo2_ctx* c, int32_t* per_group, int64_t* scratch_elems, int32_t* scratch_sets) {
+    if (!c) return ZO2_EINVAL;
+    if (per_group) *per_group = (c->planned && c->phased) ? 1 : 0;
+    if (scratch_elems) *scratch_elems = c->planned ? c->scratch_elems : 0;
+    if (scratch_sets) *scratch_sets = c->planned ? (c->overlap_k1 ? 2 : 1) : 0;
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_set_scratch_plan(zo2_ctx* c, int32_t mode) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (mode != 0 && mode != 1) return fail(c, ZO2_EINVAL, "zo2_set_scratch_plan: mode %d (0 or 1)", mode);
+    c->scratch_plan_forced = mode;
+    c->need_plan = true;   // re-plan at the next step
     return ZO2_OK;
 }
 
@@ -1164,6 +1185,32 @@ extern "C" zo2_status zo2_op_update_perturb(void* theta, int32_t wire_dtype, voi
     a.k_prev = philox_keys(seed_prev); a.k_cur = philox_keys(seed);
     a.seg[0].off = 0; a.seg[0].e0 = e0; a.seg[0].n = n; a.seg[0].tensor_id = tensor_id; a.seg[0].scale = scale;
     return k1_launch(a, wire_dtype, compute_dtype, has_pending != 0, w_plus != nullptr, as_stream(stream));
+}
+
+// One block bucket, all 16 tensors in one grid: the launch the context issues per decoder block.
+extern "C" zo2_status zo2_op_update_perturb_block(const zo2_config* cfg, int32_t layer, void* bucket, void* w_plus, void* w_minus,
+                                                  int32_t has_pending, uint64_t seed_prev, float cval, uint64_t seed, float eps,
+                                                  const float* host_scales, int32_t stochastic, void* stream) {
+    char why[256];
+    ZO2_OP_CHECK(config_ok(cfg, why, sizeof(why)), ZO2_EINVAL, "update_perturb_block: %s", why);
+    ZO2_OP_CHECK(layer >= 0 && bucket != nullptr, ZO2_EINVAL, "update_perturb_block: bad layer or NULL bucket");
+    ZO2_OP_CHECK(w_plus != nullptr || w_minus == nullptr, ZO2_EINVAL, "update_perturb_block: W- without W+");
+    const size_t ws = zo2_dtype_size(cfg->wire_dtype), cs = zo2_dtype_size(cfg->compute_dtype);
+    ZO2_OP_CHECK(((uintptr_t)bucket % (8 * ws)) == 0 && ((uintptr_t)w_plus % (8 * cs)) == 0 && ((uintptr_t)w_minus % (8 * cs)) == 0,
+                 ZO2_EINVAL, "update_perturb_block: pointers must be aligned to 8 elements");
+    int64_t offs[ZO2_BLOCK_TENSORS + 1], tn[ZO2_BLOCK_TENSORS];
+    zo2_block_tensor_offsets(cfg, offs);
+    block_tensor_elems(cfg, tn);
+    K1Args a;
+    memset(&a, 0, sizeof(a));
+    a.theta = bucket; a.w_plus = w_plus; a.w_minus = w_minus; a.w_off0 = 0; a.nseg = ZO2_BLOCK_TENSORS;
+    a.c_imm = cval; a.c_ptr = nullptr; a.eps = eps; a.stochastic = stochastic != 0;
+    a.k_prev = philox_keys(seed_prev); a.k_cur = philox_keys(seed);
+    for (int k = 0; k < ZO2_BLOCK_TENSORS; ++k) {
+        K1Seg& sg = a.seg[k];
+        sg.off = offs[k]; sg.e0 = 0; sg.n = (uint64_t)tn[k]; sg.tensor_id = block_tid(layer, k); sg.scale = host_scales ? host_scales[k] : 1.0f;
+    }
+    return k1_launch(a, cfg->wire_dtype, cfg->compute_dtype, has_pending != 0, w_plus != nullptr, as_stream(stream));
 }
 
 extern "C" zo2_status zo2_op_convert(const void* src, int32_t sdt, float sscale, void* dst, int32_t ddt, float dscale, uint64_t n, void* stream) {

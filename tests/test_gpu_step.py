@@ -32,6 +32,20 @@ def _run_pair(cfg, P, tok, lab, steps, eps, lrs, wire="f32", compute="f32", budg
     return oz, ctx, res_o, res_g
 
 
+def _replay_updates(shape, P, wire, seeds, lrs, gs):
+    """theta after the updates of Eq. 3 with given projected gradients: theta <- store(fma(-fl32(lr g), z(seed), theta))
+    per step, with the oracle's z and rounding.  Used where g itself is only known to the low-precision bar."""
+    from oracle import philox
+    from oracle.zo_step import _fma32, _store
+    Q = {n: (codec.round_to(a, wire) if wire != "f32" else a.copy()) for n, a in P.items()}
+    for seed, lr, g in zip(seeds, lrs, gs):
+        c = np.float32(np.float32(lr) * np.float32(g))
+        for name, tid, shp in opt_model.tensor_table(shape):
+            z = philox.gaussian(seed, tid, 0, int(np.prod(shp))).reshape(shp)
+            Q[name] = _store(_fma32(-c, z, Q[name]), wire)
+    return Q
+
+
 @pytest.mark.parametrize("tied", [True, False])
 def test_fp32_steps_match_oracle(tied):
     cfg = si.tiny_config(n_layers=3, d_model=64, n_heads=4, d_ffn=136, vocab=211, max_pos=40, tied=tied)
@@ -199,17 +213,23 @@ def test_low_precision_steps_track_oracle(wire, compute):
         assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
     oz.flush(); ctx.flush(); ctx.sync_to_host()
     Pg = ctx.parameters()
-    # The spec bar for the low-precision modes is on the losses only: g = (l+ - l-) / 2 eps
-    # amplifies a 1e-3 relative loss difference into a different step.  What can still be checked
-    # is that the parameters moved by the library's own g along the same z: the two sides differ by
-    # at most lr * |dg| * max|z| per step, plus one rounding step of the storage format per update.
-    dg = sum(abs(float(g[2]) - float(a[2])) for a, g in zip(ro, rg))
-    rel = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -23}[wire]
-    for n in oz.P:
-        d = np.abs(Pg[n] - oz.P[n])
-        bound = 1e-2 * dg * 5.8 + 4 * rel * np.maximum(np.abs(oz.P[n]), 1e-3)
-        assert np.all(d <= bound), n
+    # The bar for the low-precision modes is on the losses: g = (l+ - l-) / 2 eps turns a 1e-3 relative loss
+    # difference into a different step, so the two parameter sets legitimately drift apart by lr |dg| |z|.  What
+    # has a tight bound is the update itself (Eq. 3) given the g each step reported: replaying theta <- store(theta -
+    # fl32(lr g_j) z_j) with the oracle's z and the oracle's rounding must reproduce the stored parameters, up to
+    # the 2e-6 tolerance on z nudging a value across a rounding boundary (one unit of the format, rarely).
+    want = _replay_updates(opt_model.OptShape(**cfg), P, wire, [42 + j for j in range(3)], [1e-2] * 3, [g[2] for g in rg])
+    rel = {"bf16": 2.0 ** -7, "f16": 2.0 ** -10, "f32": 2.0 ** -22}[wire]
+    tot = same = 0
+    for n in want:
+        d = np.abs(Pg[n] - want[n])
+        assert np.all(d <= rel * np.abs(want[n]) + 1e-2 * 40.0 * 2e-6 + 1e-30), n      # lr * |g| * dz, |g| <= 40 here
+        tot += d.size; same += int(np.sum(d == 0))
         assert not np.array_equal(Pg[n], codec.round_to(P[n], wire) if wire != "f32" else P[n]), n
+    print(wire, compute, "parameters identical to the replayed update:", same / tot)
+    if wire != "f32":           # (in float32 storage lr |g| dz is many units in the last place: only the bound above applies)
+        assert same / tot > 0.98
+    assert max(abs(float(g[2])) for g in rg) <= 40.0
     ctx.close()
 
 

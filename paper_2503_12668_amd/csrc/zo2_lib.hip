@@ -1255,6 +1255,22 @@ extern "C" size_t zo2_op_lm_head_ce_workspace_bytes(int32_t M, int32_t N) {
     return (2 * parts + 1) * (size_t)M * sizeof(float);
 }
 
+static zo2_status lm_head_ce_on(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                                const int32_t* labels, float* row_loss, void* workspace, hipStream_t st) {
+    const int parts = 4 * ((N + 255) / 256);
+    float* pmax = (float*)workspace;
+    float* psum = pmax + (size_t)parts * M;
+    float* lab = psum + (size_t)parts * M;
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.M = M; ga.N = N; ga.K = K; ga.ldx = ldx; ga.ldw = ldw; ga.ldy = N; ga.out_f32 = 1; ga.nprob = 1; ga.ce_mode = 1; ga.part_ld = M;
+    ga.p[0].X = X; ga.p[0].W = W; ga.p[0].out_scale = 1.0f; ga.p[0].labels = labels;
+    ga.p[0].part_max = pmax; ga.p[0].part_sum = psum; ga.p[0].label_logit = lab;
+    const zo2_status s = gemm_launch(ga, dtype, st);
+    if (s != ZO2_OK) return s;
+    return ce_combine(pmax, psum, lab, labels, M, parts, M, 0, M, row_loss, st);
+}
+
 extern "C" zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W,
                                         int64_t ldw, const int32_t* labels, float* row_loss, void* workspace, size_t workspace_bytes,
                                         void* stream) {
@@ -1265,16 +1281,5 @@ extern "C" zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int
                  "lm_head_ce: needs M, N >= 256, K %% 128 == 0, N %% 4 == 0 (got %d x %d x %d)", M, N, K);
     ZO2_OP_CHECK(((uintptr_t)workspace & 255) == 0 && workspace_bytes >= zo2_op_lm_head_ce_workspace_bytes(M, N) && M > 0 && N > 0,
                  ZO2_EINVAL, "lm_head_ce: workspace too small or not 256-byte aligned");
-    const int parts = 4 * ((N + 255) / 256);
-    float* pmax = (float*)workspace;
-    float* psum = pmax + (size_t)parts * M;
-    float* lab = psum + (size_t)parts * M;
-    GemmArgs ga;
-    memset(&ga, 0, sizeof(ga));
-    ga.M = M; ga.N = N; ga.K = K; ga.ldx = ldx; ga.ldw = ldw; ga.ldy = N; ga.out_f32 = 1; ga.nprob = 1; ga.ce_mode = 1; ga.part_ld = M;
-    ga.p[0].X = X; ga.p[0].W = W; ga.p[0].out_scale = 1.0f; ga.p[0].labels = labels;
-    ga.p[0].part_max = pmax; ga.p[0].part_sum = psum; ga.p[0].label_logit = lab;
-    const zo2_status s = gemm_launch(ga, dtype, as_stream(stream));
-    if (s != ZO2_OK) return s;
-    return ce_combine(pmax, psum, lab, labels, M, parts, M, 0, M, row_loss, as_stream(stream));
+    return lm_head_ce_on(dtype, M, N, K, X, ldx, W, ldw, labels, row_loss, workspace, as_stream(stream));
 }

@@ -330,6 +330,19 @@ zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int32_t K, con
                              void* workspace, size_t workspace_bytes, void* stream);
 size_t zo2_op_lm_head_ce_workspace_bytes(int32_t M, int32_t N);
 
+/* zo2_op_lm_head_ce for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and therefore have no workspace to pass: same arguments without the
+ * workspace, same kernels, same results bit for bit.  The (max, sum exp) partials go to a buffer of
+ * ZO2_STATIC_SCRATCH_BYTES built into the library (one copy per GPU, held until the process ends); the call
+ * allocates nothing and frees nothing.  Shapes whose partials need more - (8 ceil(N / 256) + 1) * M * 4 bytes, e.g.
+ * beyond 2659 rows at N = 50272 - are refused with ZO2_EINVAL; use zo2_op_lm_head_ce for those.  All calls on one
+ * GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams or threads) race and must
+ * be serialised by the caller; calls on one stream are ordered by the stream.  The buffer keeps the previous
+ * call's contents; nothing in it needs clearing, every value read is written earlier in the same call. */
+#define ZO2_STATIC_SCRATCH_BYTES (16u << 20)
+zo2_status zo2_op_lm_head_ce_static(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx,
+                                    const void* W, int64_t ldw, const int32_t* labels, float* row_loss, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

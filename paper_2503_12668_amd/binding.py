@@ -96,6 +96,7 @@ def lib():
         "zo2_op_cross_entropy_rows": (i32, [vp, i64, vp, i32, i32, vp, vp]),
         "zo2_op_lm_head_ce": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, C.c_size_t, vp]),
         "zo2_op_lm_head_ce_workspace_bytes": (C.c_size_t, [i32, i32]),
+        "zo2_op_lm_head_ce_static": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(L, name)
@@ -110,7 +111,7 @@ EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_r
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
-            "zo2_op_lm_head_ce_workspace_bytes"]
+            "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
 
 
 def _op_check(st):
@@ -242,6 +243,18 @@ def op_lm_head_ce(X, W, labels, stream=None):
     out = torch.empty(M, dtype=torch.float32, device="cuda")
     _op_check(lib().zo2_op_lm_head_ce(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(labels), _ptr(out),
                                       _ptr(ws), nb, _stream_ptr(stream)))
+    return out
+
+
+def op_lm_head_ce_static(X, W, labels, out=None, stream=None):
+    """op_lm_head_ce without a workspace: the library's built-in scratch buffer is used; nothing is allocated by the
+    call itself (pass `out` to keep the binding from allocating the result either)."""
+    M, K = X.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty(M, dtype=torch.float32, device="cuda")
+    _op_check(lib().zo2_op_lm_head_ce_static(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(labels),
+                                             _ptr(out), _stream_ptr(stream)))
     return out
 
 

@@ -13,6 +13,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "attention.h"
@@ -1282,4 +1283,53 @@ extern "C" zo2_status zo2_op_lm_head_ce(int32_t dtype, int32_t M, int32_t N, int
     ZO2_OP_CHECK(((uintptr_t)workspace & 255) == 0 && workspace_bytes >= zo2_op_lm_head_ce_workspace_bytes(M, N) && M > 0 && N > 0,
                  ZO2_EINVAL, "lm_head_ce: workspace too small or not 256-byte aligned");
     return lm_head_ce_on(dtype, M, N, K, X, ldx, W, ldw, labels, row_loss, workspace, as_stream(stream));
+}
+
+// ---------------------------------------------------------------------------------- LM head + cross-entropy without a workspace
+// For callers that cannot allocate device memory: the partials live in a fixed array inside the library's
+// code object.  Every GPU the library runs on holds its own copy of the array at its own address; in host
+// code the array's name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[ZO2_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxStaticDevices = 64;
+static void* g_static_scratch[kMaxStaticDevices];      // per device: where `scratch` lives there (NULL: not asked yet)
+static std::mutex g_static_scratch_lock;
+
+// The address of `scratch` on the current device, looked up once per device.
+static zo2_status static_scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_op_error("lm_head_ce_static: hipGetDevice failed: %s", hipGetErrorString(e)); return ZO2_EHIP; }
+    ZO2_OP_CHECK(dev >= 0 && dev < kMaxStaticDevices, ZO2_EINVAL, "lm_head_ce_static: device index %d beyond %d", dev, kMaxStaticDevices);
+    std::lock_guard<std::mutex> guard(g_static_scratch_lock);
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_op_error("lm_head_ce_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+            return ZO2_EHIP;
+        }
+        g_static_scratch[dev] = p;
+    }
+    *out = g_static_scratch[dev];
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_op_lm_head_ce_static(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W,
+                                               int64_t ldw, const int32_t* labels, float* row_loss, void* stream) {
+    if (M == 0) return ZO2_OK;
+    ZO2_OP_CHECK(X && W && labels && row_loss, ZO2_EINVAL, "lm_head_ce_static: NULL argument");
+    ZO2_OP_CHECK(dtype == ZO2_BF16 || dtype == ZO2_F16, ZO2_EINVAL, "lm_head_ce_static: dtype must be BF16 or F16");
+    ZO2_OP_CHECK(M >= 256 && N >= 256 && K > 0 && K % 128 == 0 && N % 4 == 0, ZO2_EINVAL,
+                 "lm_head_ce_static: needs M, N >= 256, K %% 128 == 0, N %% 4 == 0 (got %d x %d x %d)", M, N, K);
+    const size_t need = zo2_op_lm_head_ce_workspace_bytes(M, N);
+    ZO2_OP_CHECK(need <= (size_t)ZO2_STATIC_SCRATCH_BYTES, ZO2_EINVAL,
+                 "lm_head_ce_static: %d rows x %d columns need %zu bytes of partials, the built-in buffer holds %zu; "
+                 "use zo2_op_lm_head_ce with a workspace", M, N, need, (size_t)ZO2_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    const zo2_status s = static_scratch_address(&ws);
+    if (s != ZO2_OK) return s;
+    // every partial and label logit the second kernel reads is written by the first in the same call: nothing in the
+    // buffer has to start at zero, and what an earlier (larger) call left behind is never read
+    return lm_head_ce_on(dtype, M, N, K, X, ldx, W, ldw, labels, row_loss, ws, as_stream(stream));
 }

@@ -180,19 +180,20 @@ zo2_status zo2_sync_to_host(zo2_ctx* ctx);
  * resident, how many arena bytes are in use.  Any pointer may be NULL. */
 zo2_status zo2_get_plan(const zo2_ctx* ctx, int32_t* n_slots, int32_t* resident, size_t* bytes_used);
 
-/* How the W+ / W- scratch of the last plan is organised (Sec. 5.3's reusable block space, applied to the
- * perturbed copies): *per_group = 0 when it holds a whole block's 16 tensors at once (one update + perturb
- * sweep per block), 1 when it is sized for the largest of the four tensor groups {ln1, q, k, v} {o} {ln2, fc1}
- * {fc2} and is refilled by a sweep per group, between the projections (what a tight budget forces for wide
- * blocks: the two whole-block copies of the OPT-175B shape alone would take 7 GB); *scratch_elems = elements of
- * one copy; *scratch_sets = 1, or 2 when zo2_device.stream_k1 is in use.  Any pointer may be NULL.  Results do
- * not depend on the organisation. */
-zo2_status zo2_get_scratch_plan(const zo2_ctx* ctx, int32_t* per_group, int64_t* scratch_elems, int32_t* scratch_sets);
+/* How the W+ / W- scratch of the last plan is organised (Sec. 5.3's reusable block space, applied to the perturbed
+ * copies).  The forward of a block needs its tensors in four groups, {ln1, q, k, v} {o} {ln2, fc1} {fc2}, one after
+ * the other.  *sweeps_per_block = 1: the scratch holds a whole block and one update + perturb sweep per block fills
+ * it; 2: it holds the larger half ({ln1 .. o} or {ln2 .. fc2}) and is refilled before the FFN; 4: it holds the
+ * largest group and is refilled before every projection.  More sweeps need less memory (the two whole-block copies
+ * of the OPT-175B shape alone would take 7 GB) and hand each copy to its projection while it is still in the
+ * memory-side cache.  *scratch_elems = elements of one copy; *scratch_sets = 1, or 2 when zo2_device.stream_k1 is in
+ * use.  Any pointer may be NULL.  Results do not depend on the organisation. */
+zo2_status zo2_get_scratch_plan(const zo2_ctx* ctx, int32_t* sweeps_per_block, int64_t* scratch_elems, int32_t* scratch_sets);
 
-/* mode 1: always organise the scratch per tensor group, whatever the budget would allow; mode 0 (default): the
- * planner prefers whole-block scratch and falls back to per-group scratch when the budget is too small for
- * 3 block slots otherwise.  Takes effect at the next step.  ZO2_EINVAL for any other mode. */
-zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t mode);
+/* sweeps = 1, 2 or 4: use exactly that organisation (ZO2_EBUDGET at the next step if 3 block slots do not fit next to
+ * it); 0 (default): the planner starts from its preferred organisation and moves to smaller scratch sets until 3
+ * block slots fit.  Takes effect at the next step.  ZO2_EINVAL for any other value. */
+zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t sweeps);
 
 /* Per-stream busy time of the last step in milliseconds (compute, upload, offload) and the
  * bytes copied each way; for host-link rate reporting.  Any pointer may be NULL. */

@@ -427,12 +427,13 @@ class Zo2Context:
         self._check(lib().zo2_get_plan(self.handle, C.byref(n), C.byref(r), C.byref(b)))
         pg, se, ss = C.c_int32(), C.c_int64(), C.c_int32()
         self._check(lib().zo2_get_scratch_plan(self.handle, C.byref(pg), C.byref(se), C.byref(ss)))
-        return dict(n_slots=n.value, resident=bool(r.value), bytes_used=b.value, per_group_scratch=bool(pg.value),
+        return dict(n_slots=n.value, resident=bool(r.value), bytes_used=b.value, sweeps_per_block=pg.value,
                     scratch_elems=se.value, scratch_sets=ss.value)
 
-    def set_scratch_plan(self, per_group):
-        """True: W+ / W- scratch sized for the largest tensor group, refilled per group; False: the planner chooses."""
-        self._check(lib().zo2_set_scratch_plan(self.handle, 1 if per_group else 0))
+    def set_scratch_plan(self, sweeps):
+        """1, 2 or 4 update + perturb sweeps per block (W+ / W- scratch for a whole block, a half, a tensor group);
+        0: the planner chooses."""
+        self._check(lib().zo2_set_scratch_plan(self.handle, int(sweeps)))
 
     def step_stats(self):
         a, b, c_ = C.c_float(), C.c_float(), C.c_float()

@@ -5,7 +5,7 @@
 // 8 consecutive k of row l % 32.  So tiles go global -> LDS -> registers as 16-byte chunks
 // with no transposition; an XOR swizzle of the chunk index keeps the 128-bit LDS accesses
 // conflict free.  bf16 / fp16 inputs use v_mfma_f32_32x32x16 (float32 accumulate); the
-// float32 mode uses a register-tiled vector-ALU kernel.
+// float32 mode uses v_mfma_f32_32x32x2_f32 (gemm_f32_mfma_kernel).
 //
 // The +/- streams (and q, k, v) are independent problems of one shape: they share a launch
 // through grid.z so that even the narrow projections fill 256 compute units.
@@ -148,58 +148,152 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// float32 kernel: 64 x 64 x 16 tiles, 256 threads, 4 x 4 outputs per thread.
+// float32 kernel on the matrix cores: v_mfma_f32_32x32x2_f32 (true float32 products, float32 accumulate).
+// Block tile 128 x 128 x 32, four wavefronts in a 2 x 2 grid, each owning 64 x 64 = 2 x 2 MFMA tiles; two
+// workgroups per compute unit.  LDS layout as in the 16-bit kernel: rows of 8 chunks of 16 bytes (4 floats), chunk
+// index XOR-swizzled by (row & 7).
+//
+// The instruction contracts two k per issue: lanes 0..31 supply k = 0, lanes 32..63 k = 1 of a row.  A dot product does
+// not care in which order its k are visited, as long as both operands visit them in the same order; so a lane of half
+// h reads one chunk - the four consecutive k = 8 g + 4 h .. + 3 of its row - with a single 128-bit LDS read, and issue t
+// of group g contracts k = 8 g + t (lower half) with k = 8 g + 4 + t (upper half).  One LDS read per operand tile feeds
+// four MFMAs.  The weight tile is the instruction's first operand, which leaves a lane with one output row m and runs
+// of four consecutive columns n: 16-byte stores.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs a) {
-    constexpr int BM = 64, BN = 64, BK = 16, PAD = 4;
-    __shared__ float As[BK][BM + PAD];
-    __shared__ float Bs[BK][BN + PAD];
+__global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a) {
+    constexpr int BM = 128, BN = 128, BK = 32, KC = BK / 4;       // 8 chunks of 4 floats per row
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int CA = BM * KC / 256, CB = BN * KC / 256;         // chunks each thread stages per tile
+    __shared__ float4 lds[2][(BM + BN) * KC];
+
     const GemmProblem p = a.p[blockIdx.z];
     const int tiles_n = (a.N + BN - 1) / BN;
     const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    const int lrow = tid >> 2, lk = (tid & 3) * 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, r = lane & 31, kh = lane >> 5;
     const float* __restrict__ X = reinterpret_cast<const float*>(p.X);
     const float* __restrict__ W = reinterpret_cast<const float*>(p.W);
-    const float* gx = X + (size_t)min(m0 + lrow, a.M - 1) * a.ldx + lk;
-    const float* gw = W + (size_t)min(n0 + lrow, a.N - 1) * a.ldw + lk;
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < a.K; k0 += BK) {
-        float4 xa = make_float4(0, 0, 0, 0), wb = make_float4(0, 0, 0, 0);
-        if (k0 + lk < a.K) {
-            xa = *reinterpret_cast<const float4*>(gx + k0);
-            wb = *reinterpret_cast<const float4*>(gw + k0);
-        }
-        __syncthreads();
-        As[lk + 0][lrow] = xa.x; As[lk + 1][lrow] = xa.y; As[lk + 2][lrow] = xa.z; As[lk + 3][lrow] = xa.w;
-        Bs[lk + 0][lrow] = wb.x; Bs[lk + 1][lrow] = wb.y; Bs[lk + 2][lrow] = wb.z; Bs[lk + 3][lrow] = wb.w;
-        __syncthreads();
+
+    const float* ga[CA];
+    const float* gb[CB];
+    int la[CA], lb[CB], kca[CA], kcb[CB];
 #pragma unroll
-        for (int k = 0; k < BK; ++k) {
-            const float4 av = *reinterpret_cast<const float4*>(&As[k][ty * 4]);
-            const float4 bv = *reinterpret_cast<const float4*>(&Bs[k][tx * 4]);
-            const float ar[4] = {av.x, av.y, av.z, av.w}, br[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(ar[i], br[j], acc[i][j]);
-        }
+    for (int i = 0; i < CA; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        ga[i] = X + (size_t)min(m0 + row, a.M - 1) * a.ldx + kc * 4;
+        la[i] = row * KC + (kc ^ (row & 7));
+        kca[i] = kc * 4;
     }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        gb[i] = W + (size_t)min(n0 + row, a.N - 1) * a.ldw + kc * 4;
+        lb[i] = BM * KC + row * KC + (kc ^ (row & 7));
+        kcb[i] = kc * 4;
+    }
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float4 ra[CA], rb[CB];
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto load_tile = [&](int k0) {        // K is a multiple of 4: a chunk is inside the row or entirely past its end
+#pragma unroll
+        for (int i = 0; i < CA; ++i) ra[i] = (k0 + kca[i] < a.K) ? *reinterpret_cast<const float4*>(ga[i] + k0) : zero4;
+#pragma unroll
+        for (int i = 0; i < CB; ++i) rb[i] = (k0 + kcb[i] < a.K) ? *reinterpret_cast<const float4*>(gb[i] + k0) : zero4;
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) lds[buf][la[i]] = ra[i];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) lds[buf][lb[i]] = rb[i];
+    };
+
+    const int nk = (a.K + BK - 1) / BK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_tile((kt + 1) * BK);
+#pragma unroll
+        for (int g = 0; g < BK / 8; ++g) {
+            const int kc = 2 * g + kh;
+            float4 fx[TM], fw[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * WM + i * 32 + r;
+                fx[i] = lds[cur][row * KC + (kc ^ (row & 7))];
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * WN + j * 32 + r;
+                fw[j] = lds[cur][BM * KC + row * KC + (kc ^ (row & 7))];
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[j].x, fx[i].x, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[j].y, fx[i].y, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[j].z, fx[i].z, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[j].w, fx[i].w, acc[i][j], 0, 0, 0);
+                }
+        }
+        if (kt + 1 < nk) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: in MFMA tile (i, j) a lane holds output row m = r (the second operand's row) and the columns
+    // n = 8 (v / 4) + 4 kh + v % 4 (the first operand's rows): four runs of four consecutive columns
     const float* __restrict__ bias = reinterpret_cast<const float*>(p.bias);
     float* __restrict__ Y = reinterpret_cast<float*>(p.Y);
+    const bool vec_ok = (a.N % 4 == 0) && (a.ldy % 4 == 0) && (((uintptr_t)Y & 15) == 0) &&
+                        (!p.residual || ((uintptr_t)p.residual & 15) == 0) && (!bias || ((uintptr_t)bias & 15) == 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty * 4 + i;
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * WM + i * 32 + r;
         if (m >= a.M) continue;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + tx * 4 + j;
-            if (n >= a.N) continue;
-            float y = (acc[i][j] + (bias ? bias[n] : 0.f)) * p.out_scale;
-            if (a.relu) y = fmaxf(y, 0.f);
-            const size_t o = (size_t)m * a.ldy + n;
-            if (p.residual) y += p.residual[o];
-            Y[o] = y;
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * kh;
+                if (n >= a.N) continue;
+                const size_t o = (size_t)m * a.ldy + n;
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * q + e];
+                if (vec_ok) {                      // N % 4 == 0: the run of four is inside the row or entirely past its end
+                    const float4 b4 = bias ? *reinterpret_cast<const float4*>(bias + n) : zero4;
+                    const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        y[e] = (y[e] + bb[e]) * p.out_scale;
+                        if (a.relu) y[e] = fmaxf(y[e], 0.f);
+                    }
+                    if (p.residual) {
+                        const float4 r4 = *reinterpret_cast<const float4*>(p.residual + o);
+                        y[0] += r4.x; y[1] += r4.y; y[2] += r4.z; y[3] += r4.w;
+                    }
+                    *reinterpret_cast<float4*>(Y + o) = make_float4(y[0], y[1], y[2], y[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (n + e >= a.N) continue;
+                        float v = (y[e] + (bias ? bias[n + e] : 0.f)) * p.out_scale;
+                        if (a.relu) v = fmaxf(v, 0.f);
+                        if (p.residual) v += p.residual[o + e];
+                        Y[o + e] = v;
+                    }
+                }
+            }
         }
     }
 }
@@ -233,8 +327,8 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
                  "gemm: cross-entropy mode needs the 256 x 256 kernel (16-bit inputs, K %% 128 == 0, M, N >= 256, N %% 4 == 0)");
     if (dtype == ZO2_F32) {
         ZO2_OP_CHECK(a.out_f32, ZO2_EINVAL, "gemm: the float32 kernel writes float32 output");
-        const unsigned tiles = (unsigned)(((a.M + 63) / 64) * ((a.N + 63) / 64));
-        hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
+        const unsigned tiles = (unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128));
+        hipLaunchKernelGGL(gemm_f32_mfma_kernel, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
         ZO2_HIP_LAUNCH_CHECK();
         return ZO2_OK;
     }

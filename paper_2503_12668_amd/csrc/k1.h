@@ -24,6 +24,7 @@ struct K1Args {
     uint32_t total_chunks;
     float c_imm;          // eta_prev * g_prev, used when c_ptr == nullptr
     int32_t stochastic;   // 1: theta' is stored with stochastic rounding (low-bit wire formats), 0: to nearest
+    int32_t reverse;      // 1: the grid walks the chunks from the last to the first
     float eps;
     const float* c_ptr;   // device scalar holding eta_prev * g_prev (stays on the GPU between steps)
     PhiloxKeys k_prev, k_cur;

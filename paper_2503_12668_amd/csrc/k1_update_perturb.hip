@@ -69,11 +69,15 @@ template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR>
 __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
     // which tensor does this workgroup work on: first_chunk[] ascends (0xffffffff past the last segment),
     // so the segment index is the number of entries at or below this workgroup's index
+    // Workgroups are dispatched in index order; chunks are taken in the opposite order, so that the sweep ends with
+    // the first tensors of the list: the projections that run right after the sweep (q, k, v of a block) then find
+    // their perturbed copies still in the memory-side cache, which a whole block's copies exceed.
+    const uint32_t chunk = a.reverse ? a.total_chunks - 1u - blockIdx.x : blockIdx.x;
     int s = 0;
 #pragma unroll
-    for (int i = 1; i < K1Args::kMaxSeg; ++i) s += (blockIdx.x >= a.first_chunk[i]) ? 1 : 0;
+    for (int i = 1; i < K1Args::kMaxSeg; ++i) s += (chunk >= a.first_chunk[i]) ? 1 : 0;
     const K1Seg sg = a.seg[s];
-    const uint64_t chunk0 = (uint64_t)(blockIdx.x - a.first_chunk[s]) * kChunk;
+    const uint64_t chunk0 = (uint64_t)(chunk - a.first_chunk[s]) * kChunk;
     W* __restrict__ theta = reinterpret_cast<W*>(a.theta) + sg.off;
     C* __restrict__ wp = PERTURB ? reinterpret_cast<C*>(a.w_plus) + (sg.off - a.w_off0) : nullptr;
     const bool has_m = PERTURB && a.w_minus != nullptr;            // a single forward needs W+ only

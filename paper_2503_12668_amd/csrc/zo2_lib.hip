@@ -34,6 +34,7 @@ void set_op_error(const char* fmt, ...) {
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static constexpr int64_t kTensorAlign = 256;   // elements
+static constexpr int kDefaultSweeps = 1;       // update + perturb sweeps per block when the budget leaves the choice
 
 static bool config_ok(const zo2_config* c, char* why, size_t n) {
 #define BAD(...) do { snprintf(why, n, __VA_ARGS__); return false; } while (0)
@@ -91,8 +92,10 @@ struct zo2_ctx {
     // plan (depends on budget and batch x seq)
     bool planned, need_plan;
     int plan_T, plan_seq;
-    bool resident, phased;
-    int scratch_plan_forced;            // 0: the planner chooses; 1: one scratch set sized for the largest tensor group
+    bool resident;
+    int sweeps;                         // update + perturb sweeps per block: 1 (whole-block scratch), 2 (per half) or 4 (per tensor group)
+    int pb[5];                          // sweep p, issued at point p of the block's forward, covers tensors pb[p] .. pb[p + 1] - 1 (may be empty)
+    int scratch_plan_forced;            // 0: the planner chooses; 1 / 2 / 4: that many sweeps per block
     int n_slots;
     char* slots;
     char *wp, *wm;                      // W+ / W- scratch in use (compute dtype)
@@ -348,7 +351,7 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     prof_reset(c);
     c->n_slots = 0;
     c->resident = false;
-    c->phased = false;
+    c->sweeps = 1;
     c->scratch_plan_forced = 0;
     c->scratch_elems = 0;
     *out = c;   // from here on errors are reported through the context
@@ -431,9 +434,14 @@ extern "C" zo2_status zo2_sync_to_host(zo2_ctx* c) {
 }
 
 // ---------------------------------------------------------------------------------- planning
-// Tensor groups whose perturbed copies are needed together (used when the scratch cannot
-// hold a whole block): {ln1, q, k, v}, {o}, {ln2, fc1}, {fc2}.
-static const int kPhase[5] = {0, 8, 10, 14, 16};
+// The W+ / W- scratch holds the perturbed copies of the tensors one sweep of K1 writes.  The forward of a block needs
+// them at four points: {ln1, q, k, v} before the QKV projection, {o} before the output projection, {ln2, fc1} before the
+// first FFN projection, {fc2} before the second.  Three organisations: one sweep over the whole block at point 0; two
+// sweeps (attention half at point 0, FFN half at point 2); four sweeps (one per group).  Fewer tensors per sweep = a
+// smaller scratch, and the copies are consumed right after they are written, while they still sit in the memory-side
+// cache; more sweeps = more, shorter launches.
+static const int kSweepBounds[3][5] = {{0, 16, 16, 16, 16}, {0, 10, 10, 16, 16}, {0, 8, 10, 14, 16}};
+static inline const int* sweep_bounds(int sweeps) { return kSweepBounds[sweeps == 1 ? 0 : sweeps == 2 ? 1 : 2]; }
 
 static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const zo2_config& g = c->cfg;
@@ -457,21 +465,28 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
                  o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
     const size_t act_bytes = act;
 
-    int64_t phase_max = 0;
-    for (int p = 0; p < 4; ++p) phase_max = std::max(phase_max, c->offs[kPhase[p + 1]] - c->offs[kPhase[p]]);
     const int64_t head_elems = (int64_t)align_up(c->tok_elems, kTensorAlign);
-    bool phased = false, resident = false, two_sets = false;
+    auto scratch_for = [&](int sweeps) {
+        const int* pb = sweep_bounds(sweeps);
+        int64_t m = 0;
+        for (int p = 0; p < 4; ++p) m = std::max(m, c->offs[pb[p + 1]] - c->offs[pb[p]]);
+        return std::max(m, head_elems);
+    };
+    bool resident = false, two_sets = false;
+    int sweeps = 1;
     int64_t scratch = 0;
     long slots = 0;
-    // preference: two whole-block scratch sets (K1 of the next block overlaps this block's forwards),
-    // then one whole-block set, then one set sized for the largest tensor group
-    for (int attempt = (c->scratch_plan_forced == 1 ? 2 : (c->sk ? 0 : 1)); attempt < 3; ++attempt) {
-        phased = attempt == 2;
+    // preference: two whole-block scratch sets (K1 of the next block overlaps this block's forwards) when a stream for
+    // it was given, then the default organisation, then ever smaller scratch sets until 3 block slots fit
+    const int forced = c->scratch_plan_forced;
+    const int first = forced ? forced : kDefaultSweeps;
+    for (int attempt = (c->sk && !forced ? 0 : 1); attempt < 4; ++attempt) {
         two_sets = attempt == 0;
-        scratch = std::max(phased ? phase_max : c->offs[ZO2_BLOCK_TENSORS], head_elems);
+        sweeps = attempt == 0 ? 1 : attempt == 1 ? first : attempt == 2 ? std::max(first, 2) : 4;
+        scratch = scratch_for(sweeps);
         const size_t fixed = c->persistent_bytes + act_bytes + (two_sets ? 4 : 2) * align_up((size_t)scratch * c->csz, 256);
         slots = fixed > budget ? -1 : (long)((budget - fixed) / align_up(c->bucket_bytes, 256));
-        if (slots >= g.n_layers || slots >= 3) break;
+        if (slots >= g.n_layers || slots >= 3 || forced) break;      // a forced organisation is not traded for a smaller one
     }
     if (g.n_layers > 0 && slots < g.n_layers && slots < 3)
         return fail(c, ZO2_EBUDGET, "budget of %zu bytes cannot hold embeddings + 3 block slots + scratch + activations for %d tokens", budget, T);
@@ -511,7 +526,8 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     c->bytes_used = off;
     c->logit_rows = (int)lrows;
     c->scratch_elems = scratch;
-    c->phased = phased;
+    c->sweeps = sweeps;
+    for (int p = 0; p < 5; ++p) c->pb[p] = sweep_bounds(sweeps)[p];
     if (c->bucket_bytes % 256) return fail(c, ZO2_EINVAL, "internal: bucket size not aligned");
 
     // events per slot
@@ -554,9 +570,9 @@ extern "C" zo2_status zo2_get_plan(const zo2_ctx* c, int32_t* n_slots, int32_t* 
     return ZO2_OK;
 }
 
-extern "C" zo2_status zo2_get_scratch_plan(const zo2_ctx* c, int32_t* per_group, int64_t* scratch_elems, int32_t* scratch_sets) {
+extern "C" zo2_status zo2_get_scratch_plan(const zo2_ctx* c, int32_t* sweeps_per_block, int64_t* scratch_elems, int32_t* scratch_sets) {
     if (!c) return ZO2_EINVAL;
-    if (per_group) *per_group = (c->planned && c->phased) ? 1 : 0;
+    if (sweeps_per_block) *sweeps_per_block = c->planned ? c->sweeps : 0;
     if (scratch_elems) *scratch_elems = c->planned ? c->scratch_elems : 0;
     if (scratch_sets) *scratch_sets = c->planned ? (c->overlap_k1 ? 2 : 1) : 0;
     return ZO2_OK;
@@ -565,7 +581,7 @@ extern "C" zo2_status zo2_get_scratch_plan(const zo2_ctx* c, int32_t* per_group,
 extern "C" zo2_status zo2_set_scratch_plan(zo2_ctx* c, int32_t mode) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
-    if (mode != 0 && mode != 1) return fail(c, ZO2_EINVAL, "zo2_set_scratch_plan: mode %d (0 or 1)", mode);
+    if (mode != 0 && mode != 1 && mode != 2 && mode != 4) return fail(c, ZO2_EINVAL, "zo2_set_scratch_plan: %d sweeps per block (0, 1, 2 or 4)", mode);
     c->scratch_plan_forced = mode;
     c->need_plan = true;   // re-plan at the next step
     return ZO2_OK;
@@ -653,6 +669,7 @@ static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool
     K1Args a;
     k1_common(c, a, seed, eps, pend);
     a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->ns == 2 ? c->wm : nullptr; a.w_off0 = c->offs[t0]; a.nseg = t1 - t0;
+    a.reverse = perturb ? 1 : 0;      // end with the tensors the next projection reads (see k1_kernel)
     for (int k = t0; k < t1; ++k) {
         K1Seg& s = a.seg[k - t0];
         s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
@@ -712,18 +729,23 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     const bool f32 = dt == ZO2_F32;
     const int ns = c->ns;                 // 2: both perturbation streams (rows 0..T-1 and T..2T-1); 1: a single forward
     auto phase = [&](int p) -> zo2_status {
-        if (k1_enqueued) return ZO2_OK;
-        if (c->phased) return k1_block(c, l, bucket, kPhase[p], kPhase[p + 1], true, seed, eps);
-        if (p == 0) return k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, true, seed, eps);
-        return ZO2_OK;
+        if (k1_enqueued || c->pb[p + 1] == c->pb[p]) return ZO2_OK;
+        zo2_status s = k1_block(c, l, bucket, c->pb[p], c->pb[p + 1], true, seed, eps);
+        // the block's parameters are final after its last sweep: the offload may start (streamed mode)
+        if (s == ZO2_OK && c->pb[p + 1] == ZO2_BLOCK_TENSORS && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
+        return s;
     };
-    auto view = [&](int p) { return PhaseView{c, c->phased ? c->offs[kPhase[p]] : 0}; };
+    // the scratch holds the tensors of the last sweep issued at or before point p, the first of them at its start
+    auto view = [&](int p) {
+        int q = p;
+        while (c->pb[q + 1] == c->pb[q]) --q;       // sweep 0 is never empty
+        return PhaseView{c, c->offs[c->pb[q]]};
+    };
     GemmArgs ga;
 
     // ---- attention half: h += O(Attn(LN1(h)))
     if (!k1_enqueued) { zo2_status s = earlier_updates_block(c, l, bucket); if (s != ZO2_OK) return s; }
     { zo2_status s = phase(0); if (s != ZO2_OK) return s; }
-    if (!c->phased && k1_done && !k1_enqueued) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     PhaseView w = view(0);
     OPK(c, ZO2_KC_LN, layernorm(dt, c->h, w.P(0), w.P(1), w.M(0), w.M(1), c->x, ns * T, T, d, g.ln_eps, c->sc));
     memset(&ga, 0, sizeof(ga));
@@ -765,7 +787,6 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     }
     OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
     { zo2_status s = phase(3); if (s != ZO2_OK) return s; }
-    if (c->phased && k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));
     w = view(3);
     memset(&ga, 0, sizeof(ga));
     ga.M = T; ga.N = d; ga.K = f; ga.ldx = f; ga.ldw = f; ga.ldy = d; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;

@@ -14,6 +14,8 @@ from oracle import codec, opt_model, zo_step
 
 pytestmark = pytest.mark.gpu
 
+DEFAULT_SWEEPS = 1          # the planner's preferred organisation when the budget leaves the choice
+
 
 def _b():
     from paper_2503_12668_amd import binding
@@ -39,14 +41,14 @@ def test_per_group_scratch_fp32_steps_match_oracle(tied):
     P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
     oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), copy.deepcopy(P))
     ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
-    ctx.set_scratch_plan(True)
+    ctx.set_scratch_plan(4)
     lrs = [1e-4, 2e-4, 5e-5, 1e-4]
     for j in range(4):
         a, g = oz.step(tok, lab, 42 + j, 1e-3, lrs[j]), ctx.step(tok, lab, 42 + j, 1e-3, lrs[j])
         assert abs(float(g[0]) - float(a[0])) <= 1e-5 * abs(float(a[0])), j
         assert abs(float(g[1]) - float(a[1])) <= 1e-5 * abs(float(a[1])), j
     pl = ctx.plan()
-    assert pl["per_group_scratch"] and pl["resident"], pl
+    assert pl["sweeps_per_block"] == 4 and pl["resident"], pl
     assert abs(float(ctx.eval(tok, lab)) - float(oz.eval_loss(tok, lab))) <= 1e-5 * 6.0      # applies the pending update on the way
     a, g = oz.step(tok, lab, 50, 1e-3, 1e-4), ctx.step(tok, lab, 50, 1e-3, 1e-4)
     assert abs(float(g[0]) - float(a[0])) <= 1e-5 * abs(float(a[0]))
@@ -60,8 +62,8 @@ def test_per_group_scratch_fp32_steps_match_oracle(tied):
 @pytest.mark.parametrize("wire,compute,scale,sr", [("f32", "f32", 1.0, False), ("bf16", "bf16", 1.0, False),
                                                   ("fp8_e4m3", "bf16", 64.0, False), ("bf16", "bf16", 1.0, True)])
 def test_per_group_scratch_streamed_equals_whole_block_resident_bitwise(wire, compute, scale, sr):
-    """Three contexts on the same model: whole-block scratch resident (the reference), per-group scratch resident,
-    per-group scratch streamed through 3 slots.  Steps with a pending update, a round of several directions,
+    """Five contexts on the same model: whole-block scratch resident (the reference); per-half and per-group scratch,
+    each resident and streamed through 3 slots.  Steps with a pending update, a round of several directions,
     an evaluation in between and the final flush all give identical losses, g and stored parameters."""
     b = _b()
     cfg, P, tok, lab = _tiny(6)
@@ -69,13 +71,13 @@ def test_per_group_scratch_streamed_equals_whole_block_resident_bitwise(wire, co
     scales = np.full(nt, scale, np.float32) if scale != 1.0 else None
     wsz = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}[wire]
     runs = {}
-    for name in ("whole_resident", "group_resident", "group_streamed"):
+    want_sweeps = {"whole_resident": 1, "half_resident": 2, "group_resident": 4, "half_streamed": 2, "group_streamed": 4}
+    for name in want_sweeps:
         ctx = b.Zo2Context(cfg, P, wire=wire, compute=compute, arena_bytes=64 << 20, scales=scales)
         ctx.set_wire_rounding(sr)
-        if name != "whole_resident":
-            ctx.set_scratch_plan(True)
+        ctx.set_scratch_plan(want_sweeps[name])
         r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
-        if name == "group_streamed":
+        if name.endswith("streamed"):
             ctx.set_resident_budget(ctx.plan()["bytes_used"] - 3 * ctx.offs[16] * wsz)        # 3 slots for 6 blocks
         r.append(ctx.step(tok, lab, 6, 1e-3, 1e-3))
         r.append(ctx.step_extra(tok, lab, 7, 1e-3, 5e-4))                                   # a second direction of the round
@@ -83,14 +85,14 @@ def test_per_group_scratch_streamed_equals_whole_block_resident_bitwise(wire, co
         ev = ctx.eval(tok, lab)
         r.append(ctx.step(tok, lab, 9, 1e-3, 1e-3))
         pl = ctx.plan()
-        assert pl["per_group_scratch"] == (name != "whole_resident"), (name, pl)
-        assert pl["resident"] == (name != "group_streamed") and (pl["resident"] or pl["n_slots"] == 3), (name, pl)
+        assert pl["sweeps_per_block"] == want_sweeps[name], (name, pl)
+        assert pl["resident"] == (not name.endswith("streamed")) and (pl["resident"] or pl["n_slots"] == 3), (name, pl)
         if name != "whole_resident":
             assert pl["scratch_elems"] < ctx.offs[16]
         ctx.flush(); ctx.sync_to_host()
         runs[name] = ([tuple(map(float, x)) for x in r] + [float(ev)], ctx.parameters())
         ctx.close()
-    for name in ("group_resident", "group_streamed"):
+    for name in ("half_resident", "group_resident", "half_streamed", "group_streamed"):
         assert runs[name][0] == runs["whole_resident"][0], name
         for n in runs[name][1]:
             assert np.array_equal(runs[name][1][n], runs["whole_resident"][1][n]), (name, n)
@@ -109,7 +111,7 @@ def test_budget_too_small_for_whole_block_scratch_falls_back_to_per_group():
     ctx = b.Zo2Context(cfg, P, arena_bytes=64 << 20)
     r0, r1 = [ref.step(tok, lab, 5, 1e-3, 1e-3)], [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
     pl = ctx.plan()
-    assert pl["resident"] and not pl["per_group_scratch"]
+    assert pl["resident"] and pl["sweeps_per_block"] == DEFAULT_SWEEPS
     bucket = ctx.offs[16] * 4
     whole3 = pl["bytes_used"] - 2 * bucket                    # exactly 3 slots next to the whole-block scratch
     ctx.set_resident_budget(whole3 - 4096)                    # a little less: 3 slots only fit with the smaller scratch
@@ -117,7 +119,7 @@ def test_budget_too_small_for_whole_block_scratch_falls_back_to_per_group():
         r0.append(ref.step(tok, lab, 6 + j, 1e-3, 1e-3))
         r1.append(ctx.step(tok, lab, 6 + j, 1e-3, 1e-3))
     pl = ctx.plan()
-    assert pl["per_group_scratch"] and not pl["resident"] and pl["n_slots"] >= 3, pl
+    assert pl["sweeps_per_block"] > DEFAULT_SWEEPS and not pl["resident"] and pl["n_slots"] >= 3, pl
     assert [tuple(map(float, x)) for x in r0] == [tuple(map(float, x)) for x in r1]
     ref.flush(); ctx.flush(); ref.sync_to_host(); ctx.sync_to_host()
     Pr, Pc = ref.parameters(), ctx.parameters()
@@ -127,7 +129,7 @@ def test_budget_too_small_for_whole_block_scratch_falls_back_to_per_group():
     with pytest.raises(b.Zo2Error) as e:
         ctx.step(tok, lab, 99, 1e-3, 1e-3)
     assert e.value.status == 3
-    assert b.lib().zo2_set_scratch_plan(ctx.handle, 2) == 1          # ZO2_EINVAL: only modes 0 and 1 exist
+    assert b.lib().zo2_set_scratch_plan(ctx.handle, 3) == 1          # ZO2_EINVAL: 0, 1, 2 or 4
     ref.close(); ctx.close()
 
 
@@ -145,12 +147,12 @@ def test_per_group_scratch_at_13b_width_two_blocks_matches_oracle_losses():
     tok = si.make_tokens(cfg["vocab"], 2, 128, seed=2, dist="zipf")
     lab = si.next_token_labels(tok)
     ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=8 << 30)
-    ctx.set_scratch_plan(True)
+    ctx.set_scratch_plan(4)
     ctx.set_pending(True, 41, 2.5e-3)
     g = ctx.step(tok, lab, 42, 1e-3, 1e-7)
     pl = ctx.plan()
     print("gpu", g, pl, flush=True)
-    assert pl["per_group_scratch"] and pl["scratch_elems"] < ctx.offs[16], pl
+    assert pl["sweeps_per_block"] == 4 and pl["scratch_elems"] < ctx.offs[16], pl
     ctx.close()
     Po = {n: codec.round_to(a, "bf16") for n, a in P.items()}
     del P

@@ -21,10 +21,18 @@ MODEL, BATCH, SEQ = "opt-1.3b", 16, 256
 EPS, LR, SEED0 = 1e-3, 1e-7, 42
 PEAK_BF16_MFMA = 2500.0      # TFLOP/s, dense
 PEAK_HBM = 8000.0            # GB/s
-# HBM bytes per step from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE) over this same command, scaled by
-# a 1 GiB copy through the same counters (profiles/step_opt1.3b_bf16_resident_hbm_traffic.md); not measured live
-PMC_GEMM_BYTES_PER_STEP = 44.0e9      # over the 97 GEMM launches of a step
-PMC_K1_BYTES_PER_STEP = 11.02e9       # over the 27 K1 launches of a step
+# HBM bytes per launch come from two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE) over this same command, scaled by
+# a 1 GiB copy through the same counters: `paper_2503_12668_amd/measure.py traffic` turns the profiler's CSVs into this
+# file (with the commit it was measured at); it is read here, not measured live
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic_opt1.3b_bf16_resident.json")
+
+
+def measured_traffic():
+    try:
+        with open(TRAFFIC_JSON) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return None
 
 
 def gemm_flops_per_step(cfg, T):
@@ -72,12 +80,66 @@ def cpu_baseline(cfg_full, T_batch, T_seq):
                       f"{cfg_full['n_layers']} blocks ({total:.0f} s per step)"}
 
 
+def offload_leg(steps=3):
+    """The streamed mode on the driver's clock: OPT-13B shape (40 layers, d 5120, 40 heads, FFN 20480, bf16 weights in
+    pinned host memory), blocks streamed through exactly 3 slots on three HIP streams (Alg. 3).  Batch 8 x seq 512 is
+    the configuration as given (host-link bound on this machine); batch 32 x seq 512 is the point where a block's dual
+    forward outlasts its copy, measured streamed and fully resident on the same context."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2503_12668_amd import binding, run_config
+
+    cfg = si.opt_config("opt-13b")
+    L = cfg["n_layers"]
+    ctx = binding.Zo2Context(cfg, run_config.gpu_weight_source(), wire="bf16", compute="bf16", arena_bytes=36 << 30)
+    bucket = ctx.offs[16] * 2
+
+    def timed(batch, seq, slots):
+        tok = si.make_tokens(cfg["vocab"], batch, seq, seed=2, dist="zipf")
+        lab = si.next_token_labels(tok)
+        ctx.set_resident_budget(36 << 30)
+        ctx.step(tok, lab, 40, EPS, LR)                       # plans with everything resident: tells the bytes in use
+        if slots:
+            ctx.set_resident_budget(ctx.plan()["bytes_used"] - (L - slots) * bucket)
+        ctx.step(tok, lab, 41, EPS, LR)
+        plan = ctx.plan()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        up = down = 0
+        ms_u = ms_o = 0.0
+        for j in range(steps):
+            ctx.step(tok, lab, 100 + j, EPS, LR)
+            st = ctx.step_stats()
+            up += st["bytes_up"]; down += st["bytes_down"]; ms_u += st["ms_upload"]; ms_o += st["ms_offload"]
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        return {"batch": batch, "seq": seq, "resident": plan["resident"], "n_slots": plan["n_slots"], "ms_per_step": dt * 1e3,
+                "tokens_per_s": batch * seq / dt, "arena_bytes_used": plan["bytes_used"],
+                "link_up_GBps_over_step": up / steps / dt / 1e9, "link_down_GBps_over_step": down / steps / dt / 1e9,
+                "upload_stream_GBps": (up / 1e9) / (ms_u / 1e3) if ms_u else None,
+                "offload_stream_GBps": (down / 1e9) / (ms_o / 1e3) if ms_o else None}
+
+    res32 = timed(32, 512, None)
+    str32 = timed(32, 512, 3)
+    str8 = timed(8, 512, 3)
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    assert str8["n_slots"] == 3 and not str8["resident"] and str32["n_slots"] == 3 and res32["resident"], (str8, str32, res32)
+    return {"workload": f"opt-13b-shaped decoder ({L} layers, d {cfg['d_model']}, ffn {cfg['d_ffn']}), bf16 weights in pinned host "
+                        f"memory ({bucket / 1e6:.0f} MB per block), streamed through 3 block slots on upload / compute / offload streams",
+            "batch8_seq512_streamed": str8, "batch32_seq512_streamed": str32, "batch32_seq512_resident": res32,
+            "streamed_over_resident_at_32x512": str32["ms_per_step"] / res32["ms_per_step"], "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-offload", action="store_true", help="skip the streamed (offload-mode) leg")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -141,6 +203,7 @@ def main():
     tflops = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     k1_bytes = k1_bytes_per_step(cfg, 2, 2) * args.steps
     k1_gbs = k1_bytes / (k1_ms * 1e-3) / 1e9 if k1_ms > 0 else 0.0
+    traffic = measured_traffic()
     out = {
         "metric": "zo_step_tokens_per_s", "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
@@ -151,13 +214,14 @@ def main():
                    "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"]},
         "roofline": {"kernel": "gemm_mfma256_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
                      "achieved": tflops, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_MFMA,
-                     "traffic": (PMC_GEMM_BYTES_PER_STEP / (gemm_n / args.steps)) if (gemm_n and args.layers is None) else None,
+                     "traffic": traffic["kernels"]["gemm"]["bytes_per_launch"] if (traffic and args.layers is None) else None,
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, calibrated, offline)",
+                     "traffic_measured_at_commit": traffic["measured_at_commit"] if traffic else None,
                      "algorithmic_flops_per_launch": flops / gemm_n if gemm_n else None,
                      "launches_per_step": gemm_n / args.steps, "ms_per_step": gemm_ms / args.steps},
         "roofline_k1": {"kernel": "k1_kernel (fused regenerate + update + perturb)", "bound": "hbm", "achieved": k1_gbs,
                         "peak": PEAK_HBM, "unit": "GB/s", "frac": k1_gbs / PEAK_HBM,
-                        "traffic": (PMC_K1_BYTES_PER_STEP / (k1_n / args.steps)) if (k1_n and args.layers is None) else None,
+                        "traffic": traffic["kernels"]["k1"]["bytes_per_launch"] if (traffic and args.layers is None) else None,
                         "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated, offline)",
                         "algorithmic_bytes_per_launch": k1_bytes / k1_n if k1_n else None,
                         "launches_per_step": k1_n / args.steps, "ms_per_step": k1_ms / args.steps},
@@ -168,6 +232,8 @@ def main():
     ctx.close()
     del ctx
     torch.cuda.empty_cache()
+    if not args.no_offload and args.layers is None:
+        out["offload"] = offload_leg()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, BATCH, SEQ)
     print(json.dumps(out), flush=True)

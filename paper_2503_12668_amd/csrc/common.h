@@ -181,6 +181,25 @@ __device__ __forceinline__ void store_vec(T* p, const Vec<T, N>& v) {
     *reinterpret_cast<Vec<T, N>*>(p) = v;
 }
 
+// The same with the streaming ("non-temporal") cache policy: for data this kernel touches once and nobody reads soon.
+typedef uint32_t stream_u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t stream_u32x4_t __attribute__((ext_vector_type(4)));
+template <typename T, int N>
+__device__ __forceinline__ Vec<T, N> load_vec_stream(const T* p) {
+    static_assert(sizeof(T) * N == 16 || sizeof(T) * N == 8 || sizeof(T) * N == 32, "vector of 8, 16 or 32 bytes");
+    Vec<T, N> v;
+    if constexpr (sizeof(T) * N == 8) {
+        const stream_u32x2_t r = __builtin_nontemporal_load(reinterpret_cast<const stream_u32x2_t*>(p));
+        __builtin_memcpy(&v, &r, 8);
+    } else {
+        constexpr int Q = sizeof(T) * N / 16;
+        stream_u32x4_t r[Q];
+#pragma unroll
+        for (int i = 0; i < Q; ++i) r[i] = __builtin_nontemporal_load(reinterpret_cast<const stream_u32x4_t*>(p) + i);
+        __builtin_memcpy(&v, r, sizeof(v));
+    }
+    return v;
+}
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // dispatch a zo2_dtype to a type tag

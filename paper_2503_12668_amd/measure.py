@@ -1,0 +1,189 @@
+"""The one measurement entry of the package: times single library kernels through the C ABI and turns rocprofv3
+counter output into the traffic figures bench.py reports.
+
+    python3 paper_2503_12668_amd/measure.py gemm [--dtype bf16|f16|f32] [--n N] [--k K] [--const] [--cold]
+        zo2_op_gemm alone for M = 512 .. 16384: time per launch, TFLOP/s, TFLOP/s per active compute unit.
+        --const: operands filled with one value instead of random ones; --cold: every launch takes operands from a
+        ring of buffers larger than the memory-side cache (the situation inside a step) instead of the same ones.
+    python3 paper_2503_12668_amd/measure.py streams
+        what this machine delivers for plain HBM streams issued by the library's own kernels, nothing computed:
+        copy (zo2_op_convert float32 -> float32: read 1, write 1) and read 1 / write 2 (zo2_op_update_perturb with no
+        update and eps = 0: W+ = W- = theta), next to the fused update + perturb itself (read 1 / write 3 with two
+        Gaussians per element); GB/s of algorithmic bytes.
+    python3 paper_2503_12668_amd/measure.py copy
+        three 1 GiB copies and nothing else: the calibration run for rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
+    python3 paper_2503_12668_amd/measure.py traffic --fetch F.csv --write W.csv --cal-fetch CF.csv --cal-write CW.csv \\
+            --steps S --out profiles/hbm_traffic_opt1.3b_bf16_resident.json
+        reads the counter_collection CSVs of two `rocprofv3 --pmc` runs of bench.py (FETCH_SIZE, WRITE_SIZE) and of
+        the two calibration runs of `measure.py copy`, and writes HBM bytes per step and per launch for the GEMM and K1
+        kernels (last step of the run), with the scale factors and the commit they were measured at.
+"""
+import argparse
+import csv
+import json
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def _time_launches(fn, launches):
+    import torch
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(launches):
+        fn(i)
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches          # microseconds per launch
+
+
+def cmd_gemm(args):
+    import torch
+
+    from paper_2503_12668_amd import binding
+    td = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[args.dtype]
+    g = torch.Generator(device="cuda").manual_seed(3)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    tile = 128 if args.dtype == "f32" else 256
+    print(f"N {args.n}  K {args.k}  {args.dtype}  operands {'constant' if args.const else 'random N(0, 1)'}, "
+          f"{'cold (ring of buffers)' if args.cold else 'hot (same buffers every launch)'}  ({args.launches} launches each)")
+    print("| M | tiles | active CUs | us per launch | TFLOP/s | TFLOP/s per active CU |")
+    print("|---|---|---|---|---|---|")
+    for m in (512, 1024, 2048, 4096, 8192, 16384):
+        esz = 4 if args.dtype == "f32" else 2
+        nbuf = max(1, min(16, int(600e6 // ((m + args.n) * args.k * esz)) + 1)) if args.cold else 1
+        if args.const:
+            Xs = [torch.full((m, args.k), 0.5, dtype=td, device="cuda") for _ in range(nbuf)]
+            Ws = [torch.full((args.n, args.k), 0.25, dtype=td, device="cuda") for _ in range(nbuf)]
+        else:
+            Xs = [torch.randn(m, args.k, device="cuda", generator=g).to(td) for _ in range(nbuf)]
+            Ws = [torch.randn(args.n, args.k, device="cuda", generator=g).to(td) for _ in range(nbuf)]
+        Y = torch.empty(m, args.n, dtype=td, device="cuda")
+        for i in range(5):
+            binding.op_gemm(Xs[i % nbuf], Ws[i % nbuf], Y=Y)
+        us = _time_launches(lambda i: binding.op_gemm(Xs[i % nbuf], Ws[i % nbuf], Y=Y), args.launches)
+        tiles = ((m + tile - 1) // tile) * ((args.n + tile - 1) // tile)
+        active = min(tiles, cus * (2 if args.dtype == "f32" else 1))
+        tf = 2.0 * m * args.n * args.k / us / 1e6
+        print(f"| {m} | {tiles} | {min(active, cus)} | {us:.1f} | {tf:.1f} | {tf / min(active, cus):.2f} |", flush=True)
+
+
+def cmd_streams(args):
+    import torch
+
+    from paper_2503_12668_amd import binding
+    n = args.elements
+    g = torch.Generator(device="cuda").manual_seed(5)
+    print(f"{n} elements per launch, {args.launches} launches each, buffers rotated over {args.ring} sets")
+    print("| stream | bytes per element | us per launch | GB/s |")
+    print("|---|---|---|---|")
+    ring = args.ring
+    # copy: float32 -> float32
+    src = [torch.randn(n // 2, device="cuda", generator=g) for _ in range(ring)]
+    dst = [torch.empty(n // 2, device="cuda") for _ in range(ring)]
+    for i in range(3):
+        binding.op_convert(src[i % ring], dst[i % ring])
+    us = _time_launches(lambda i: binding.op_convert(src[i % ring], dst[i % ring]), args.launches)
+    print(f"| copy (convert float32 -> float32), read 1 / write 1 | 8 (over {n // 2} elements) | {us:.1f} | {n // 2 * 8 / us / 1e3:.0f} |", flush=True)
+    del src, dst
+    th = [(torch.randn(n, device="cuda", generator=g) * 0.02).bfloat16() for _ in range(ring)]
+    wp = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(ring)]
+    wm = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(ring)]
+    cases = [("read 1 / write 2, nothing computed (bf16: no update, eps = 0)", 6, dict(has_pending=False, eps=0.0)),
+             ("read 1 / write 2 with one Gaussian per element (no update, eps > 0)", 6, dict(has_pending=False, eps=1e-3)),
+             ("fused update + perturb: read 1 / write 3, two Gaussians per element", 8, dict(has_pending=True, eps=1e-3))]
+    for name, bpe, kw in cases:
+        f = lambda i: binding.op_update_perturb(th[i % ring], wp[i % ring], wm[i % ring], 7, 0, kw["has_pending"], 41, 1e-9, 42, kw["eps"])
+        for i in range(3):
+            f(i)
+        us = _time_launches(f, args.launches)
+        print(f"| {name} | {bpe} | {us:.1f} | {n * bpe / us / 1e3:.0f} |", flush=True)
+
+
+def cmd_copy(args):
+    import torch
+
+    from paper_2503_12668_amd import binding
+    n = (1 << 30) // 4
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        binding.op_convert(src, dst)
+    torch.cuda.synchronize()
+    print("copied 3 x 1 GiB")
+
+
+def _counter_rows(path, counter):
+    """(kernel name, counter value) per dispatch, in dispatch order, from a rocprofv3 counter_collection CSV."""
+    out = []
+    with open(path, newline="") as f:
+        for row in csv.DictReader(f):
+            if row.get("Counter_Name") == counter:
+                out.append((int(row["Dispatch_Id"]), row["Kernel_Name"], float(row["Counter_Value"])))
+    out.sort()
+    return [(k, v) for _, k, v in out]
+
+
+def cmd_traffic(args):
+    GIB_KIB = float(1 << 20)                       # the calibration copy moves 1 GiB each way; counters are in KiB
+    def cal(path, counter):
+        vals = [v for k, v in _counter_rows(path, counter) if "convert" in k]
+        return GIB_KIB / (sum(vals) / len(vals))
+    kf, kw = cal(args.cal_fetch, "FETCH_SIZE"), cal(args.cal_write, "WRITE_SIZE")
+    res = {}
+    for cls, pat in (("gemm", "gemm_mfma256_kernel"), ("k1", "k1_kernel")):
+        per = {}
+        for counter, path, k in (("FETCH_SIZE", args.fetch, kf), ("WRITE_SIZE", args.write, kw)):
+            vals = [v for name, v in _counter_rows(path, counter) if pat in name]
+            n = len(vals) // args.steps             # launches per step; the last step of the run is the steady state
+            last = vals[-n:]
+            per[counter] = (sum(last) * 1024.0 * k, n)
+        launches = per["FETCH_SIZE"][1]
+        total = per["FETCH_SIZE"][0] + per["WRITE_SIZE"][0]
+        res[cls] = {"kernel": pat, "launches_per_step": launches, "fetch_bytes_per_step": per["FETCH_SIZE"][0],
+                    "write_bytes_per_step": per["WRITE_SIZE"][0], "bytes_per_step": total, "bytes_per_launch": total / launches}
+    try:
+        commit = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], text=True).strip()
+    except Exception:
+        commit = None
+    out = {"workload": args.workload, "measured_at_commit": commit, "steps_in_run": args.steps,
+           "scale": {"FETCH_SIZE": kf, "WRITE_SIZE": kw,
+                     "note": "bytes moved by a 1 GiB copy / KiB the counter reported for it"},
+           "kernels": res}
+    with open(args.out, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out, indent=1))
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    g = sub.add_parser("gemm")
+    g.add_argument("--n", type=int, default=2048)
+    g.add_argument("--k", type=int, default=2048)
+    g.add_argument("--dtype", default="bf16", choices=["bf16", "f16", "f32"])
+    g.add_argument("--const", action="store_true")
+    g.add_argument("--cold", action="store_true")
+    g.add_argument("--launches", type=int, default=50)
+    s = sub.add_parser("streams")
+    s.add_argument("--elements", type=int, default=100 * 1024 * 1024)
+    s.add_argument("--ring", type=int, default=4)
+    s.add_argument("--launches", type=int, default=40)
+    sub.add_parser("copy")
+    t = sub.add_parser("traffic")
+    for k in ("fetch", "write", "cal-fetch", "cal-write", "out"):
+        t.add_argument("--" + k, required=True)
+    t.add_argument("--steps", type=int, required=True)
+    t.add_argument("--workload", default="opt-1.3b shape, bf16 resident, batch 16 x seq 256 (bench.py)")
+    args = ap.parse_args()
+    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "traffic": cmd_traffic}[args.cmd](args)
+
+
+if __name__ == "__main__":
+    main()

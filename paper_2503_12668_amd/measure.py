@@ -1,10 +1,11 @@
 """The one measurement entry of the package: times single library kernels through the C ABI and turns rocprofv3
 counter output into the traffic figures bench.py reports.
 
-    python3 paper_2503_12668_amd/measure.py gemm [--dtype bf16|f16|f32] [--n N] [--k K] [--const] [--cold]
+    python3 paper_2503_12668_amd/measure.py gemm [--dtype bf16|f16|f32] [--n N] [--k K] [--const] [--cold] [--library]
         zo2_op_gemm alone for M = 512 .. 16384: time per launch, TFLOP/s, TFLOP/s per active compute unit.
         --const: operands filled with one value instead of random ones; --cold: every launch takes operands from a
-        ring of buffers larger than the memory-side cache (the situation inside a step) instead of the same ones.
+        ring of buffers larger than the memory-side cache (the situation inside a step) instead of the same ones;
+        --library: a last column with torch.matmul (the vendor BLAS) on the same buffers, as a yardstick.
     python3 paper_2503_12668_amd/measure.py streams
         what this machine delivers for plain HBM streams issued by the library's own kernels, nothing computed:
         copy (zo2_op_convert float32 -> float32: read 1, write 1) and read 1 / write 2 (zo2_op_update_perturb with no
@@ -52,8 +53,8 @@ def cmd_gemm(args):
     tile = 128 if args.dtype == "f32" else 256
     print(f"N {args.n}  K {args.k}  {args.dtype}  operands {'constant' if args.const else 'random N(0, 1)'}, "
           f"{'cold (ring of buffers)' if args.cold else 'hot (same buffers every launch)'}  ({args.launches} launches each)")
-    print("| M | tiles | active CUs | us per launch | TFLOP/s | TFLOP/s per active CU |")
-    print("|---|---|---|---|---|---|")
+    print("| M | tiles | active CUs | us per launch | TFLOP/s | TFLOP/s per active CU |" + (" torch.matmul TFLOP/s |" if args.library else ""))
+    print("|---|---|---|---|---|---|" + ("---|" if args.library else ""))
     for m in (512, 1024, 2048, 4096, 8192, 16384):
         esz = 4 if args.dtype == "f32" else 2
         nbuf = max(1, min(16, int(600e6 // ((m + args.n) * args.k * esz)) + 1)) if args.cold else 1
@@ -70,7 +71,14 @@ def cmd_gemm(args):
         tiles = ((m + tile - 1) // tile) * ((args.n + tile - 1) // tile)
         active = min(tiles, cus * (2 if args.dtype == "f32" else 1))
         tf = 2.0 * m * args.n * args.k / us / 1e6
-        print(f"| {m} | {tiles} | {min(active, cus)} | {us:.1f} | {tf:.1f} | {tf / min(active, cus):.2f} |", flush=True)
+        extra = ""
+        if args.library:
+            WT = [w.t() for w in Ws]
+            for i in range(5):
+                torch.matmul(Xs[i % nbuf], WT[i % nbuf], out=Y)
+            us_l = _time_launches(lambda i: torch.matmul(Xs[i % nbuf], WT[i % nbuf], out=Y), args.launches)
+            extra = f" {2.0 * m * args.n * args.k / us_l / 1e6:.1f} |"
+        print(f"| {m} | {tiles} | {min(active, cus)} | {us:.1f} | {tf:.1f} | {tf / min(active, cus):.2f} |" + extra, flush=True)
 
 
 def cmd_streams(args):
@@ -140,7 +148,7 @@ def cmd_traffic(args):
         per = {}
         for counter, path, k in (("FETCH_SIZE", args.fetch, kf), ("WRITE_SIZE", args.write, kw)):
             vals = [v for name, v in _counter_rows(path, counter) if pat in name]
-            n = len(vals) // args.steps             # launches per step; the last step of the run is the steady state
+            n = int(round(len(vals) / args.steps))   # launches per step (the first step, with nothing pending, has one fewer K1 launch); the last step of the run is the steady state
             last = vals[-n:]
             per[counter] = (sum(last) * 1024.0 * k, n)
         launches = per["FETCH_SIZE"][1]
@@ -170,6 +178,7 @@ def main():
     g.add_argument("--dtype", default="bf16", choices=["bf16", "f16", "f32"])
     g.add_argument("--const", action="store_true")
     g.add_argument("--cold", action="store_true")
+    g.add_argument("--library", action="store_true")
     g.add_argument("--launches", type=int, default=50)
     s = sub.add_parser("streams")
     s.add_argument("--elements", type=int, default=100 * 1024 * 1024)

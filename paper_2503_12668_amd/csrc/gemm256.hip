@@ -6,9 +6,12 @@
 // sustains a higher clock with the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster
 // in an MFMA-only loop.)
 //
-// Data path: global memory -> LDS with the direct-to-LDS loads of gfx950 (16 bytes per
-// lane, no staging through vector registers), two LDS stages, 128-bit LDS reads
-// into MFMA operand registers.  The tile is stored as rows of 8 chunks of 16 bytes with the
+// Data path: three k-slabs deep.  Two slabs live in two LDS stages; the third is on its way from global memory in
+// vector registers (buffer loads issued two k-steps before the registers are stored to the stage that has just been
+// retired), so that a load has two full k-steps - about 2000 cycles - to come back, enough for a trip to HBM: inside a
+// step the operands are cold (the weights were just rewritten and exceed the memory-side cache).  The first two
+// slabs of a tile travel by the direct-to-LDS loads of gfx950 (16 bytes per lane, no staging through vector registers),
+// the first of them under the previous tile's epilogue.  128-bit LDS reads into MFMA operand registers.  The tile is stored as rows of 8 chunks of 16 bytes with the
 // chunk index XOR-swizzled by (row & 7); because a direct-to-LDS load writes lane i's 16 bytes
 // at LDS offset 16 i, the swizzle is applied on the global side: lane i fetches the chunk that
 // belongs at position i.
@@ -88,6 +91,16 @@ __device__ __forceinline__ void load_to_lds_at_m0_masked(const void* sbase, uint
     asm volatile("s_mov_b64 exec, %2\n\tglobal_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1" : : "v"(voff), "s"(sbase), "s"(lanes) : "memory");
 }
 
+// Buffer load of 16 bytes per lane: resource (wave-uniform, base = first row of the tile's operand panel) + per-lane 32-bit
+// byte offset + wave-uniform byte offset.  An ordinary load as far as the compiler is concerned: it keeps track of the
+// registers in flight and places the waits itself.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t panel_rsrc(const void* base, size_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes > 0x7fffffffull ? 0x7fffffffull : bytes), 0x00020000);
+}
+__device__ __forceinline__ u32x4_t panel_load(__amdgpu_buffer_rsrc_t rs, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (int)soff, 0);
+}
+
 // The lane index, derived anew from the execution mask (all 64 lanes active) through an operand the compiler cannot
 // see through: values computed from it cannot be hoisted out of the loop that contains the call.
 __device__ __forceinline__ int fresh_lane_id() {
@@ -163,6 +176,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     uint32_t pa[MI], pb[8];             // per-lane byte offsets from the tile's first row
     const T* base_x;                    // wave-uniform: first row of the tile in X / W
     const T* base_w;
+    __amdgpu_buffer_rsrc_t rs_x, rs_w;  // the same two panels as buffer resources, for the register-staged loads
+    // where this lane's 16 bytes of load t go in a stage: the layout the direct-to-LDS loads produce (lane i at 16 i)
+    char* wr_a[2];
+    char* wr_b[2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        wr_a[st] = smem + st * kStageBytes + wave * (MI * 1024) + lane * 16;
+        wr_b[st] = smem + st * kStageBytes + kBM * 128 + wave * 8192 + lane * 16;
+    }
     auto plan_loads = [&](const TileCoord& tc) {
         const GemmProblem& pp = a.p[tc.prob];
         // (a freshly derived lane index: this arithmetic is redone per tile instead of being kept in registers, or
@@ -172,6 +194,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         base_x = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.X) + (size_t)tc.m0 * a.ldx));
         base_w = reinterpret_cast<const T*>(uniform_ptr(reinterpret_cast<const T*>(pp.W) + (size_t)tc.n0 * a.ldw));
         const int mrem = a.M - 1 - tc.m0, nrem = a.N - 1 - tc.n0;
+        rs_x = panel_rsrc(base_x, ((size_t)mrem * a.ldx + a.K) * sizeof(T));        // up to the end of the matrix's last row
+        rs_w = panel_rsrc(base_w, ((size_t)nrem * a.ldw + a.K) * sizeof(T));
         const int lkc = (lane & 7) ^ swz(lrow);             // rows of one instruction differ in their low three bits only
 #pragma unroll
         for (int t = 0; t < MI; ++t) pa[t] = (uint32_t)((size_t)min(wave * (8 * MI) + t * 8 + lrow, mrem) * a.ldx + lkc * 8) * (uint32_t)sizeof(T);
@@ -207,39 +231,40 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                 mfma16_clear(acc[i][j], zero_operand);
 
         uint4 fa[MI], fb[2][8];      // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
+        u32x4_t sx[MI], sw[8];       // the slab in flight: this lane's 16 bytes of each of the wavefront's MI + 8 loads
         // One "group" = the eight MFMAs of X row-block i at k-step buffer `buf`, with the two LDS reads
         // that fetch row-block i of both operands for the next k-step into buffer `nbuf` and optionally
         // two direct-to-LDS loads of a later k-slab dealt out between them.  With one wavefront per SIMD
         // every instruction takes an issue slot of this wavefront and only about three fit under one
         // 16-cycle MFMA: scheduling barriers pin one piece of memory work behind each of the first MFMAs.
-        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool do_dma, uint64_t dma_lanes, int dma_stage, int dma_k0) {
-            // do_dma: direct-to-LDS loads of a later slab: rows 8 i .. 8 i + 7 of this wavefront's share of X, and WPG
-            // times as many of its 64 rows of W
-            const uint32_t so = dma_stage * kStageBytes;
+        // stage_out: this group also moves its share of the register-staged slab on: row-block i of X and WPG row-blocks of W
+        // are stored to stage `st` (retired by the barrier just passed) and their registers are reloaded with the same
+        // pieces of the slab at byte offset `soff` of the panels.
+        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff) {
             Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) m0_set(ld_a + so + i * 1024);
+            if (stage_out) *reinterpret_cast<u32x4_t*>(wr_a[st] + i * 1024) = sx[i];
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][1], fa[i], acc[i][1]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) load_to_lds_at_m0_masked(base_x + dma_k0, pa[i], dma_lanes);
+            if (stage_out) sx[i] = panel_load(rs_x, pa[i], soff);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][2], fa[i], acc[i][2]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) m0_set(ld_b + so + (i * WPG) * 1024);
+            if (stage_out) *reinterpret_cast<u32x4_t*>(wr_b[st] + (i * WPG) * 1024) = sw[i * WPG];
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][3], fa[i], acc[i][3]);
             __builtin_amdgcn_sched_barrier(0);
-            if (do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i * WPG], dma_lanes);
+            if (stage_out) sw[i * WPG] = panel_load(rs_w, pb[i * WPG], soff);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][4], fa[i], acc[i][4]);
             __builtin_amdgcn_sched_barrier(0);
             fb[nbuf][i * WPG] = *reinterpret_cast<const uint4*>(sb + (i * WPG) * 2048);
-            if (WPG == 2 && do_dma) m0_set(ld_b + so + (i * WPG + 1) * 1024);
+            if (WPG == 2 && stage_out) *reinterpret_cast<u32x4_t*>(wr_b[st] + (i * WPG + 1) * 1024) = sw[i * WPG + WPG - 1];
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][5], fa[i], acc[i][5]);
             __builtin_amdgcn_sched_barrier(0);
-            if (WPG == 2 && do_dma) load_to_lds_at_m0_masked(base_w + dma_k0, pb[i * WPG + WPG - 1], dma_lanes);
+            if (WPG == 2 && stage_out) sw[i * WPG + WPG - 1] = panel_load(rs_w, pb[i * WPG + WPG - 1], soff);
             __builtin_amdgcn_sched_barrier(0);
             Mfma16<T>::run(fb[buf][6], fa[i], acc[i][6]);
             __builtin_amdgcn_sched_barrier(0);
@@ -269,35 +294,52 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             }
         }
         // A slab is two k-steps of 32.  Under k-step 0 the fragments of k-step 1 are read; then one barrier
-        // (publishes slab kt+1: every wavefront waited for its own loads; retires stage cur: every wavefront
-        // has its last fragments in registers); under k-step 1 the first fragments of slab kt+1 are read and
-        // all direct-to-LDS loads of slab kt+2 are issued into the retired stage, so that they have k-step 0
-        // of the next slab to land.  Every slab runs the same instructions: where slab kt+2 does not exist the
-        // loads run with an empty execution mask (more_slabs == 0), and where slab kt+1 does not exist
-        // the fragment reads fetch bytes nobody uses.  A separate copy of the loop body for the last slabs
-        // would invite the compiler to give the accumulators another register assignment there and to move
-        // them between MFMAs that it does not know to be MFMAs.
-        auto slab_iter = [&](int kt, auto stage_c, uint64_t more_slabs) {
+        // (publishes slab kt+1: every wavefront waited for its own stores to it; retires stage cur: every wavefront
+        // has its last fragments in registers); under k-step 1 the first fragments of slab kt+1 are read, the registers
+        // holding slab kt+2 - loaded during k-step 1 of the previous slab - are stored to the retired stage and reloaded
+        // with slab kt+3.  Every slab runs the same instructions: where slab kt+3 does not exist the loads fetch the
+        // panel's last slab again, and where slab kt+2 does not exist that is also what gets stored (nobody reads it);
+        // the fragment reads of a slab kt+1 that does not exist fetch bytes nobody uses.  A separate copy of the loop
+        // body for the last slabs would invite the compiler to give the accumulators another register assignment there
+        // and to move them between MFMAs that it does not know to be MFMAs.
+        // The wait in the middle of a slab leaves the MI + 8 register loads in flight; what it does wait for, besides
+        // this wavefront's LDS traffic, is older: in a tile's first slab, the direct-to-LDS loads of slab 1.
+        const uint32_t last_slab = (uint32_t)(a.K - kBK) * (uint32_t)sizeof(T);
+        auto slab_iter = [&](int kt, auto stage_c) {
             constexpr int cur = decltype(stage_c)::value;          // kt & 1
+            const uint32_t soff = min((uint32_t)((kt + 3) * kBK) * (uint32_t)sizeof(T), last_slab);
 #pragma unroll
-            for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0ull, 0, 0);
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);
+            if constexpr (MI == 8) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, more_slabs, cur, (kt + 2) * kBK);
+            for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, cur, soff);
         };
         // slab 1 of a later tile: stage 1 held the previous tile's epilogue staging and is free once the barrier above is passed
         if (!slab1_in_flight) issue_slab(1, kBK);
         slab1_in_flight = false;
+        __builtin_amdgcn_sched_barrier(0);
+        {   // slab 2 (or, if the tile has only two, slab 1 again) starts its trip through the registers
+            const uint32_t soff = min((uint32_t)(2 * kBK) * (uint32_t)sizeof(T), last_slab);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (t < MI) sx[t] = panel_load(rs_x, pa[t], soff);
+                sw[t] = panel_load(rs_w, pb[t], soff);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
         // nk is even (K % 128 == 0): slabs alternate between the two stages, two per trip
         using St0 = std::integral_constant<int, 0>;
         using St1 = std::integral_constant<int, 1>;
         for (int kt = 0; kt < nk; kt += 2) {
-            const uint32_t m32 = __builtin_amdgcn_readfirstlane(kt + 2 < nk ? 0xffffffffu : 0u);
-            const uint64_t more = ((uint64_t)m32 << 32) | m32;
-            slab_iter(kt, St0{}, more);
-            slab_iter(kt + 1, St1{}, more);
+            slab_iter(kt, St0{});
+            slab_iter(kt + 1, St1{});
         }
+        // the last k-step stored a slab nobody reads into stage 1, which the epilogue's output staging overlaps: every
+        // wavefront's stores must have landed before any wavefront starts its epilogue
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
         // the last MFMAs' results must have left the pipeline before the epilogue reads them (see Mfma16)
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 

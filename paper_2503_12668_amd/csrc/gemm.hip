@@ -16,15 +16,19 @@ namespace zo2 {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+// (native vector types for everything staged in registers: arrays of HIP's struct-based float4 / uint4 are not always
+// taken apart into registers by the compiler and then live in scratch memory)
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u_t __attribute__((ext_vector_type(4)));
 
 template <typename T> struct Mfma;
 template <> struct Mfma<bf16_t> {
-    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
+    static __device__ __forceinline__ f32x16_t run(v4u_t a, v4u_t b, f32x16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 };
 template <> struct Mfma<f16_t> {
-    static __device__ __forceinline__ f32x16_t run(uint4 a, uint4 b, f32x16_t c) {
+    static __device__ __forceinline__ f32x16_t run(v4u_t a, v4u_t b, f32x16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
     }
 };
@@ -39,7 +43,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
     constexpr int BK = 64, KC = BK / 8;            // 8 chunks of 8 elements per row
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int CA = BM * KC / 256, CB = BN * KC / 256;   // chunks each thread stages per tile
-    __shared__ uint4 lds[2][(BM + BN) * KC];
+    __shared__ v4u_t lds[2][(BM + BN) * KC];
 
     const GemmProblem p = a.p[blockIdx.z];
     const int tiles_n = (a.N + BN - 1) / BN;
@@ -78,13 +82,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[CA], rb[CB];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    v4u_t ra[CA], rb[CB];
+    const v4u_t zero4 = v4u_t{0u, 0u, 0u, 0u};
     auto load_tile = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < CA; ++i) ra[i] = (k0 + kca[i] < a.K) ? *reinterpret_cast<const uint4*>(ga[i] + k0) : zero4;
+        for (int i = 0; i < CA; ++i) ra[i] = (k0 + kca[i] < a.K) ? *reinterpret_cast<const v4u_t*>(ga[i] + k0) : zero4;
 #pragma unroll
-        for (int i = 0; i < CB; ++i) rb[i] = (k0 + kcb[i] < a.K) ? *reinterpret_cast<const uint4*>(gb[i] + k0) : zero4;
+        for (int i = 0; i < CB; ++i) rb[i] = (k0 + kcb[i] < a.K) ? *reinterpret_cast<const v4u_t*>(gb[i] + k0) : zero4;
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int kc = ks * 2 + kh;
-            uint4 fa[TM], fb[TN];
+            v4u_t fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * WM + i * 32 + r;
@@ -160,11 +164,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const GemmArgs a) {
 // four MFMAs.  The weight tile is the instruction's first operand, which leaves a lane with one output row m and runs
 // of four consecutive columns n: 16-byte stores.
 // ---------------------------------------------------------------------------------------
+template <bool KTAIL>      // KTAIL: K is not a multiple of 32, the last slab is zero-filled past the end of the rows
 __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a) {
     constexpr int BM = 128, BN = 128, BK = 32, KC = BK / 4;       // 8 chunks of 4 floats per row
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int CA = BM * KC / 256, CB = BN * KC / 256;         // chunks each thread stages per tile
-    __shared__ float4 lds[2][(BM + BN) * KC];
+    __shared__ v4f_t lds[2][(BM + BN) * KC];
 
     const GemmProblem p = a.p[blockIdx.z];
     const int tiles_n = (a.N + BN - 1) / BN;
@@ -200,13 +205,13 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    float4 ra[CA], rb[CB];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    v4f_t ra[CA], rb[CB];
+    const v4f_t zero4 = v4f_t{0.f, 0.f, 0.f, 0.f};
     auto load_tile = [&](int k0) {        // K is a multiple of 4: a chunk is inside the row or entirely past its end
 #pragma unroll
-        for (int i = 0; i < CA; ++i) ra[i] = (k0 + kca[i] < a.K) ? *reinterpret_cast<const float4*>(ga[i] + k0) : zero4;
+        for (int i = 0; i < CA; ++i) ra[i] = (!KTAIL || k0 + kca[i] < a.K) ? *reinterpret_cast<const v4f_t*>(ga[i] + k0) : zero4;
 #pragma unroll
-        for (int i = 0; i < CB; ++i) rb[i] = (k0 + kcb[i] < a.K) ? *reinterpret_cast<const float4*>(gb[i] + k0) : zero4;
+        for (int i = 0; i < CB; ++i) rb[i] = (!KTAIL || k0 + kcb[i] < a.K) ? *reinterpret_cast<const v4f_t*>(gb[i] + k0) : zero4;
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
@@ -225,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
 #pragma unroll
         for (int g = 0; g < BK / 8; ++g) {
             const int kc = 2 * g + kh;
-            float4 fx[TM], fw[TN];
+            v4f_t fx[TM], fw[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * WM + i * 32 + r;
@@ -271,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * q + e];
                 if (vec_ok) {                      // N % 4 == 0: the run of four is inside the row or entirely past its end
-                    const float4 b4 = bias ? *reinterpret_cast<const float4*>(bias + n) : zero4;
+                    const v4f_t b4 = bias ? *reinterpret_cast<const v4f_t*>(bias + n) : zero4;
                     const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -279,10 +284,10 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
                         if (a.relu) y[e] = fmaxf(y[e], 0.f);
                     }
                     if (p.residual) {
-                        const float4 r4 = *reinterpret_cast<const float4*>(p.residual + o);
+                        const v4f_t r4 = *reinterpret_cast<const v4f_t*>(p.residual + o);
                         y[0] += r4.x; y[1] += r4.y; y[2] += r4.z; y[3] += r4.w;
                     }
-                    *reinterpret_cast<float4*>(Y + o) = make_float4(y[0], y[1], y[2], y[3]);
+                    *reinterpret_cast<v4f_t*>(Y + o) = v4f_t{y[0], y[1], y[2], y[3]};
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -328,7 +333,8 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
     if (dtype == ZO2_F32) {
         ZO2_OP_CHECK(a.out_f32, ZO2_EINVAL, "gemm: the float32 kernel writes float32 output");
         const unsigned tiles = (unsigned)(((a.M + 127) / 128) * ((a.N + 127) / 128));
-        hipLaunchKernelGGL(gemm_f32_mfma_kernel, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
+        if (a.K % 32 == 0) hipLaunchKernelGGL(gemm_f32_mfma_kernel<false>, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(gemm_f32_mfma_kernel<true>, dim3(tiles, 1, a.nprob), dim3(256), 0, st, a);
         ZO2_HIP_LAUNCH_CHECK();
         return ZO2_OK;
     }

@@ -50,17 +50,13 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
         }
     }
     if (PERTURB) {
-        if (eps == 0.f) {                      // evaluation: W+ = theta' in the compute format, no draw needed
+        // (with eps = 0, the single forward of an evaluation, fma(0, z, theta') is theta' itself: no separate path)
+        float z[kPerLane];
+        gaussian8(a.k_cur, tensor_id, q, z);
 #pragma unroll
-            for (int j = 0; j < kPerLane; ++j) p.v[j] = m.v[j] = Fmt<C>::store(th[j]);
-        } else {
-            float z[kPerLane];
-            gaussian8(a.k_cur, tensor_id, q, z);
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
-                m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
-            }
+        for (int j = 0; j < kPerLane; ++j) {
+            p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
+            m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
         }
     }
 }

@@ -8,9 +8,9 @@ counter output into the traffic figures bench.py reports.
         --library: a last column with torch.matmul (the vendor BLAS) on the same buffers, as a yardstick.
     python3 paper_2503_12668_amd/measure.py streams
         what this machine delivers for plain HBM streams issued by the library's own kernels, nothing computed:
-        copy (zo2_op_convert float32 -> float32: read 1, write 1) and read 1 / write 2 (zo2_op_update_perturb with no
-        update and eps = 0: W+ = W- = theta), next to the fused update + perturb itself (read 1 / write 3 with two
-        Gaussians per element); GB/s of algorithmic bytes.
+        copy (zo2_op_convert float32 -> float32: read 1, write 1), next to the perturbation alone (zo2_op_update_perturb
+        with no update: read 1 / write 2, one Gaussian per element) and the fused update + perturb (read 1 / write 3,
+        two Gaussians per element); GB/s of algorithmic bytes.
     python3 paper_2503_12668_amd/measure.py copy
         three 1 GiB copies and nothing else: the calibration run for rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
     python3 paper_2503_12668_amd/measure.py traffic --fetch F.csv --write W.csv --cal-fetch CF.csv --cal-write CW.csv \\
@@ -102,8 +102,7 @@ def cmd_streams(args):
     th = [(torch.randn(n, device="cuda", generator=g) * 0.02).bfloat16() for _ in range(ring)]
     wp = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(ring)]
     wm = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(ring)]
-    cases = [("read 1 / write 2, nothing computed (bf16: no update, eps = 0)", 6, dict(has_pending=False, eps=0.0)),
-             ("read 1 / write 2 with one Gaussian per element (no update, eps > 0)", 6, dict(has_pending=False, eps=1e-3)),
+    cases = [("perturb only: read 1 / write 2, one Gaussian per element (bf16)", 6, dict(has_pending=False, eps=1e-3)),
              ("fused update + perturb: read 1 / write 3, two Gaussians per element", 8, dict(has_pending=True, eps=1e-3))]
     for name, bpe, kw in cases:
         f = lambda i: binding.op_update_perturb(th[i % ring], wp[i % ring], wm[i % ring], 7, 0, kw["has_pending"], 41, 1e-9, 42, kw["eps"])

@@ -80,7 +80,60 @@ def cpu_baseline(cfg_full, T_batch, T_seq):
                       f"{cfg_full['n_layers']} blocks ({total:.0f} s per step)"}
 
 
-def offload_leg(steps=3):
+def _release(ctx):
+    """Close a context and give its device arena and its pinned host buffers back (torch caches both)."""
+    import gc
+
+    import torch
+    ctx.close()
+    for name in ("h_buckets", "h_tok", "h_pos", "h_flnw", "h_flnb", "h_lm", "arena"):
+        setattr(ctx, name, None)
+    gc.collect()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
+def budget_leg(model, layers, batch, seq, wire, compute, steps):
+    """A streamed configuration under a fixed HBM budget of 18e9 bytes (everything the library touches: embeddings,
+    block slots, W+ / W- scratch, activations): weights held on the host in the 8-bit transfer format (Sec. 5.5) and
+    unpacked to bf16 on the device.  `layers`: None = the model's own depth; a number = that many blocks of the true
+    shape (what fits the host memory this process may pin), reported per block."""
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2503_12668_amd import binding, run_config
+
+    cfg = si.opt_config(model, n_layers=layers)
+    L = cfg["n_layers"]
+    scales = np.full(4 + 16 * L, 64.0, dtype=np.float32)
+    ctx = binding.Zo2Context(cfg, run_config.gpu_weight_source(), wire=wire, compute=compute, arena_bytes=int(18e9), scales=scales)
+    tok = si.make_tokens(cfg["vocab"], batch, seq, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    ctx.step(tok, lab, 40, EPS, LR)
+    ctx.step(tok, lab, 41, EPS, LR)
+    plan = ctx.plan()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    up = 0
+    for j in range(steps):
+        ctx.step(tok, lab, 100 + j, EPS, LR)
+        up += ctx.step_stats()["bytes_up"]
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    full = si.opt_config(model)["n_layers"]
+    out = {"model": model, "layers_run": L, "layers_of_model": full, "batch": batch, "seq": seq, "wire": wire, "compute": compute,
+           "budget_bytes": int(18e9), "arena_bytes_used": plan["bytes_used"], "resident": plan["resident"], "n_slots": plan["n_slots"],
+           "sweeps_per_block": plan["sweeps_per_block"], "block_MB": ctx.offs[16] * binding.lib().zo2_dtype_size(ctx.wire_id) / 1e6,
+           "ms_per_step": dt * 1e3, "ms_per_block": dt * 1e3 / L, "link_GBps_each_way_over_step": up / steps / dt / 1e9}
+    if L == full:
+        out["tokens_per_s"] = batch * seq / dt
+    _release(ctx)
+    return out
+
+
+def offload_leg(steps=3, budget_legs=True):
     """The streamed mode on the driver's clock: OPT-13B shape (40 layers, d 5120, 40 heads, FFN 20480, bf16 weights in
     pinned host memory), blocks streamed through exactly 3 slots on three HIP streams (Alg. 3).  Batch 8 x seq 512 is
     the configuration as given (host-link bound on this machine); batch 32 x seq 512 is the point where a block's dual
@@ -123,11 +176,13 @@ def offload_leg(steps=3):
     res32 = timed(32, 512, None)
     str32 = timed(32, 512, 3)
     str8 = timed(8, 512, 3)
-    ctx.close()
-    del ctx
-    torch.cuda.empty_cache()
+    _release(ctx)
     assert str8["n_slots"] == 3 and not str8["resident"] and str32["n_slots"] == 3 and res32["resident"], (str8, str32, res32)
-    return {"workload": f"opt-13b-shaped decoder ({L} layers, d {cfg['d_model']}, ffn {cfg['d_ffn']}), bf16 weights in pinned host "
+    big = {}
+    if budget_legs:
+        big["opt30b_fp8_wire_18e9"] = budget_leg("opt-30b", None, 4, 1024, "fp8_e4m3", "bf16", steps)
+        big["opt175b_fp8_wire_18e9"] = budget_leg("opt-175b", 12, 1, 2048, "fp8_e4m3", "bf16", steps)
+    return {**big, "workload": f"opt-13b-shaped decoder ({L} layers, d {cfg['d_model']}, ffn {cfg['d_ffn']}), bf16 weights in pinned host "
                         f"memory ({bucket / 1e6:.0f} MB per block), streamed through 3 block slots on upload / compute / offload streams",
             "batch8_seq512_streamed": str8, "batch32_seq512_streamed": str32, "batch32_seq512_resident": res32,
             "streamed_over_resident_at_32x512": str32["ms_per_step"] / res32["ms_per_step"], "steps": steps}

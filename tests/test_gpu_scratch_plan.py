@@ -163,3 +163,54 @@ def test_per_group_scratch_at_13b_width_two_blocks_matches_oracle_losses():
     print("oracle", a, flush=True)
     assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
     assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
+
+
+@pytest.mark.timeout(900)
+def test_fp8_wire_at_30b_width_one_block_matches_oracle():
+    """OPT-30B width (d 7168, 56 heads of 128, FFN 28672: 617 M parameters per block) with the parameters held in
+    fp8-E4M3 at scale 64 (Sec. 5.5) and bf16 compute, one block, batch 1 x 256, the planner's own scratch choice:
+    one step in steady state (an update of visible size is pending) against the oracle's Alg. 2.  Losses to the
+    bf16 bar; the block's stored fp8 codes after the update against the oracle's, on windows of every tensor.  The
+    vocabulary is cut to 4096 entries to keep the oracle's share within minutes."""
+    b = _b()
+    from oracle import philox
+    from oracle.zo_step import _fma32, _store
+    cfg = si.opt_config("opt-30b", n_layers=1)
+    cfg["vocab"] = 4096
+    P = si.make_weights(cfg, seed=1)
+    tok = si.make_tokens(cfg["vocab"], 1, 256, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    shape = opt_model.OptShape(**cfg)
+    names = [n for n, _, _ in opt_model.tensor_table(shape)]
+    scale, c_prev = 64.0, 4e-3
+    ctx = b.Zo2Context(cfg, P, wire="fp8_e4m3", compute="bf16", arena_bytes=8 << 30, scales=np.full(len(names), scale, np.float32))
+    ctx.set_pending(True, 41, c_prev)
+    g = ctx.step(tok, lab, 42, 1e-3, 1e-7)
+    print("gpu", g, ctx.plan(), flush=True)
+    ctx.sync_to_host()
+    Pg = ctx.parameters()
+    ctx.close()
+    Po = {n: _store(P[n], "fp8_e4m3", scale) for n in names}
+    del P
+    print("oracle: parameters packed", flush=True)
+    # the update alone, on windows of every block tensor: same codes wherever dz cannot move the decision
+    ids = {n: tid for n, tid, _ in opt_model.tensor_table(shape)}
+    tot = same = 0
+    for n in names:
+        if not n.startswith("blocks."):
+            continue
+        flat, got = Po[n].reshape(-1), Pg[n].reshape(-1)
+        for e0 in sorted({0, max(0, (flat.size - 4096) // 8 * 8)}):
+            w = min(4096, flat.size - e0)
+            want = _store(_fma32(np.float32(-c_prev), philox.gaussian(41, ids[n], e0, w), flat[e0:e0 + w]), "fp8_e4m3", scale)
+            d = np.abs(got[e0:e0 + w] - want)
+            tot += w; same += int(np.sum(d == 0))
+            assert np.all(d <= np.abs(want) * 2.0 ** -3 + 2.0 ** -9 / scale), (n, e0)
+    print("stored fp8 codes identical to the oracle's:", same / tot, flush=True)
+    assert same / tot > 0.98
+    oz = zo_step.Zo2Blockwise(shape, Po, store="fp8_e4m3", compute="bf16", scales={n: scale for n in names})
+    oz.pending = (np.float32(c_prev), 41, np.float32(1.0))
+    a = oz.step(tok, lab, 42, 1e-3, 1e-7)
+    print("oracle", a, flush=True)
+    assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
+    assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))

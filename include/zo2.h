@@ -23,7 +23,9 @@
  *     default stream).  Op calls only enqueue work on that stream; they never synchronise;
  *   - matrices are row-major; a linear layer's weight is [out_features, in_features];
  *   - nothing here allocates device memory: the caller hands in an arena (context) or the
- *     buffers themselves (ops).
+ *     buffers themselves (ops);
+ *   - zo2_step / zo2_step_extra / zo2_eval emit named ranges ("zo2_step", "block 7", "lm_head + loss") through the
+ *     profiler's marker library when it can be loaded (rocprofv3 --marker-trace), bracketing the enqueue of each phase.
  */
 #ifndef ZO2_H
 #define ZO2_H
@@ -218,6 +220,12 @@ zo2_status zo2_get_kernel_times(const zo2_ctx* ctx, float ms[ZO2_KERNEL_CLASSES]
  * (0 compute, 1 upload, 2 offload) an idle kernel of the given duration (<= 100 ms) is enqueued.  With the
  * dependency rules of Sec. 5.2 in place no choice of delays can change any result. */
 zo2_status zo2_debug_set_stream_delay(zo2_ctx* ctx, int32_t which, uint32_t microseconds);
+
+/* Second test aid for the same rules: with enabled != 0 every slot is filled with 0xFF bytes (a NaN pattern in each of
+ * the five formats) on the upload stream right before a block is copied into it.  A kernel that read a slot before its
+ * upload had landed ("computing on a half-uploaded block", Sec. 5.2) would turn the losses into NaN; with the
+ * dependencies in place nothing changes. */
+zo2_status zo2_debug_set_slot_poison(zo2_ctx* ctx, int32_t enabled);
 
 /* Rounding of the updated parameters into a low-bit wire format (Sec. 5.5 leaves it open; default 0 = to
  * nearest, ties to even, which is what a plain cast does).  With stochastic != 0, theta' = theta - eta g z is

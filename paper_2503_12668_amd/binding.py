@@ -81,6 +81,7 @@ def lib():
         "zo2_set_wire_rounding": (i32, [vp, i32]),
         "zo2_get_kernel_times": (i32, [vp, C.POINTER(f32), C.POINTER(i32)]),
         "zo2_debug_set_stream_delay": (i32, [vp, i32, u32]),
+        "zo2_debug_set_slot_poison": (i32, [vp, i32]),
         "zo2_last_error": (C.c_char_p, [vp]),
         "zo2_destroy": (None, [vp]),
         "zo2_op_last_error": (C.c_char_p, []),
@@ -108,7 +109,7 @@ def lib():
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
@@ -449,6 +450,9 @@ class Zo2Context:
 
     def debug_set_stream_delay(self, which, microseconds):
         self._check(lib().zo2_debug_set_stream_delay(self.handle, {"compute": 0, "upload": 1, "offload": 2}[which], int(microseconds)))
+
+    def debug_set_slot_poison(self, enabled):
+        self._check(lib().zo2_debug_set_slot_poison(self.handle, 1 if enabled else 0))
 
     KERNEL_CLASSES = ("k1", "gemm", "attn", "ln", "embed", "ce")
 

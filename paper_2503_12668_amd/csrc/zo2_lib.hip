@@ -8,6 +8,7 @@
 // (Sec. 5.2); blocks cycle through a ring of equal slots carved out of the caller's arena
 // (Sec. 5.3); each block crosses the host link once per direction per step because the
 // update of iteration j-1 is applied when the block is visited in iteration j (Sec. 5.4).
+#include <dlfcn.h>
 #include <math.h>
 #include <stdarg.h>
 #include <stdlib.h>
@@ -33,6 +34,40 @@ void set_op_error(const char* fmt, ...) {
 }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Named ranges for profiler timelines (rocprofv3 --marker-trace): the tool's marker library is looked up at run time,
+// once; without it the ranges cost one branch.  A range brackets the host-side enqueue of a phase of the step.
+struct TraceRange {
+    typedef int (*push_fn)(const char*);
+    typedef int (*pop_fn)();
+    static void lookup(push_fn& push, pop_fn& pop) {
+        static push_fn p_push = nullptr;
+        static pop_fn p_pop = nullptr;
+        static std::once_flag once;
+        std::call_once(once, [] {
+            void* h = dlopen("librocprofiler-sdk-roctx.so.1", RTLD_NOW | RTLD_GLOBAL);     // what rocprofv3 listens to
+            if (!h) h = dlopen("librocprofiler-sdk-roctx.so", RTLD_NOW | RTLD_GLOBAL);
+            if (!h) h = dlopen("libroctx64.so.4", RTLD_NOW | RTLD_GLOBAL);                 // the older tools' library
+            if (!h) h = dlopen("libroctx64.so", RTLD_NOW | RTLD_GLOBAL);
+            if (!h) return;
+            p_push = (push_fn)dlsym(h, "roctxRangePushA");
+            p_pop = (pop_fn)dlsym(h, "roctxRangePop");
+            if (!p_push || !p_pop) p_push = nullptr, p_pop = nullptr;
+        });
+        push = p_push;
+        pop = p_pop;
+    }
+    pop_fn pop_;
+    explicit TraceRange(const char* fmt, int arg = 0) : pop_(nullptr) {
+        push_fn push;
+        lookup(push, pop_);
+        if (!push) { pop_ = nullptr; return; }
+        char name[64];
+        snprintf(name, sizeof(name), fmt, arg);
+        push(name);
+    }
+    ~TraceRange() { if (pop_) pop_(); }
+};
 static constexpr int64_t kTensorAlign = 256;   // elements
 static constexpr int kDefaultSweeps = 1;       // update + perturb sweeps per block when the budget leaves the choice
 
@@ -137,6 +172,7 @@ struct zo2_ctx {
     float ms_c, ms_u, ms_o;
 
     uint32_t debug_delay_us[3];         // test aid: idle time inserted before each block's work on compute / upload / offload
+    bool debug_poison;                  // test aid: a slot is filled with 0xFF bytes (NaN in every format) before each upload into it
 
     // optional per-kernel-class timing with events on the compute stream
     uint32_t prof_mask;
@@ -232,6 +268,9 @@ static void prof_collect(zo2_ctx* c) {   // after the compute stream has been sy
 __global__ void delay_kernel(unsigned long long ticks_100mhz) {
     const unsigned long long t0 = wall_clock64();
     while (wall_clock64() - t0 < ticks_100mhz) { __builtin_amdgcn_s_sleep(32); }
+}
+__global__ void poison_kernel(uint32_t* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0xffffffffu;
 }
 static zo2_status debug_delay(zo2_ctx* c, int which, hipStream_t st) {
     const uint32_t us = c->debug_delay_us[which];
@@ -602,6 +641,12 @@ extern "C" zo2_status zo2_get_kernel_times(const zo2_ctx* c, float ms[ZO2_KERNEL
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_debug_set_slot_poison(zo2_ctx* c, int32_t enabled) {
+    if (!c) return ZO2_EINVAL;
+    c->debug_poison = enabled != 0;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_debug_set_stream_delay(zo2_ctx* c, int32_t which, uint32_t microseconds) {
     if (!c || which < 0 || which > 2 || microseconds > 100000u) return ZO2_EINVAL;
     c->debug_delay_us[which] = microseconds;
@@ -806,6 +851,11 @@ static zo2_status enqueue_upload(zo2_ctx* c, int l) {
     if (c->ev_free_valid[s]) HIPCHK(c, hipStreamWaitEvent(c->su, c->ev_free[s], 0));
     if (!c->stat_u) { HIPCHK(c, hipEventRecord(c->ev_u0, c->su)); c->stat_u = true; }
     { zo2_status ds = debug_delay(c, 1, c->su); if (ds != ZO2_OK) return ds; }
+    if (c->debug_poison) {      // whoever reads the slot before the copy below has landed computes NaN
+        hipLaunchKernelGGL(poison_kernel, dim3(1024), dim3(256), 0, c->su, (uint32_t*)(c->slots + (size_t)s * c->bucket_bytes), c->bucket_bytes / 4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(c, ZO2_EHIP, "poison kernel: %s", hipGetErrorString(e));
+    }
     HIPCHK(c, hipMemcpyAsync(c->slots + (size_t)s * c->bucket_bytes, c->host_bucket[l], c->bucket_bytes, hipMemcpyHostToDevice, c->su));
     HIPCHK(c, hipEventRecord(c->ev_up[s], c->su));
     c->bytes_up += c->bucket_bytes;
@@ -873,6 +923,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             if (s != ZO2_OK) return s;
         }
 
+    TraceRange step_range(ns == 2 ? (extra ? "zo2_step_extra" : "zo2_step") : "zo2_eval");
     // DualForward(Embedding)
     {   // earlier directions of the last round: the tables first, the gather then sees them
         zo2_status s = earlier_updates_tensor(c, c->d_tok, c->tok_elems, 0);
@@ -896,6 +947,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     // forwards of block l-1 (K1 is bound by the vector ALU and HBM, the forwards by the matrix cores).
     if (c->overlap_k1) HIPCHK(c, hipEventRecord(c->ev_embed, c->sc));
     for (int l = 0; l < g.n_layers; ++l) {
+        TraceRange block_range("block %d", l);
         const int sl = c->resident ? l : l % c->n_slots;
         char* bucket = c->slots + (size_t)sl * c->bucket_bytes;
         const int sb = l & 1;
@@ -939,6 +991,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     }
 
     // DualForward(LM head): final LayerNorm, (tied) vocabulary matrix, loss
+    TraceRange head_range("lm_head + loss");
     if (c->apply_now)
         for (int k = 0; k + 1 < c->n_pend; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
     { zo2_status s = k1_final_ln(c, true, seed, eps); if (s != ZO2_OK) return s; }

@@ -126,6 +126,7 @@ def test_scheduler_dependencies_hold_under_adversarial_delays(slow):
         ctx.set_resident_budget(ctx.plan()["bytes_used"] - 6 * ctx.offs[16] * 4)      # 3 slots for 9 blocks
         if delayed:
             ctx.debug_set_stream_delay(slow, 300)
+            ctx.debug_set_slot_poison(True)          # a read of a slot before its upload has landed would see NaN
         r += [ctx.step(tok, lab, 6 + j, 1e-3, 1e-3) for j in range(3)]
         assert ctx.plan()["n_slots"] == 3 and not ctx.plan()["resident"]
         ctx.flush(); ctx.sync_to_host()

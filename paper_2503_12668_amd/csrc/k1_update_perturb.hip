@@ -24,7 +24,7 @@ static constexpr int kChunk = kThreads * kPerLane * kIters;   // 8192 elements p
 
 // The arithmetic of one group of 8 consecutive elements (one Philox call q per random stream): tv holds
 // theta on entry and theta' on return.
-template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR>
+template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR, bool DRAW>
 __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, uint64_t q, float c, float eps, float scale,
                                          float inv_scale, Vec<W, kPerLane>& tv, Vec<C, kPerLane>& p, Vec<C, kPerLane>& m) {
     constexpr bool kScaled = (Fmt<W>::kBytes == 1);
@@ -49,8 +49,7 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
             if (kScaled) th[j] *= inv_scale;
         }
     }
-    if (PERTURB) {
-        // (with eps = 0, the single forward of an evaluation, fma(0, z, theta') is theta' itself: no separate path)
+    if constexpr (PERTURB && DRAW) {
         float z[kPerLane];
         gaussian8(a.k_cur, tensor_id, q, z);
 #pragma unroll
@@ -58,10 +57,16 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
             p.v[j] = Fmt<C>::store(__builtin_fmaf(eps, z[j], th[j]));
             m.v[j] = Fmt<C>::store(__builtin_fmaf(-eps, z[j], th[j]));
         }
+    } else if constexpr (PERTURB) {
+        // eps = 0 (the single forward of an evaluation): W+ = theta' in the compute format, nothing to draw.  A kernel
+        // instance of its own, chosen on the host: as a branch on eps inside one instance the two paths' 16-bit results
+        // were merged through scratch memory.
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) p.v[j] = m.v[j] = Fmt<C>::store(th[j]);
     }
 }
 
-template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR>
+template <typename W, typename C, bool UPDATE, bool PERTURB, bool SR, bool DRAW>
 __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
     // which tensor does this workgroup work on: first_chunk[] ascends (0xffffffff past the last segment),
     // so the segment index is the number of entries at or below this workgroup's index
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
         for (int it = 0; it < kIters; ++it) {
             const uint64_t i = i0 + (uint64_t)it * kStride;
             Vec<C, kPerLane> p, m;
-            k1_group<W, C, UPDATE, PERTURB, SR>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
+            k1_group<W, C, UPDATE, PERTURB, SR, DRAW>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
             if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i, p);
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
             for (int j = 0; j < kPerLane; ++j) tv.v[j] = (j < valid) ? theta[i0 + j] : Fmt<W>::store(0.f);
         }
         Vec<C, kPerLane> p, m;
-        k1_group<W, C, UPDATE, PERTURB, SR>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
+        k1_group<W, C, UPDATE, PERTURB, SR, DRAW>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
         if (valid == kPerLane) {
             if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
             if (PERTURB) {
@@ -141,11 +146,14 @@ template <typename W, typename C>
 static zo2_status launch_wc(const K1Args& a, bool update, bool perturb, hipStream_t st) {
     const dim3 grid(a.total_chunks), block(kThreads);
     const bool sr = update && a.stochastic != 0 && sizeof(W) < 4;      // stochastic rounding only concerns a low-bit theta'
-    if (update && perturb && sr) hipLaunchKernelGGL((k1_kernel<W, C, true, true, true>), grid, block, 0, st, a);
-    else if (update && perturb) hipLaunchKernelGGL((k1_kernel<W, C, true, true, false>), grid, block, 0, st, a);
-    else if (update && sr) hipLaunchKernelGGL((k1_kernel<W, C, true, false, true>), grid, block, 0, st, a);
-    else if (update) hipLaunchKernelGGL((k1_kernel<W, C, true, false, false>), grid, block, 0, st, a);
-    else if (perturb) hipLaunchKernelGGL((k1_kernel<W, C, false, true, false>), grid, block, 0, st, a);
+    const bool draw = a.eps != 0.f;
+#define ZO2_K1_LAUNCH(U, P, S, D) hipLaunchKernelGGL((k1_kernel<W, C, U, P, S, D>), grid, block, 0, st, a)
+    if (update && perturb && sr) { if (draw) ZO2_K1_LAUNCH(true, true, true, true); else ZO2_K1_LAUNCH(true, true, true, false); }
+    else if (update && perturb) { if (draw) ZO2_K1_LAUNCH(true, true, false, true); else ZO2_K1_LAUNCH(true, true, false, false); }
+    else if (update && sr) ZO2_K1_LAUNCH(true, false, true, false);
+    else if (update) ZO2_K1_LAUNCH(true, false, false, false);
+    else if (perturb) { if (draw) ZO2_K1_LAUNCH(false, true, false, true); else ZO2_K1_LAUNCH(false, true, false, false); }
+#undef ZO2_K1_LAUNCH
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
 }

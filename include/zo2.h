@@ -299,6 +299,28 @@ zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K,
                        const float* residual, void* Y, int32_t out_dtype, int64_t ldy,
                        float out_scale, int32_t relu, void* stream);
 
+/* The same projection for both perturbation streams at once, with the perturbation generated in the weight loader
+ * (Alg. 2 "perturb" folded into the forward; for steps of few tokens, where the projections are bound by reading the
+ * weights): Y+- [M, N] = act( (X+- [M, K] . (theta +- eps z)^T + bias+-) * out_scale ) + residual+-, where theta [N, K]
+ * is the stored weight (dense, leading dimension K, in `dtype` = BF16 or F16, its pending update already applied) and
+ * z its random direction at `seed` (tensor_id selects the stream).  W+ = store(fma(+eps, z, theta)) and
+ * W- = store(fma(-eps, z, theta)) are formed tile by tile on chip - bit for bit what zo2_op_update_perturb writes - and
+ * theta is read once for both streams.  M <= 256, K % 64 == 0, N % 4 == 0, operands 16-byte aligned; bias+-: already
+ * perturbed [N] vectors of `dtype` or both NULL; residual+-: float32 [M, ldy] or both NULL (needs F32 output).  The k
+ * range is cut into slices whose float32 partial sums live in `workspace` (device, 16-byte aligned, at least
+ * zo2_op_gemm_perturbed_workspace_bytes(M, N, K) bytes) and are added in slice order: results are deterministic. */
+zo2_status zo2_op_gemm_perturbed(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X_plus, const void* X_minus, int64_t ldx,
+                                 const void* theta, uint32_t tensor_id, uint64_t seed, float eps,
+                                 const void* bias_plus, const void* bias_minus, const float* residual_plus, const float* residual_minus,
+                                 void* Y_plus, void* Y_minus, int32_t out_dtype, int64_t ldy, float out_scale, int32_t relu,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+size_t zo2_op_gemm_perturbed_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/* W+ and W- of rows n0 .. n0 + rows - 1 of a dense [N, K] tensor through the code path of that loader (test hook:
+ * the bits must equal those of zo2_op_update_perturb without an update).  theta points at row n0. */
+zo2_status zo2_op_perturbed_rows(int32_t dtype, const void* theta, int64_t K, int64_t n0, int64_t rows, uint32_t tensor_id,
+                                 uint64_t seed, float eps, void* w_plus, void* w_minus, void* stream);
+
 /* The large-tile GEMM kernel works on 256- or 128-row tiles and picks the height per launch (whichever fills the
  * rounds of tiles over the compute units better).  rows = 128 or 256 forces one height for every later launch of the
  * process, step calls included; 0 restores the choice per launch.  For tests and measurements: results are the same

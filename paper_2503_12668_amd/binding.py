@@ -92,6 +92,9 @@ def lib():
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
         "zo2_op_set_gemm_tile_rows": (i32, [i32]),
+        "zo2_op_gemm_perturbed": (i32, [i32, i32, i32, i32, vp, vp, i64, vp, u32, u64, f32, vp, vp, vp, vp, vp, vp, i32, i64, f32, i32, vp, C.c_size_t, vp]),
+        "zo2_op_gemm_perturbed_workspace_bytes": (C.c_size_t, [i32, i32, i32]),
+        "zo2_op_perturbed_rows": (i32, [i32, vp, i64, i64, i64, u32, u64, f32, vp, vp, vp]),
         "zo2_op_attention": (i32, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i32, vp]),
         "zo2_op_layernorm": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
         "zo2_op_cross_entropy_rows": (i32, [vp, i64, vp, i32, i32, vp, vp]),
@@ -110,7 +113,7 @@ def lib():
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
-            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows",
+            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
 
@@ -204,6 +207,30 @@ def op_gemm(X, W, bias=None, residual=None, out_dtype=None, out_scale=1.0, relu=
     _op_check(lib().zo2_op_gemm(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(residual),
                                 _ptr(Y), odt, Y.stride(0), out_scale, 1 if relu else 0, _stream_ptr(stream)))
     return Y
+
+
+def op_gemm_perturbed(Xp, Xm, theta, tensor_id, seed, eps, bias_p=None, bias_m=None, res_p=None, res_m=None, out_dtype=None,
+                      out_scale=1.0, relu=False, stream=None):
+    """Both streams' projection with W+- generated in the weight loader; returns (Y+, Y-)."""
+    M, K = Xp.shape
+    N = theta.shape[0]
+    odt = _dt(Xp) if out_dtype is None else out_dtype
+    Yp = torch.empty(M, N, dtype=TORCH_DTYPE[odt], device="cuda")
+    Ym = torch.empty(M, N, dtype=TORCH_DTYPE[odt], device="cuda")
+    nb = lib().zo2_op_gemm_perturbed_workspace_bytes(M, N, K)
+    ws = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
+    _op_check(lib().zo2_op_gemm_perturbed(_dt(Xp), M, N, K, _ptr(Xp), _ptr(Xm), Xp.stride(0), _ptr(theta), tensor_id, seed, eps,
+                                          _ptr(bias_p), _ptr(bias_m), _ptr(res_p), _ptr(res_m), _ptr(Yp), _ptr(Ym), odt, Yp.stride(0),
+                                          out_scale, 1 if relu else 0, _ptr(ws), nb, _stream_ptr(stream)))
+    return Yp, Ym
+
+
+def op_perturbed_rows(theta_rows, K, n0, tensor_id, seed, eps, stream=None):
+    """W+ and W- of rows n0 .. of a dense [N, K] tensor (theta_rows: those rows) through the loader's code path."""
+    wp, wm = torch.empty_like(theta_rows), torch.empty_like(theta_rows)
+    _op_check(lib().zo2_op_perturbed_rows(_dt(theta_rows), _ptr(theta_rows), K, n0, theta_rows.numel() // K, tensor_id, seed, eps,
+                                          _ptr(wp), _ptr(wm), _stream_ptr(stream)))
+    return wp, wm
 
 
 def op_set_gemm_tile_rows(rows):

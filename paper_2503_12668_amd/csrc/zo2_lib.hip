@@ -20,6 +20,7 @@
 #include "attention.h"
 #include "common.h"
 #include "gemm.h"
+#include "gemm_skinny.h"
 #include "k1.h"
 #include "rowops.h"
 
@@ -1301,6 +1302,30 @@ extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K
     a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldw = ldw; a.ldy = ldy; a.relu = relu; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1;
     a.p[0].X = X; a.p[0].W = W; a.p[0].bias = bias; a.p[0].residual = residual; a.p[0].Y = Y; a.p[0].out_scale = out_scale;
     return gemm_launch(a, dtype, as_stream(stream));
+}
+
+extern "C" size_t zo2_op_gemm_perturbed_workspace_bytes(int32_t M, int32_t N, int32_t K) { return skinny_workspace_bytes(M, N, K, 1); }
+
+extern "C" zo2_status zo2_op_gemm_perturbed(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X_plus, const void* X_minus, int64_t ldx,
+                                            const void* theta, uint32_t tensor_id, uint64_t seed, float eps, const void* bias_plus,
+                                            const void* bias_minus, const float* residual_plus, const float* residual_minus, void* Y_plus,
+                                            void* Y_minus, int32_t out_dtype, int64_t ldy, float out_scale, int32_t relu, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+    if (M == 0 || N == 0) return ZO2_OK;
+    ZO2_OP_CHECK(out_dtype == ZO2_F32 || out_dtype == dtype, ZO2_EINVAL, "gemm_perturbed: output dtype must be F32 or the input dtype");
+    SkinnyArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldy = ldy; a.relu = relu; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1; a.eps = eps;
+    a.key = philox_keys(seed);
+    SkinnyProblem& p = a.p[0];
+    p.Xp = X_plus; p.Xm = X_minus; p.theta = theta; p.bias_p = bias_plus; p.bias_m = bias_minus; p.res_p = residual_plus; p.res_m = residual_minus;
+    p.Yp = Y_plus; p.Ym = Y_minus; p.out_scale = out_scale; p.tensor_id = tensor_id;
+    return skinny_launch(a, dtype, workspace, workspace_bytes, as_stream(stream));
+}
+
+extern "C" zo2_status zo2_op_perturbed_rows(int32_t dtype, const void* theta, int64_t K, int64_t n0, int64_t rows, uint32_t tensor_id,
+                                            uint64_t seed, float eps, void* w_plus, void* w_minus, void* stream) {
+    return skinny_perturbed_rows(dtype, theta, K, n0, rows, tensor_id, seed, eps, w_plus, w_minus, as_stream(stream));
 }
 
 extern "C" zo2_status zo2_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, int32_t n_seq,

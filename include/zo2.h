@@ -197,6 +197,19 @@ zo2_status zo2_get_scratch_plan(const zo2_ctx* ctx, int32_t* sweeps_per_block, i
  * block slots fit.  Takes effect at the next step.  ZO2_EINVAL for any other value. */
 zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t sweeps);
 
+/* Where the perturbation of a block's six weight matrices is generated.  By default (mode 0) a step of at most 256
+ * tokens per stream - where the projections are bound by reading the weights - lets the projections read the stored
+ * weights and form W+ / W- in their loader (zo2_op_gemm_perturbed), the sweep kernel then only applies the pending
+ * update and perturbs the block's one-dimensional tensors; larger steps write the perturbed copies with the sweep kernel,
+ * because a weight tile would otherwise be regenerated once per 256-row tile of activations.  mode 1: in the loader
+ * whenever the shapes allow (16-bit storage equal to the compute format, d_model and d_ffn multiples of 64, at most
+ * 256 tokens per stream); mode -1: never.  The two paths give the same W+- bit for bit; their projections add the
+ * same products in a different order (results agree to float32 rounding, each path is deterministic by itself).
+ * Evaluation passes (zo2_eval) always take the sweep-kernel path.  Takes effect at the next step. */
+zo2_status zo2_set_loader_fusion(zo2_ctx* ctx, int32_t mode);
+/* *active = 1 if the last plan lets the projections perturb in their loader. */
+zo2_status zo2_get_loader_fusion(const zo2_ctx* ctx, int32_t* active);
+
 /* Per-stream busy time of the last step in milliseconds (compute, upload, offload) and the
  * bytes copied each way; for host-link rate reporting.  Any pointer may be NULL. */
 zo2_status zo2_get_step_stats(const zo2_ctx* ctx, float* ms_compute, float* ms_upload, float* ms_offload,

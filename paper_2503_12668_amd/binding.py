@@ -75,6 +75,8 @@ def lib():
         "zo2_get_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_size_t)]),
         "zo2_get_scratch_plan": (i32, [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]),
         "zo2_set_scratch_plan": (i32, [vp, i32]),
+        "zo2_set_loader_fusion": (i32, [vp, i32]),
+        "zo2_get_loader_fusion": (i32, [vp, C.POINTER(i32)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
         "zo2_set_stream_overlap": (i32, [vp, i32]),
@@ -112,7 +114,7 @@ def lib():
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
@@ -455,8 +457,14 @@ class Zo2Context:
         self._check(lib().zo2_get_plan(self.handle, C.byref(n), C.byref(r), C.byref(b)))
         pg, se, ss = C.c_int32(), C.c_int64(), C.c_int32()
         self._check(lib().zo2_get_scratch_plan(self.handle, C.byref(pg), C.byref(se), C.byref(ss)))
+        lf = C.c_int32()
+        self._check(lib().zo2_get_loader_fusion(self.handle, C.byref(lf)))
         return dict(n_slots=n.value, resident=bool(r.value), bytes_used=b.value, sweeps_per_block=pg.value,
-                    scratch_elems=se.value, scratch_sets=ss.value)
+                    scratch_elems=se.value, scratch_sets=ss.value, loader_fusion=bool(lf.value))
+
+    def set_loader_fusion(self, mode):
+        """0: the projections perturb in their weight loader for steps of few tokens; 1: whenever possible; -1: never."""
+        self._check(lib().zo2_set_loader_fusion(self.handle, int(mode)))
 
     def set_scratch_plan(self, sweeps):
         """1, 2 or 4 update + perturb sweeps per block (W+ / W- scratch for a whole block, a half, a tensor group);

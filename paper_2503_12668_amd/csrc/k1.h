@@ -11,7 +11,7 @@ struct K1Seg {
     uint64_t n;           // elements
     uint32_t tensor_id;   // selects the random stream
     float scale;          // wire scale of the tensor (8-bit formats), else 1
-    uint32_t pad_[2];
+    int64_t woff;         // with K1Args::packed_w: element offset of the segment inside w_plus / w_minus
 };
 
 struct K1Args {
@@ -25,6 +25,8 @@ struct K1Args {
     float c_imm;          // eta_prev * g_prev, used when c_ptr == nullptr
     int32_t stochastic;   // 1: theta' is stored with stochastic rounding (low-bit wire formats), 0: to nearest
     int32_t reverse;      // 1: the grid walks the chunks from the last to the first
+    int32_t packed_w;     // 1: a segment's copies start at w_plus[seg.woff] (segments packed densely) instead of w_plus[off - w_off0]
+    int32_t pad_;
     float eps;
     const float* c_ptr;   // device scalar holding eta_prev * g_prev (stays on the GPU between steps)
     PhiloxKeys k_prev, k_cur;

@@ -80,9 +80,10 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
     const K1Seg sg = a.seg[s];
     const uint64_t chunk0 = (uint64_t)(chunk - a.first_chunk[s]) * kChunk;
     W* __restrict__ theta = reinterpret_cast<W*>(a.theta) + sg.off;
-    C* __restrict__ wp = PERTURB ? reinterpret_cast<C*>(a.w_plus) + (sg.off - a.w_off0) : nullptr;
+    const int64_t wofs = a.packed_w ? sg.woff : sg.off - a.w_off0;
+    C* __restrict__ wp = PERTURB ? reinterpret_cast<C*>(a.w_plus) + wofs : nullptr;
     const bool has_m = PERTURB && a.w_minus != nullptr;            // a single forward needs W+ only
-    C* __restrict__ wm = has_m ? reinterpret_cast<C*>(a.w_minus) + (sg.off - a.w_off0) : nullptr;
+    C* __restrict__ wm = has_m ? reinterpret_cast<C*>(a.w_minus) + wofs : nullptr;
     const float c = UPDATE ? (a.c_ptr ? *a.c_ptr : a.c_imm) : 0.f;
     const float eps = a.eps;
     const float scale = sg.scale, inv_scale = 1.0f / sg.scale;

@@ -71,6 +71,7 @@ struct TraceRange {
 };
 static constexpr int64_t kTensorAlign = 256;   // elements
 static constexpr int kDefaultSweeps = 1;       // update + perturb sweeps per block when the budget leaves the choice
+static constexpr int kFuseMaxTokens = 256;     // up to this many tokens per stream the projections perturb in their weight loader
 
 static bool config_ok(const zo2_config* c, char* why, size_t n) {
 #define BAD(...) do { snprintf(why, n, __VA_ARGS__); return false; } while (0)
@@ -132,6 +133,10 @@ struct zo2_ctx {
     int sweeps;                         // update + perturb sweeps per block: 1 (whole-block scratch), 2 (per half) or 4 (per tensor group)
     int pb[5];                          // sweep p, issued at point p of the block's forward, covers tensors pb[p] .. pb[p + 1] - 1 (may be empty)
     int scratch_plan_forced;            // 0: the planner chooses; 1 / 2 / 4: that many sweeps per block
+    int loader_fusion;                  // 0: for few tokens per step (kFuseMaxTokens); 1: whenever the shapes allow; -1: never
+    bool fuse;                          // this plan: the projections of a block perturb in their weight loader (step passes only)
+    char* sk_ws;                        // their workspace (float32 partial sums of the k slices)
+    size_t sk_ws_bytes;
     int n_slots;
     char* slots;
     char *wp, *wm;                      // W+ / W- scratch in use (compute dtype)
@@ -165,8 +170,8 @@ struct zo2_ctx {
 
     // streams / events
     hipStream_t sc, su, so;
-    std::vector<hipEvent_t> ev_up, ev_k1, ev_free;
-    std::vector<char> ev_free_valid;
+    std::vector<hipEvent_t> ev_up, ev_k1, ev_free, ev_read;
+    std::vector<char> ev_free_valid, ev_read_valid;    // ev_read: the forwards that read the slot itself (loader fusion) are done
     hipEvent_t ev_step0, ev_c1, ev_u0, ev_u1, ev_o0, ev_o1;
     bool stat_u, stat_o;
     uint64_t bytes_up, bytes_down;
@@ -393,6 +398,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->resident = false;
     c->sweeps = 1;
     c->scratch_plan_forced = 0;
+    c->loader_fusion = 0;
+    c->fuse = false;
     c->scratch_elems = 0;
     *out = c;   // from here on errors are reported through the context
 
@@ -432,6 +439,7 @@ extern "C" void zo2_destroy(zo2_ctx* c) {
     for (auto e : c->ev_up) hipEventDestroy(e);
     for (auto e : c->ev_k1) hipEventDestroy(e);
     for (auto e : c->ev_free) hipEventDestroy(e);
+    for (auto e : c->ev_read) hipEventDestroy(e);
     for (auto e : c->prof_ev) hipEventDestroy(e);
     hipEvent_t evs[] = {c->ev_step0, c->ev_c1, c->ev_u0, c->ev_u1, c->ev_o0, c->ev_o1, c->ev_k1done[0], c->ev_k1done[1], c->ev_fwd_done[0], c->ev_fwd_done[1], c->ev_embed};
     if (c->h_result) for (hipEvent_t e : evs) hipEventDestroy(e);
@@ -496,13 +504,23 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     lrows = lrows / 128 * 128;
     if (lrows < 128) lrows = 128;
     if (lrows > (size_t)T) lrows = T;
+    // few tokens per step: the block projections read the stored weights and perturb in their loader (16-bit storage
+    // that is also the compute format, no wire scale)
+    const bool fuse_shapes = g.wire_dtype == g.compute_dtype && g.compute_dtype != ZO2_F32 && T <= 256 && d % 64 == 0 && f % 64 == 0 &&
+                             (size_t)T * f * 2 < 0xffffffffull;
+    const bool fuse = fuse_shapes && c->loader_fusion >= 0 && (c->loader_fusion == 1 || T <= kFuseMaxTokens) && !c->sk;
+    size_t sk_ws_bytes = 0;
+    if (fuse) {
+        sk_ws_bytes = std::max(std::max(skinny_workspace_bytes(T, (int)d, (int)d, 3), skinny_workspace_bytes(T, (int)d, (int)d, 1)),
+                               std::max(skinny_workspace_bytes(T, (int)f, (int)d, 1), skinny_workspace_bytes(T, (int)d, (int)f, 1)));
+    }
     size_t act = 0;
     auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
     const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
                  o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
                  o_logits = sz(fused_ce ? 0 : 2 * lrows * V * 4), o_rl = sz(rows2 * 4),
                  o_cpm = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cps = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cl = sz(fused_ce ? rows2 * 4 : 0), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
-                 o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz);
+                 o_fwp = sz((size_t)c->fln_elems * c->csz), o_fwm = sz((size_t)c->fln_elems * c->csz), o_skws = sz(sk_ws_bytes);
     const size_t act_bytes = act;
 
     const int64_t head_elems = (int64_t)align_up(c->tok_elems, kTensorAlign);
@@ -560,6 +578,7 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     c->mid = a0 + o_mid; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
     c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
     c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
+    c->fuse = fuse; c->sk_ws = a0 + o_skws; c->sk_ws_bytes = sk_ws_bytes;
     c->fused_ce = fused_ce; c->ce_parts = (int)ce_parts;
     c->ce_pmax = (float*)(a0 + o_cpm); c->ce_psum = (float*)(a0 + o_cps); c->ce_lab = (float*)(a0 + o_cl);
     off += act_bytes;
@@ -572,13 +591,15 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
 
     // events per slot
     while ((int)c->ev_up.size() < n_slots) {
-        hipEvent_t e1, e2, e3;
+        hipEvent_t e1, e2, e3, e4;
         HIPCHK(c, hipEventCreateWithFlags(&e1, hipEventDisableTiming));
         HIPCHK(c, hipEventCreateWithFlags(&e2, hipEventDisableTiming));
         HIPCHK(c, hipEventCreateWithFlags(&e3, hipEventDisableTiming));
-        c->ev_up.push_back(e1); c->ev_k1.push_back(e2); c->ev_free.push_back(e3);
+        HIPCHK(c, hipEventCreateWithFlags(&e4, hipEventDisableTiming));
+        c->ev_up.push_back(e1); c->ev_k1.push_back(e2); c->ev_free.push_back(e3); c->ev_read.push_back(e4);
     }
     c->ev_free_valid.assign(c->ev_up.size(), 0);
+    c->ev_read_valid.assign(c->ev_up.size(), 0);
 
     if (resident && !(c->planned && c->resident && c->blocks_on_device && c->n_slots == n_slots)) {
         for (int l = 0; l < g.n_layers; ++l)
@@ -624,6 +645,21 @@ extern "C" zo2_status zo2_set_scratch_plan(zo2_ctx* c, int32_t mode) {
     if (mode != 0 && mode != 1 && mode != 2 && mode != 4) return fail(c, ZO2_EINVAL, "zo2_set_scratch_plan: %d sweeps per block (0, 1, 2 or 4)", mode);
     c->scratch_plan_forced = mode;
     c->need_plan = true;   // re-plan at the next step
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_set_loader_fusion(zo2_ctx* c, int32_t mode) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (mode < -1 || mode > 1) return fail(c, ZO2_EINVAL, "zo2_set_loader_fusion: mode %d (-1, 0 or 1)", mode);
+    c->loader_fusion = mode;
+    c->need_plan = true;   // re-plan at the next step
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_loader_fusion(const zo2_ctx* c, int32_t* active) {
+    if (!c || !active) return ZO2_EINVAL;
+    *active = (c->planned && c->fuse) ? 1 : 0;
     return ZO2_OK;
 }
 
@@ -845,11 +881,90 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
     return ZO2_OK;
 }
 
+// The same block for a step of few tokens: K1 only applies the pending update (theta' is final after it) and perturbs
+// the block's ten one-dimensional tensors into a densely packed scratch; the six projections read theta' itself and
+// perturb in their weight loader, both streams per pass over the weights (gemm_skinny.hip).
+static const int kVecTensors[10] = {0, 1, 3, 5, 7, 9, 10, 11, 13, 15};      // ln1.w ln1.b q.b k.b v.b o.b ln2.w ln2.b fc1.b fc2.b
+
+static zo2_status block_forward_fused(zo2_ctx* c, int l, char* bucket, int batch, int seq, uint64_t seed, float eps, hipEvent_t k1_done) {
+    const zo2_config& g = c->cfg;
+    const int T = batch * seq, d = g.d_model, f = g.d_ffn, dh = d / g.n_heads;
+    const int dt = g.compute_dtype;
+    const size_t cs = c->csz;
+    const size_t half_d = (size_t)T * d * cs, half_f = (size_t)T * f * cs;
+    { zo2_status s = earlier_updates_block(c, l, bucket); if (s != ZO2_OK) return s; }
+    { zo2_status s = k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, false, seed, eps); if (s != ZO2_OK) return s; }     // the update alone
+    if (k1_done) HIPCHK(c, hipEventRecord(k1_done, c->sc));      // the block's parameters are final: the offload may start
+    int64_t voff[ZO2_BLOCK_TENSORS] = {0};
+    {
+        K1Args a;
+        k1_common(c, a, seed, eps);
+        a.theta = bucket; a.w_plus = c->wp; a.w_minus = c->wm; a.packed_w = 1; a.nseg = 10;
+        int64_t o = 0;
+        for (int i = 0; i < 10; ++i) {
+            const int k = kVecTensors[i];
+            K1Seg& sg = a.seg[i];
+            sg.off = c->offs[k]; sg.e0 = 0; sg.n = (uint64_t)c->tn[k]; sg.tensor_id = block_tid(l, k); sg.scale = 1.0f; sg.woff = o;
+            voff[k] = o;
+            o += (c->tn[k] + kTensorAlign - 1) / kTensorAlign * kTensorAlign;
+        }
+        OPK(c, ZO2_KC_K1, k1_launch(a, g.wire_dtype, g.compute_dtype, false, true, c->sc));
+    }
+    auto VP = [&](int k) { return (const void*)(c->wp + (size_t)voff[k] * cs); };
+    auto VM = [&](int k) { return (const void*)(c->wm + (size_t)voff[k] * cs); };
+    auto TH = [&](int k) { return (const void*)(bucket + (size_t)c->offs[k] * cs); };
+    SkinnyArgs sa;
+    auto common = [&](int N, int K, int ldx, int ldy, int relu, int out_f32, int nprob) {
+        memset(&sa, 0, sizeof(sa));
+        sa.M = T; sa.N = N; sa.K = K; sa.ldx = ldx; sa.ldy = ldy; sa.relu = relu; sa.out_f32 = out_f32; sa.nprob = nprob; sa.eps = eps;
+        sa.key = philox_keys(seed);
+    };
+
+    // ---- attention half: h += O(Attn(LN1(h)))
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, VP(0), VP(1), VM(0), VM(1), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    common(d, d, d, d, 0, 0, 3);
+    char* outs[3] = {c->qb, c->kb, c->vb};
+    for (int t = 0; t < 3; ++t) {
+        SkinnyProblem& p = sa.p[t];
+        p.Xp = c->x; p.Xm = c->x + half_d; p.theta = TH(2 + 2 * t); p.bias_p = VP(3 + 2 * t); p.bias_m = VM(3 + 2 * t);
+        p.Yp = outs[t]; p.Ym = outs[t] + half_d; p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f; p.tensor_id = block_tid(l, 2 + 2 * t);
+    }
+    OPK(c, ZO2_KC_GEMM, skinny_launch(sa, dt, c->sk_ws, c->sk_ws_bytes, c->sc));
+    OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, 2 * batch, seq, g.n_heads, dh, d, 0, c->sc));
+    common(d, d, d, d, 0, 1, 1);
+    {
+        SkinnyProblem& p = sa.p[0];
+        p.Xp = c->ctxb; p.Xm = c->ctxb + half_d; p.theta = TH(8); p.bias_p = VP(9); p.bias_m = VM(9);
+        p.res_p = c->h; p.res_m = c->h + (size_t)T * d; p.Yp = c->h; p.Ym = c->h + (size_t)T * d; p.out_scale = 1.0f; p.tensor_id = block_tid(l, 8);
+    }
+    OPK(c, ZO2_KC_GEMM, skinny_launch(sa, dt, c->sk_ws, c->sk_ws_bytes, c->sc));
+
+    // ---- FFN half: h += FC2(ReLU(FC1(LN2(h))))
+    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, VP(10), VP(11), VM(10), VM(11), c->x, 2 * T, T, d, g.ln_eps, c->sc));
+    common(f, d, d, f, 1, 0, 1);
+    {
+        SkinnyProblem& p = sa.p[0];
+        p.Xp = c->x; p.Xm = c->x + half_d; p.theta = TH(12); p.bias_p = VP(13); p.bias_m = VM(13);
+        p.Yp = c->mid; p.Ym = c->mid + half_f; p.out_scale = 1.0f; p.tensor_id = block_tid(l, 12);
+    }
+    OPK(c, ZO2_KC_GEMM, skinny_launch(sa, dt, c->sk_ws, c->sk_ws_bytes, c->sc));
+    common(d, f, f, d, 0, 1, 1);
+    {
+        SkinnyProblem& p = sa.p[0];
+        p.Xp = c->mid; p.Xm = c->mid + half_f; p.theta = TH(14); p.bias_p = VP(15); p.bias_m = VM(15);
+        p.res_p = c->h; p.res_m = c->h + (size_t)T * d; p.Yp = c->h; p.Ym = c->h + (size_t)T * d; p.out_scale = 1.0f; p.tensor_id = block_tid(l, 14);
+    }
+    OPK(c, ZO2_KC_GEMM, skinny_launch(sa, dt, c->sk_ws, c->sk_ws_bytes, c->sc));
+    return ZO2_OK;
+}
+
 // ---------------------------------------------------------------------------------- streaming (Alg. 3)
 // U(W_i): runs on the upload stream once the slot's previous occupant has left it.
 static zo2_status enqueue_upload(zo2_ctx* c, int l) {
     const int s = l % c->n_slots;
     if (c->ev_free_valid[s]) HIPCHK(c, hipStreamWaitEvent(c->su, c->ev_free[s], 0));
+    // with the perturbation in the projections' loader the forwards read the slot itself: its next occupant also waits for them
+    if (c->ev_read_valid[s]) HIPCHK(c, hipStreamWaitEvent(c->su, c->ev_read[s], 0));
     if (!c->stat_u) { HIPCHK(c, hipEventRecord(c->ev_u0, c->su)); c->stat_u = true; }
     { zo2_status ds = debug_delay(c, 1, c->su); if (ds != ZO2_OK) return ds; }
     if (c->debug_poison) {      // whoever reads the slot before the copy below has landed computes NaN
@@ -973,8 +1088,14 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             }
             if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
             { zo2_status ds = debug_delay(c, 0, c->sc); if (ds != ZO2_OK) return ds; }
-            zo2_status s = block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
+            const bool fused_block = c->fuse && ns == 2;
+            zo2_status s = fused_block ? block_forward_fused(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl])
+                                       : block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
             if (s != ZO2_OK) return s;
+            if (!c->resident) {
+                if (fused_block) HIPCHK(c, hipEventRecord(c->ev_read[sl], c->sc));
+                c->ev_read_valid[sl] = fused_block ? 1 : 0;
+            }
         }
         if (!c->resident && serial) {
             HIPCHK(c, hipStreamSynchronize(c->sc));

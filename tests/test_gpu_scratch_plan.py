@@ -76,6 +76,7 @@ def test_per_group_scratch_streamed_equals_whole_block_resident_bitwise(wire, co
         ctx = b.Zo2Context(cfg, P, wire=wire, compute=compute, arena_bytes=64 << 20, scales=scales)
         ctx.set_wire_rounding(sr)
         ctx.set_scratch_plan(want_sweeps[name])
+        ctx.set_loader_fusion(-1)       # this test is about the sweep kernel's scratch
         r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
         if name.endswith("streamed"):
             ctx.set_resident_budget(ctx.plan()["bytes_used"] - 3 * ctx.offs[16] * wsz)        # 3 slots for 6 blocks
@@ -148,6 +149,7 @@ def test_per_group_scratch_at_13b_width_two_blocks_matches_oracle_losses():
     lab = si.next_token_labels(tok)
     ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=8 << 30)
     ctx.set_scratch_plan(4)
+    ctx.set_loader_fusion(-1)           # 256 tokens per stream would otherwise perturb in the projections' loader: no sweeps to organise
     ctx.set_pending(True, 41, 2.5e-3)
     g = ctx.step(tok, lab, 42, 1e-3, 1e-7)
     pl = ctx.plan()

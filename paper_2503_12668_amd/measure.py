@@ -11,6 +11,10 @@ counter output into the traffic figures bench.py reports.
         copy (zo2_op_convert float32 -> float32: read 1, write 1), next to the perturbation alone (zo2_op_update_perturb
         with no update: read 1 / write 2, one Gaussian per element) and the fused update + perturb (read 1 / write 3,
         two Gaussians per element); GB/s of algorithmic bytes.
+    python3 paper_2503_12668_amd/measure.py small-steps [--model opt-1.3b] [--steps 20]
+        whole steps of few tokens (1 x 16 .. 1 x 512, 4 x 64, 8 x 64), resident bf16: ms per step with the perturbation
+        generated in the projections' loader switched off (the sweep writes W+ and W- for every tensor) and on, the
+        ratio, and the time the K1 and projection kernels take per step in each mode.
     python3 paper_2503_12668_amd/measure.py copy
         three 1 GiB copies and nothing else: the calibration run for rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
     python3 paper_2503_12668_amd/measure.py traffic --fetch F.csv --write W.csv --cal-fetch CF.csv --cal-write CW.csv \\
@@ -112,6 +116,48 @@ def cmd_streams(args):
         print(f"| {name} | {bpe} | {us:.1f} | {n * bpe / us / 1e3:.0f} |", flush=True)
 
 
+def cmd_small_steps(args):
+    import time
+    import torch
+    import synth_inputs as si
+    from paper_2503_12668_amd import binding
+    cfg = si.opt_config(args.model)
+    P = si.make_weights(cfg, seed=1)
+    ctx = binding.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=args.arena_gib << 30)
+    print(f"# {args.model} shape, bf16 resident; ms per step (mean of {args.steps}); k1 / gemm = their kernels' ms per step",
+          flush=True)
+    print("| batch x seq | off: ms | k1 | gemm | on: ms | k1 | gemm | off / on |", flush=True)
+    print("|---|---|---|---|---|---|---|---|", flush=True)
+    for (B, S) in ((1, 16), (1, 64), (1, 128), (1, 256), (4, 64), (8, 64), (1, 512)):
+        tok = si.make_tokens(cfg["vocab"], B, S, seed=2, dist="zipf")
+        lab = si.next_token_labels(tok)
+        row = []
+        for mode in (-1, 1):
+            ctx.set_loader_fusion(mode)
+            for j in range(3):
+                ctx.step(tok, lab, 42 + j, 1e-3, 1e-7)
+            active = ctx.plan()["loader_fusion"]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for j in range(args.steps):
+                ctx.step(tok, lab, 50 + j, 1e-3, 1e-7)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) / args.steps * 1e3
+            ctx.set_profiling(("gemm", "k1"))
+            acc = {"gemm": 0.0, "k1": 0.0}
+            for j in range(5):
+                ctx.step(tok, lab, 80 + j, 1e-3, 1e-7)
+                for k, (m, n) in ctx.kernel_times().items():
+                    if k in acc:
+                        acc[k] += m / 5
+            ctx.set_profiling(())
+            row.append((ms, acc["k1"], acc["gemm"], active))
+        (m0, k0, g0, a0), (m1, k1, g1, a1) = row
+        on = f"{m1:.2f} | {k1:.2f} | {g1:.2f}" if a1 else "not applicable | | "
+        print(f"| {B} x {S} | {m0:.2f} | {k0:.2f} | {g0:.2f} | {on} | {m0 / m1:.2f} |", flush=True)
+    ctx.close()
+
+
 def cmd_copy(args):
     import torch
 
@@ -184,13 +230,17 @@ def main():
     s.add_argument("--ring", type=int, default=4)
     s.add_argument("--launches", type=int, default=40)
     sub.add_parser("copy")
+    ss = sub.add_parser("small-steps")
+    ss.add_argument("--model", default="opt-1.3b")
+    ss.add_argument("--steps", type=int, default=20)
+    ss.add_argument("--arena-gib", type=int, default=20)
     t = sub.add_parser("traffic")
     for k in ("fetch", "write", "cal-fetch", "cal-write", "out"):
         t.add_argument("--" + k, required=True)
     t.add_argument("--steps", type=int, required=True)
     t.add_argument("--workload", default="opt-1.3b shape, bf16 resident, batch 16 x seq 256 (bench.py)")
     args = ap.parse_args()
-    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "traffic": cmd_traffic}[args.cmd](args)
+    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "small-steps": cmd_small_steps, "traffic": cmd_traffic}[args.cmd](args)
 
 
 if __name__ == "__main__":

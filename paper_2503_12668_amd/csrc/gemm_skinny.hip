@@ -1,11 +1,11 @@
 // Projections of the dual forward when a step has few tokens (at most 256 per stream).
 //
 // With so few rows the projections are bound by reading the weights, not by the matrix cores, and the large-tile
-// kernel has a handful of tiles for 256 compute units.  This kernel turns the layout around: a workgroup owns 64 output
+// kernel has a handful of tiles for 256 compute units.  This kernel turns the layout around: a workgroup owns 128 output
 // features and a slice of k, streams the stored weights theta through once for BOTH perturbation streams, and forms
-// W+ = theta + eps z, W- = theta - eps z in its loader, tile by tile in LDS (z regenerated from the counters, Alg. 2
-// "perturb"; the same arithmetic and rounding as the sweep kernel, so the same bits) - the two perturbed copies of a
-// block are never written to memory nor read back.  The k range is cut into slices so that a launch has a few hundred
+// W+ = theta + eps z, W- = theta - eps z in its loader, chunk by chunk in registers (z regenerated from the counters,
+// Alg. 2 "perturb"; the same arithmetic and rounding as the sweep kernel, so the same bits) - the two perturbed copies
+// of a block are never written to memory nor read back.  The k range is cut into slices so that a launch has a few hundred
 // workgroups; the slices' float32 partial sums go to a workspace and a second kernel adds them in slice order
 // (deterministic, unlike atomics) and applies bias, scale, ReLU and residual.
 #include "gemm_skinny.h"
@@ -48,15 +48,20 @@ __device__ __forceinline__ void perturb_chunk(const PhiloxKeys& key, uint32_t te
     __builtin_memcpy(&wm, &m8, 16);
 }
 
-static constexpr int kSkBN = 64, kSkBK = 64, kSkKC = 8;       // weight rows per workgroup, k per slab, 16-byte chunks per slab row
+static constexpr int kSkBN = 128, kSkBK = 64, kSkKC = 8;      // weight rows per workgroup, k per slab, 16-byte chunks per slab row
 
-// MW: 32-row MFMA tiles per wavefront and stream; a workgroup covers 128 MW rows of each stream.
-template <typename T, int MW>
-__global__ __launch_bounds__(256) void skinny_dual_kernel(const SkinnyArgs a) {
-    constexpr int MP = 128 * MW, CX = 4 * MW;                 // rows per stream; X chunks each thread stages per stream and slab
+// MT: 32-row MFMA tiles per stream (the workgroup covers 32 MT rows of each stream, every wavefront all of them).
+//
+// A wavefront owns 32 of the workgroup's 128 output features.  The MFMA's weight operand wants, in lane (r, kh), the 8
+// consecutive k of feature r starting at 16 ks + 8 kh: exactly one 16-byte chunk of the stored weight and one call of
+// the generator, so a lane loads its chunk of theta, perturbs it in registers and feeds both MFMAs from there - the
+// weights never pass through LDS and no wavefront waits for another's generation.  Only the activations are shared:
+// their slab (2 streams x 32 MT rows x 64 k) is staged in LDS, double-buffered, one barrier per slab.
+template <typename T, int MT>
+__global__ __launch_bounds__(256, (MT <= 4 ? 2 : 1)) void skinny_dual_kernel(const SkinnyArgs a) {
+    constexpr int MP = 32 * MT, CX = MT;                      // rows per stream; X chunks each thread stages per stream and slab
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    v4u_t* Xs = reinterpret_cast<v4u_t*>(smem);               // [2 streams][MP rows][8 chunks], chunk index XOR-swizzled by (row & 7)
-    v4u_t* Ws = Xs + 2 * MP * kSkKC;                           // [2 signs][64 rows][8 chunks]
+    v4u_t* Xs = reinterpret_cast<v4u_t*>(smem);               // [2 buffers][2 streams][MP rows][8 chunks], chunk index XOR-swizzled
 
     const SkinnyProblem p = a.p[blockIdx.z];
     const int n0 = blockIdx.x * kSkBN;
@@ -66,106 +71,94 @@ __global__ __launch_bounds__(256) void skinny_dual_kernel(const SkinnyArgs a) {
     const T* __restrict__ Xm = reinterpret_cast<const T*>(p.Xm);
     const T* __restrict__ Th = reinterpret_cast<const T*>(p.theta);
 
-    // staging plan.  X: chunk c = tid + 256 i of a stream's slab is (row c >> 3, position c & 7); rows past M re-read row M - 1
+    // staging plan of the activations: chunk c = tid + 256 i of a stream's slab is (row c >> 3, position c & 7); rows past
+    // M re-read row M - 1.  Position kc of row m sits at chunk kc ^ ((m >> 1) & 7): sixteen lanes that read one position
+    // of sixteen consecutive rows, and eight that write one row, each touch every bank once.
     uint32_t xoff[CX];
     int xl[CX];
 #pragma unroll
     for (int i = 0; i < CX; ++i) {
         const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
         xoff[i] = (uint32_t)((size_t)min(row, a.M - 1) * a.ldx + kc * 8);
-        xl[i] = row * kSkKC + (kc ^ (row & 7));
+        xl[i] = row * kSkKC + (kc ^ ((row >> 1) & 7));
     }
-    // theta: 64 rows x 8 chunks = 2 chunks per thread; e = element index of the chunk inside the tensor (random-stream counter)
-    uint64_t we[2];
-    int wl[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-        we[i] = (uint64_t)min(n0 + row, a.N - 1) * (uint64_t)a.K + (uint64_t)(kc * 8);
-        wl[i] = row * kSkKC + (kc ^ (row & 7));
-    }
+    // this lane's weight row (features past N re-read row N - 1; their sums are dropped) and, in elements from the
+    // tensor's start, where its first chunk begins: the random stream's counter and the load address in one
+    const int n = n0 + wave * 32 + r;
+    const uint64_t we = (uint64_t)min(n, a.N - 1) * (uint64_t)a.K + (uint64_t)(kh * 8);
 
-    f32x16_t acc[2][MW][2];
+    f32x16_t acc[2][MT];
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int i = 0; i < MW; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[s][i][j][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[s][i][v] = 0.f;
 
-    v4u_t xr[2][CX], tr[2];
-    auto load_slab = [&](int k0) {
+    v4u_t xr[2][CX], tr[4], tn[4];
+    auto load_x = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < CX; ++i) {
             xr[0][i] = *reinterpret_cast<const v4u_t*>(Xp + xoff[i] + k0);
             xr[1][i] = *reinterpret_cast<const v4u_t*>(Xm + xoff[i] + k0);
         }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) tr[i] = *reinterpret_cast<const v4u_t*>(Th + we[i] + k0);
     };
-    auto store_slab = [&](int k0) {
+    auto store_x = [&](int buf) {
+        v4u_t* Xb = Xs + buf * (2 * MP * kSkKC);
 #pragma unroll
         for (int i = 0; i < CX; ++i) {
-            Xs[xl[i]] = xr[0][i];
-            Xs[MP * kSkKC + xl[i]] = xr[1][i];
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            v4u_t wp, wm;
-            perturb_chunk<T>(a.key, p.tensor_id, we[i] + (uint64_t)k0, a.eps, tr[i], wp, wm);
-            Ws[wl[i]] = wp;
-            Ws[kSkBN * kSkKC + wl[i]] = wm;
+            Xb[xl[i]] = xr[0][i];
+            Xb[MP * kSkKC + xl[i]] = xr[1][i];
         }
     };
 
-    load_slab(k_begin);
-    for (int k0 = k_begin; k0 < k_end; k0 += kSkBK) {
-        store_slab(k0);
-        __syncthreads();
-        if (k0 + kSkBK < k_end) load_slab(k0 + kSkBK);
+    load_x(k_begin);
 #pragma unroll
-        for (int ks = 0; ks < kSkBK / 16; ++ks) {
+    for (int ks = 0; ks < 4; ++ks) tr[ks] = *reinterpret_cast<const v4u_t*>(Th + we + k_begin + 16 * ks);
+    store_x(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += kSkBK, buf ^= 1) {
+        const bool more = k0 + kSkBK < k_end;
+        if (more) {
+            load_x(k0 + kSkBK);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) tn[ks] = *reinterpret_cast<const v4u_t*>(Th + we + k0 + kSkBK + 16 * ks);
+        }
+        const v4u_t* Xb = Xs + buf * (2 * MP * kSkKC);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            v4u_t wp, wm;
+            perturb_chunk<T>(a.key, p.tensor_id, we + (uint64_t)(k0 + 16 * ks), a.eps, tr[ks], wp, wm);
             const int kc = ks * 2 + kh;
-            v4u_t fb[2][2];
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+            for (int i = 0; i < MT; ++i) {
+                const int row = i * 32 + r, at = row * kSkKC + (kc ^ ((row >> 1) & 7));
+                acc[0][i] = SkMfma<T>::run(Xb[at], wp, acc[0][i]);
+                acc[1][i] = SkMfma<T>::run(Xb[MP * kSkKC + at], wm, acc[1][i]);
+            }
+        }
+        if (more) {
+            store_x(buf ^ 1);              // last read before the barrier that ended the previous slab
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int row = j * 32 + r;
-                    fb[s][j] = Ws[s * kSkBN * kSkKC + row * kSkKC + (kc ^ (row & 7))];
-                }
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int i = 0; i < MW; ++i) {
-                    const int row = wave * (32 * MW) + i * 32 + r;
-                    const v4u_t fa = Xs[s * MP * kSkKC + row * kSkKC + (kc ^ (row & 7))];
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) acc[s][i][j] = SkMfma<T>::run(fa, fb[s][j], acc[s][i][j]);
-                }
+            for (int ks = 0; ks < 4; ++ks) tr[ks] = tn[ks];
         }
         __syncthreads();
     }
 
-    // partial sums of this k slice: lane holds column n = r of each 32 x 32 tile and rows 8 (v / 4) + 4 kh + v % 4
+    // partial sums of this k slice: lane holds column n of each 32 x 32 tile and rows 8 (v / 4) + 4 kh + v % 4
+    if (n >= a.N) return;
     const size_t plane = (size_t)a.M * a.N;
     float* __restrict__ part = a.partial + ((size_t)blockIdx.z * a.splits + blockIdx.y) * 2 * plane;
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + j * 32 + r;
-            if (n >= a.N) continue;
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int i = 0; i < MW; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = wave * (32 * MW) + i * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
-                    if (m < a.M) part[s * plane + (size_t)m * a.N + n] = acc[s][i][j][v];
-                }
-        }
+            for (int v = 0; v < 16; ++v) {
+                const int m = i * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
+                if (m < a.M) part[s * plane + (size_t)m * a.N + n] = acc[s][i][v];
+            }
 }
 
 // Sum of the k slices in slice order, then bias, scale, ReLU, residual; four consecutive columns per thread.
@@ -181,8 +174,18 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyArgs a) 
     const int m = (int)(rem / n4), n = (int)(rem % n4) * 4;
     const size_t plane = (size_t)a.M * a.N;
     const float* part = a.partial + (size_t)blockIdx.y * a.splits * 2 * plane + (size_t)s * plane + (size_t)m * a.N + n;
-    v4f_t sum = *reinterpret_cast<const v4f_t*>(part);
-    for (int k = 1; k < a.splits; ++k) sum += *reinterpret_cast<const v4f_t*>(part + (size_t)k * 2 * plane);
+    // slice order; the loads of sixteen slices are in flight together (one after the other, a thread would wait out the
+    // memory latency once per slice, and so few threads run here that nothing else would hide it)
+    v4f_t sum = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < a.splits; k0 += 16) {
+        v4f_t t[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (k0 + j < a.splits) t[j] = *reinterpret_cast<const v4f_t*>(part + (size_t)(k0 + j) * 2 * plane);
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (k0 + j < a.splits) sum += t[j];
+    }
     const T* bias = reinterpret_cast<const T*>(s ? p.bias_m : p.bias_p);
     const float* res = s ? p.res_m : p.res_p;
     OutT* Y = reinterpret_cast<OutT*>(s ? p.Ym : p.Yp);
@@ -213,9 +216,14 @@ bool skinny_applicable(int M, int N, int K, int dtype) {
     return (dtype == ZO2_BF16 || dtype == ZO2_F16) && M >= 1 && M <= 256 && N >= 1 && N % 4 == 0 && K >= 64 && K % 64 == 0;
 }
 
-static void pick_splits(int N, int K, int nprob, int& splits, int& k_per_split) {
+// How many pieces the k range is cut into: enough workgroups to occupy the chip (about two per compute unit for up to
+// 32 rows, one above - measured on d_model 2048 shapes), but never more float32 partial sums than four times the bytes
+// of the weights themselves (a piece writes 2 M x 128 sums for the 128 x k_per_split weights it reads).
+static void pick_splits(int M, int N, int K, int nprob, int& splits, int& k_per_split) {
     const int n_tiles = (N + kSkBN - 1) / kSkBN, slabs = K / kSkBK;
-    int want = 512 / (n_tiles * nprob);                  // about two workgroups per compute unit
+    int want = (M <= 32 ? 512 : 256) / (n_tiles * nprob);
+    const int cap = K / M > 1 ? K / M : 1;
+    want = want > cap ? cap : want;
     want = want < 1 ? 1 : (want > slabs ? slabs : want);
     const int slabs_per = (slabs + want - 1) / want;
     k_per_split = slabs_per * kSkBK;
@@ -225,39 +233,34 @@ static void pick_splits(int N, int K, int nprob, int& splits, int& k_per_split) 
 size_t skinny_workspace_bytes(int M, int N, int K, int nprob) {
     if (M <= 0 || N <= 0 || K < kSkBK || nprob <= 0) return 0;
     int splits, kps;
-    pick_splits(N, K, nprob, splits, kps);
+    pick_splits(M, N, K, nprob, splits, kps);
     return (size_t)nprob * splits * 2 * (size_t)M * N * sizeof(float);
+}
+
+template <typename T, int MT>
+static zo2_status skinny_launch_mt(const SkinnyArgs& a, hipStream_t st) {
+    const dim3 grid((a.N + kSkBN - 1) / kSkBN, a.splits, a.nprob), block(256);
+    constexpr int lds = 2 * 2 * 32 * MT * kSkKC * 16;
+    static bool reserved = false;
+    auto kern = skinny_dual_kernel<T, MT>;
+    if (!reserved) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) {
+            set_op_error("skinny gemm: cannot reserve %d bytes of LDS", lds);
+            return ZO2_EHIP;
+        }
+        reserved = true;
+    }
+    hipLaunchKernelGGL(kern, grid, block, lds, st, a);
+    ZO2_HIP_LAUNCH_CHECK();
+    return ZO2_OK;
 }
 
 template <typename T>
 static zo2_status skinny_launch_t(const SkinnyArgs& a, hipStream_t st) {
-    const dim3 grid((a.N + kSkBN - 1) / kSkBN, a.splits, a.nprob), block(256);
-    if (a.M <= 128) {
-        constexpr int lds = (2 * 128 + 2 * kSkBN) * kSkKC * 16;
-        static bool set1 = false;
-        auto kern = skinny_dual_kernel<T, 1>;
-        if (!set1) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) {
-                set_op_error("skinny gemm: cannot reserve %d bytes of LDS", lds);
-                return ZO2_EHIP;
-            }
-            set1 = true;
-        }
-        hipLaunchKernelGGL(kern, grid, block, lds, st, a);
-    } else {
-        constexpr int lds = (2 * 256 + 2 * kSkBN) * kSkKC * 16;
-        static bool set2 = false;
-        auto kern = skinny_dual_kernel<T, 2>;
-        if (!set2) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) {
-                set_op_error("skinny gemm: cannot reserve %d bytes of LDS", lds);
-                return ZO2_EHIP;
-            }
-            set2 = true;
-        }
-        hipLaunchKernelGGL(kern, grid, block, lds, st, a);
-    }
-    ZO2_HIP_LAUNCH_CHECK();
+    const dim3 block(256);
+    zo2_status s = a.M <= 32 ? skinny_launch_mt<T, 1>(a, st) : a.M <= 64 ? skinny_launch_mt<T, 2>(a, st)
+                 : a.M <= 128 ? skinny_launch_mt<T, 4>(a, st) : skinny_launch_mt<T, 8>(a, st);
+    if (s != ZO2_OK) return s;
     const size_t work = 2 * (size_t)a.M * (a.N / 4);
     const dim3 rgrid((unsigned)((work + 255) / 256), a.nprob);
     if (a.out_f32) hipLaunchKernelGGL((skinny_reduce_kernel<T, float>), rgrid, block, 0, st, a);
@@ -282,7 +285,7 @@ zo2_status skinny_launch(SkinnyArgs& a, int dtype, void* workspace, size_t works
                      "skinny gemm: bias / residual must be given for both streams or neither");
         ZO2_OP_CHECK(!p.res_p || a.out_f32, ZO2_EINVAL, "skinny gemm: a residual needs float32 output");
     }
-    pick_splits(a.N, a.K, a.nprob, a.splits, a.k_per_split);
+    pick_splits(a.M, a.N, a.K, a.nprob, a.splits, a.k_per_split);
     const size_t need = (size_t)a.nprob * a.splits * 2 * (size_t)a.M * a.N * sizeof(float);
     ZO2_OP_CHECK(workspace && ((uintptr_t)workspace & 15) == 0 && workspace_bytes >= need, ZO2_EINVAL,
                  "skinny gemm: workspace of %zu bytes needed (16-byte aligned)", need);

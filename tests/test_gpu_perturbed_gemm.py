@@ -41,7 +41,7 @@ def test_loader_perturbation_has_the_bits_of_the_sweep_kernel_and_of_the_oracle(
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
-@pytest.mark.parametrize("M,N,K,res,relu", [(1, 64, 64, False, False), (19, 136, 192, True, False), (64, 2048, 2048, False, True),
+@pytest.mark.parametrize("M,N,K,res,relu", [(1, 64, 64, False, False), (19, 136, 192, True, False), (32, 128, 64, False, False), (33, 200, 448, True, True), (64, 2048, 2048, False, True),
                                             (100, 520, 8192, True, False), (128, 260, 256, False, False), (129, 64, 128, True, True),
                                             (256, 768, 3072, True, False), (200, 6144, 2048, False, False)])
 def test_perturbed_gemm_against_oracle_linear(dt, M, N, K, res, relu):

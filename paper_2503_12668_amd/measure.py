@@ -11,10 +11,11 @@ counter output into the traffic figures bench.py reports.
         copy (zo2_op_convert float32 -> float32: read 1, write 1), next to the perturbation alone (zo2_op_update_perturb
         with no update: read 1 / write 2, one Gaussian per element) and the fused update + perturb (read 1 / write 3,
         two Gaussians per element); GB/s of algorithmic bytes.
-    python3 paper_2503_12668_amd/measure.py small-steps [--model opt-1.3b] [--steps 20]
-        whole steps of few tokens (1 x 16 .. 1 x 512, 4 x 64, 8 x 64), resident bf16: ms per step with the perturbation
-        generated in the projections' loader switched off (the sweep writes W+ and W- for every tensor) and on, the
-        ratio, and the time the K1 and projection kernels take per step in each mode.
+    python3 paper_2503_12668_amd/measure.py small-steps [--model opt-1.3b] [--steps 20] [--shape BxS ...] [--only off|on]
+        whole steps of few tokens (default 1 x 16 .. 1 x 512, 4 x 64, 8 x 64), resident bf16: ms per step with the
+        perturbation generated in the projections' loader switched off (the sweep writes W+ and W- for every tensor)
+        and on, the ratio, and the time the K1 and projection kernels take per step in each mode.  --shape / --only
+        restrict the run to some shapes and one mode (for a profiler run).
     python3 paper_2503_12668_amd/measure.py copy
         three 1 GiB copies and nothing else: the calibration run for rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
     python3 paper_2503_12668_amd/measure.py traffic --fetch F.csv --write W.csv --cal-fetch CF.csv --cal-write CW.csv \\
@@ -128,11 +129,14 @@ def cmd_small_steps(args):
           flush=True)
     print("| batch x seq | off: ms | k1 | gemm | on: ms | k1 | gemm | off / on |", flush=True)
     print("|---|---|---|---|---|---|---|---|", flush=True)
-    for (B, S) in ((1, 16), (1, 64), (1, 128), (1, 256), (4, 64), (8, 64), (1, 512)):
+    shapes = [tuple(int(v) for v in sh.lower().split("x")) for sh in args.shape] if args.shape else \
+        [(1, 16), (1, 64), (1, 128), (1, 256), (4, 64), (8, 64), (1, 512)]
+    modes = {"off": (-1,), "on": (1,), None: (-1, 1)}[args.only]
+    for (B, S) in shapes:
         tok = si.make_tokens(cfg["vocab"], B, S, seed=2, dist="zipf")
         lab = si.next_token_labels(tok)
         row = []
-        for mode in (-1, 1):
+        for mode in modes:
             ctx.set_loader_fusion(mode)
             for j in range(3):
                 ctx.step(tok, lab, 42 + j, 1e-3, 1e-7)
@@ -152,6 +156,10 @@ def cmd_small_steps(args):
                         acc[k] += m / 5
             ctx.set_profiling(())
             row.append((ms, acc["k1"], acc["gemm"], active))
+        if len(row) == 1:
+            m, k, g, a = row[0]
+            print(f"| {B} x {S} | {args.only}{'' if a or args.only == 'off' else ' (not applicable)'}: {m:.2f} | {k:.2f} | {g:.2f} |", flush=True)
+            continue
         (m0, k0, g0, a0), (m1, k1, g1, a1) = row
         on = f"{m1:.2f} | {k1:.2f} | {g1:.2f}" if a1 else "not applicable | | "
         print(f"| {B} x {S} | {m0:.2f} | {k0:.2f} | {g0:.2f} | {on} | {m0 / m1:.2f} |", flush=True)
@@ -234,6 +242,8 @@ def main():
     ss.add_argument("--model", default="opt-1.3b")
     ss.add_argument("--steps", type=int, default=20)
     ss.add_argument("--arena-gib", type=int, default=20)
+    ss.add_argument("--shape", action="append", help="BxS, e.g. 1x16 (repeatable)")
+    ss.add_argument("--only", choices=["off", "on"], default=None)
     t = sub.add_parser("traffic")
     for k in ("fetch", "write", "cal-fetch", "cal-write", "out"):
         t.add_argument("--" + k, required=True)

@@ -188,6 +188,35 @@ def offload_leg(steps=3, budget_legs=True):
             "streamed_over_resident_at_32x512": str32["ms_per_step"] / res32["ms_per_step"], "steps": steps}
 
 
+def small_steps_leg(ctx, cfg, steps=10):
+    """Steps of few tokens on the benchmark's resident context: the perturbation written by the sweep kernel (as in the
+    benchmark step) against generated in the projections' weight loader (what the library does by default up to 128
+    tokens per stream).  ms per step, wall clock around `steps` steps each."""
+    import torch
+
+    import synth_inputs as si
+    out = {"note": "same resident bf16 context; 'sweep_copies' = zo2_set_loader_fusion(-1), 'loader' = the default", "steps": steps}
+    for (b, s_) in ((1, 16), (1, 128)):
+        tok = si.make_tokens(cfg["vocab"], b, s_, seed=2, dist="zipf")
+        lab = si.next_token_labels(tok)
+        row = {}
+        for name, mode in (("sweep_copies", -1), ("loader", 0)):
+            ctx.set_loader_fusion(mode)
+            for j in range(2):
+                ctx.step(tok, lab, SEED0 + 500 + j, EPS, LR)
+            row[name + "_active"] = ctx.plan()["loader_fusion"]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for j in range(steps):
+                ctx.step(tok, lab, SEED0 + 510 + j, EPS, LR)
+            torch.cuda.synchronize()
+            row["ms_per_step_" + name] = (time.perf_counter() - t0) / steps * 1e3
+        row["ratio"] = row["ms_per_step_sweep_copies"] / row["ms_per_step_loader"]
+        out[f"{b}x{s_}"] = row
+    ctx.set_loader_fusion(0)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,6 +224,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offload", action="store_true", help="skip the streamed (offload-mode) leg")
+    ap.add_argument("--no-small-steps", action="store_true", help="skip the leg with steps of 16 and 128 tokens")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -284,6 +314,8 @@ def main():
                                "note": "from a second pass of the same number of steps with HIP events around every launch",
                                "ms_per_step_with_events": ms_step_profiled},
     }
+    if not args.no_small_steps:
+        out["small_steps"] = small_steps_leg(ctx, cfg)
     ctx.close()
     del ctx
     torch.cuda.empty_cache()

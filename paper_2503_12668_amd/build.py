@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzo2.so")
+LIB_HOSTSAN = os.path.join(HERE, "libzo2_hostsan.so")     # same device code, host code under UndefinedBehaviorSanitizer (a test aid)
 
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result",
                # keep the compiler from forming packed-fp32 instructions
@@ -110,5 +111,43 @@ def build(force=False, verbose=True):
     return LIB
 
 
+def build_host_sanitized(verbose=True):
+    """libzo2_hostsan.so: the same sources and device code, the host side compiled with -fsanitize=undefined (and bounds),
+    not recovering: the first finding ends the process.  A test aid (tests/test_host_sanitizer.py loads it in a child
+    process); device code cannot be sanitized on the test machines, host code can."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    rt = sorted(glob.glob("/opt/rocm*/lib/llvm/lib/clang/*/lib/linux/libclang_rt.ubsan_standalone-x86_64.so"))
+    if not rt:
+        raise RuntimeError("no shared UndefinedBehaviorSanitizer runtime under /opt/rocm*/lib/llvm")
+    rt_dir = os.path.dirname(os.path.realpath(rt[-1]))
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    bdir = os.path.join(HERE, "_build", "hostsan")
+    os.makedirs(bdir, exist_ok=True)
+    # (without the indirect-call check: under -fsanitize=function a kernel launched through a function-pointer variable,
+    # as the two kernels with dynamic LDS are, is pushed but never launched by this toolchain's host stub)
+    san = ["-g1", "-Xarch_host", "-fsanitize=undefined,bounds", "-Xarch_host", "-fno-sanitize=function",
+           "-Xarch_host", "-fno-sanitize-recover=undefined,bounds"]
+    objs, procs = [], []
+    for s in srcs:
+        o = os.path.join(bdir, os.path.basename(s) + ".o")
+        objs.append(o)
+        cmd = [hipcc] + HIPCC_FLAGS + san + ["-c", s, "-o", o]
+        if verbose:
+            print("[build]", " ".join(cmd), flush=True)
+        procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for s, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {s}\n{out}")
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-fsanitize=undefined", "-shared-libsan", "-Wno-option-ignored",
+           "-Wl,-rpath," + rt_dir, "-o", LIB_HOSTSAN] + objs
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return LIB_HOSTSAN
+
+
 if __name__ == "__main__":
     build(force="--force" in sys.argv)
+    if "--host-sanitize" in sys.argv:
+        build_host_sanitized()

@@ -106,7 +106,7 @@ def test_update_perturb_window(wire, compute, scale, pending):
 
 def test_update_only_and_small_windows():
     b = _b()
-    for n in (1, 7, 8, 9, 2048, 8192, 8193):
+    for n in (1, 7, 8, 9, 2040, 2048, 2049, 4095, 8192, 8193):
         raw = (np.random.default_rng(n).standard_normal(n) * 0.02).astype(np.float32)
         t = torch.from_numpy(raw.copy()).cuda()
         b.op_update_perturb(t, None, None, 3, 0, True, 5, 1e-3, 0, 0.0)

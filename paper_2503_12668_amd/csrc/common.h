@@ -167,6 +167,15 @@ __device__ __forceinline__ bf16_t store_stochastic<bf16_t>(float x, uint32_t r16
 }
 
 // A group of N elements moved with one (or two) wide memory operations.
+// One-time, per-device set-up (a kernel's LDS reservation, the compute-unit count) keeps its flags in arrays indexed by
+// the current device: a process may hold contexts on several GPUs.
+static constexpr int kMaxDevices = 64;
+inline int current_device() {
+    int d = 0;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
+    return d;
+}
+
 template <typename T, int N>
 struct alignas(sizeof(T) * N) Vec {
     T v[N];

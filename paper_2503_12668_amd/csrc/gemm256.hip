@@ -548,18 +548,19 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 }
 
 static int device_cu_count() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
-        else n = 256;
+    static int n[kMaxDevices] = {0};
+    const int dev = current_device();
+    if (n[dev] == 0) {
+        int v = 0;
+        n[dev] = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
     }
-    return n;
+    return n[dev];
 }
 
 template <typename T, typename OutT, int MI>
 static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
-    static bool attr_set = false;
+    static bool attr_set_on[kMaxDevices] = {false};
+    bool& attr_set = attr_set_on[current_device()];
     constexpr int BM = Tile256<MI>::BM, lds = Tile256<MI>::kLdsBytes;
     auto kern = gemm_mfma256_kernel<T, OutT, MI>;
     if (!attr_set) {

@@ -241,7 +241,8 @@ template <typename T, int MT>
 static zo2_status skinny_launch_mt(const SkinnyArgs& a, hipStream_t st) {
     const dim3 grid((a.N + kSkBN - 1) / kSkBN, a.splits, a.nprob), block(256);
     constexpr int lds = 2 * 2 * 32 * MT * kSkKC * 16;
-    static bool reserved = false;
+    static bool reserved_on[kMaxDevices] = {false};
+    bool& reserved = reserved_on[current_device()];
     auto kern = skinny_dual_kernel<T, MT>;
     if (!reserved) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) {

@@ -4,7 +4,8 @@
         --slots 3 --steps 5
 
 Weights are synthetic (N(0, 0.02), LayerNorm gain 1 / bias 0), generated on the GPU with torch's generator
-and copied to pinned host buckets in the transfer format.  --slots N caps the HBM budget so that exactly N
+and copied to pinned host buckets in the transfer format (--no-pin: pageable ones, for fully resident runs of the
+larger shapes: the host copy is then only read once, at set-up).  --slots N caps the HBM budget so that exactly N
 blocks fit (streamed mode, Alg. 3); --budget-bytes sets the cap directly; neither = everything resident.
 --layers trims the depth (per-block numbers stay those of the full-width model)."""
 import argparse
@@ -49,6 +50,7 @@ def main():
     ap.add_argument("--directions", type=int, default=1, help="directions per update (1 = the paper's estimator; q > 1: one step + q - 1 extra directions per round, eta / q each)")
     ap.add_argument("--no-overlap", action="store_true", help="ablation: upload, compute, offload of a block strictly in sequence")
     ap.add_argument("--flush-each-step", action="store_true", help="ablation: no deferred update (every block travels twice per step)")
+    ap.add_argument("--no-pin", action="store_true", help="pageable host buckets: for fully resident runs of models whose buckets exceed what the box lets a process pin")
     args = ap.parse_args()
 
     import numpy as np
@@ -71,7 +73,7 @@ def main():
     arena = int(args.arena_gb * 2 ** 30) if args.arena_gb else None
     if arena is None and (args.slots or args.budget_bytes):
         arena = int(args.budget_bytes) if args.budget_bytes else 64 << 30
-    ctx = binding.Zo2Context(cfg, gpu_weight_source(), wire=args.wire, compute=args.compute, arena_bytes=arena, scales=scales)
+    ctx = binding.Zo2Context(cfg, gpu_weight_source(), wire=args.wire, compute=args.compute, arena_bytes=arena, scales=scales, pin=not args.no_pin)
     setup_s = time.time() - t0
     if args.budget_bytes:
         ctx.set_resident_budget(int(args.budget_bytes))

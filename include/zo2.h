@@ -209,6 +209,11 @@ zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t sweeps);
 zo2_status zo2_set_loader_fusion(zo2_ctx* ctx, int32_t mode);
 /* *active = 1 if the last plan lets the projections perturb in their loader. */
 zo2_status zo2_get_loader_fusion(const zo2_ctx* ctx, int32_t* active);
+/* Split-k of the block projections (Alg. 2 "forward"; a launch-shape decision, not part of the method).  mode 0 (default):
+ * a projection whose tiles would occupy at most half of the compute units - few tokens per stream - is cut into 2 or 4
+ * pieces along k that run side by side into float32 partial sums, added in piece order by a second kernel (deterministic;
+ * results differ from the unsplit launch by float32 rounding order only).  mode -1: never.  Takes effect at the next step. */
+zo2_status zo2_set_split_k(zo2_ctx* ctx, int32_t mode);
 
 /* Per-stream busy time of the last step in milliseconds (compute, upload, offload) and the
  * bytes copied each way; for host-link rate reporting.  Any pointer may be NULL. */
@@ -312,6 +317,16 @@ zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K,
                        const float* residual, void* Y, int32_t out_dtype, int64_t ldy,
                        float out_scale, int32_t relu, void* stream);
 
+/* zo2_op_gemm with the k range cut into `splits` (2 or 4) pieces: the pieces run as one launch into float32 partial sums
+ * in `workspace` (device, 16-byte aligned, zo2_op_gemm_split_k_workspace_bytes(M, N, splits) bytes, overwritten), a second
+ * kernel adds them in piece order and applies bias, scale, ReLU and residual.  16-bit dtypes; N % 4 == 0, ldy % 4 == 0,
+ * K % (8 splits) == 0.  zo2_op_gemm_split_k_pieces: the number of pieces (1, 2 or 4) zo2_step would use for a launch of `nprob`
+ * problems of this shape.  ZO2_EINVAL on anything else. */
+zo2_status zo2_op_gemm_split_k(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                               const void* bias, const float* residual, void* Y, int32_t out_dtype, int64_t ldy, float out_scale,
+                               int32_t relu, int32_t splits, void* workspace, size_t workspace_bytes, void* stream);
+size_t zo2_op_gemm_split_k_workspace_bytes(int32_t M, int32_t N, int32_t splits);
+int32_t zo2_op_gemm_split_k_pieces(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t nprob);
 /* The same projection for both perturbation streams at once, with the perturbation generated in the weight loader
  * (Alg. 2 "perturb" folded into the forward; for steps of few tokens, where the projections are bound by reading the
  * weights): Y+- [M, N] = act( (X+- [M, K] . (theta +- eps z)^T + bias+-) * out_scale ) + residual+-, where theta [N, K]

@@ -77,6 +77,7 @@ def lib():
         "zo2_set_scratch_plan": (i32, [vp, i32]),
         "zo2_set_loader_fusion": (i32, [vp, i32]),
         "zo2_get_loader_fusion": (i32, [vp, C.POINTER(i32)]),
+        "zo2_set_split_k": (i32, [vp, i32]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
         "zo2_set_stream_overlap": (i32, [vp, i32]),
@@ -93,6 +94,9 @@ def lib():
         "zo2_op_update_perturb_block": (i32, [C.POINTER(Config), i32, vp, vp, vp, i32, u64, f32, u64, f32, C.POINTER(f32), i32, vp]),
         "zo2_op_convert": (i32, [vp, i32, f32, vp, i32, f32, u64, vp]),
         "zo2_op_gemm": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, vp]),
+        "zo2_op_gemm_split_k": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, vp, i32, i64, f32, i32, i32, vp, C.c_size_t, vp]),
+        "zo2_op_gemm_split_k_workspace_bytes": (C.c_size_t, [i32, i32, i32]),
+        "zo2_op_gemm_split_k_pieces": (i32, [i32, i32, i32, i32, i32]),
         "zo2_op_set_gemm_tile_rows": (i32, [i32]),
         "zo2_op_gemm_perturbed": (i32, [i32, i32, i32, i32, vp, vp, i64, vp, u32, u64, f32, vp, vp, vp, vp, vp, vp, i32, i64, f32, i32, vp, C.c_size_t, vp]),
         "zo2_op_gemm_perturbed_workspace_bytes": (C.c_size_t, [i32, i32, i32]),
@@ -114,8 +118,8 @@ def lib():
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
-            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_set_gemm_tile_rows", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_set_split_k", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_gemm_split_k", "zo2_op_gemm_split_k_workspace_bytes", "zo2_op_gemm_split_k_pieces", "zo2_op_set_gemm_tile_rows", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
 
@@ -209,6 +213,22 @@ def op_gemm(X, W, bias=None, residual=None, out_dtype=None, out_scale=1.0, relu=
     _op_check(lib().zo2_op_gemm(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(residual),
                                 _ptr(Y), odt, Y.stride(0), out_scale, 1 if relu else 0, _stream_ptr(stream)))
     return Y
+
+
+def op_gemm_split_k(X, W, splits, bias=None, residual=None, out_dtype=None, out_scale=1.0, relu=False, stream=None):
+    M, K = X.shape
+    N = W.shape[0]
+    odt = _dt(X) if out_dtype is None else out_dtype
+    Y = torch.empty(M, N, dtype=TORCH_DTYPE[odt], device="cuda")
+    nbytes = lib().zo2_op_gemm_split_k_workspace_bytes(M, N, splits)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    _op_check(lib().zo2_op_gemm_split_k(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(residual),
+                                        _ptr(Y), odt, Y.stride(0), out_scale, 1 if relu else 0, splits, _ptr(ws), nbytes, _stream_ptr(stream)))
+    return Y
+
+
+def op_gemm_split_k_pieces(dtype_id, M, N, K, nprob):
+    return int(lib().zo2_op_gemm_split_k_pieces(dtype_id, M, N, K, nprob))
 
 
 def op_gemm_perturbed(Xp, Xm, theta, tensor_id, seed, eps, bias_p=None, bias_m=None, res_p=None, res_m=None, out_dtype=None,
@@ -465,6 +485,10 @@ class Zo2Context:
     def set_loader_fusion(self, mode):
         """0: the projections perturb in their weight loader for steps of few tokens; 1: whenever possible; -1: never."""
         self._check(lib().zo2_set_loader_fusion(self.handle, int(mode)))
+
+    def set_split_k(self, mode):
+        """0: projections that would leave most compute units idle are split along k; -1: never."""
+        self._check(lib().zo2_set_split_k(self.handle, int(mode)))
 
     def set_scratch_plan(self, sweeps):
         """1, 2 or 4 update + perturb sweeps per block (W+ / W- scratch for a whole block, a half, a tensor group);

@@ -22,7 +22,7 @@ struct GemmProblem {
 };
 
 struct GemmArgs {
-    static constexpr int kMaxProblems = 6;
+    static constexpr int kMaxProblems = 12;      // q/k/v x two streams x two k pieces
     int32_t M, N, K;
     int64_t ldx, ldw, ldy;
     int64_t part_ld;        // cross-entropy mode: elements between consecutive spans of the partial arrays (>= M)
@@ -37,6 +37,13 @@ struct GemmArgs {
 zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st);
 // the 256 x 256 x 64 kernel (bf16 / fp16, K % 128 == 0); gemm_launch picks it for large problems
 zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st);
+// Split-k for launches that leave most compute units idle (few rows per stream): each problem is cut into `splits` pieces
+// of K / splits along k, the pieces run as problems of their own into float32 partial sums
+// ([nprob][splits][M][N] in `workspace`), and a second kernel adds a problem's pieces in order (deterministic) and applies
+// bias, scale, ReLU and residual.  gemm_pick_splits: 1 (do not split), 2 or 4 for a launch of `nprob` problems.
+int gemm_pick_splits(int M, int N, int K, int nprob, int dtype);
+size_t gemm_splitk_workspace_bytes(int M, int N, int nprob, int splits);
+zo2_status gemm_launch_splitk(const GemmArgs& a, int dtype, int splits, void* workspace, size_t workspace_bytes, hipStream_t st);
 // 0 (default): the 256 x 256 kernel picks 256- or 128-row tiles per launch; 128 / 256: every launch uses that height
 void gemm256_force_tile_rows(int rows);
 bool gemm256_applicable(const GemmArgs& a, int dtype);

@@ -9,6 +9,8 @@
 //
 // The +/- streams (and q, k, v) are independent problems of one shape: they share a launch
 // through grid.z so that even the narrow projections fill 256 compute units.
+#include <string.h>
+
 #include "gemm.h"
 
 namespace zo2 {
@@ -343,6 +345,106 @@ zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st) {
     if (dtype == ZO2_F16) return launch_mfma<f16_t>(a, st);
     set_op_error("gemm: dtype %d is not a compute dtype", dtype);
     return ZO2_EINVAL;
+}
+
+
+// ---------------------------------------------------------------------------------------- split-k
+// With few rows per stream a projection has a handful of tiles for 256 compute units (attention output and FC2 of a
+// d_model 2048 block at 512 tokens per stream: 64 tiles of 128 rows).  The k range is then cut into 2 or 4 pieces that
+// run as problems of their own - the kernels take a list of problems of one shape - and a small second kernel sums a
+// problem's pieces in piece order and finishes the values.
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a, const float* __restrict__ part, int splits) {
+    const int n4 = a.N >> 2;
+    const size_t gi = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gi >= (size_t)a.M * n4) return;
+    const GemmProblem p = a.p[blockIdx.y];
+    const int m = (int)(gi / n4), n = (int)(gi % n4) * 4;
+    const size_t plane = (size_t)a.M * a.N;
+    const float* src = part + (size_t)blockIdx.y * splits * plane + (size_t)m * a.N + n;
+    v4f_t t[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (k < splits) t[k] = *reinterpret_cast<const v4f_t*>(src + (size_t)k * plane);
+    v4f_t sum = t[0];
+#pragma unroll
+    for (int k = 1; k < 4; ++k)
+        if (k < splits) sum += t[k];
+    const T* bias = reinterpret_cast<const T*>(p.bias);
+    OutT* Y = reinterpret_cast<OutT*>(p.Y);
+    const size_t o = (size_t)m * a.ldy + n;
+    Vec<OutT, 4> out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float y = (sum[e] + (bias ? Fmt<T>::load(bias[n + e]) : 0.f)) * p.out_scale;
+        if (a.relu) y = fmaxf(y, 0.f);
+        if (p.residual) y += p.residual[o + e];
+        out.v[e] = Fmt<OutT>::store(y);
+    }
+    store_vec<OutT, 4>(Y + o, out);
+}
+
+int gemm_pick_splits(int M, int N, int K, int nprob, int dtype) {
+    if (!(dtype == ZO2_BF16 || dtype == ZO2_F16) || M <= 0 || N <= 0 || N % 4 != 0 || nprob <= 0) return 1;
+    const long tiles = (long)nprob * ((M + 127) / 128) * ((N + 255) / 256);       // the large kernel's 128-row tiles
+    const long cu = 256;
+    int s = 1;
+    // double while the doubled launch still has room on the chip, the pieces stay at least 512 long (eight k-slabs of the
+    // large kernel) and multiples of 128, and the problem list holds them
+    while (s < 4 && tiles * s * 2 <= cu && K % (2 * s * 128) == 0 && K / (2 * s) >= 512 && nprob * 2 * s <= GemmArgs::kMaxProblems) s *= 2;
+    return s;
+}
+
+size_t gemm_splitk_workspace_bytes(int M, int N, int nprob, int splits) {
+    return splits > 1 ? (size_t)nprob * splits * (size_t)M * N * sizeof(float) : 0;
+}
+
+template <typename T>
+static void launch_splitk_reduce(const GemmArgs& a, const float* part, int splits, hipStream_t st) {
+    const size_t work = (size_t)a.M * (a.N / 4);
+    const dim3 grid((unsigned)((work + 255) / 256), a.nprob), block(256);
+    if (a.out_f32) hipLaunchKernelGGL((splitk_reduce_kernel<T, float>), grid, block, 0, st, a, part, splits);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<T, T>), grid, block, 0, st, a, part, splits);
+}
+
+zo2_status gemm_launch_splitk(const GemmArgs& a, int dtype, int splits, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    if (splits <= 1) return gemm_launch(a, dtype, st);
+    ZO2_OP_CHECK(dtype == ZO2_BF16 || dtype == ZO2_F16, ZO2_EINVAL, "gemm split-k: 16-bit compute formats only");
+    ZO2_OP_CHECK(!a.ce_mode, ZO2_EINVAL, "gemm split-k: not with the cross-entropy epilogue");
+    ZO2_OP_CHECK(splits == 2 || splits == 4, ZO2_EINVAL, "gemm split-k: %d pieces (2 or 4)", splits);
+    ZO2_OP_CHECK(a.M > 0 && a.N > 0 && a.N % 4 == 0 && a.ldy % 4 == 0 && a.K % (splits * 8) == 0, ZO2_EINVAL,
+                 "gemm split-k: bad shape %d x %d x %d for %d pieces", a.M, a.N, a.K, splits);
+    ZO2_OP_CHECK(a.nprob >= 1 && a.nprob * splits <= GemmArgs::kMaxProblems, ZO2_EINVAL, "gemm split-k: %d problems x %d pieces", a.nprob, splits);
+    const size_t need = gemm_splitk_workspace_bytes(a.M, a.N, a.nprob, splits);
+    ZO2_OP_CHECK(workspace && ((uintptr_t)workspace & 15) == 0 && workspace_bytes >= need, ZO2_EINVAL,
+                 "gemm split-k: workspace of %zu bytes needed (16-byte aligned)", need);
+    const size_t osz = a.out_f32 ? 4 : 2;
+    for (int i = 0; i < a.nprob; ++i) {
+        ZO2_OP_CHECK(a.p[i].X && a.p[i].W && a.p[i].Y, ZO2_EINVAL, "gemm split-k: NULL operand in problem %d", i);
+        ZO2_OP_CHECK(((uintptr_t)a.p[i].Y & (4 * osz - 1)) == 0 && ((uintptr_t)a.p[i].residual & 15) == 0 && ((uintptr_t)a.p[i].bias & 7) == 0,
+                     ZO2_EINVAL, "gemm split-k: output, residual and bias must be aligned to 4 elements");
+        ZO2_OP_CHECK(!a.p[i].residual || a.out_f32, ZO2_EINVAL, "gemm split-k: a residual needs float32 output");
+    }
+    float* part = reinterpret_cast<float*>(workspace);
+    const size_t plane = (size_t)a.M * a.N, esz = 2;
+    const int kp = a.K / splits;
+    GemmArgs e;
+    memset(&e, 0, sizeof(e));
+    e.M = a.M; e.N = a.N; e.K = kp; e.ldx = a.ldx; e.ldw = a.ldw; e.ldy = a.N; e.relu = 0; e.out_f32 = 1; e.nprob = a.nprob * splits;
+    for (int i = 0; i < a.nprob; ++i)
+        for (int k = 0; k < splits; ++k) {
+            GemmProblem& q = e.p[i * splits + k];
+            q.X = reinterpret_cast<const char*>(a.p[i].X) + (size_t)k * kp * esz;
+            q.W = reinterpret_cast<const char*>(a.p[i].W) + (size_t)k * kp * esz;
+            q.Y = part + ((size_t)i * splits + k) * plane;
+            q.out_scale = 1.0f;
+        }
+    zo2_status s = gemm_launch(e, dtype, st);
+    if (s != ZO2_OK) return s;
+    if (dtype == ZO2_BF16) launch_splitk_reduce<bf16_t>(a, part, splits, st);
+    else launch_splitk_reduce<f16_t>(a, part, splits, st);
+    ZO2_HIP_LAUNCH_CHECK();
+    return ZO2_OK;
 }
 
 }  // namespace zo2

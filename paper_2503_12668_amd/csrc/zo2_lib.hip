@@ -134,6 +134,7 @@ struct zo2_ctx {
     int pb[5];                          // sweep p, issued at point p of the block's forward, covers tensors pb[p] .. pb[p + 1] - 1 (may be empty)
     int scratch_plan_forced;            // 0: the planner chooses; 1 / 2 / 4: that many sweeps per block
     int loader_fusion;                  // 0: for few tokens per step (kFuseMaxTokens); 1: whenever the shapes allow; -1: never
+    int split_k;                        // 0: projections that leave most compute units idle are split along k; -1: never
     bool fuse;                          // this plan: the projections of a block perturb in their weight loader (step passes only)
     char* sk_ws;                        // their workspace (float32 partial sums of the k slices)
     size_t sk_ws_bytes;
@@ -399,6 +400,7 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->sweeps = 1;
     c->scratch_plan_forced = 0;
     c->loader_fusion = 0;
+    c->split_k = 0;
     c->fuse = false;
     c->scratch_elems = 0;
     *out = c;   // from here on errors are reported through the context
@@ -513,6 +515,13 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     if (fuse) {
         sk_ws_bytes = std::max(std::max(skinny_workspace_bytes(T, (int)d, (int)d, 3), skinny_workspace_bytes(T, (int)d, (int)d, 1)),
                                std::max(skinny_workspace_bytes(T, (int)f, (int)d, 1), skinny_workspace_bytes(T, (int)d, (int)f, 1)));
+    }
+    if (c->split_k >= 0 && g.compute_dtype != ZO2_F32) {      // split-k partial sums of the block projections (steps and single forwards)
+        for (int ns_ = 1; ns_ <= 2; ++ns_) {
+            const int shapes[4][3] = {{(int)d, (int)d, 3 * ns_}, {(int)d, (int)d, ns_}, {(int)f, (int)d, ns_}, {(int)d, (int)f, ns_}};      // N, K, problems
+            for (const auto& sh : shapes)
+                sk_ws_bytes = std::max(sk_ws_bytes, gemm_splitk_workspace_bytes(T, sh[0], sh[2], gemm_pick_splits(T, sh[0], sh[1], sh[2], g.compute_dtype)));
+        }
     }
     size_t act = 0;
     auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
@@ -657,6 +666,15 @@ extern "C" zo2_status zo2_set_loader_fusion(zo2_ctx* c, int32_t mode) {
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_set_split_k(zo2_ctx* c, int32_t mode) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (mode < -1 || mode > 0) return fail(c, ZO2_EINVAL, "zo2_set_split_k: mode %d (-1 or 0)", mode);
+    c->split_k = mode;
+    c->need_plan = true;   // re-plan at the next step
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_loader_fusion(const zo2_ctx* c, int32_t* active) {
     if (!c || !active) return ZO2_EINVAL;
     *active = (c->planned && c->fuse) ? 1 : 0;
@@ -794,6 +812,15 @@ static zo2_status earlier_updates_block(zo2_ctx* c, int l, char* bucket, hipStre
 }
 
 // ---------------------------------------------------------------------------------- block forward
+// A block projection: split along k when the launch would leave most compute units idle (few rows per stream)
+static zo2_status block_gemm(zo2_ctx* c, const GemmArgs& ga) {
+    const int dt = c->cfg.compute_dtype;
+    const int splits = c->split_k >= 0 ? gemm_pick_splits(ga.M, ga.N, ga.K, ga.nprob, dt) : 1;
+    if (splits > 1 && gemm_splitk_workspace_bytes(ga.M, ga.N, ga.nprob, splits) <= c->sk_ws_bytes)
+        return gemm_launch_splitk(ga, dt, splits, c->sk_ws, c->sk_ws_bytes, c->sc);
+    return gemm_launch(ga, dt, c->sc);
+}
+
 struct PhaseView {       // where tensor k's perturbed copies are inside the scratch
     const zo2_ctx* c;
     int64_t off0;
@@ -843,7 +870,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
             p.Y = outs[t] + s * half_d;
             p.out_scale = t == 0 ? 1.0f / sqrtf((float)dh) : 1.0f;
         }
-    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, block_gemm(c, ga));
     OPK(c, ZO2_KC_ATTN, attention_launch(dt, c->qb, c->kb, c->vb, c->ctxb, ns * batch, seq, g.n_heads, dh, d, 0, c->sc));
     { zo2_status s = phase(1); if (s != ZO2_OK) return s; }
     w = view(1);
@@ -854,7 +881,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->ctxb + s * half_d; p.W = s ? w.M(8) : w.P(8); p.bias = s ? w.M(9) : w.P(9);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
     }
-    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, block_gemm(c, ga));
 
     // ---- FFN half: h += FC2(ReLU(FC1(LN2(h))))
     { zo2_status s = phase(2); if (s != ZO2_OK) return s; }
@@ -867,7 +894,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->x + s * half_d; p.W = s ? w.M(12) : w.P(12); p.bias = s ? w.M(13) : w.P(13);
         p.residual = nullptr; p.Y = c->mid + s * half_f; p.out_scale = 1.0f;
     }
-    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, block_gemm(c, ga));
     { zo2_status s = phase(3); if (s != ZO2_OK) return s; }
     w = view(3);
     memset(&ga, 0, sizeof(ga));
@@ -877,7 +904,7 @@ static zo2_status block_forward(zo2_ctx* c, int l, char* bucket, int batch, int 
         p.X = c->mid + s * half_f; p.W = s ? w.M(14) : w.P(14); p.bias = s ? w.M(15) : w.P(15);
         p.residual = c->h + (size_t)s * T * d; p.Y = c->h + (size_t)s * T * d; p.out_scale = 1.0f;
     }
-    OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+    OPK(c, ZO2_KC_GEMM, block_gemm(c, ga));
     return ZO2_OK;
 }
 
@@ -1423,6 +1450,22 @@ extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K
     a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldw = ldw; a.ldy = ldy; a.relu = relu; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1;
     a.p[0].X = X; a.p[0].W = W; a.p[0].bias = bias; a.p[0].residual = residual; a.p[0].Y = Y; a.p[0].out_scale = out_scale;
     return gemm_launch(a, dtype, as_stream(stream));
+}
+
+extern "C" size_t zo2_op_gemm_split_k_workspace_bytes(int32_t M, int32_t N, int32_t splits) { return gemm_splitk_workspace_bytes(M, N, 1, splits); }
+
+extern "C" int32_t zo2_op_gemm_split_k_pieces(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t nprob) { return gemm_pick_splits(M, N, K, nprob, dtype); }
+
+extern "C" zo2_status zo2_op_gemm_split_k(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                                          const void* bias, const float* residual, void* Y, int32_t out_dtype, int64_t ldy, float out_scale,
+                                          int32_t relu, int32_t splits, void* workspace, size_t workspace_bytes, void* stream) {
+    if (M == 0 || N == 0) return ZO2_OK;
+    ZO2_OP_CHECK(out_dtype == ZO2_F32 || out_dtype == dtype, ZO2_EINVAL, "gemm: output dtype must be F32 or the input dtype");
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldw = ldw; a.ldy = ldy; a.relu = relu; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1;
+    a.p[0].X = X; a.p[0].W = W; a.p[0].bias = bias; a.p[0].residual = residual; a.p[0].Y = Y; a.p[0].out_scale = out_scale;
+    return gemm_launch_splitk(a, dtype, splits, workspace, workspace_bytes, as_stream(stream));
 }
 
 extern "C" size_t zo2_op_gemm_perturbed_workspace_bytes(int32_t M, int32_t N, int32_t K) { return skinny_workspace_bytes(M, N, K, 1); }

@@ -118,7 +118,7 @@ def test_attention_against_float64(dt, n_seq, seq, H, dh, vector_kernel):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,d", [(5, 32), (64, 768), (9, 2048), (6, 5120), (3, 12288), (2, 16384)])
+@pytest.mark.parametrize("rows,d", [(5, 32), (64, 768), (9, 2048), (7, 2056), (6, 5120), (5, 7168), (4, 9216), (3, 12288), (3, 12296), (2, 16384), (3, 1028)])
 def test_layernorm_two_parameter_sets(dt, rows, d):
     b = _b()
     g = torch.Generator().manual_seed(d)

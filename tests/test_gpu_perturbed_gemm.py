@@ -96,6 +96,42 @@ def test_perturbed_gemm_equals_the_ordinary_path_and_is_deterministic():
     assert not torch.equal(Yp, Ym)
 
 
+@pytest.mark.parametrize("M,N,K,layer,k", [(48, 5120, 5120, 39, 2), (48, 20480, 5120, 39, 12), (48, 5120, 20480, 39, 14),
+                                           (16, 49152, 12288, 95, 12), (16, 12288, 49152, 95, 14), (128, 7168, 7168, 47, 8)])
+def test_perturbed_gemm_sampled_columns_at_the_13b_30b_175b_widths(M, N, K, layer, k):
+    """Projections of the larger shapes (whole weight matrices of OPT-13B / 30B / 175B blocks, their real tensor ids): 96
+    sampled output features, each against the oracle - z and the rounding of W+- from the oracle for that feature's row
+    of the matrix (element offset n K inside the tensor), the dot products in float64."""
+    b = _b()
+    tid, seed, eps = 2 + 16 * layer + k, 77, 1e-3
+    g = torch.Generator(device="cuda").manual_seed(N + K)
+    theta = torch.empty(N, K, device="cuda", dtype=torch.bfloat16)
+    step = max(1, (64 << 20) // K)
+    for r0 in range(0, N, step):
+        theta[r0:r0 + step] = (torch.randn(min(step, N - r0), K, device="cuda", generator=g) * 0.02).bfloat16()
+    Xp = (torch.randn(M, K, device="cuda", generator=g) * 0.5).bfloat16()
+    Xm = (torch.randn(M, K, device="cuda", generator=g) * 0.5).bfloat16()
+    bias = (torch.randn(N, device="cuda", generator=g) * 0.1).bfloat16()
+    Yp, Ym = b.op_gemm_perturbed(Xp, Xm, theta, tid, seed, eps, bias, bias, out_dtype=b.F32)
+    torch.cuda.synchronize()
+    rs = np.random.RandomState(N % 1000 + K % 1000)
+    cols = np.unique(np.concatenate([[0, 1, 127, 128, N - 129, N - 2, N - 1], rs.randint(0, N, 89)]))
+    xp, xm = Xp.double().cpu(), Xm.double().cpu()
+    bcpu = bias.double().cpu()
+    worst = 0.0
+    for n in cols:
+        th = theta[n].float().cpu().numpy()
+        z = philox.gaussian(seed, tid, int(n) * K, K)
+        for Y, X, sign in ((Yp, xp, 1.0), (Ym, xm, -1.0)):
+            w = torch.from_numpy(_store(_fma32(np.float32(sign * eps), z, th), "bf16")).double()
+            ref = X @ w + bcpu[n]
+            d = (Y[:, n].double().cpu() - ref).abs()
+            # float32 accumulation plus the ~1 % of weights that sit one unit away (z agrees to 2e-6)
+            bound = 2e-5 * max(1.0, float(ref.abs().max())) + 0.02 * 0.5 * 4 * 0.02 * 2.0 ** -7 * np.sqrt(K)
+            worst = max(worst, float((d - bound).max()))
+    assert worst <= 0.0, worst
+
+
 def test_perturbed_gemm_rejects_what_it_does_not_cover():
     b = _b()
     X = torch.zeros(300, 128, device="cuda", dtype=torch.bfloat16)

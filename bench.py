@@ -5,7 +5,7 @@ fused update + perturb and dual forward, LM head + loss for both streams, g.  Th
 the OPT-1.3B-shaped configuration: 24 layers, d 2048, 32 heads, FFN 8192, vocab 50272, bf16
 weights fully resident in HBM, batch 16 x seq 256, Zipf(1.1) token ids, eps 1e-3, lr 1e-7.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line.
 """
 import argparse
 import json
@@ -229,7 +229,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the ZO2 step is single-GPU; see DESIGN.md for how it "
+        print("bench.py: this build runs on one GPU only (the ZO2 step is single-GPU; the design notes say how it "
               "would shard); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -97,16 +97,21 @@ template <> struct Fmt<f16_t> {
 };
 template <> struct Fmt<fp8_e4m3_t> {
     static constexpr int kBytes = 1;
-    static __device__ __forceinline__ float load(fp8_e4m3_t v) { return decode_fp8<4, 3, 7, false>(v.v); }
+    // gfx950 converts the OCP 8-bit formats in hardware (round to nearest even, subnormals included): one instruction per
+    // direction instead of about twenty.  What the instruction does beyond the largest finite magnitude is not relied on:
+    // the value is clamped to it first (the format saturates here), and NaN keeps this library's code for it.
+    static __device__ __forceinline__ float load(fp8_e4m3_t v) { return __builtin_amdgcn_cvt_f32_fp8((int)v.v, 0); }
     static __device__ __forceinline__ fp8_e4m3_t store(float v) {
-        return fp8_e4m3_t{(uint8_t)encode_fp8<4, 3, 7, 0x7eu, 0x7fu>(v)};
+        const int c = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(v, -448.0f, 448.0f), 0.0f, 0, false) & 0xff;
+        return fp8_e4m3_t{(uint8_t)(v != v ? (((f2u(v) >> 31) << 7) | 0x7fu) : (uint32_t)c)};
     }
 };
 template <> struct Fmt<fp8_e5m2_t> {
     static constexpr int kBytes = 1;
-    static __device__ __forceinline__ float load(fp8_e5m2_t v) { return decode_fp8<5, 2, 15, true>(v.v); }
+    static __device__ __forceinline__ float load(fp8_e5m2_t v) { return __builtin_amdgcn_cvt_f32_bf8((int)v.v, 0); }
     static __device__ __forceinline__ fp8_e5m2_t store(float v) {
-        return fp8_e5m2_t{(uint8_t)encode_fp8<5, 2, 15, 0x7bu, 0x7eu>(v)};
+        const int c = __builtin_amdgcn_cvt_pk_bf8_f32(__builtin_amdgcn_fmed3f(v, -57344.0f, 57344.0f), 0.0f, 0, false) & 0xff;
+        return fp8_e5m2_t{(uint8_t)(v != v ? (((f2u(v) >> 31) << 7) | 0x7eu) : (uint32_t)c)};
     }
 };
 
@@ -228,5 +233,49 @@ inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s);
         case ZO2_F16: { typedef zo2::f16_t T; __VA_ARGS__; break; }               \
         default: zo2::set_op_error("dtype %d is not a compute dtype", (int)(dt)); return ZO2_EINVAL; \
     }
+
+// Eight consecutive elements of an 8-bit format at once: the hardware conversions read a chosen byte of a 32-bit word and
+// write two results into a chosen half of one, so a group of eight needs no byte extraction or assembly at all.
+template <typename W> struct Fp8Pack;
+template <> struct Fp8Pack<fp8_e4m3_t> {
+    static constexpr float kMax = 448.0f;
+    template <int B> static __device__ __forceinline__ float dec(uint32_t w) { return __builtin_amdgcn_cvt_f32_fp8((int)w, B); }
+    template <bool HI> static __device__ __forceinline__ uint32_t enc2(float a, float b, uint32_t old) { return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, HI); }
+};
+template <> struct Fp8Pack<fp8_e5m2_t> {
+    static constexpr float kMax = 57344.0f;
+    template <int B> static __device__ __forceinline__ float dec(uint32_t w) { return __builtin_amdgcn_cvt_f32_bf8((int)w, B); }
+    template <bool HI> static __device__ __forceinline__ uint32_t enc2(float a, float b, uint32_t old) { return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, HI); }
+};
+template <typename W>
+__device__ __forceinline__ void fp8_decode8(const Vec<W, 8>& v, float out[8]) {
+    uint32_t w[2];
+    __builtin_memcpy(w, &v, 8);
+    out[0] = Fp8Pack<W>::template dec<0>(w[0]); out[1] = Fp8Pack<W>::template dec<1>(w[0]);
+    out[2] = Fp8Pack<W>::template dec<2>(w[0]); out[3] = Fp8Pack<W>::template dec<3>(w[0]);
+    out[4] = Fp8Pack<W>::template dec<0>(w[1]); out[5] = Fp8Pack<W>::template dec<1>(w[1]);
+    out[6] = Fp8Pack<W>::template dec<2>(w[1]); out[7] = Fp8Pack<W>::template dec<3>(w[1]);
+}
+// round to nearest even, saturating; a group that contains a NaN (never the case for finite parameters) goes element by
+// element through Fmt<W>::store, which keeps this library's NaN code
+template <typename W>
+__device__ __forceinline__ void fp8_encode8(const float in[8], Vec<W, 8>& v) {
+    const float s = ((in[0] + in[1]) + (in[2] + in[3])) + ((in[4] + in[5]) + (in[6] + in[7]));
+    if (s != s) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v.v[j] = Fmt<W>::store(in[j]);
+        return;
+    }
+    constexpr float m = Fp8Pack<W>::kMax;
+    float c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = __builtin_amdgcn_fmed3f(in[j], -m, m);
+    uint32_t w[2];
+    w[0] = Fp8Pack<W>::template enc2<false>(c[0], c[1], 0u);
+    w[0] = Fp8Pack<W>::template enc2<true>(c[2], c[3], w[0]);
+    w[1] = Fp8Pack<W>::template enc2<false>(c[4], c[5], 0u);
+    w[1] = Fp8Pack<W>::template enc2<true>(c[6], c[7], w[1]);
+    __builtin_memcpy(&v, w, 8);
+}
 
 }  // namespace zo2

@@ -32,10 +32,13 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
                                          float inv_scale, Vec<W, kPerLane>& tv, Vec<C, kPerLane>& p, Vec<C, kPerLane>& m) {
     constexpr bool kScaled = (Fmt<W>::kBytes == 1);
     float th[kPerLane];
+    if constexpr (kScaled) {        // 8-bit storage: the group's eight bytes are converted by the packed hardware instructions
+        fp8_decode8<W>(tv, th);
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-        th[j] = Fmt<W>::load(tv.v[j]);
-        if (kScaled) th[j] *= inv_scale;
+        for (int j = 0; j < kPerLane; ++j) th[j] *= inv_scale;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) th[j] = Fmt<W>::load(tv.v[j]);
     }
     if (UPDATE) {
         float zp[kPerLane];
@@ -43,13 +46,23 @@ __device__ __forceinline__ void k1_group(const K1Args& a, uint32_t tensor_id, ui
         uint32_t rw[4] = {0u, 0u, 0u, 0u};
         constexpr bool sr = SR && Fmt<W>::kBytes < 4;
         if (sr) rounding_words(a.k_prev, tensor_id, q, rw);
+        if constexpr (kScaled && !sr) {
+            float ts[kPerLane];
 #pragma unroll
-        for (int j = 0; j < kPerLane; ++j) {
-            const float t = __builtin_fmaf(-c, zp[j], th[j]);
-            const float ts = kScaled ? t * scale : t;
-            tv.v[j] = sr ? store_stochastic<W>(ts, rounding_bits_of(rw, j)) : Fmt<W>::store(ts);
-            th[j] = Fmt<W>::load(tv.v[j]);
-            if (kScaled) th[j] *= inv_scale;
+            for (int j = 0; j < kPerLane; ++j) ts[j] = __builtin_fmaf(-c, zp[j], th[j]) * scale;
+            fp8_encode8<W>(ts, tv);
+            fp8_decode8<W>(tv, th);
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) th[j] *= inv_scale;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const float t = __builtin_fmaf(-c, zp[j], th[j]);
+                const float ts = kScaled ? t * scale : t;
+                tv.v[j] = sr ? store_stochastic<W>(ts, rounding_bits_of(rw, j)) : Fmt<W>::store(ts);
+                th[j] = Fmt<W>::load(tv.v[j]);
+                if (kScaled) th[j] *= inv_scale;
+            }
         }
     }
     if constexpr (PERTURB && DRAW) {

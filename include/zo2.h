@@ -210,8 +210,8 @@ zo2_status zo2_set_loader_fusion(zo2_ctx* ctx, int32_t mode);
 /* *active = 1 if the last plan lets the projections perturb in their loader. */
 zo2_status zo2_get_loader_fusion(const zo2_ctx* ctx, int32_t* active);
 /* Split-k of the block projections (Alg. 2 "forward"; a launch-shape decision, not part of the method).  mode 0 (default):
- * a projection whose tiles would occupy at most half of the compute units - few tokens per stream - is cut into 2 or 4
- * pieces along k that run side by side into float32 partial sums, added in piece order by a second kernel (deterministic;
+ * a projection whose tiles would fill the compute units badly - few tokens per stream, or a tile count just above a
+ * multiple of the compute units with a long k - is cut into 2 or 4 pieces along k that run side by side into float32 partial sums, added in piece order by a second kernel (deterministic;
  * results differ from the unsplit launch by float32 rounding order only).  mode -1: never.  Takes effect at the next step. */
 zo2_status zo2_set_split_k(zo2_ctx* ctx, int32_t mode);
 

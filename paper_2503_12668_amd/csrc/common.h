@@ -180,6 +180,15 @@ inline int current_device() {
     if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
     return d;
 }
+inline int device_cu_count() {          // compute units of the current device (256 if the query fails)
+    static int n[kMaxDevices] = {0};
+    const int dev = current_device();
+    if (n[dev] == 0) {
+        int v = 0;
+        n[dev] = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+    }
+    return n[dev];
+}
 
 template <typename T, int N>
 struct alignas(sizeof(T) * N) Vec {

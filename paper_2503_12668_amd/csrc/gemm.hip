@@ -9,6 +9,7 @@
 //
 // The +/- streams (and q, k, v) are independent problems of one shape: they share a launch
 // through grid.z so that even the narrow projections fill 256 compute units.
+#include <math.h>
 #include <string.h>
 
 #include "gemm.h"
@@ -384,15 +385,34 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a, co
     store_vec<OutT, 4>(Y + o, out);
 }
 
+// Pieces per problem: a small cost model of the large kernel.  A launch of t tiles runs in ceil(t / CUs) rounds; a tile
+// costs its k range plus a fixed part (prologue and epilogue, about 256 k), a 128-row tile two thirds of a 256-row one;
+// split pieces add the write and the re-read of their float32 partial sums.  One k of a 256 x 256 tile is 26.75 ns at the
+// rate the kernel reaches (1.25 PFLOP/s over 256 compute units), the partial sums move at about 4 TB/s.  A split, and a
+// further doubling, must win 8 % to be taken (measured launches agree with the model to a few percent).  Splits are
+// taken where tiles are few (128 - 1024 tokens per stream at d_model 2048) and where the tile count sits badly on the
+// rounds with a long k (FC2 of the OPT-13B shape at 2048 tokens: 320 tiles, 1.25 rounds).
 int gemm_pick_splits(int M, int N, int K, int nprob, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16) || M <= 0 || N <= 0 || N % 4 != 0 || nprob <= 0) return 1;
-    const long tiles = (long)nprob * ((M + 127) / 128) * ((N + 255) / 256);       // the large kernel's 128-row tiles
-    const long cu = 256;
-    int s = 1;
-    // double while the doubled launch still has room on the chip, the pieces stay at least 512 long (eight k-slabs of the
-    // large kernel) and multiples of 128, and the problem list holds them
-    while (s < 4 && tiles * s * 2 <= cu && K % (2 * s * 128) == 0 && K / (2 * s) >= 512 && nprob * 2 * s <= GemmArgs::kMaxProblems) s *= 2;
-    return s;
+    const double cu = (double)device_cu_count();
+    const double tn = (double)((N + 255) / 256);
+    auto launch_ns = [&](int s) {
+        const double kk = (double)K / s + 256.0;
+        const double t256 = nprob * s * (double)((M + 255) / 256) * tn, t128 = nprob * s * (double)((M + 127) / 128) * tn;
+        double ns = ceil(t128 / cu) * kk * (2.0 / 3.0);
+        if (M >= 256) ns = fmin(ns, ceil(t256 / cu) * kk);
+        ns *= 26.75;
+        if (s > 1) ns += (double)nprob * s * (double)M * (double)N * 8.0 / 4.0e3;      // bytes / (4e12 B/s) in ns
+        return ns;
+    };
+    int best = 1;
+    double best_ns = launch_ns(1);
+    for (int s = 2; s <= 4; s *= 2) {
+        if (K % (s * 128) != 0 || K / s < 512 || nprob * s > GemmArgs::kMaxProblems) break;
+        const double ns = launch_ns(s);
+        if (ns < 0.92 * best_ns) { best = s; best_ns = ns; }
+    }
+    return best;
 }
 
 size_t gemm_splitk_workspace_bytes(int M, int N, int nprob, int splits) {

@@ -547,16 +547,6 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     }
 }
 
-static int device_cu_count() {
-    static int n[kMaxDevices] = {0};
-    const int dev = current_device();
-    if (n[dev] == 0) {
-        int v = 0;
-        n[dev] = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
-    }
-    return n[dev];
-}
-
 template <typename T, typename OutT, int MI>
 static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
     static bool attr_set_on[kMaxDevices] = {false};

@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--directions", type=int, default=1, help="directions per update (1 = the paper's estimator; q > 1: one step + q - 1 extra directions per round, eta / q each)")
     ap.add_argument("--no-overlap", action="store_true", help="ablation: upload, compute, offload of a block strictly in sequence")
     ap.add_argument("--flush-each-step", action="store_true", help="ablation: no deferred update (every block travels twice per step)")
+    ap.add_argument("--no-split-k", action="store_true", help="never split a projection along k (for comparison)")
     ap.add_argument("--no-pin", action="store_true", help="pageable host buckets: for fully resident runs of models whose buckets exceed what the box lets a process pin")
     args = ap.parse_args()
 
@@ -75,6 +76,8 @@ def main():
         arena = int(args.budget_bytes) if args.budget_bytes else 64 << 30
     ctx = binding.Zo2Context(cfg, gpu_weight_source(), wire=args.wire, compute=args.compute, arena_bytes=arena, scales=scales, pin=not args.no_pin)
     setup_s = time.time() - t0
+    if args.no_split_k:
+        ctx.set_split_k(-1)
     if args.budget_bytes:
         ctx.set_resident_budget(int(args.budget_bytes))
     T = args.batch * args.seq

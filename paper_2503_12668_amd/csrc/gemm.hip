@@ -226,12 +226,20 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
     const int nk = (a.K + BK - 1) / BK;
     load_tile(0);
     store_tile(0);
+    if (nk > 1) load_tile(BK);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) load_tile((kt + 1) * BK);
 #pragma unroll
         for (int g = 0; g < BK / 8; ++g) {
+            // the other buffer is free for the whole slab (its last readers passed the barrier that ended the previous
+            // one): the next slab is parked there half-way through, not at the end, where every wavefront would arrive
+            // at the barrier behind a burst of LDS stores; the registers it leaves are reloaded at once with the slab
+            // after it, which then has a whole slab's time (4096 cycles of MFMA) to arrive
+            if (g == BK / 16 && kt + 1 < nk) {
+                store_tile(cur ^ 1);
+                if (kt + 2 < nk) load_tile((kt + 2) * BK);
+            }
             const int kc = 2 * g + kh;
             v4f_t fx[TM], fw[TN];
 #pragma unroll
@@ -254,7 +262,6 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_mfma_kernel(const GemmArgs a)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[j].w, fx[i].w, acc[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < nk) store_tile(cur ^ 1);
         __syncthreads();
     }
 

@@ -577,6 +577,7 @@ static int g_forced_tile_rows = 0;      // 0: per launch; 128 / 256: every launc
 void gemm256_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
 static int pick_tile_rows(const GemmArgs& a) {
     if (g_forced_tile_rows == 128 || g_forced_tile_rows == 256) return g_forced_tile_rows;
+    if (a.M <= 128) return 128;
     const long cu = device_cu_count();
     const long tn = (a.N + kBN - 1) / kBN;
     auto filling = [&](long rows) {        // useful tile rows over the tile rows the rounds have room for
@@ -589,7 +590,10 @@ static int pick_tile_rows(const GemmArgs& a) {
 
 bool gemm256_applicable(const GemmArgs& a, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16)) return false;
-    if (a.K % 128 != 0 || a.M < 256 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
+    // any number of rows: rows past M are clamped on load and masked on store, and a launch of fewer than 256 rows takes
+    // the 128-row tile (few rows make a launch bound by reading W, which this kernel's loader does far better than the
+    // small-shape kernel)
+    if (a.K % 128 != 0 || a.M < 1 || a.N < 256 || a.N % 4 != 0 || a.ldy % 4 != 0) return false;
     if (!a.out_f32 && (a.N % 8 != 0 || a.ldy % 8 != 0)) return false;
     if (a.ce_mode && !a.out_f32) return false;
     const size_t tsz = 2;

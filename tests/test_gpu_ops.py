@@ -37,7 +37,9 @@ def _within(got, ref, out_fmt):
 @pytest.mark.parametrize("M,N,K", [(64, 64, 64), (22, 32, 32), (200, 136, 72), (257, 515, 264), (128, 97 * 8, 40), (4, 8, 8),
                                    (256, 256, 64), (512, 768, 128), (300, 515, 192), (1024, 384, 2048), (700, 1030, 320),
                                    # the 256 x 256 kernel (K % 128 == 0) with ragged rows and columns, two to six k-slabs
-                                   (257, 260, 128), (300, 520, 256), (700, 1032, 384)])
+                                   (257, 260, 128), (300, 520, 256), (700, 1032, 384),
+                                   # the same kernel with fewer rows than a tile has (128-row tiles, rows clamped and masked)
+                                   (1, 256, 128), (16, 512, 256), (100, 264, 128), (130, 2048, 2048), (200, 520, 384)])
 def test_gemm_against_float64(dt, M, N, K):
     b = _b()
     g = torch.Generator().manual_seed(M * 1000 + N + K)

@@ -16,6 +16,10 @@ counter output into the traffic figures bench.py reports.
         perturbation generated in the projections' loader switched off (the sweep writes W+ and W- for every tensor)
         and on, the ratio, and the time the K1 and projection kernels take per step in each mode.  --shape / --only
         restrict the run to some shapes and one mode (for a profiler run).
+    python3 paper_2503_12668_amd/measure.py link
+        what the host link delivers for 640 MB copies between pinned host memory and HBM (the size of an OPT-13B block
+        bucket): host to device alone, device to host alone, and both at once on two streams - the situation of the
+        upload and offload streams of a streamed step.
     python3 paper_2503_12668_amd/measure.py copy
         three 1 GiB copies and nothing else: the calibration run for rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
     python3 paper_2503_12668_amd/measure.py traffic --fetch F.csv --write W.csv --cal-fetch CF.csv --cal-write CW.csv \\
@@ -166,6 +170,39 @@ def cmd_small_steps(args):
     ctx.close()
 
 
+def cmd_link(args):
+    import time
+    import torch
+    n = 160 * 1024 * 1024                              # float32 elements: 640 MB
+    h_up = torch.ones(n, dtype=torch.float32).pin_memory()
+    h_down = torch.empty(n, dtype=torch.float32).pin_memory()
+    d_up = torch.empty(n, dtype=torch.float32, device="cuda")
+    d_down = torch.ones(n, dtype=torch.float32, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    def both():
+        with torch.cuda.stream(s1):
+            d_up.copy_(h_up, non_blocking=True)
+        with torch.cuda.stream(s2):
+            h_down.copy_(d_down, non_blocking=True)
+
+    gb = n * 4 / 1e9
+    print("| copy of 640 MB (pinned host memory, asynchronous copies) | GB/s |")
+    print("|---|---|")
+    print(f"| host to device alone | {gb / timed(lambda: d_up.copy_(h_up, non_blocking=True)):.1f} |")
+    print(f"| device to host alone | {gb / timed(lambda: h_down.copy_(d_down, non_blocking=True)):.1f} |")
+    print(f"| both at once, two streams | {gb / timed(both):.1f} each way |")
+
+
 def cmd_copy(args):
     import torch
 
@@ -238,6 +275,7 @@ def main():
     s.add_argument("--ring", type=int, default=4)
     s.add_argument("--launches", type=int, default=40)
     sub.add_parser("copy")
+    sub.add_parser("link")
     ss = sub.add_parser("small-steps")
     ss.add_argument("--model", default="opt-1.3b")
     ss.add_argument("--steps", type=int, default=20)
@@ -250,7 +288,7 @@ def main():
     t.add_argument("--steps", type=int, required=True)
     t.add_argument("--workload", default="opt-1.3b shape, bf16 resident, batch 16 x seq 256 (bench.py)")
     args = ap.parse_args()
-    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "small-steps": cmd_small_steps, "traffic": cmd_traffic}[args.cmd](args)
+    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "link": cmd_link, "small-steps": cmd_small_steps, "traffic": cmd_traffic}[args.cmd](args)
 
 
 if __name__ == "__main__":

@@ -209,6 +209,16 @@ zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t sweeps);
 zo2_status zo2_set_loader_fusion(zo2_ctx* ctx, int32_t mode);
 /* *active = 1 if the last plan lets the projections perturb in their loader. */
 zo2_status zo2_get_loader_fusion(const zo2_ctx* ctx, int32_t* active);
+/* How often streamed blocks travel back to the host (Sec. 5.2 offloads a block after every update; this is an option on
+ * top of it).  A block's update is a function of (seed, eta g) alone (Sec. 5.1, 5.4), so a block whose host copy lacks a
+ * few updates can take them - in order, with the same roundings - the next time it is uploaded, and skip the trip back:
+ * with an interval of k updates the offload stream carries a block every k-th step only, the other steps move half the
+ * bytes over the host link.  Losses, g and (after zo2_flush / zo2_sync_to_host) parameters are bit-identical to an
+ * interval of 1.  While updates are lacking the caller's block buffers are NOT current: zo2_flush, zo2_sync_to_host,
+ * a new memory plan and zo2_destroy bring them up to date first.  1 (default) .. 16.  No effect on resident blocks. */
+zo2_status zo2_set_writeback_interval(zo2_ctx* ctx, int32_t updates);
+/* *interval: the setting; *lacking: updates the host copies of streamed blocks lack at the moment. */
+zo2_status zo2_get_writeback_state(const zo2_ctx* ctx, int32_t* interval, int32_t* lacking);
 /* Split-k of the block projections (Alg. 2 "forward"; a launch-shape decision, not part of the method).  mode 0 (default):
  * a projection whose tiles would fill the compute units badly - few tokens per stream, or a tile count just above a
  * multiple of the compute units with a long k - is cut into 2 or 4 pieces along k that run side by side into float32 partial sums, added in piece order by a second kernel (deterministic;

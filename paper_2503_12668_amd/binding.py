@@ -78,6 +78,8 @@ def lib():
         "zo2_set_loader_fusion": (i32, [vp, i32]),
         "zo2_get_loader_fusion": (i32, [vp, C.POINTER(i32)]),
         "zo2_set_split_k": (i32, [vp, i32]),
+        "zo2_set_writeback_interval": (i32, [vp, i32]),
+        "zo2_get_writeback_state": (i32, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "zo2_get_step_stats": (i32, [vp, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32), C.POINTER(u64), C.POINTER(u64)]),
         "zo2_set_profiling": (i32, [vp, u32]),
         "zo2_set_stream_overlap": (i32, [vp, i32]),
@@ -118,7 +120,7 @@ def lib():
 
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
-            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_set_split_k", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
+            "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_set_split_k", "zo2_set_writeback_interval", "zo2_get_writeback_state", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_gemm_split_k", "zo2_op_gemm_split_k_workspace_bytes", "zo2_op_gemm_split_k_pieces", "zo2_op_set_gemm_tile_rows", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
@@ -485,6 +487,15 @@ class Zo2Context:
     def set_loader_fusion(self, mode):
         """0: the projections perturb in their weight loader for steps of few tokens; 1: whenever possible; -1: never."""
         self._check(lib().zo2_set_loader_fusion(self.handle, int(mode)))
+
+    def set_writeback_interval(self, updates):
+        """Streamed blocks go back to the host once their host copy would lack this many updates (1: after every update)."""
+        self._check(lib().zo2_set_writeback_interval(self.handle, int(updates)))
+
+    def writeback_state(self):
+        a, b_ = C.c_int32(), C.c_int32()
+        self._check(lib().zo2_get_writeback_state(self.handle, C.byref(a), C.byref(b_)))
+        return dict(interval=a.value, lacking=b_.value)
 
     def set_split_k(self, mode):
         """0: projections that would leave most compute units idle are split along k; -1: never."""

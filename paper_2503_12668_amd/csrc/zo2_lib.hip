@@ -168,6 +168,14 @@ struct zo2_ctx {
     int n_pend;
     uint64_t pend_seed[kMaxPending];
     bool apply_now;                      // the pass in progress applies them (false: a further direction at unchanged parameters)
+    // Streamed blocks with a write-back interval above one: updates already applied wherever parameters stay on the device
+    // (embeddings, head) that the host copies of the blocks still lack.  Every upload of a block replays them, in order,
+    // before anything else; coefficient k sits at d_state[32 + k].  Empty whenever the blocks are resident.
+    static constexpr int kMaxStale = 32;
+    int wb_interval;                     // a block is written back once its host copy would lack this many updates (1: after every update, as in Alg. 2)
+    int n_stale;
+    uint64_t stale_seed[kMaxStale];
+    bool pass_writes_back;               // decided at the start of a pass
 
     // streams / events
     hipStream_t sc, su, so;
@@ -386,6 +394,9 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->blocks_on_device = false;
     c->n_pend = 0;
     c->apply_now = true;
+    c->wb_interval = 1;
+    c->n_stale = 0;
+    c->pass_writes_back = true;
     c->h_ids = nullptr;
     c->h_ids_cap = 0;
     c->h_result = nullptr;
@@ -432,8 +443,11 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     return ZO2_OK;
 }
 
+static zo2_status writeback_pass(zo2_ctx* c);
+
 extern "C" void zo2_destroy(zo2_ctx* c) {
     if (!c) return;
+    if (!c->dead) (void)writeback_pass(c);       // the caller's block buffers are left current (best effort: no status to report)
     hipStreamSynchronize(c->sc);
     hipStreamSynchronize(c->su);
     hipStreamSynchronize(c->so);
@@ -472,6 +486,7 @@ static zo2_status sync_blocks_to_host(zo2_ctx* c) {
 extern "C" zo2_status zo2_sync_to_host(zo2_ctx* c) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
+    { zo2_status s = writeback_pass(c); if (s != ZO2_OK) return s; }
     HIPCHK(c, hipStreamSynchronize(c->sc));
     HIPCHK(c, hipStreamSynchronize(c->so));
     const size_t d = c->cfg.d_model;
@@ -495,6 +510,8 @@ static inline const int* sweep_bounds(int sweeps) { return kSweepBounds[sweeps =
 
 static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     const zo2_config& g = c->cfg;
+    // a new layout starts from current host copies of the blocks (it may make them resident)
+    { zo2_status s = writeback_pass(c); if (s != ZO2_OK) return s; }
     const size_t d = g.d_model, f = g.d_ffn, V = g.vocab;
     const size_t budget = c->budget;
     const size_t rows2 = 2 * (size_t)T;
@@ -675,6 +692,22 @@ extern "C" zo2_status zo2_set_split_k(zo2_ctx* c, int32_t mode) {
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_set_writeback_interval(zo2_ctx* c, int32_t updates) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (updates < 1 || updates > zo2_ctx::kMaxStale - zo2_ctx::kMaxPending)
+        return fail(c, ZO2_EINVAL, "zo2_set_writeback_interval: %d (1 .. %d)", updates, zo2_ctx::kMaxStale - zo2_ctx::kMaxPending);
+    c->wb_interval = updates;
+    return ZO2_OK;
+}
+
+extern "C" zo2_status zo2_get_writeback_state(const zo2_ctx* c, int32_t* interval, int32_t* lacking) {
+    if (!c || !interval || !lacking) return ZO2_EINVAL;
+    *interval = c->wb_interval;
+    *lacking = c->n_stale;
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_get_loader_fusion(const zo2_ctx* c, int32_t* active) {
     if (!c || !active) return ZO2_EINVAL;
     *active = (c->planned && c->fuse) ? 1 : 0;
@@ -778,6 +811,32 @@ static zo2_status k1_block(zo2_ctx* c, int l, char* bucket, int t0, int t1, bool
     return ZO2_OK;
 }
 
+// update-only sweep over block l with an explicit coefficient (device scalar) and seed: replays an update the block's
+// host copy lacks
+static inline float* stale_slot(const zo2_ctx* c, int k) { return c->d_state + 32 + k; }
+static zo2_status k1_block_replay(zo2_ctx* c, int l, char* bucket, const float* coef, uint64_t seed_prev, hipStream_t st) {
+    if (!st) st = c->sc;
+    K1Args a;
+    k1_common(c, a, 0, 0.f, -1);
+    a.c_ptr = coef;
+    a.k_prev = philox_keys(seed_prev);
+    a.theta = bucket; a.w_plus = nullptr; a.w_minus = nullptr; a.w_off0 = 0; a.nseg = ZO2_BLOCK_TENSORS;
+    for (int k = 0; k < ZO2_BLOCK_TENSORS; ++k) {
+        K1Seg& s = a.seg[k];
+        s.off = c->offs[k]; s.e0 = 0; s.n = (uint64_t)c->tn[k]; s.tensor_id = block_tid(l, k); s.scale = c->scales[s.tensor_id];
+    }
+    OPKS(c, ZO2_KC_K1, st, k1_launch(a, c->cfg.wire_dtype, c->cfg.compute_dtype, true, false, st));
+    return ZO2_OK;
+}
+static zo2_status stale_updates_block(zo2_ctx* c, int l, char* bucket, hipStream_t st = nullptr) {
+    if (c->resident) return ZO2_OK;
+    for (int k = 0; k < c->n_stale; ++k) {
+        zo2_status s = k1_block_replay(c, l, bucket, stale_slot(c, k), c->stale_seed[k], st);
+        if (s != ZO2_OK) return s;
+    }
+    return ZO2_OK;
+}
+
 // the final LayerNorm's two vectors
 static zo2_status k1_final_ln(zo2_ctx* c, bool perturb, uint64_t seed, float eps, int pend = -1) {
     K1Args a;
@@ -803,6 +862,7 @@ static zo2_status earlier_updates_tensor(zo2_ctx* c, void* theta, int64_t n, uin
     return ZO2_OK;
 }
 static zo2_status earlier_updates_block(zo2_ctx* c, int l, char* bucket, hipStream_t st = nullptr) {
+    { zo2_status s = stale_updates_block(c, l, bucket, st); if (s != ZO2_OK) return s; }      // what the host copy lacks comes first, whatever the pass
     if (!c->apply_now) return ZO2_OK;
     for (int k = 0; k + 1 < c->n_pend; ++k) {
         zo2_status s = k1_block(c, l, bucket, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f, st, k);
@@ -1024,6 +1084,38 @@ static zo2_status enqueue_offload(zo2_ctx* c, int l, bool changed) {
     return ZO2_OK;
 }
 
+// Brings the host copies of streamed blocks up to date: every block travels once, takes the updates its host copy lacks
+// and goes back.  Nothing to do when the blocks are resident or nothing is lacking.
+static zo2_status writeback_pass(zo2_ctx* c) {
+    if (!c->planned || c->resident || c->n_stale == 0) return ZO2_OK;
+    const zo2_config& g = c->cfg;
+    TraceRange range("zo2 write-back");
+    c->stat_u = c->stat_o = true;   // no span statistics
+    int next_upload = 0;
+    for (; next_upload < c->n_slots && next_upload < g.n_layers; ++next_upload) {
+        zo2_status s = enqueue_upload(c, next_upload);
+        if (s != ZO2_OK) return s;
+    }
+    for (int l = 0; l < g.n_layers; ++l) {
+        const int sl = l % c->n_slots;
+        HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));
+        { zo2_status s = stale_updates_block(c, l, c->slots + (size_t)sl * c->bucket_bytes); if (s != ZO2_OK) return s; }
+        HIPCHK(c, hipEventRecord(c->ev_k1[sl], c->sc));
+        c->ev_read_valid[sl] = 0;
+        zo2_status s = enqueue_offload(c, l, true);
+        if (s != ZO2_OK) return s;
+        if (next_upload < g.n_layers) {
+            s = enqueue_upload(c, next_upload++);
+            if (s != ZO2_OK) return s;
+        }
+    }
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->su));
+    HIPCHK(c, hipStreamSynchronize(c->so));
+    c->n_stale = 0;
+    return ZO2_OK;
+}
+
 // ---------------------------------------------------------------------------------- one pass over the model
 // ns = 2: Alg. 2's iteration (update, perturb both ways, dual forward, g).  ns = 1: the same walk with a
 // single unperturbed forward (evaluation): the pending update is still applied on the way, W+ = theta'.
@@ -1047,6 +1139,11 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     const int d = g.d_model, dt = g.compute_dtype;
     c->apply_now = !extra;
     const bool upd = fused_update(c);
+    // streamed blocks: does this pass write them back?  Their host copies lack n_stale updates already; this pass adds the
+    // deferred ones it applies.  (The list of lacking updates must keep room for a whole round of the next pass.)
+    const int lack = c->resident ? 0 : c->n_stale + (upd ? c->n_pend : 0);
+    c->pass_writes_back = c->resident || lack >= c->wb_interval || lack > zo2_ctx::kMaxStale - zo2_ctx::kMaxPending;
+    const bool changed = upd || (!c->resident && c->n_stale > 0);
     c->bytes_up = c->bytes_down = 0;
     c->stat_u = c->stat_o = false;
     prof_reset(c);
@@ -1126,11 +1223,11 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         }
         if (!c->resident && serial) {
             HIPCHK(c, hipStreamSynchronize(c->sc));
-            zo2_status s = enqueue_offload(c, l, upd);
+            zo2_status s = enqueue_offload(c, l, changed && c->pass_writes_back);
             if (s != ZO2_OK) return s;
             HIPCHK(c, hipStreamSynchronize(c->so));
         } else if (!c->resident) {
-            zo2_status s = enqueue_offload(c, l, upd);                             // O(W_i) after its update
+            zo2_status s = enqueue_offload(c, l, changed && c->pass_writes_back);                             // O(W_i) after its update
             if (s != ZO2_OK) return s;
             if (next_upload < g.n_layers) {                                        // U(W_{i+n}) into the slot O(W_i) frees
                 s = enqueue_upload(c, next_upload++);
@@ -1198,6 +1295,8 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     }
     // eta g of this pass: deferred update 0 of a new round (every older one has been applied on the way), or one more of
     // the current round
+    if (!c->resident && upd && !c->pass_writes_back)      // the coefficients of the updates the blocks' host copies now lack, before slot 0 is rewritten
+        HIPCHK(c, hipMemcpyAsync(stale_slot(c, c->n_stale), coef_slot(c, 0), (size_t)c->n_pend * sizeof(float), hipMemcpyDeviceToDevice, c->sc));
     OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : 0), c->sc));
     HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
@@ -1217,6 +1316,13 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     if (c->stat_o) (void)hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
 
     c->apply_now = true;
+    if (!c->resident) {
+        if (c->pass_writes_back) {
+            if (changed) c->n_stale = 0;          // the host copies are current again
+        } else if (upd) {
+            for (int k = 0; k < c->n_pend; ++k) c->stale_seed[c->n_stale++] = c->pend_seed[k];
+        }
+    }
     if (ns == 1) {
         c->n_pend = 0;            // the pending updates have been applied to every module on the way
         return ZO2_OK;
@@ -1336,7 +1442,7 @@ extern "C" zo2_status zo2_set_pending(zo2_ctx* c, int32_t has_pending, uint64_t 
 extern "C" zo2_status zo2_flush(zo2_ctx* c) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
-    if (c->n_pend == 0) return ZO2_OK;
+    if (c->n_pend == 0) return writeback_pass(c);
     const zo2_config& g = c->cfg;
     if (!c->planned) return fail(c, ZO2_EINVAL, "zo2_flush: nothing to flush");
     c->apply_now = true;
@@ -1360,6 +1466,7 @@ extern "C" zo2_status zo2_flush(zo2_ctx* c) {
         } else {
             const int sl = l % c->n_slots;
             HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));
+            { zo2_status s = stale_updates_block(c, l, c->slots + (size_t)sl * c->bucket_bytes); if (s != ZO2_OK) return s; }
             for (int k = 0; k < np; ++k) {
                 zo2_status s = k1_block(c, l, c->slots + (size_t)sl * c->bucket_bytes, 0, ZO2_BLOCK_TENSORS, false, 0, 0.f, nullptr, k);
                 if (s != ZO2_OK) return s;
@@ -1380,6 +1487,7 @@ extern "C" zo2_status zo2_flush(zo2_ctx* c) {
     HIPCHK(c, hipStreamSynchronize(c->su));
     HIPCHK(c, hipStreamSynchronize(c->so));
     c->n_pend = 0;
+    c->n_stale = 0;
     return ZO2_OK;
 }
 

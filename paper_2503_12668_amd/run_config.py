@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--directions", type=int, default=1, help="directions per update (1 = the paper's estimator; q > 1: one step + q - 1 extra directions per round, eta / q each)")
     ap.add_argument("--no-overlap", action="store_true", help="ablation: upload, compute, offload of a block strictly in sequence")
     ap.add_argument("--flush-each-step", action="store_true", help="ablation: no deferred update (every block travels twice per step)")
+    ap.add_argument("--writeback-interval", type=int, default=1, help="streamed blocks go back to the host once their host copy would lack this many updates (1: after every update, as in the paper's schedule)")
     ap.add_argument("--no-split-k", action="store_true", help="never split a projection along k (for comparison)")
     ap.add_argument("--no-pin", action="store_true", help="pageable host buckets: for fully resident runs of models whose buckets exceed what the box lets a process pin")
     args = ap.parse_args()
@@ -78,6 +79,7 @@ def main():
     setup_s = time.time() - t0
     if args.no_split_k:
         ctx.set_split_k(-1)
+    ctx.set_writeback_interval(args.writeback_interval)
     if args.budget_bytes:
         ctx.set_resident_budget(int(args.budget_bytes))
     T = args.batch * args.seq
@@ -109,7 +111,7 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
     out = {"model": args.model, "layers": L, "batch": args.batch, "seq": args.seq, "wire": args.wire, "compute": args.compute,
-           "resident": plan["resident"], "n_slots": plan["n_slots"], "directions": q, "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
+           "resident": plan["resident"], "n_slots": plan["n_slots"], "directions": q, "writeback_interval": args.writeback_interval, "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
            "ms_per_step": dt * 1e3, "tokens_per_s": T / dt, "ms_per_block": dt * 1e3 / max(L, 1),
            "bucket_MB": bucket_bytes / 1e6,
            "upload_GBps": (up / 1e9) / (ms_u / 1e3) if ms_u else None,

@@ -1,0 +1,130 @@
+"""Streamed blocks that travel back to the host only every k-th update (an option on top of Sec. 5.2's schedule): the
+updates a block's host copy lacks are replayed, in order and with the same roundings, each time the block is uploaded
+(an update is a function of its seed and eta g alone, Sec. 5.1 / 5.4).  Everything a caller can observe - losses, g,
+parameters after a flush or a synchronisation - must be bit-identical to writing back after every update, and to the
+resident run; only the bytes on the offload stream change."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def _b():
+    from paper_2503_12668_amd import binding
+    return binding
+
+
+def _tiny(n_layers=6, d_model=64, d_ffn=128):
+    cfg = si.tiny_config(n_layers=n_layers, d_model=d_model, n_heads=4, d_ffn=d_ffn, vocab=211, max_pos=48)
+    P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
+    tok = si.make_tokens(cfg["vocab"], 3, 37, seed=12)         # 111 tokens: the loader path is active for 16-bit storage
+    lab = si.next_token_labels(tok)
+    lab[1, 4] = -100
+    return cfg, P, tok, lab
+
+
+def _run(b, cfg, P, tok, lab, wire, compute, mode, interval, sr=False, scales=None, fusion=0):
+    ctx = b.Zo2Context(cfg, P, wire=wire, compute=compute, arena_bytes=64 << 20, scales=scales)
+    ctx.set_wire_rounding(sr)
+    ctx.set_loader_fusion(fusion)
+    out, down = [], []
+    out.append(ctx.step(tok, lab, 1, 1e-3, 1e-3))
+    if mode == "streamed":
+        wsz = b.lib().zo2_dtype_size(ctx.wire_id)
+        ctx.set_resident_budget(ctx.plan()["bytes_used"] - 3 * ctx.offs[16] * wsz)        # 3 slots for 6 blocks
+        ctx.set_writeback_interval(interval)
+        ctx.debug_set_slot_poison(True)
+    for j in range(2, 8):
+        out.append(ctx.step(tok, lab, j, 1e-3, 1e-3))
+        down.append(ctx.step_stats()["bytes_down"])
+        if j == 4:
+            out.append(ctx.step_extra(tok, lab, 40, 1e-3, 5e-4))      # a second direction of this round
+            down.append(ctx.step_stats()["bytes_down"])
+        if j == 6:
+            out.append((ctx.eval(tok, lab),))
+            down.append(ctx.step_stats()["bytes_down"])
+    state = ctx.writeback_state()
+    plan = ctx.plan()
+    mid = None
+    if mode == "streamed" and interval > 1:
+        mid = {n: a.copy() for n, a in ctx.parameters().items() if n.startswith("blocks.0.")}      # the host copy as it stands
+    ctx.flush(); ctx.sync_to_host()
+    assert ctx.writeback_state()["lacking"] == 0
+    res = dict(out=[tuple(float(v) for v in x) for x in out], down=down, P=ctx.parameters(), state=state, plan=plan, mid=mid)
+    ctx.close()
+    return res
+
+
+@pytest.mark.parametrize("wire,compute,sr", [("f32", "f32", False), ("bf16", "bf16", False), ("bf16", "bf16", True), ("fp8_e4m3", "bf16", True)])
+def test_writeback_every_kth_update_is_bit_identical_and_moves_fewer_bytes(wire, compute, sr):
+    b = _b()
+    cfg, P, tok, lab = _tiny()
+    scales = None
+    if wire.startswith("fp8"):
+        scales = np.full(4 + 16 * cfg["n_layers"], 64.0, dtype=np.float32)
+    ref = _run(b, cfg, P, tok, lab, wire, compute, "resident", 1, sr, scales)
+    every = _run(b, cfg, P, tok, lab, wire, compute, "streamed", 1, sr, scales)
+    lazy = _run(b, cfg, P, tok, lab, wire, compute, "streamed", 3, sr, scales)
+    assert not every["plan"]["resident"] and not lazy["plan"]["resident"] and ref["plan"]["resident"]
+    assert every["out"] == ref["out"] and lazy["out"] == ref["out"]
+    for n in ref["P"]:
+        assert np.array_equal(lazy["P"][n], ref["P"][n]), n
+        assert np.array_equal(every["P"][n], ref["P"][n]), n
+    assert all(np.isfinite(v) for x in ref["out"] for v in x)
+    # every update travels back at once with interval 1; with interval 3 most passes send nothing down
+    assert sum(1 for d in every["down"] if d > 0) >= 6
+    assert sum(1 for d in lazy["down"] if d == 0) >= 4 and sum(lazy["down"]) < 0.6 * sum(every["down"])
+    assert 0 < lazy["state"]["lacking"] < 3 or lazy["state"]["lacking"] == 0
+    # while updates are lacking the caller's block buffers are behind (that is the documented price)
+    if lazy["state"]["lacking"] > 0:
+        assert any(not np.array_equal(lazy["mid"][n], ref["P"][n]) for n in lazy["mid"])
+
+
+def test_writeback_interval_with_the_sweep_copies_path_and_plan_changes():
+    """The ordinary path (no loader fusion) at an interval of 4, a change of the memory plan in between (which brings
+    the host copies up to date first), then resident again: same results as a resident run throughout."""
+    b = _b()
+    cfg, P, tok, lab = _tiny()
+    runs = {}
+    for name in ("resident", "lazy"):
+        ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
+        ctx.set_loader_fusion(-1)
+        out = [ctx.step(tok, lab, 1, 1e-3, 1e-3)]
+        full = ctx.plan()["bytes_used"]
+        if name == "lazy":
+            ctx.set_resident_budget(full - 3 * ctx.offs[16] * 2)
+            ctx.set_writeback_interval(4)
+        for j in range(2, 5):
+            out.append(ctx.step(tok, lab, j, 1e-3, 1e-3))
+        if name == "lazy":
+            assert ctx.writeback_state()["lacking"] == 3
+            ctx.set_resident_budget(full - 2 * ctx.offs[16] * 2)          # 4 slots: a new plan
+        out.append(ctx.step(tok, lab, 5, 1e-3, 1e-3))
+        if name == "lazy":
+            assert ctx.writeback_state()["lacking"] == 1                   # the plan change wrote back, this step's update is lacking again
+            ctx.set_resident_budget(full)                                  # everything resident again
+        out.append(ctx.step(tok, lab, 6, 1e-3, 1e-3))
+        if name == "lazy":
+            assert ctx.plan()["resident"] and ctx.writeback_state()["lacking"] == 0
+        ctx.flush(); ctx.sync_to_host()
+        runs[name] = ([tuple(float(v) for v in x) for x in out], ctx.parameters())
+        ctx.close()
+    assert runs["lazy"][0] == runs["resident"][0]
+    for n in runs["resident"][1]:
+        assert np.array_equal(runs["lazy"][1][n], runs["resident"][1][n]), n
+
+
+def test_writeback_interval_argument_checks():
+    b = _b()
+    cfg, P, tok, lab = _tiny(n_layers=2)
+    ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
+    for bad in (0, -1, 17):
+        with pytest.raises(b.Zo2Error):
+            ctx.set_writeback_interval(bad)
+    ctx.set_writeback_interval(16)
+    assert ctx.writeback_state() == dict(interval=16, lacking=0)
+    ctx.step(tok, lab, 1, 1e-3, 1e-3); ctx.step(tok, lab, 2, 1e-3, 1e-3)
+    assert ctx.writeback_state()["lacking"] == 0          # resident blocks never lack anything
+    ctx.close()

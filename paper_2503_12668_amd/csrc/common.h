@@ -223,6 +223,21 @@ __device__ __forceinline__ Vec<T, N> load_vec_stream(const T* p) {
     }
     return v;
 }
+template <typename T, int N>
+__device__ __forceinline__ void store_vec_stream(T* p, const Vec<T, N>& v) {
+    static_assert(sizeof(T) * N == 16 || sizeof(T) * N == 8 || sizeof(T) * N == 32, "vector of 8, 16 or 32 bytes");
+    if constexpr (sizeof(T) * N == 8) {
+        stream_u32x2_t r;
+        __builtin_memcpy(&r, &v, 8);
+        __builtin_nontemporal_store(r, reinterpret_cast<stream_u32x2_t*>(p));
+    } else {
+        constexpr int Q = sizeof(T) * N / 16;
+        stream_u32x4_t r[Q];
+        __builtin_memcpy(r, &v, sizeof(v));
+#pragma unroll
+        for (int i = 0; i < Q; ++i) __builtin_nontemporal_store(r[i], reinterpret_cast<stream_u32x4_t*>(p) + i);
+    }
+}
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // dispatch a zo2_dtype to a type tag

@@ -1,20 +1,23 @@
-// Large-tile MFMA GEMM for the big projections: 256 x 256 x 64 block tile, four wavefronts
-// (2 x 2), each owning 128 x 128 = 8 x 8 MFMA tiles of 16 x 16 (v_mfma_f32_16x16x32) with float32
-// accumulators in the accumulation registers; a second instance with 128-row tiles (wavefronts of 64 x 128)
-// serves launches that 256-row tiles would spread badly over the compute units.  One workgroup per compute
-// unit.  (Under this kernel's full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip
-// sustains a higher clock with the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster
-// in an MFMA-only loop.)
+// Large-tile MFMA GEMM for the big projections: 256 x 256 x 64 block tile, one workgroup per compute unit,
+// v_mfma_f32_16x16x32 with float32 accumulators in the accumulation registers.  Two instances:
+//   256-row tiles: eight wavefronts (2 x 4, two per SIMD), each owning 128 x 64 = 8 x 4 MFMA tiles.  While one
+//     wavefront of a SIMD issues LDS reads, loads or waits, the other one's MFMAs keep the matrix pipeline busy.
+//   128-row tiles: four wavefronts (2 x 2) of 64 x 128, for launches that 256-row tiles would spread badly over
+//     the compute units.
+// (Under this kernel's full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip sustains a
+// higher clock with the 16 x 16 x 32 shape than with 32 x 32 x 16, although the latter is faster in an MFMA-only loop.)
 //
-// Data path: three k-slabs deep.  Two slabs live in two LDS stages; the third is on its way from global memory in
-// vector registers (buffer loads issued two k-steps before the registers are stored to the stage that has just been
-// retired), so that a load has two full k-steps - about 2000 cycles - to come back, enough for a trip to HBM: inside a
-// step the operands are cold (the weights were just rewritten and exceed the memory-side cache).  The first two
-// slabs of a tile travel by the direct-to-LDS loads of gfx950 (16 bytes per lane, no staging through vector registers),
-// the first of them under the previous tile's epilogue.  128-bit LDS reads into MFMA operand registers.  The tile is stored as rows of 8 chunks of 16 bytes with the
-// chunk index XOR-swizzled by (row & 7); because a direct-to-LDS load writes lane i's 16 bytes
-// at LDS offset 16 i, the swizzle is applied on the global side: lane i fetches the chunk that
-// belongs at position i.
+// Data path.  The tile is stored in LDS as rows of 8 chunks of 16 bytes with the chunk index XOR-swizzled by
+// (row & 7), two stages of one k-slab each, read with 128-bit LDS reads into MFMA operand registers.  Slabs arrive by
+// the direct-to-LDS loads of gfx950 (16 bytes per lane, no staging through vector registers); because such a load
+// writes lane i's 16 bytes at LDS offset 16 i, the swizzle is applied on the global side: lane i fetches the chunk
+// that belongs at position i.  The first slab of a tile is loaded under the previous tile's epilogue.
+//   Eight wavefronts: slab kt + 2 is loaded straight into the stage that the barrier in the middle of slab kt
+//     retires, one load per group of four MFMAs (the register budget of two wavefronts per SIMD, 128 + 128, has
+//     no room for a slab in flight in registers).
+//   Four wavefronts: three k-slabs deep.  Two slabs live in the LDS stages; the third is on its way in vector
+//     registers (buffer loads issued two k-steps before the registers are stored to the stage that has just been
+//     retired), so that a load has two full k-steps to come back.
 //
 // Requires K % 128 == 0 (an even number of k-slabs), N % 4 == 0, ldy % 4 == 0 and 16-byte aligned Y / residual (gemm256_applicable);
 // M and N are otherwise arbitrary (rows are clamped on load, masked on store).
@@ -87,6 +90,9 @@ __device__ __forceinline__ void m0_set(uint32_t lds_base) { asm volatile("s_mov_
 // `lanes` (wave-uniform: all ones or zero) is the execution mask of the load: zero turns it into a no-op without a
 // branch, so that the compiler sees straight-line code and keeps one register assignment for the accumulators over the
 // whole k loop (see Mfma16).  The k loop runs with all 64 lanes active, which is what the mask is restored to.
+__device__ __forceinline__ void load_to_lds_masked(const void* sbase, uint32_t voff, uint32_t lds_base, uint64_t lanes) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_mov_b64 exec, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, -1" : : "s"(lds_base), "v"(voff), "s"(sbase), "s"(lanes) : "memory");
+}
 __device__ __forceinline__ void load_to_lds_at_m0_masked(const void* sbase, uint32_t voff, uint64_t lanes) {
     asm volatile("s_mov_b64 exec, %2\n\tglobal_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1" : : "v"(voff), "s"(sbase), "s"(lanes) : "memory");
 }
@@ -134,11 +140,17 @@ __device__ __forceinline__ TileCoord tile_coord(int vid, int ntiles, int tiles_m
 // Persistent kernel: gridDim.x workgroups (one per compute unit) walk the tile list with stride
 // gridDim.x.  Consecutive workgroup ids sit on different XCDs (8 of them, each with its own L2),
 // so within a round of gridDim.x tiles XCD x takes a contiguous run of tile ids.
-template <typename T, typename OutT, int MI>
-__global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, int total_tiles) {
+template <typename T, typename OutT, int MI, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs a, int total_tiles) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int kBM = Tile256<MI>::BM, kStageBytes = Tile256<MI>::kStageBytes;
     constexpr int WPG = 8 / MI;                 // W row-blocks handled per group of eight MFMAs: 1 or 2
+    static_assert(NW == 4 || (NW == 8 && MI == 8), "eight wavefronts: 256-row tiles only");
+    constexpr int WAVES_N = NW / 2;             // wavefronts side by side along the columns: 2 or 4
+    constexpr int NJ = 16 / WAVES_N;            // 16-column MFMA tiles per wavefront: 8 or 4
+    constexpr int XA = 4 * MI / NW;             // 8-row X loads per wavefront per slab
+    constexpr int WB = 32 / NW;                 // 8-row W loads per wavefront per slab
+    constexpr int kEpi = 4 * kEpiRegion / NW;   // output staging per wavefront
     const int tiles_n = (a.N + kBN - 1) / kBN;
     const int tiles_m = (a.M + kBM - 1) / kBM;
     const int ntiles = tiles_m * tiles_n;
@@ -147,13 +159,13 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 
     const int tid = threadIdx.x, lane_id = tid & 63, lane = lane_id;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, r = lane & 15, kg = lane >> 4;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N, r = lane & 15, kg = lane >> 4;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
     // a stage holds the X rows (128 bytes each), then the W rows; a wavefront loads a quarter of each
-    const uint32_t ld_a = lds0 + wave * (MI * 1024), ld_b = lds0 + kBM * 128 + wave * 8192;
+    const uint32_t ld_a = lds0 + wave * (XA * 1024), ld_b = lds0 + kBM * 128 + wave * (WB * 1024);
     // fragment read plan: row (w*16 MI + i*16 + r) of X, (w*128 + j*16 + r) of W, chunk (4 ks + kg) ^ swz(row); swz(row) = swz(r); two k-steps of 32 per slab
-    const uint32_t fr_a = (wm * (16 * MI) + r) * 128, fr_b = kBM * 128 + (wn * 128 + r) * 128;
+    const uint32_t fr_a = (wm * (16 * MI) + r) * 128, fr_b = kBM * 128 + (wn * (16 * NJ) + r) * 128;
     uint32_t koff[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) koff[ks] = (uint32_t)(((ks * 4 + kg) ^ swz(r)) * 16);
@@ -173,7 +185,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     // loader plan: per stage each wavefront brings 8 MI rows of X and 64 rows of W, 8 rows per
     // instruction; lane -> (row lane/8, position lane%8) and the chunk that belongs there
     // (rows past the end of the matrix are clamped to its last row; their products are never stored)
-    uint32_t pa[MI], pb[8];             // per-lane byte offsets from the tile's first row
+    uint32_t pa[XA], pb[WB];            // per-lane byte offsets from the tile's first row
     const T* base_x;                    // wave-uniform: first row of the tile in X / W
     const T* base_w;
     __amdgpu_buffer_rsrc_t rs_x, rs_w;  // the same two panels as buffer resources, for the register-staged loads
@@ -182,8 +194,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     char* wr_b[2];
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
-        wr_a[st] = smem + st * kStageBytes + wave * (MI * 1024) + lane * 16;
-        wr_b[st] = smem + st * kStageBytes + kBM * 128 + wave * 8192 + lane * 16;
+        wr_a[st] = smem + st * kStageBytes + wave * (XA * 1024) + lane * 16;
+        wr_b[st] = smem + st * kStageBytes + kBM * 128 + wave * (WB * 1024) + lane * 16;
     }
     auto plan_loads = [&](const TileCoord& tc) {
         const GemmProblem& pp = a.p[tc.prob];
@@ -198,15 +210,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         rs_w = panel_rsrc(base_w, ((size_t)nrem * a.ldw + a.K) * sizeof(T));
         const int lkc = (lane & 7) ^ swz(lrow);             // rows of one instruction differ in their low three bits only
 #pragma unroll
-        for (int t = 0; t < MI; ++t) pa[t] = (uint32_t)((size_t)min(wave * (8 * MI) + t * 8 + lrow, mrem) * a.ldx + lkc * 8) * (uint32_t)sizeof(T);
+        for (int t = 0; t < XA; ++t) pa[t] = (uint32_t)((size_t)min(wave * (8 * XA) + t * 8 + lrow, mrem) * a.ldx + lkc * 8) * (uint32_t)sizeof(T);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) pb[t] = (uint32_t)((size_t)min(wave * 64 + t * 8 + lrow, nrem) * a.ldw + lkc * 8) * (uint32_t)sizeof(T);
+        for (int t = 0; t < WB; ++t) pb[t] = (uint32_t)((size_t)min(wave * (8 * WB) + t * 8 + lrow, nrem) * a.ldw + lkc * 8) * (uint32_t)sizeof(T);
     };
     auto issue_slab = [&](int stage, int k0) {          // one k-slab of the planned tile, all at once
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            if (t < MI) load_to_lds(base_x + k0, pa[t], ld_a + stage * kStageBytes + t * 1024);
-            load_to_lds(base_w + k0, pb[t], ld_b + stage * kStageBytes + t * 1024);
+            if (t < XA) load_to_lds(base_x + k0, pa[t], ld_a + stage * kStageBytes + t * 1024);
+            if (t < WB) load_to_lds(base_w + k0, pb[t], ld_b + stage * kStageBytes + t * 1024);
         }
     };
     auto issue_slab0 = [&]() { issue_slab(0, 0); };     // k-slab 0 into stage 0
@@ -222,25 +234,49 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     for (;;) {
         // acc[i][j]: X rows (m) i-th 16-block, W rows (n) j-th 16-block.  The W fragment is the
         // MFMA "A" operand, so a lane ends up with one m (= r) and a run of 4 consecutive n (4 kg ..).
-        f32x4_t acc[MI][8];
+        f32x4_t acc[MI][NJ];
         const u32x4_t zero_operand = mfma16_zero_operand();
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < NJ; ++j)
                 mfma16_clear(acc[i][j], zero_operand);
 
-        uint4 fa[MI], fb[2][8];      // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
-        u32x4_t sx[MI], sw[8];       // the slab in flight: this lane's 16 bytes of each of the wavefront's MI + 8 loads
-        // One "group" = the eight MFMAs of X row-block i at k-step buffer `buf`, with the two LDS reads
-        // that fetch row-block i of both operands for the next k-step into buffer `nbuf` and optionally
-        // two direct-to-LDS loads of a later k-slab dealt out between them.  With one wavefront per SIMD
-        // every instruction takes an issue slot of this wavefront and only about three fit under one
-        // 16-cycle MFMA: scheduling barriers pin one piece of memory work behind each of the first MFMAs.
-        // stage_out: this group also moves its share of the register-staged slab on: row-block i of X and WPG row-blocks of W
-        // are stored to stage `st` (retired by the barrier just passed) and their registers are reloaded with the same
-        // pieces of the slab at byte offset `soff` of the panels.
-        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff) {
+        uint4 fa[MI], fb[2][NJ];     // X fragments: one set, each refilled as soon as its group is done; W fragments: two sets
+        constexpr bool kStaged = NW == 4;
+        u32x4_t sx[kStaged ? XA : 1], sw[kStaged ? WB : 1];      // the slab in flight: this lane's 16 bytes of each of the wavefront's MI + 8 loads
+        // One "group" = the NJ MFMAs of X row-block i at k-step buffer `buf`, with the LDS reads that fetch
+        // row-block i of X (and the group's share of W) for the next k-step into buffer `nbuf`, and the group's share of
+        // the traffic that brings a later k-slab in, dealt out between them.  Every instruction takes an issue slot
+        // of its wavefront and only about three fit under one 16-cycle MFMA: scheduling barriers pin one piece of
+        // memory work behind each MFMA.
+        // stage_out, four wavefronts: the group moves its share of the register-staged slab on: row-block i of X and WPG
+        // row-blocks of W are stored to stage `st` (retired by the barrier just passed) and their registers are reloaded
+        // with the same pieces of the slab at byte offset `soff` of the panels.
+        // stage_out, eight wavefronts: the group issues one of the wavefront's eight direct-to-LDS loads of the slab at k
+        // offset `soff` (elements) into stage `st`; `lanes` is all ones, or zero where that slab does not exist.
+        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff, uint64_t lanes = 0) {
+          if constexpr (NW == 8) {
+            // four MFMAs per group; group i issues load i of the incoming slab (X rows in groups 0 - 3, W rows in
+            // groups 4 - 7), even groups read a W fragment of the next k-step, every group reads its own X fragment at its end
+            Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (stage_out) {
+                if (i < 4) load_to_lds_masked(base_x + soff, pa[i & 3], ld_a + st * kStageBytes + (i & 3) * 1024, lanes);
+                else load_to_lds_masked(base_w + soff, pb[i & 3], ld_b + st * kStageBytes + (i & 3) * 1024, lanes);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            Mfma16<T>::run(fb[buf][1], fa[i], acc[i][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            Mfma16<T>::run(fb[buf][2], fa[i], acc[i][2]);
+            __builtin_amdgcn_sched_barrier(0);
+            if ((i & 1) == 0) fb[nbuf][(i >> 1) & 3] = *reinterpret_cast<const uint4*>(sb + ((i >> 1) & 3) * 2048);
+            __builtin_amdgcn_sched_barrier(0);
+            Mfma16<T>::run(fb[buf][3], fa[i], acc[i][3]);
+            __builtin_amdgcn_sched_barrier(0);
+            fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);
+            __builtin_amdgcn_sched_barrier(0);
+          } else {
             Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
             __builtin_amdgcn_sched_barrier(0);
             if (stage_out) *reinterpret_cast<u32x4_t*>(wr_a[st] + i * 1024) = sx[i];
@@ -274,6 +310,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             __builtin_amdgcn_sched_barrier(0);
             fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);      // this group's X fragment is free now
             __builtin_amdgcn_sched_barrier(0);
+          }
         };
 
         // k-slab 0 of this tile is in flight into stage 0 (issued before the loop or under the
@@ -290,28 +327,44 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if (i < MI) fa[i] = *reinterpret_cast<const uint4*>(sa + i * 2048);
-                fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
+                if (i < NJ) fb[0][i] = *reinterpret_cast<const uint4*>(sb + i * 2048);
             }
         }
         // A slab is two k-steps of 32.  Under k-step 0 the fragments of k-step 1 are read; then one barrier
-        // (publishes slab kt+1: every wavefront waited for its own stores to it; retires stage cur: every wavefront
-        // has its last fragments in registers); under k-step 1 the first fragments of slab kt+1 are read, the registers
+        // (publishes slab kt+1: every wavefront waited for its own loads or stores to it; retires stage cur: every wavefront
+        // has its last fragments in registers); under k-step 1 the first fragments of slab kt+1 are read and the retired
+        // stage is refilled.  Eight wavefronts: with the direct-to-LDS loads of slab kt+2, which have until the barrier of
+        // the next slab to land (masked off where that slab does not exist: a load landing after the k loop would hit
+        // the epilogue's staging or the next tile's first slab).  Four wavefronts: the registers
         // holding slab kt+2 - loaded during k-step 1 of the previous slab - are stored to the retired stage and reloaded
         // with slab kt+3.  Every slab runs the same instructions: where slab kt+3 does not exist the loads fetch the
         // panel's last slab again, and where slab kt+2 does not exist that is also what gets stored (nobody reads it);
         // the fragment reads of a slab kt+1 that does not exist fetch bytes nobody uses.  A separate copy of the loop
         // body for the last slabs would invite the compiler to give the accumulators another register assignment there
         // and to move them between MFMAs that it does not know to be MFMAs.
-        // The wait in the middle of a slab leaves the MI + 8 register loads in flight; what it does wait for, besides
-        // this wavefront's LDS traffic, is older: in a tile's first slab, the direct-to-LDS loads of slab 1.
+        // Four wavefronts: the wait in the middle of a slab leaves the MI + 8 register loads in flight; what it does wait
+        // for, besides this wavefront's LDS traffic, is older: in a tile's first slab, the direct-to-LDS loads of slab 1.
         const uint32_t last_slab = (uint32_t)(a.K - kBK) * (uint32_t)sizeof(T);
         auto slab_iter = [&](int kt, auto stage_c) {
             constexpr int cur = decltype(stage_c)::value;          // kt & 1
+            if constexpr (!kStaged) {
+                const uint32_t lm = __builtin_amdgcn_readfirstlane(kt + 2 < nk ? 0xffffffffu : 0u);
+                const uint64_t lanes = ((uint64_t)lm << 32) | lm;
+                const uint32_t k2 = (uint32_t)((kt + 2 < nk ? kt + 2 : kt) * kBK);
+#pragma unroll
+                for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, cur, k2, lanes);
+                return;
+            }
             const uint32_t soff = min((uint32_t)((kt + 3) * kBK) * (uint32_t)sizeof(T), last_slab);
 #pragma unroll
             for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);
-            if constexpr (MI == 8) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+            if constexpr (XA + WB == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+            else if constexpr (XA + WB == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, cur, soff);
@@ -320,12 +373,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
         if (!slab1_in_flight) issue_slab(1, kBK);
         slab1_in_flight = false;
         __builtin_amdgcn_sched_barrier(0);
-        {   // slab 2 (or, if the tile has only two, slab 1 again) starts its trip through the registers
+        if constexpr (kStaged) {   // slab 2 (or, if the tile has only two, slab 1 again) starts its trip through the registers
             const uint32_t soff = min((uint32_t)(2 * kBK) * (uint32_t)sizeof(T), last_slab);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                if (t < MI) sx[t] = panel_load(rs_x, pa[t], soff);
-                sw[t] = panel_load(rs_w, pb[t], soff);
+                if (t < XA) sx[t] = panel_load(rs_x, pa[t], soff);
+                if (t < WB) sw[t] = panel_load(rs_w, pb[t], soff);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -373,14 +426,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             // 16-bit output without residual (QKV, FC1): finish the values in registers (the 8 bias
             // vectors a lane needs are fetched together up front), park them in LDS as 16-bit values,
             // two 32-row passes in flight (double-buffered region), and store 16 bytes per lane.
-            constexpr int ROWH = 128 * 2 + 16;                     // padded 16-bit row
-            char* reg = smem + kStageBytes + wave * kEpiRegion;
+            constexpr int ROWH = NJ * 32 + 16;                     // padded 16-bit row of the wave's sub-tile
+            constexpr int PIECES = 2 * NJ, RPI = 64 / PIECES, U16 = 32 / RPI;     // 16-byte pieces per row, rows per store instruction, stores per pass
+            char* reg = smem + kStageBytes + wave * kEpi;
             const float lower = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(a.relu ? 0u : 0xff800000u));   // 0 or -inf, in a scalar register
             const float sc = p.out_scale;
-            float bvv[8][4];
+            float bvv[NJ][4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int n = n0 + wn * 128 + j * 16 + 4 * kg;
+            for (int j = 0; j < NJ; ++j) {
+                const int n = n0 + wn * (16 * NJ) + j * 16 + 4 * kg;
                 Vec<T, 4> b4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) b4.v[e] = Fmt<T>::store(0.f);
@@ -388,8 +442,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) bvv[j][e] = Fmt<T>::load(b4.v[e]) * sc;      // (acc + b) s = acc s + b s: one FMA per value
             }
-            const int rr = lane >> 4, ch = lane & 15;              // 4 rows x 16 pieces of 8 elements per store
-            const int n = n0 + wn * 128 + ch * 8;
+            const int rr = lane / PIECES, ch = lane % PIECES;      // RPI rows x PIECES pieces of 8 elements per store
+            const int n = n0 + wn * (16 * NJ) + ch * 8;
             const bool n_ok = n < a.N;                             // N % 8 == 0 is required for this path
             const bool interior = (m0 + kBM <= a.M) && (n0 + kBN <= a.N);
 #pragma unroll
@@ -398,7 +452,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)                 // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < NJ; ++j) {
                         Vec<OutT, 4> ov;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
@@ -406,26 +460,27 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                         store_vec<OutT, 4>(reinterpret_cast<OutT*>(buf + (mb * 16 + r) * ROWH) + j * 16 + 4 * kg, ov);
                     }
                 __builtin_amdgcn_wave_barrier();
-                uint4 v8[8];
+                uint4 v8[U16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) v8[u] = *reinterpret_cast<const uint4*>(buf + (4 * u + rr) * ROWH + ch * 16);
+                for (int u = 0; u < U16; ++u) v8[u] = *reinterpret_cast<const uint4*>(buf + (RPI * u + rr) * ROWH + ch * 16);
                 const int mf = m0 + wm * (16 * MI) + i * 32 + rr;
                 OutT* yp = Y + (size_t)mf * a.ldy + n;
                 if (interior) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) *reinterpret_cast<uint4*>(yp + (size_t)(4 * u) * a.ldy) = v8[u];
+                    for (int u = 0; u < U16; ++u) *reinterpret_cast<uint4*>(yp + (size_t)(RPI * u) * a.ldy) = v8[u];
                 } else {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (n_ok && mf + 4 * u < a.M) *reinterpret_cast<uint4*>(yp + (size_t)(4 * u) * a.ldy) = v8[u];
+                    for (int u = 0; u < U16; ++u)
+                        if (n_ok && mf + RPI * u < a.M) *reinterpret_cast<uint4*>(yp + (size_t)(RPI * u) * a.ldy) = v8[u];
                 }
             }
         } else {
-        constexpr int ROWB = 128 * 4 + 16;                         // padded float32 row of the wave's sub-tile
+        constexpr int ROWB = NJ * 64 + 16;                         // padded float32 row of the wave's sub-tile
+        constexpr int CH32 = 4 * NJ, RPI32 = 64 / CH32, U32 = 32 / RPI32;     // float4 pieces per row, rows per store instruction, stores per pass
         {
-            char* reg = smem + kStageBytes + wave * kEpiRegion;
-            const int rr = lane >> 5, ch = lane & 31;
-            const int n = n0 + wn * 128 + ch * 4;
+            char* reg = smem + kStageBytes + wave * kEpi;
+            const int rr = lane / CH32, ch = lane % CH32;
+            const int n = n0 + wn * (16 * NJ) + ch * 4;
             const bool n_ok = n < a.N;
             float bv[4] = {0.f, 0.f, 0.f, 0.f};
             if (bias && n_ok) {
@@ -438,7 +493,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             // interior tiles (the common case) run without any masking; the residual branch is
             // taken once per tile, not per store
             const bool interior = (m0 + kBM <= a.M) && (n0 + kBN <= a.N);
-            const size_t row_step = 2 * (size_t)a.ldy;
+            const size_t row_step = RPI32 * (size_t)a.ldy;
             auto run_passes = [&](auto masked_c, auto res_c) {
                 constexpr bool MASKED = decltype(masked_c)::value, RES = decltype(res_c)::value;
 #pragma unroll
@@ -447,26 +502,26 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
+                        for (int j = 0; j < NJ; ++j) {
                             const f32x4_t t4 = acc[2 * i + mb][j];
                             *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
-                    const int mf = m0 + wm * (16 * MI) + i * 32 + rr;                 // row of u = 0; u adds 2 rows
+                    const int mf = m0 + wm * (16 * MI) + i * 32 + rr;                 // row of u = 0; u adds RPI32 rows
                     const size_t off0 = (size_t)(MASKED ? min(mf, a.M - 1) : mf) * a.ldy + (MASKED && !n_ok ? 0 : n);
-                    float4 v4[16], rv[16];
+                    float4 v4[U32], rv[U32];
 #pragma unroll
-                    for (int u = 0; u < 16; ++u) v4[u] = *reinterpret_cast<const float4*>(reg + (2 * u + rr) * ROWB + ch * 16);
+                    for (int u = 0; u < U32; ++u) v4[u] = *reinterpret_cast<const float4*>(reg + (RPI32 * u + rr) * ROWB + ch * 16);
                     if (RES) {
 #pragma unroll
-                        for (int u = 0; u < 16; ++u) {
+                        for (int u = 0; u < U32; ++u) {
                             // masked rows re-read a valid row (their sums are never stored)
-                            const size_t o = MASKED ? (mf + 2 * u < a.M ? off0 + u * row_step : off0) : off0 + u * row_step;
+                            const size_t o = MASKED ? (mf + RPI32 * u < a.M ? off0 + u * row_step : off0) : off0 + u * row_step;
                             rv[u] = *reinterpret_cast<const float4*>(p.residual + o);
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < 16; ++u) {
+                    for (int u = 0; u < U32; ++u) {
                         float y0 = fmaxf(__builtin_fmaf(v4[u].x, sc, bv[0]), lower), y1 = fmaxf(__builtin_fmaf(v4[u].y, sc, bv[1]), lower);
                         float y2 = fmaxf(__builtin_fmaf(v4[u].z, sc, bv[2]), lower), y3 = fmaxf(__builtin_fmaf(v4[u].w, sc, bv[3]), lower);
                         if (RES) { y0 += rv[u].x; y1 += rv[u].y; y2 += rv[u].z; y3 += rv[u].w; }
@@ -474,7 +529,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                             Vec<OutT, 4> ov;
                             ov.v[0] = Fmt<OutT>::store(y0); ov.v[1] = Fmt<OutT>::store(y1);
                             ov.v[2] = Fmt<OutT>::store(y2); ov.v[3] = Fmt<OutT>::store(y3);
-                            if (!MASKED || (n_ok && mf + 2 * u < a.M)) store_vec<OutT, 4>(Y + off0 + u * row_step, ov);
+                            if (!MASKED || (n_ok && mf + RPI32 * u < a.M)) store_vec<OutT, 4>(Y + off0 + u * row_step, ov);
                         }
                     }
                 }
@@ -485,32 +540,34 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
             auto run_ce = [&](auto masked_c) {
                 constexpr bool MASKED = decltype(masked_c)::value;
                 constexpr float kL2e = 1.4426950408889634f;
+                constexpr int SPANC = 8 * NJ, NV = SPANC / 4;         // columns a lane reduces (64 or 32), as float4
                 const int crow = lane & 31, chalf = lane >> 5;
-                const int ncol0 = n0 + wn * 128 + chalf * 64;
-                const size_t span = (size_t)(4 * (n0 / kBN) + 2 * wn + chalf) * (size_t)a.part_ld;
+                const int ncol0 = n0 + wn * (16 * NJ) + chalf * SPANC;
+                // partials are kept per 64-column span: with 32 columns per lane the two halves of the wavefront are merged below
+                const size_t span = (size_t)(NW == 4 ? 4 * (n0 / kBN) + 2 * wn + chalf : 4 * (n0 / kBN) + wn) * (size_t)a.part_ld;
 #pragma unroll
                 for (int i = 0; i < MI / 2; ++i) {
                     if (i) __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)             // pass i = X row-blocks 2 i and 2 i + 1
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
+                        for (int j = 0; j < NJ; ++j) {
                             const f32x4_t t4 = acc[2 * i + mb][j];
                             *reinterpret_cast<float4*>(reg + (mb * 16 + r) * ROWB + (j * 16 + 4 * kg) * 4) = make_float4(t4[0], t4[1], t4[2], t4[3]);
                         }
                     __builtin_amdgcn_wave_barrier();
                     const int row = m0 + wm * (16 * MI) + i * 32 + crow;
                     const bool row_ok = !MASKED || row < a.M;
-                    const char* rp = reg + crow * ROWB + chalf * 256;
+                    const char* rp = reg + crow * ROWB + chalf * (SPANC * 4);
                     const int lab = p.labels[MASKED ? min(row, a.M - 1) : row];
-                    float4 v4[16];
+                    float4 v4[NV];
 #pragma unroll
-                    for (int t = 0; t < 16; ++t) v4[t] = *reinterpret_cast<const float4*>(rp + t * 16);
+                    for (int t = 0; t < NV; ++t) v4[t] = *reinterpret_cast<const float4*>(rp + t * 16);
                     const int dl = lab - ncol0;
-                    if (row_ok && dl >= 0 && dl < 64) p.label_logit[row] = *reinterpret_cast<const float*>(rp + dl * 4) * sc;
+                    if (row_ok && dl >= 0 && dl < SPANC) p.label_logit[row] = *reinterpret_cast<const float*>(rp + dl * 4) * sc;
                     float mx = -INFINITY;
 #pragma unroll
-                    for (int t = 0; t < 16; ++t) {
+                    for (int t = 0; t < NV; ++t) {
                         v4[t].x *= sc; v4[t].y *= sc; v4[t].z *= sc; v4[t].w *= sc;
                         if (MASKED && ncol0 + 4 * t >= a.N) v4[t] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);   // N % 4 == 0
                         mx = fmaxf(mx, fmaxf(fmaxf(v4[t].x, v4[t].y), fmaxf(v4[t].z, v4[t].w)));
@@ -518,13 +575,22 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
                     const float mb = mx == -INFINITY ? 0.f : mx;        // a fully masked span sums to 0
                     float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-                    for (int t = 0; t < 16; ++t) {
+                    for (int t = 0; t < NV; ++t) {
                         s0 += __builtin_amdgcn_exp2f((v4[t].x - mb) * kL2e) + __builtin_amdgcn_exp2f((v4[t].y - mb) * kL2e);
                         s1 += __builtin_amdgcn_exp2f((v4[t].z - mb) * kL2e) + __builtin_amdgcn_exp2f((v4[t].w - mb) * kL2e);
                     }
-                    if (row_ok) {
+                    float ssum = s0 + s1;
+                    if constexpr (NW == 8) {
+                        // lanes l and l + 32 hold the two 32-column halves of one row's span
+                        const float mxo = __shfl_xor(mx, 32), so = __shfl_xor(ssum, 32);
+                        const float mbo = mxo == -INFINITY ? 0.f : mxo;
+                        const float mall = fmaxf(mx, mxo), mab = mall == -INFINITY ? 0.f : mall;
+                        ssum = ssum * __builtin_amdgcn_exp2f((mb - mab) * kL2e) + so * __builtin_amdgcn_exp2f((mbo - mab) * kL2e);
+                        mx = mall;
+                    }
+                    if (row_ok && (NW == 4 || chalf == 0)) {
                         p.part_max[span + row] = mx;
-                        p.part_sum[span + row] = s0 + s1;
+                        p.part_sum[span + row] = ssum;
                     }
                 }
             };
@@ -547,12 +613,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_kernel(const GemmArgs a, 
     }
 }
 
-template <typename T, typename OutT, int MI>
+template <typename T, typename OutT, int MI, int NW = (MI == 8 ? 8 : 4)>
 static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
     static bool attr_set_on[kMaxDevices] = {false};
     bool& attr_set = attr_set_on[current_device()];
     constexpr int BM = Tile256<MI>::BM, lds = Tile256<MI>::kLdsBytes;
-    auto kern = gemm_mfma256_kernel<T, OutT, MI>;
+    auto kern = gemm_mfma256_kernel<T, OutT, MI, NW>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) {
@@ -563,7 +629,7 @@ static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
     }
     const int total = ((a.M + BM - 1) / BM) * ((a.N + kBN - 1) / kBN) * a.nprob;
     const int grid = total < device_cu_count() ? total : device_cu_count();
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, total);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, st, a, total);
     ZO2_HIP_LAUNCH_CHECK();
     return ZO2_OK;
 }

@@ -119,7 +119,10 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
             const uint64_t i = i0 + (uint64_t)it * kStride;
             Vec<C, kPerLane> p, m;
             k1_group<W, C, UPDATE, PERTURB, SR, DRAW>(a, sg.tensor_id, (sg.e0 + i) >> 3, c, eps, scale, inv_scale, tv[it], p, m);
-            if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
+            // (theta' is not read again before the next step when the perturbed copies are written here: streamed past the
+            // caches it leaves them to the copies; in an update-only sweep the projections read theta' next, so it stays)
+            if (UPDATE && PERTURB) store_vec_stream<W, kPerLane>(theta + i, tv[it]);
+            else if (UPDATE) store_vec<W, kPerLane>(theta + i, tv[it]);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i, p);
                 if (has_m) store_vec<C, kPerLane>(wm + i, m);
@@ -143,7 +146,8 @@ __global__ __launch_bounds__(kThreads) void k1_kernel(const K1Args a) {
         Vec<C, kPerLane> p, m;
         k1_group<W, C, UPDATE, PERTURB, SR, DRAW>(a, sg.tensor_id, (sg.e0 + i0) >> 3, c, eps, scale, inv_scale, tv, p, m);
         if (valid == kPerLane) {
-            if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
+            if (UPDATE && PERTURB) store_vec_stream<W, kPerLane>(theta + i0, tv);
+            else if (UPDATE) store_vec<W, kPerLane>(theta + i0, tv);
             if (PERTURB) {
                 store_vec<C, kPerLane>(wp + i0, p);
                 if (has_m) store_vec<C, kPerLane>(wm + i0, m);

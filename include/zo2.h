@@ -366,6 +366,12 @@ zo2_status zo2_op_perturbed_rows(int32_t dtype, const void* theta, int64_t K, in
  * Returns ZO2_EINVAL for any other value. */
 zo2_status zo2_op_set_gemm_tile_rows(int32_t rows);
 
+/* Launches of 256-row tiles run with eight wavefronts per workgroup (two per SIMD, one k-slab of prefetch) or with
+ * four (a further slab in flight in registers), chosen per launch by the length of k.  waves = 4 or 8 forces one form
+ * for every later launch of the process, step calls included; 0 restores the choice per launch.  For tests and
+ * measurements: results are the same bit for bit either way.  Returns ZO2_EINVAL for any other value. */
+zo2_status zo2_op_set_gemm_wavefronts(int32_t waves);
+
 /* Causal multi-head self-attention.  q, k, v, out: [n_seq * seq, ld] of `dtype`, head h in
  * columns h*d_head .. (h+1)*d_head-1; q already carries the 1/sqrt(d_head) factor.
  * out[i] = softmax_{j <= i}(q_i . k_j) v_j within each sequence.  d_head in {8,16,32,64,80,128}.

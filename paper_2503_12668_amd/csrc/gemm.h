@@ -46,6 +46,7 @@ size_t gemm_splitk_workspace_bytes(int M, int N, int nprob, int splits);
 zo2_status gemm_launch_splitk(const GemmArgs& a, int dtype, int splits, void* workspace, size_t workspace_bytes, hipStream_t st);
 // 0 (default): the 256 x 256 kernel picks 256- or 128-row tiles per launch; 128 / 256: every launch uses that height
 void gemm256_force_tile_rows(int rows);
+void gemm256_force_waves(int waves);      // 0: chosen per launch; 4 or 8: every launch of 256-row tiles
 bool gemm256_applicable(const GemmArgs& a, int dtype);
 
 }  // namespace zo2

@@ -1,7 +1,8 @@
 // Large-tile MFMA GEMM for the big projections: 256 x 256 x 64 block tile, one workgroup per compute unit,
-// v_mfma_f32_16x16x32 with float32 accumulators in the accumulation registers.  Two instances:
-//   256-row tiles: eight wavefronts (2 x 4, two per SIMD), each owning 128 x 64 = 8 x 4 MFMA tiles.  While one
+// v_mfma_f32_16x16x32 with float32 accumulators in the accumulation registers.  Three instances:
+//   256-row tiles, eight wavefronts (2 x 4, two per SIMD), each owning 128 x 64 = 8 x 4 MFMA tiles.  While one
 //     wavefront of a SIMD issues LDS reads, loads or waits, the other one's MFMAs keep the matrix pipeline busy.
+//   256-row tiles, four wavefronts (2 x 2) of 128 x 128: the deeper prefetch below; taken for long k (pick_waves).
 //   128-row tiles: four wavefronts (2 x 2) of 64 x 128, for launches that 256-row tiles would spread badly over
 //     the compute units.
 // (Under this kernel's full load - MFMA, LDS reads, 64 KB per k-slab streaming from L2 - the chip sustains a
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
     }
 }
 
-template <typename T, typename OutT, int MI, int NW = (MI == 8 ? 8 : 4)>
+template <typename T, typename OutT, int MI, int NW>
 static zo2_status launch256_t(const GemmArgs& a, hipStream_t st) {
     static bool attr_set_on[kMaxDevices] = {false};
     bool& attr_set = attr_set_on[current_device()];
@@ -654,6 +655,18 @@ static int pick_tile_rows(const GemmArgs& a) {
     return filling(128) * small_tile_rate > filling(256) ? 128 : 256;
 }
 
+// Wavefronts per workgroup for a launch of 256-row tiles.  Eight wavefronts keep the matrix pipeline busier (two per
+// SIMD) but can only prefetch one k-slab ahead; four wavefronts hold a further slab in registers.  Measured inside the
+// benchmark step, same box: eight are 3 - 4 % faster at K = 2048 (QKV, FC1, LM head), four are 4 % faster at K = 8192
+// (FC2), where a panel's rows lie 16 KB apart and a slab takes longer to arrive from HBM.
+static int g_forced_waves = 0;          // 0: per launch; 4 / 8: every launch of 256-row tiles (tests and measurements)
+void gemm256_force_waves(int waves) { g_forced_waves = waves; }
+static constexpr int kLongK = 6144;
+static int pick_waves(const GemmArgs& a) {
+    if (g_forced_waves == 4 || g_forced_waves == 8) return g_forced_waves;
+    return a.K >= kLongK ? 4 : 8;
+}
+
 bool gemm256_applicable(const GemmArgs& a, int dtype) {
     if (!(dtype == ZO2_BF16 || dtype == ZO2_F16)) return false;
     // any number of rows: rows past M are clamped on load and masked on store, and a launch of fewer than 256 rows takes
@@ -683,13 +696,16 @@ zo2_status gemm_launch_256(const GemmArgs& a, int dtype, hipStream_t st) {
         return ZO2_EINVAL;
     }
     const bool small = pick_tile_rows(a) == 128;
+    const bool eight = !small && pick_waves(a) == 8;
     if (dtype == ZO2_BF16) {
-        if (small) return a.out_f32 ? launch256_t<bf16_t, float, 4>(a, st) : launch256_t<bf16_t, bf16_t, 4>(a, st);
-        return a.out_f32 ? launch256_t<bf16_t, float, 8>(a, st) : launch256_t<bf16_t, bf16_t, 8>(a, st);
+        if (small) return a.out_f32 ? launch256_t<bf16_t, float, 4, 4>(a, st) : launch256_t<bf16_t, bf16_t, 4, 4>(a, st);
+        if (eight) return a.out_f32 ? launch256_t<bf16_t, float, 8, 8>(a, st) : launch256_t<bf16_t, bf16_t, 8, 8>(a, st);
+        return a.out_f32 ? launch256_t<bf16_t, float, 8, 4>(a, st) : launch256_t<bf16_t, bf16_t, 8, 4>(a, st);
     }
     if (dtype == ZO2_F16) {
-        if (small) return a.out_f32 ? launch256_t<f16_t, float, 4>(a, st) : launch256_t<f16_t, f16_t, 4>(a, st);
-        return a.out_f32 ? launch256_t<f16_t, float, 8>(a, st) : launch256_t<f16_t, f16_t, 8>(a, st);
+        if (small) return a.out_f32 ? launch256_t<f16_t, float, 4, 4>(a, st) : launch256_t<f16_t, f16_t, 4, 4>(a, st);
+        if (eight) return a.out_f32 ? launch256_t<f16_t, float, 8, 8>(a, st) : launch256_t<f16_t, f16_t, 8, 8>(a, st);
+        return a.out_f32 ? launch256_t<f16_t, float, 8, 4>(a, st) : launch256_t<f16_t, f16_t, 8, 4>(a, st);
     }
     set_op_error("gemm256: dtype %d unsupported", dtype);
     return ZO2_EINVAL;

@@ -1611,6 +1611,12 @@ extern "C" zo2_status zo2_op_set_gemm_tile_rows(int32_t rows) {
     return ZO2_OK;
 }
 
+extern "C" zo2_status zo2_op_set_gemm_wavefronts(int32_t waves) {
+    ZO2_OP_CHECK(waves == 0 || waves == 4 || waves == 8, ZO2_EINVAL, "zo2_op_set_gemm_wavefronts: %d (0, 4 or 8)", waves);
+    gemm256_force_waves(waves);
+    return ZO2_OK;
+}
+
 extern "C" zo2_status zo2_op_layernorm(int32_t dtype, const float* x, const void* w, const void* b, const void* w2, const void* b2, void* y,
                                        int32_t rows, int32_t rows_first, int32_t d, float eps, void* stream) {
     return layernorm(dtype, x, w, b, w2, b2, y, rows, rows_first, d, eps, as_stream(stream));

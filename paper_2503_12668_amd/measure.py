@@ -61,10 +61,12 @@ def cmd_gemm(args):
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     tile = 128 if args.dtype == "f32" else 256
     print(f"N {args.n}  K {args.k}  {args.dtype}  operands {'constant' if args.const else 'random N(0, 1)'}, "
-          f"{'cold (ring of buffers)' if args.cold else 'hot (same buffers every launch)'}  ({args.launches} launches each)")
+          f"{'cold (ring of buffers)' if args.cold else 'hot (same buffers every launch)'}  ({args.launches} launches each)"
+          + (f"  {args.waves} wavefronts per workgroup" if args.waves else ""))
     print("| M | tiles | active CUs | us per launch | TFLOP/s | TFLOP/s per active CU |" + (" torch.matmul TFLOP/s |" if args.library else ""))
     print("|---|---|---|---|---|---|" + ("---|" if args.library else ""))
-    for m in (512, 1024, 2048, 4096, 8192, 16384):
+    binding.op_set_gemm_wavefronts(args.waves)
+    for m in (args.rows or (512, 1024, 2048, 4096, 8192, 16384)):
         esz = 4 if args.dtype == "f32" else 2
         nbuf = max(1, min(16, int(600e6 // ((m + args.n) * args.k * esz)) + 1)) if args.cold else 1
         if args.const:
@@ -270,6 +272,8 @@ def main():
     g.add_argument("--cold", action="store_true")
     g.add_argument("--library", action="store_true")
     g.add_argument("--launches", type=int, default=50)
+    g.add_argument("--waves", type=int, default=0, choices=[0, 4, 8], help="wavefronts per workgroup for 256-row tiles (0: chosen per launch)")
+    g.add_argument("--rows", type=int, nargs="*", default=None, help="row counts M to run (default: 512 .. 16384)")
     s = sub.add_parser("streams")
     s.add_argument("--elements", type=int, default=100 * 1024 * 1024)
     s.add_argument("--ring", type=int, default=4)

@@ -131,16 +131,19 @@ def _gemm_sampled_case(b, M, N, K, out32, res, dtype=torch.bfloat16, samples=64)
     assert bool(((got - ref).abs() <= bound).all())
 
 
-@pytest.mark.parametrize("tile_rows", [256, 128])
+@pytest.mark.parametrize("tile_rows,waves", [(256, 8), (256, 4), (128, 0)])
 @pytest.mark.parametrize("M,N,K,out32,res", [(T, 3 * D, D, False, False), (T, D, F, True, True), (T, F, D, False, False), (1024, V, D, True, False)])
-def test_gemm_full_size_sampled_outputs(M, N, K, out32, res, tile_rows):
-    """The large-tile kernel at the benchmark's shapes, with either tile height."""
+def test_gemm_full_size_sampled_outputs(M, N, K, out32, res, tile_rows, waves):
+    """The large-tile kernel at the benchmark's shapes, in each of its three forms (256-row tiles run by eight or by four
+    wavefronts, 128-row tiles)."""
     b = _b()
     b.op_set_gemm_tile_rows(tile_rows)
+    b.op_set_gemm_wavefronts(waves)
     try:
         _gemm_sampled_case(b, M, N, K, out32, res)
     finally:
         b.op_set_gemm_tile_rows(0)
+        b.op_set_gemm_wavefronts(0)
 
 
 # projection shapes of the larger configurations: (tokens, d, f) of the OPT-13B, OPT-30B and OPT-175B workloads

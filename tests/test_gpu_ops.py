@@ -63,9 +63,9 @@ def test_gemm_against_float64(dt, M, N, K):
 
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("M,N,K", [(257, 260, 128), (300, 520, 256), (700, 1032, 384), (1024, 384, 2048), (2048, 512, 512)])
-def test_gemm_both_tile_heights(dt, M, N, K):
-    """The large-tile kernel with 256-row and with 128-row tiles: each against float64, and against each other bit for
-    bit (the order in which a dot product is accumulated does not depend on the tile height)."""
+def test_gemm_tile_heights_and_wavefront_counts(dt, M, N, K):
+    """The large-tile kernel with 128-row tiles and with 256-row tiles run by four and by eight wavefronts: each against
+    float64, and against each other bit for bit (the order in which a dot product is accumulated depends on neither)."""
     b = _b()
     g = torch.Generator().manual_seed(M + N + K)
     X = (torch.randn(M, K, generator=g) * 0.5).to(TD[dt]).cuda()
@@ -76,19 +76,24 @@ def test_gemm_both_tile_heights(dt, M, N, K):
     ref2 = torch.relu(ref) + R.double().cpu()
     out = {}
     try:
-        for rows in (128, 256):
+        for rows, waves in ((128, 0), (256, 4), (256, 8)):
             b.op_set_gemm_tile_rows(rows)
+            b.op_set_gemm_wavefronts(waves)
             Y = b.op_gemm(X, W, bias, out_scale=0.125)
             Y2 = b.op_gemm(X, W, bias, residual=R, out_scale=0.125, relu=True, out_dtype=b.F32)
-            assert _within(Y, ref, dt), rows
-            assert _within(Y2, ref2, "f32"), rows
-            out[rows] = (Y.cpu(), Y2.cpu())
+            assert _within(Y, ref, dt), (rows, waves)
+            assert _within(Y2, ref2, "f32"), (rows, waves)
+            out[rows, waves] = (Y.cpu(), Y2.cpu())
         with pytest.raises(b.Zo2Error):
             b.op_set_gemm_tile_rows(64)
+        with pytest.raises(b.Zo2Error):
+            b.op_set_gemm_wavefronts(2)
     finally:
         b.op_set_gemm_tile_rows(0)
-    assert torch.equal(out[128][0].view(torch.int16), out[256][0].view(torch.int16))
-    assert torch.equal(out[128][1], out[256][1])
+        b.op_set_gemm_wavefronts(0)
+    for key in ((256, 4), (256, 8)):
+        assert torch.equal(out[128, 0][0].view(torch.int16), out[key][0].view(torch.int16)), key
+        assert torch.equal(out[128, 0][1], out[key][1]), key
 
 
 def test_gemm_rejects_bad_arguments():
@@ -158,12 +163,14 @@ def test_lm_head_ce_small_and_bad_shapes():
     ref = om.row_cross_entropy(om.linear(X.double(), W.double()), lab.numpy())
     assert float(ref[0]) == 0.0
     try:
-        for rows in (128, 256, 0):                           # both tile heights of the GEMM, then its own choice
+        for rows, waves in ((128, 0), (256, 4), (256, 8), (0, 0)):      # the three forms of the GEMM, then its own choice
             b.op_set_gemm_tile_rows(rows)
+            b.op_set_gemm_wavefronts(waves)
             out = b.op_lm_head_ce(X.cuda(), W.cuda(), lab.cuda()).cpu()
-            assert (out.double() - ref).abs().max() <= ACC_TOL * max(1.0, float(ref.abs().max())), rows
+            assert (out.double() - ref).abs().max() <= ACC_TOL * max(1.0, float(ref.abs().max())), (rows, waves)
     finally:
         b.op_set_gemm_tile_rows(0)
+        b.op_set_gemm_wavefronts(0)
     with pytest.raises(b.Zo2Error):
         b.op_lm_head_ce(X[:100].cuda(), W.cuda(), lab[:100].cuda())          # fewer than 256 rows
     with pytest.raises(b.Zo2Error):

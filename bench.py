@@ -234,6 +234,8 @@ def main():
     ap.add_argument("--no-offload", action="store_true", help="skip the streamed (offload-mode) leg")
     ap.add_argument("--no-small-steps", action="store_true", help="skip the leg with steps of 16 and 128 tokens")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
+    ap.add_argument("--gemm-wavefronts", type=int, default=0, choices=[0, 4, 8],
+                    help="measurement aid: run every 256-row GEMM tile with this many wavefronts (0: chosen per launch, the library's default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the ZO2 step is single-GPU; the design notes say how it "
@@ -250,6 +252,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     binding.lib()
+    binding.op_set_gemm_wavefronts(args.gemm_wavefronts)
     cfg = si.opt_config(MODEL, n_layers=args.layers)
     T = BATCH * SEQ
     t0 = time.time()
@@ -304,7 +307,8 @@ def main():
         "config": {"workload": f"{MODEL}-shaped decoder ({cfg['n_layers']} layers, d {cfg['d_model']}, {cfg['n_heads']} heads, "
                                f"ffn {cfg['d_ffn']}, vocab {cfg['vocab']}), bf16 weights resident in HBM, batch {BATCH} x seq {SEQ}, "
                                f"Zipf(1.1) tokens, eps {EPS}, lr {LR}",
-                   "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"]},
+                   "global_batch": BATCH, "seq_len": SEQ, "resident": plan["resident"], "arena_bytes_used": plan["bytes_used"],
+                   **({"gemm_wavefronts_forced": args.gemm_wavefronts} if args.gemm_wavefronts else {})},
         "roofline": {"kernel": "gemm_mfma256_kernel (QKV / output / FFN / LM-head projections)", "bound": "mfma",
                      "achieved": tflops, "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_MFMA,
                      "traffic": traffic["kernels"]["gemm"]["bytes_per_launch"] if (traffic and args.layers is None) else None,

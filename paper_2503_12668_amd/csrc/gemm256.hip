@@ -258,12 +258,14 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
         // offset `soff` (elements) into stage `st`; `lanes` is all ones, or zero where that slab does not exist.
         auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff, uint64_t lanes = 0) {
           if constexpr (NW == 8) {
-            // four MFMAs per group; group i issues load i of the incoming slab (X rows in groups 0 - 3, W rows in
-            // groups 4 - 7), even groups read a W fragment of the next k-step, every group reads its own X fragment at its end
+            // four MFMAs per group; group i issues load i of the incoming slab (W rows in groups 0 - 3, X rows in
+            // groups 4 - 7: inside a step the weights come from HBM and the activations from the caches, so the weights
+            // get the longer flight), even groups read a W fragment of the next k-step, every group reads its own X fragment
+            // at its end
             Mfma16<T>::run(fb[buf][0], fa[i], acc[i][0]);
             __builtin_amdgcn_sched_barrier(0);
             if (stage_out) {
-                if (i < 4) load_to_lds_masked(base_x + soff, pa[i & 3], ld_a + st * kStageBytes + (i & 3) * 1024, lanes);
+                if (i >= 4) load_to_lds_masked(base_x + soff, pa[i & 3], ld_a + st * kStageBytes + (i & 3) * 1024, lanes);
                 else load_to_lds_masked(base_w + soff, pb[i & 3], ld_b + st * kStageBytes + (i & 3) * 1024, lanes);
             }
             __builtin_amdgcn_sched_barrier(0);

@@ -15,7 +15,8 @@
  *      each can be checked and timed alone at full problem shapes.
  *
  * Conventions for every function:
- *   - plain C, no exceptions, no hidden global state; every call returns a zo2_status
+ *   - plain C, no exceptions, no hidden global state (the two measurement switches zo2_op_set_gemm_tile_rows and
+ *     zo2_op_set_gemm_wavefronts are process-wide and say so); every call returns a zo2_status
  *     (0 = success) and, on failure, leaves a message retrievable with zo2_last_error
  *     (context calls) or zo2_op_last_error (op calls, thread local);
  *   - "host" pointers are ordinary or pinned host memory; "device" pointers are HBM of the

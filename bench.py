@@ -149,29 +149,31 @@ def offload_leg(steps=3, budget_legs=True):
     ctx = binding.Zo2Context(cfg, run_config.gpu_weight_source(), wire="bf16", compute="bf16", arena_bytes=36 << 30)
     bucket = ctx.offs[16] * 2
 
-    def timed(batch, seq, slots, writeback_interval=1):
+    def timed(batch, seq, slots, writeback_interval=1, dirs=1):
         tok = si.make_tokens(cfg["vocab"], batch, seq, seed=2, dist="zipf")
         lab = si.next_token_labels(tok)
         ctx.set_writeback_interval(writeback_interval)
         ctx.set_resident_budget(36 << 30)
-        ctx.step(tok, lab, 40, EPS, LR)                       # plans with everything resident: tells the bytes in use
+        one = (lambda s0: ctx.step(tok, lab, s0, EPS, LR)) if dirs == 1 else \
+              (lambda s0: ctx.step_multi(tok, lab, [s0 * 16 + k for k in range(dirs)], EPS, LR / dirs))   # a round of directions in one pass
+        one(40)                                               # plans with everything resident: tells the bytes in use
         if slots:
             ctx.set_resident_budget(ctx.plan()["bytes_used"] - (L - slots) * bucket)
-        ctx.step(tok, lab, 41, EPS, LR)
+        one(41)
         plan = ctx.plan()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         up = down = 0
         ms_u = ms_o = 0.0
         for j in range(steps):
-            ctx.step(tok, lab, 100 + j, EPS, LR)
+            one(100 + j)
             st = ctx.step_stats()
             up += st["bytes_up"]; down += st["bytes_down"]; ms_u += st["ms_upload"]; ms_o += st["ms_offload"]
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         return {"batch": batch, "seq": seq, "resident": plan["resident"], "n_slots": plan["n_slots"],
-                "writeback_interval": writeback_interval, "steps": steps, "ms_per_step": dt * 1e3,
-                "tokens_per_s": batch * seq / dt, "arena_bytes_used": plan["bytes_used"],
+                "writeback_interval": writeback_interval, "directions_per_pass": dirs, "steps": steps, "ms_per_step": dt * 1e3,
+                "tokens_per_s": batch * seq / dt, "forward_tokens_per_s": 2 * dirs * batch * seq / dt, "arena_bytes_used": plan["bytes_used"],
                 "link_up_GBps_over_step": up / steps / dt / 1e9, "link_down_GBps_over_step": down / steps / dt / 1e9,
                 "upload_stream_GBps": (up / 1e9) / (ms_u / 1e3) if ms_u else None,
                 "offload_stream_GBps": (down / 1e9) / (ms_o / 1e3) if ms_o else None}
@@ -184,6 +186,8 @@ def offload_leg(steps=3, budget_legs=True):
     steps, keep = 8, steps
     str8_wb8 = timed(8, 512, 3, writeback_interval=8)
     steps = keep
+    # a round of two directions in one pass (zo2_step_multi): each block is uploaded once and runs four forwards
+    str8_q2 = timed(8, 512, 3, dirs=2)
     _release(ctx)
     assert str8["n_slots"] == 3 and not str8["resident"] and str32["n_slots"] == 3 and res32["resident"], (str8, str32, res32)
     big = {}
@@ -192,7 +196,8 @@ def offload_leg(steps=3, budget_legs=True):
         big["opt175b_fp8_wire_18e9"] = budget_leg("opt-175b", 12, 1, 2048, "fp8_e4m3", "bf16", steps)
     return {**big, "workload": f"opt-13b-shaped decoder ({L} layers, d {cfg['d_model']}, ffn {cfg['d_ffn']}), bf16 weights in pinned host "
                         f"memory ({bucket / 1e6:.0f} MB per block), streamed through 3 block slots on upload / compute / offload streams",
-            "batch8_seq512_streamed": str8, "batch8_seq512_streamed_writeback_every_8": str8_wb8, "batch32_seq512_streamed": str32, "batch32_seq512_resident": res32,
+            "batch8_seq512_streamed": str8, "batch8_seq512_streamed_writeback_every_8": str8_wb8,
+            "batch8_seq512_streamed_two_directions_one_pass": str8_q2, "batch32_seq512_streamed": str32, "batch32_seq512_resident": res32,
             "streamed_over_resident_at_32x512": str32["ms_per_step"] / res32["ms_per_step"], "steps": steps}
 
 

@@ -4,7 +4,7 @@
  *
  * Two layers of entry points:
  *
- *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_step_extra / zo2_flush / zo2_eval /
+ *   1. the training context: zo2_init / zo2_set_resident_budget / zo2_step / zo2_step_extra / zo2_step_multi / zo2_flush / zo2_eval /
  *      zo2_get_pending / zo2_set_pending / zo2_sync_to_host / zo2_get_plan / zo2_get_scratch_plan / zo2_destroy.  One call of zo2_step is one iteration of the paper's
  *      Alg. 2: for every module (embedding, decoder blocks, LM head) apply the update left
  *      pending by the previous iteration, perturb by +eps z and -eps z, run both forwards,
@@ -148,6 +148,19 @@ zo2_status zo2_step(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, 
  * a non-finite direction is dropped from the round. */
 zo2_status zo2_step_extra(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
                           uint64_t seed, float eps, float lr, float* loss_plus, float* loss_minus, float* g);
+
+/* A whole round of n_dirs directions in one pass over the model (the same estimator as zo2_step + zo2_step_extra,
+ * Sec. 3): every module - embedding, each block, head - runs the dual forwards of all directions before the pass moves
+ * on, so a streamed block is uploaded once per round instead of once per direction; where the host link bounds the step
+ * (Sec. 5.2: compute waits for uploads) further directions cost little until compute catches up with the link.
+ * seeds: host array of n_dirs seeds; lr: the step size of each direction (eta / n_dirs for the plain average);
+ * results: host array of 3 n_dirs floats, (l+, l-, g) per direction.  Losses, g and the state left behind (deferred
+ * updates, parameters) equal those of zo2_step(seeds[0]) followed by zo2_step_extra(seeds[1 ..]) bit for bit.  Needs one
+ * more residual stream (2 tokens x d_model floats) of arena per further direction; the plan is redone when n_dirs
+ * exceeds what it holds.  1 <= n_dirs <= 16 (ZO2_EINVAL beyond); ZO2_ENONFINITE if any direction's loss is not finite:
+ * then the whole round is dropped (results still filled in). */
+zo2_status zo2_step_multi(zo2_ctx* ctx, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                          int32_t n_dirs, const uint64_t* seeds, float eps, float lr, float* results);
 
 /* Apply the pending update to every parameter now (Alg. 2 leaves the last g unapplied). */
 zo2_status zo2_flush(zo2_ctx* ctx);

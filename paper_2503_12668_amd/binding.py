@@ -64,6 +64,7 @@ def lib():
         "zo2_set_resident_budget": (i32, [vp, C.c_size_t]),
         "zo2_step": (i32, [vp, vp, vp, i32, i32, u64, f32, f32, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]),
         "zo2_step_extra": (i32, [vp, vp, vp, i32, i32, u64, f32, f32, C.POINTER(f32), C.POINTER(f32), C.POINTER(f32)]),
+        "zo2_step_multi": (i32, [vp, vp, vp, i32, i32, i32, vp, f32, f32, vp]),
         "zo2_flush": (i32, [vp]),
         "zo2_eval": (i32, [vp, vp, vp, i32, i32, C.POINTER(f32)]),
         "zo2_get_pending": (i32, [vp, C.POINTER(i32), C.POINTER(u64), C.POINTER(f32)]),
@@ -119,7 +120,7 @@ def lib():
     return L
 
 
-EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
+EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_step_multi", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_set_split_k", "zo2_set_writeback_interval", "zo2_get_writeback_state", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
             "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_gemm_split_k", "zo2_op_gemm_split_k_workspace_bytes", "zo2_op_gemm_split_k_pieces", "zo2_op_set_gemm_tile_rows", "zo2_op_set_gemm_wavefronts", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
@@ -440,6 +441,18 @@ class Zo2Context:
                                          float(eps), float(lr), C.byref(lp), C.byref(lm), C.byref(g)),
                     allow=(6,) if allow_nonfinite else ())
         return np.float32(lp.value), np.float32(lm.value), np.float32(g.value)
+
+    def step_multi(self, tokens, labels, seeds, eps, lr, allow_nonfinite=False):
+        """A whole round of len(seeds) directions in one pass; returns a list of (l+, l-, g), one per direction."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        lab = np.ascontiguousarray(labels, dtype=np.int32)
+        assert tok.shape == lab.shape and tok.ndim == 2
+        sd = np.ascontiguousarray([int(x) for x in seeds], dtype=np.uint64)
+        res = np.zeros(3 * len(sd), dtype=np.float32)
+        self._check(lib().zo2_step_multi(self.handle, tok.ctypes.data, lab.ctypes.data, tok.shape[0], tok.shape[1], len(sd),
+                                         sd.ctypes.data, float(eps), float(lr), res.ctypes.data),
+                    allow=(6,) if allow_nonfinite else ())
+        return [(np.float32(res[3 * j]), np.float32(res[3 * j + 1]), np.float32(res[3 * j + 2])) for j in range(len(sd))]
 
     def flush(self):
         self._check(lib().zo2_flush(self.handle))

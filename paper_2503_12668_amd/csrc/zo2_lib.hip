@@ -168,6 +168,11 @@ struct zo2_ctx {
     int n_pend;
     uint64_t pend_seed[kMaxPending];
     bool apply_now;                      // the pass in progress applies them (false: a further direction at unchanged parameters)
+    // Several directions in one pass (zo2_step_multi): every direction keeps its own residual stream; inside a module the
+    // first direction applies the deferred updates, the later ones find the parameters final.
+    float* hs[kMaxPending];              // residual streams of the directions (hs[0] is the only one of an ordinary pass)
+    int plan_dirs, want_dirs;            // residual streams the plan holds / asked for
+    bool dir_later;                      // the direction in progress is not the first of its pass
     // Streamed blocks with a write-back interval above one: updates already applied wherever parameters stay on the device
     // (embeddings, head) that the host copies of the blocks still lack.  Every upload of a block replays them, in order,
     // before anything else; coefficient k sits at d_state[32 + k].  Empty whenever the blocks are resident.
@@ -400,6 +405,8 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     c->h_ids = nullptr;
     c->h_ids_cap = 0;
     c->h_result = nullptr;
+    c->plan_dirs = 0; c->want_dirs = 1; c->dir_later = false;
+    for (float*& hp : c->hs) hp = nullptr;
     c->bytes_up = c->bytes_down = 0;
     c->ms_c = c->ms_u = c->ms_o = 0.f;
     c->bytes_used = 0;
@@ -435,7 +442,7 @@ extern "C" zo2_status zo2_init(zo2_ctx** out, const zo2_config* cfg, const zo2_h
     HIPCHK(c, hipMemcpy(c->d_fln + (size_t)c->fln_off_b * c->wsz, w->final_ln_b, (size_t)cfg->d_model * c->wsz, hipMemcpyHostToDevice));
     if (c->d_lm) HIPCHK(c, hipMemcpy(c->d_lm, w->lm_head, (size_t)c->tok_elems * c->wsz, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemset(c->d_state, 0, 64 * sizeof(float)));
-    HIPCHK(c, hipHostMalloc((void**)&c->h_result, 16 * sizeof(float), hipHostMallocDefault));
+    HIPCHK(c, hipHostMalloc((void**)&c->h_result, (16 + 4 * zo2_ctx::kMaxPending) * sizeof(float), hipHostMallocDefault));
     hipEvent_t* evs[] = {&c->ev_step0, &c->ev_c1, &c->ev_u0, &c->ev_u1, &c->ev_o0, &c->ev_o1};
     for (hipEvent_t* e : evs) HIPCHK(c, hipEventCreate(e));
     hipEvent_t* evs2[] = {&c->ev_k1done[0], &c->ev_k1done[1], &c->ev_fwd_done[0], &c->ev_fwd_done[1], &c->ev_embed};
@@ -542,7 +549,9 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     }
     size_t act = 0;
     auto sz = [&](size_t bytes) { size_t o = act; act = align_up(act + bytes, 256); return o; };
-    const size_t o_h = sz(rows2 * d * 4), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
+    const int n_dirs = std::max(1, c->want_dirs);
+    const size_t h_bytes = align_up(rows2 * d * 4, 256);
+    const size_t o_h = sz(h_bytes * n_dirs), o_x = sz(rows2 * d * c->csz), o_q = sz(rows2 * d * c->csz), o_k = sz(rows2 * d * c->csz),
                  o_v = sz(rows2 * d * c->csz), o_ctx = sz(rows2 * d * c->csz), o_mid = sz(rows2 * f * c->csz),
                  o_logits = sz(fused_ce ? 0 : 2 * lrows * V * 4), o_rl = sz(rows2 * 4),
                  o_cpm = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cps = sz(fused_ce ? rows2 * ce_parts * 4 : 0), o_cl = sz(fused_ce ? rows2 * 4 : 0), o_tok = sz((size_t)T * 4), o_lab = sz((size_t)T * 4),
@@ -600,7 +609,9 @@ static zo2_status plan(zo2_ctx* c, int T, int batch, int seq) {
     c->wp = c->wps[0]; c->wm = c->wms[0];
     c->overlap_k1 = two_sets;
     char* a0 = base + off;
-    c->h = (float*)(a0 + o_h); c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
+    for (int j = 0; j < zo2_ctx::kMaxPending; ++j) c->hs[j] = j < n_dirs ? (float*)(a0 + o_h + (size_t)j * h_bytes) : nullptr;
+    c->plan_dirs = n_dirs;
+    c->h = c->hs[0]; c->x = a0 + o_x; c->qb = a0 + o_q; c->kb = a0 + o_k; c->vb = a0 + o_v; c->ctxb = a0 + o_ctx;
     c->mid = a0 + o_mid; c->logits = (float*)(a0 + o_logits); c->row_loss = (float*)(a0 + o_rl);
     c->d_tokens = (int32_t*)(a0 + o_tok); c->d_labels = (int32_t*)(a0 + o_lab);
     c->fln_wp = a0 + o_fwp; c->fln_wm = a0 + o_fwm;
@@ -862,6 +873,7 @@ static zo2_status earlier_updates_tensor(zo2_ctx* c, void* theta, int64_t n, uin
     return ZO2_OK;
 }
 static zo2_status earlier_updates_block(zo2_ctx* c, int l, char* bucket, hipStream_t st = nullptr) {
+    if (c->dir_later) return ZO2_OK;          // the first direction of the pass has brought the block up to date
     { zo2_status s = stale_updates_block(c, l, bucket, st); if (s != ZO2_OK) return s; }      // what the host copy lacks comes first, whatever the pass
     if (!c->apply_now) return ZO2_OK;
     for (int k = 0; k + 1 < c->n_pend; ++k) {
@@ -1121,8 +1133,13 @@ static zo2_status writeback_pass(zo2_ctx* c) {
 // single unperturbed forward (evaluation): the pending update is still applied on the way, W+ = theta'.
 // extra: a further direction of the current round (ns = 2): nothing deferred is applied, the parameters stay as
 // they are, and the pass's own (seed, eta g) joins the deferred updates instead of replacing them.
+// One pass over the model.  seeds[0 .. ndirs - 1]: the directions evaluated in this pass (ndirs > 1: zo2_step_multi; every
+// module - embedding, each block while it sits in its slot, head - runs the dual forward of all directions before the
+// pass moves on, so a streamed block travels once for all of them).  Results of direction j: pass_result(c, j).
+static inline float* pass_result(const zo2_ctx* c, int j) { return j == 0 ? c->h_result : c->h_result + 16 + 4 * (j - 1); }
 static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
-                             uint64_t seed, float eps, float lr, int ns, bool extra = false) {
+                             const uint64_t* seeds, int ndirs, float eps, float lr, int ns, bool extra = false) {
+    const uint64_t seed = seeds[0];
     const zo2_config& g = c->cfg;
     if (batch <= 0 || seq <= 0 || seq > g.max_pos) return fail(c, ZO2_EINVAL, "%s: batch %d, seq %d (max_pos %d)", who, batch, seq, g.max_pos);
     if ((int64_t)batch * seq > (1 << 24)) return fail(c, ZO2_EINVAL, "%s: too many tokens", who);
@@ -1132,12 +1149,20 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
         if (tokens[i] < 0 || tokens[i] >= g.vocab) return fail(c, ZO2_EINVAL, "%s: token %d at %d outside [0, %d)", who, tokens[i], i, g.vocab);
         if (labels[i] != -100 && (labels[i] < 0 || labels[i] >= g.vocab)) return fail(c, ZO2_EINVAL, "%s: label %d at %d invalid", who, labels[i], i);
     }
-    if (!c->planned || c->need_plan || c->plan_T != T || c->plan_seq != seq) {
+    c->want_dirs = std::max(c->want_dirs, ndirs);
+    if (!c->planned || c->need_plan || c->plan_T != T || c->plan_seq != seq || c->plan_dirs < ndirs) {
         zo2_status s = plan(c, T, batch, seq);
         if (s != ZO2_OK) return s;
     }
     const int d = g.d_model, dt = g.compute_dtype;
     c->apply_now = !extra;
+    c->dir_later = false;
+    // direction j of the pass: its residual stream; only the first direction of a pass applies deferred updates
+    auto set_dir = [&](int j) {
+        c->h = c->hs[j];
+        c->dir_later = j > 0;
+        c->apply_now = j == 0 ? !extra : false;
+    };
     const bool upd = fused_update(c);
     // streamed blocks: does this pass write them back?  Their host copies lack n_stale updates already; this pass adds the
     // deferred ones it applies.  (The list of lacking updates must keep room for a whole round of the next pass.)
@@ -1176,7 +1201,11 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     ea.T = T; ea.seq = seq; ea.d = d; ea.pos_offset = g.pos_offset; ea.eps = eps; ea.single = ns == 1; ea.stochastic = c->stochastic ? 1 : 0;
     ea.scale_tok = c->scales[0]; ea.scale_pos = c->scales[1]; ea.c_ptr = coef_slot(c, c->n_pend > 0 ? c->n_pend - 1 : 0);
     ea.k_prev = philox_keys(c->n_pend > 0 ? c->pend_seed[c->n_pend - 1] : 0); ea.k_cur = philox_keys(seed);
-    OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
+    for (int j = 0; j < ndirs; ++j) {      // every direction gathers before the tables are updated in place below
+        ea.h = c->hs[j];
+        ea.k_cur = philox_keys(seeds[j]);
+        OPK(c, ZO2_KC_EMBED, embed_gather(ea, g.wire_dtype, dt, upd, c->sc));
+    }
     if (upd) {
         { zo2_status s = k1_tensor(c, c->d_pos, c->pos_elems, 1, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
         if (!g.tied_lm_head) { zo2_status s = k1_tensor(c, c->d_tok, c->tok_elems, 0, false, nullptr, nullptr, seed, eps); if (s != ZO2_OK) return s; }
@@ -1213,9 +1242,15 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
             if (!c->resident) HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_up[sl], 0));  // C(W_i) after U(W_i)
             { zo2_status ds = debug_delay(c, 0, c->sc); if (ds != ZO2_OK) return ds; }
             const bool fused_block = c->fuse && ns == 2;
-            zo2_status s = fused_block ? block_forward_fused(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl])
-                                       : block_forward(c, l, bucket, batch, seq, seed, eps, c->resident ? nullptr : c->ev_k1[sl]);
-            if (s != ZO2_OK) return s;
+            for (int j = 0; j < ndirs; ++j) {
+                set_dir(j);
+                // the slot is read by every direction's sweep: it is released (offload, next occupant) after the last one
+                hipEvent_t k1_done = (c->resident || j + 1 < ndirs) ? nullptr : c->ev_k1[sl];
+                zo2_status s = fused_block ? block_forward_fused(c, l, bucket, batch, seq, seeds[j], eps, k1_done)
+                                           : block_forward(c, l, bucket, batch, seq, seeds[j], eps, k1_done);
+                if (s != ZO2_OK) { set_dir(0); return s; }
+            }
+            set_dir(0);
             if (!c->resident) {
                 if (fused_block) HIPCHK(c, hipEventRecord(c->ev_read[sl], c->sc));
                 c->ev_read_valid[sl] = fused_block ? 1 : 0;
@@ -1238,6 +1273,9 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
 
     // DualForward(LM head): final LayerNorm, (tied) vocabulary matrix, loss
     TraceRange head_range("lm_head + loss");
+    for (int j = 0; j < ndirs; ++j) {
+    const uint64_t seed = seeds[j];
+    set_dir(j);
     if (c->apply_now)
         for (int k = 0; k + 1 < c->n_pend; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
     { zo2_status s = k1_final_ln(c, true, seed, eps); if (s != ZO2_OK) return s; }
@@ -1295,10 +1333,12 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     }
     // eta g of this pass: deferred update 0 of a new round (every older one has been applied on the way), or one more of
     // the current round
-    if (!c->resident && upd && !c->pass_writes_back)      // the coefficients of the updates the blocks' host copies now lack, before slot 0 is rewritten
+    if (j == 0 && !c->resident && upd && !c->pass_writes_back)      // the coefficients of the updates the blocks' host copies now lack, before slot 0 is rewritten
         HIPCHK(c, hipMemcpyAsync(stale_slot(c, c->n_stale), coef_slot(c, 0), (size_t)c->n_pend * sizeof(float), hipMemcpyDeviceToDevice, c->sc));
-    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : 0), c->sc));
-    HIPCHK(c, hipMemcpyAsync(c->h_result, c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
+    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : j), c->sc));
+    HIPCHK(c, hipMemcpyAsync(pass_result(c, j), c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
+    }
+    set_dir(0);
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));
     if (c->stat_u) HIPCHK(c, hipEventRecord(c->ev_u1, c->su));
     if (c->stat_o) HIPCHK(c, hipEventRecord(c->ev_o1, c->so));
@@ -1316,6 +1356,7 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     if (c->stat_o) (void)hipEventElapsedTime(&c->ms_o, c->ev_o0, c->ev_o1);
 
     c->apply_now = true;
+    c->dir_later = false;
     if (!c->resident) {
         if (c->pass_writes_back) {
             if (changed) c->n_stale = 0;          // the host copies are current again
@@ -1325,6 +1366,18 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     }
     if (ns == 1) {
         c->n_pend = 0;            // the pending updates have been applied to every module on the way
+        return ZO2_OK;
+    }
+    if (ndirs > 1) {          // a new round of ndirs directions; a non-finite loss in any of them drops the whole round
+        for (int j = 0; j < ndirs; ++j) {
+            const float* r = pass_result(c, j);
+            if (!(isfinite(r[0]) && isfinite(r[1]) && isfinite(r[2]))) {
+                c->n_pend = 0;
+                return fail(c, ZO2_ENONFINITE, "%s: non-finite loss in direction %d (l+ %g, l- %g)", who, j, (double)r[0], (double)r[1]);
+            }
+        }
+        c->n_pend = ndirs;
+        for (int j = 0; j < ndirs; ++j) c->pend_seed[j] = seeds[j];
         return ZO2_OK;
     }
     const bool finite = isfinite(c->h_result[0]) && isfinite(c->h_result[1]) && isfinite(c->h_result[2]);
@@ -1346,7 +1399,7 @@ extern "C" zo2_status zo2_step(zo2_ctx* c, const int32_t* tokens, const int32_t*
     if (c->dead) return ZO2_ESTATE;
     if (!tokens || !labels || !loss_plus || !loss_minus || !gout) return fail(c, ZO2_EINVAL, "zo2_step: NULL argument");
     if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step: eps must be non-zero and finite, lr finite");
-    const zo2_status s = model_pass(c, "zo2_step", tokens, labels, batch, seq, seed, eps, lr, 2);
+    const zo2_status s = model_pass(c, "zo2_step", tokens, labels, batch, seq, &seed, 1, eps, lr, 2);
     if (s == ZO2_OK || s == ZO2_ENONFINITE) {
         *loss_plus = c->h_result[0];
         *loss_minus = c->h_result[1];
@@ -1365,7 +1418,7 @@ extern "C" zo2_status zo2_step_extra(zo2_ctx* c, const int32_t* tokens, const in
     if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step_extra: eps must be non-zero and finite, lr finite");
     if (c->n_pend < 1) return fail(c, ZO2_ESTATE, "zo2_step_extra: no round in progress (call zo2_step first)");
     if (c->n_pend >= zo2_ctx::kMaxPending) return fail(c, ZO2_ESTATE, "zo2_step_extra: at most %d directions per round", zo2_ctx::kMaxPending);
-    const zo2_status s = model_pass(c, "zo2_step_extra", tokens, labels, batch, seq, seed, eps, lr, 2, true);
+    const zo2_status s = model_pass(c, "zo2_step_extra", tokens, labels, batch, seq, &seed, 1, eps, lr, 2, true);
     if (s == ZO2_OK || s == ZO2_ENONFINITE) {
         *loss_plus = c->h_result[0];
         *loss_minus = c->h_result[1];
@@ -1374,12 +1427,33 @@ extern "C" zo2_status zo2_step_extra(zo2_ctx* c, const int32_t* tokens, const in
     return s;
 }
 
+// A whole round of n_dirs directions in one pass: the results and the state it leaves equal those of zo2_step(seeds[0])
+// followed by zo2_step_extra(seeds[1]) ... bit for bit, but every module is visited once - a streamed block is uploaded
+// once and runs the dual forwards of all directions while it sits in its slot.
+extern "C" zo2_status zo2_step_multi(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq,
+                                     int32_t n_dirs, const uint64_t* seeds, float eps, float lr, float* results) {
+    if (!c) return ZO2_EINVAL;
+    if (c->dead) return ZO2_ESTATE;
+    if (!tokens || !labels || !seeds || !results) return fail(c, ZO2_EINVAL, "zo2_step_multi: NULL argument");
+    if (n_dirs < 1 || n_dirs > zo2_ctx::kMaxPending) return fail(c, ZO2_EINVAL, "zo2_step_multi: %d directions (1 .. %d)", n_dirs, zo2_ctx::kMaxPending);
+    if (!(eps != 0.f) || !isfinite(eps) || !isfinite(lr)) return fail(c, ZO2_EINVAL, "zo2_step_multi: eps must be non-zero and finite, lr finite");
+    if (c->overlap_k1 && n_dirs > 1) return fail(c, ZO2_ESTATE, "zo2_step_multi: not available with the sweep kernel on a stream of its own");
+    const zo2_status s = model_pass(c, "zo2_step_multi", tokens, labels, batch, seq, seeds, n_dirs, eps, lr, 2);
+    if (s == ZO2_OK || s == ZO2_ENONFINITE)
+        for (int j = 0; j < n_dirs; ++j) {
+            const float* r = pass_result(c, j);
+            results[3 * j] = r[0]; results[3 * j + 1] = r[1]; results[3 * j + 2] = r[2];
+        }
+    return s;
+}
+
 // ---------------------------------------------------------------------------------- evaluation (single forward)
 extern "C" zo2_status zo2_eval(zo2_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t batch, int32_t seq, float* loss) {
     if (!c) return ZO2_EINVAL;
     if (c->dead) return ZO2_ESTATE;
     if (!tokens || !labels || !loss) return fail(c, ZO2_EINVAL, "zo2_eval: NULL argument");
-    const zo2_status s = model_pass(c, "zo2_eval", tokens, labels, batch, seq, 0, 0.f, 0.f, 1);
+    const uint64_t no_seed = 0;
+    const zo2_status s = model_pass(c, "zo2_eval", tokens, labels, batch, seq, &no_seed, 1, 0.f, 0.f, 1);
     if (s == ZO2_OK) *loss = c->h_result[0];
     return s;
 }

@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--directions", type=int, default=1, help="directions per update (1 = the paper's estimator; q > 1: one step + q - 1 extra directions per round, eta / q each)")
     ap.add_argument("--no-overlap", action="store_true", help="ablation: upload, compute, offload of a block strictly in sequence")
     ap.add_argument("--flush-each-step", action="store_true", help="ablation: no deferred update (every block travels twice per step)")
+    ap.add_argument("--one-pass", action="store_true", help="with --directions q > 1: the whole round in one pass over the model (zo2_step_multi: a streamed block is uploaded once per round)")
     ap.add_argument("--writeback-interval", type=int, default=1, help="streamed blocks go back to the host once their host copy would lack this many updates (1: after every update, as in the paper's schedule)")
     ap.add_argument("--no-split-k", action="store_true", help="never split a projection along k (for comparison)")
     ap.add_argument("--no-pin", action="store_true", help="pageable host buckets: for fully resident runs of models whose buckets exceed what the box lets a process pin")
@@ -83,7 +84,12 @@ def main():
     if args.budget_bytes:
         ctx.set_resident_budget(int(args.budget_bytes))
     T = args.batch * args.seq
-    res = ctx.step(tok, lab, 41, args.eps, args.lr)          # plans with the whole arena
+    q = max(1, args.directions)
+    one_pass = args.one_pass and q > 1
+    if one_pass:                                             # plans with the whole arena (and the residual streams of q directions)
+        res = ctx.step_multi(tok, lab, [41 + i for i in range(q)], args.eps, args.lr / q)[-1]
+    else:
+        res = ctx.step(tok, lab, 41, args.eps, args.lr)      # plans with the whole arena
     if args.slots:
         used = ctx.plan()["bytes_used"]
         # a resident plan holds L slots; keep exactly `slots` of them
@@ -99,10 +105,12 @@ def main():
     t0 = time.perf_counter()
     up = down = 0
     ms_u = ms_o = ms_c = 0.0
-    q = max(1, args.directions)
-    for j in range(args.steps):
-        for i in range(q):           # a "step" of the output below is one round of q directions
-            res = (ctx.step if i == 0 else ctx.step_extra)(tok, lab, 100 + 16 * j + i, args.eps, args.lr / q)
+    for j in range(args.steps):      # a "step" of the output below is one round of q directions
+        for i in range(1 if one_pass else q):
+            if one_pass:
+                res = ctx.step_multi(tok, lab, [100 + 16 * j + k for k in range(q)], args.eps, args.lr / q)[-1]
+            else:
+                res = (ctx.step if i == 0 else ctx.step_extra)(tok, lab, 100 + 16 * j + i, args.eps, args.lr / q)
             st = ctx.step_stats()
             up += st["bytes_up"]; down += st["bytes_down"]
             ms_u += st["ms_upload"]; ms_o += st["ms_offload"]; ms_c += st["ms_compute"]
@@ -111,7 +119,7 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
     out = {"model": args.model, "layers": L, "batch": args.batch, "seq": args.seq, "wire": args.wire, "compute": args.compute,
-           "resident": plan["resident"], "n_slots": plan["n_slots"], "directions": q, "writeback_interval": args.writeback_interval, "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
+           "resident": plan["resident"], "n_slots": plan["n_slots"], "directions": q, "one_pass": one_pass, "writeback_interval": args.writeback_interval, "no_overlap": args.no_overlap, "flush_each_step": args.flush_each_step, "arena_bytes_used": plan["bytes_used"],
            "ms_per_step": dt * 1e3, "tokens_per_s": T / dt, "ms_per_block": dt * 1e3 / max(L, 1),
            "bucket_MB": bucket_bytes / 1e6,
            "upload_GBps": (up / 1e9) / (ms_u / 1e3) if ms_u else None,

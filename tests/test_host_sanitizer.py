@@ -96,8 +96,10 @@ for wire, comp in (("f32", "f32"), ("bf16", "bf16"), ("fp8_e4m3", "bf16")):
     for j in range(4):
         r.append(ctx.step(tok, lab, 12 + j, 1e-3, 1e-3))
     r.append(ctx.step_extra(tok, lab, 16, 1e-3, 5e-4))
+    r += ctx.step_multi(tok, lab, [17, 18, 19], 1e-3, 3e-4)
     ctx.set_loader_fusion(-1)
     r.append(ctx.step(tok, lab, 20, 1e-3, 1e-3))
+    r += ctx.step_multi(tok, lab, [22, 23], 1e-3, 3e-4)
     ctx.set_writeback_interval(1)
     ctx.set_loader_fusion(0)
     ctx.set_resident_budget(full)

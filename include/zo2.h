@@ -380,6 +380,15 @@ zo2_status zo2_op_perturbed_rows(int32_t dtype, const void* theta, int64_t K, in
  * Returns ZO2_EINVAL for any other value. */
 zo2_status zo2_op_set_gemm_tile_rows(int32_t rows);
 
+/* Measurement aid, available in the instrumented build only (`build.py --gemm-stamps` -> libzo2_stamps.so; the ordinary
+ * library returns ZO2_ESTATE): zo2_op_gemm without bias on the large-tile kernel (K % 128 == 0, N >= 256; ZO2_EINVAL
+ * otherwise), during which workgroup 37 records the shader clock around the phases of its tiles.  stamps: 64 device
+ * words: per tile (up to 14) the clock at its start, after the wait for its first k-slab, after its k loop and after
+ * its epilogue; [60] cycles spent waiting for loads and [61] at the barriers in the middle of the k-slabs (the last
+ * launch's tiles), [62] the number of tiles.  The timer reads slow the kernel down by a few percent. */
+zo2_status zo2_op_gemm_phases(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                              const float* residual, void* Y, int32_t out_dtype, int64_t ldy, uint64_t* stamps, void* stream);
+
 /* Launches of 256-row tiles run with eight wavefronts per workgroup (two per SIMD, one k-slab of prefetch) or with
  * four (a further slab in flight in registers), chosen per launch by the length of k.  waves = 4 or 8 forces one form
  * for every later launch of the process, step calls included; 0 restores the choice per launch.  For tests and

@@ -102,6 +102,7 @@ def lib():
         "zo2_op_gemm_split_k_pieces": (i32, [i32, i32, i32, i32, i32]),
         "zo2_op_set_gemm_tile_rows": (i32, [i32]),
         "zo2_op_set_gemm_wavefronts": (i32, [i32]),
+        "zo2_op_gemm_phases": (i32, [i32, i32, i32, i32, vp, i64, vp, i64, vp, vp, i32, i64, vp, vp]),
         "zo2_op_gemm_perturbed": (i32, [i32, i32, i32, i32, vp, vp, i64, vp, u32, u64, f32, vp, vp, vp, vp, vp, vp, i32, i64, f32, i32, vp, C.c_size_t, vp]),
         "zo2_op_gemm_perturbed_workspace_bytes": (C.c_size_t, [i32, i32, i32]),
         "zo2_op_perturbed_rows": (i32, [i32, vp, i64, i64, i64, u32, u64, f32, vp, vp, vp]),
@@ -123,7 +124,7 @@ def lib():
 EXPORTED = ["zo2_block_tensor_offsets", "zo2_dtype_size", "zo2_init", "zo2_set_resident_budget", "zo2_step", "zo2_step_extra", "zo2_step_multi", "zo2_flush", "zo2_eval", "zo2_get_pending", "zo2_set_pending",
             "zo2_pending_count", "zo2_get_pending_at", "zo2_add_pending",
             "zo2_sync_to_host", "zo2_get_plan", "zo2_get_scratch_plan", "zo2_set_scratch_plan", "zo2_set_loader_fusion", "zo2_get_loader_fusion", "zo2_set_split_k", "zo2_set_writeback_interval", "zo2_get_writeback_state", "zo2_get_step_stats", "zo2_set_profiling", "zo2_set_stream_overlap", "zo2_set_wire_rounding", "zo2_get_kernel_times", "zo2_debug_set_stream_delay", "zo2_debug_set_slot_poison", "zo2_last_error", "zo2_destroy", "zo2_op_last_error",
-            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_gemm_split_k", "zo2_op_gemm_split_k_workspace_bytes", "zo2_op_gemm_split_k_pieces", "zo2_op_set_gemm_tile_rows", "zo2_op_set_gemm_wavefronts", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
+            "zo2_op_philox_words", "zo2_op_gaussian", "zo2_op_update_perturb", "zo2_op_update_perturb_block", "zo2_op_convert", "zo2_op_gemm", "zo2_op_gemm_split_k", "zo2_op_gemm_split_k_workspace_bytes", "zo2_op_gemm_split_k_pieces", "zo2_op_set_gemm_tile_rows", "zo2_op_set_gemm_wavefronts", "zo2_op_gemm_phases", "zo2_op_gemm_perturbed", "zo2_op_gemm_perturbed_workspace_bytes", "zo2_op_perturbed_rows",
             "zo2_op_attention", "zo2_op_layernorm", "zo2_op_cross_entropy_rows", "zo2_op_lm_head_ce",
             "zo2_op_lm_head_ce_workspace_bytes", "zo2_op_lm_head_ce_static"]
 
@@ -267,6 +268,14 @@ def op_set_gemm_tile_rows(rows):
 def op_set_gemm_wavefronts(waves):
     """0: 256-row tiles run with 4 or 8 wavefronts as the length of k suggests; 4 / 8: forced (tests, measurements)."""
     _op_check(lib().zo2_op_set_gemm_wavefronts(int(waves)))
+
+
+def op_gemm_phases(X, W, Y, stamps, residual=None, stream=None):
+    """The large-tile GEMM with one workgroup's cycle stamps (instrumented build only; see zo2_op_gemm_phases)."""
+    M, K = X.shape
+    N = W.shape[0]
+    _op_check(lib().zo2_op_gemm_phases(_dt(X), M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(residual) if residual is not None else None,
+                                       _ptr(Y), _dt(Y), Y.stride(0), _ptr(stamps), _stream_ptr(stream)))
 
 
 def op_attention(q, k, v, n_seq, seq, n_heads, d_head, vector_kernel=False, stream=None):

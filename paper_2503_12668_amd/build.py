@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzo2.so")
+LIB_STAMPS = os.path.join(HERE, "libzo2_stamps.so")       # the large-tile GEMM with cycle stamps compiled in (measure.py gemm-phases)
 LIB_HOSTSAN = os.path.join(HERE, "libzo2_hostsan.so")     # same device code, host code under UndefinedBehaviorSanitizer (a test aid)
 
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result",
@@ -111,6 +112,33 @@ def build(force=False, verbose=True):
     return LIB
 
 
+def build_gemm_stamps(verbose=True):
+    """libzo2_stamps.so: the library with -DZO2_GEMM_STAMPS in the two sources that know the macro (the large-tile GEMM
+    records one workgroup's shader clock around the phases of its tiles; zo2_op_gemm_phases hands the buffer in).  A
+    measurement aid for `measure.py gemm-phases`; nothing else loads it."""
+    build(verbose=verbose)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    bdir = os.path.join(HERE, "_build", "stamps")
+    os.makedirs(bdir, exist_ok=True)
+    objs = []
+    for s in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
+        name = os.path.basename(s)
+        if name in ("gemm256.hip", "zo2_lib.hip"):
+            o = os.path.join(bdir, name + ".o")
+            cmd = [hipcc] + HIPCC_FLAGS + ["-DZO2_GEMM_STAMPS", "-c", s, "-o", o]
+            if verbose:
+                print("[build]", " ".join(cmd), flush=True)
+            subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
+        else:
+            o = os.path.join(HERE, "_build", name + ".o")
+        objs.append(o)
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB_STAMPS] + objs
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return LIB_STAMPS
+
+
 def build_host_sanitized(verbose=True):
     """libzo2_hostsan.so: the same sources and device code, the host side compiled with -fsanitize=undefined (and bounds),
     not recovering: the first finding ends the process.  A test aid (tests/test_host_sanitizer.py loads it in a child
@@ -151,3 +179,5 @@ if __name__ == "__main__":
     build(force="--force" in sys.argv)
     if "--host-sanitize" in sys.argv:
         build_host_sanitized()
+    if "--gemm-stamps" in sys.argv:
+        build_gemm_stamps()

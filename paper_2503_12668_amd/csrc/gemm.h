@@ -30,8 +30,14 @@ struct GemmArgs {
     int32_t out_f32;        // Y is float32 instead of the compute dtype
     int32_t ce_mode;        // 1: LM-head + cross-entropy partials instead of an output matrix (256 x 256 kernel only)
     int32_t nprob;          // problems of identical shape, one per grid.z (the +/- streams, q/k/v)
+    // Cycle stamps of one workgroup, for the measurement build of the 256 x 256 kernel only (-DZO2_GEMM_STAMPS: build.py
+    // --gemm-stamps); NULL otherwise.  64 device words: s_memtime at the start of each tile, after the wait for its first
+    // slab, after its k loop and after its epilogue (4 per tile, up to 14 tiles), then [60] cycles spent in the waits for
+    // loads and [61] at the barriers in the middle of the slabs, [62] the number of tiles.
+    unsigned long long* stamps;
     GemmProblem p[kMaxProblems];
 };
+static constexpr int kStampWorkgroup = 37;      // the workgroup that writes them
 
 // Y = act((X W^T + bias) * out_scale) + residual for every problem; float32 accumulation.
 zo2_status gemm_launch(const GemmArgs& a, int dtype, hipStream_t st);

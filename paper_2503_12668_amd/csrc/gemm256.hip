@@ -28,6 +28,18 @@
 
 namespace zo2 {
 
+// Measurement build (-DZO2_GEMM_STAMPS): one workgroup records the shader clock around the phases of its tiles and sums
+// the cycles it spends in the waits in the middle of the slabs (GemmArgs::stamps).  The timer reads are scalar memory
+// operations and wait for the wavefront's LDS traffic, so that build runs a few percent slower; the library proper
+// compiles all of it away.
+#ifdef ZO2_GEMM_STAMPS
+#define ZO2_STAMP() do { if (tlog && blockIdx.x == kStampWorkgroup && threadIdx.x == 0 && tcount < 56) tlog[tcount++] = __builtin_amdgcn_s_memtime(); } while (0)
+#define ZO2_TIMED(sum, ...) do { const unsigned long long t0_ = __builtin_amdgcn_s_memtime(); __VA_ARGS__; sum += __builtin_amdgcn_s_memtime() - t0_; } while (0)
+#else
+#define ZO2_STAMP() do { } while (0)
+#define ZO2_TIMED(sum, ...) do { __VA_ARGS__; } while (0)
+#endif
+
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -224,6 +236,11 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
     };
     auto issue_slab0 = [&]() { issue_slab(0, 0); };     // k-slab 0 into stage 0
 
+#ifdef ZO2_GEMM_STAMPS
+    unsigned long long* tlog = a.stamps;
+    int tcount = 0;
+    unsigned long long wait_vm = 0, wait_bar = 0;
+#endif
     int vid = slot;
     if (vid >= total_tiles) return;
     TileCoord tc = tile_coord<kBM>(vid, ntiles, tiles_m, tiles_n);
@@ -233,6 +250,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
     bool slab1_in_flight = true;
 
     for (;;) {
+        ZO2_STAMP();
         // acc[i][j]: X rows (m) i-th 16-block, W rows (n) j-th 16-block.  The W fragment is the
         // MFMA "A" operand, so a lane ends up with one m (= r) and a run of 4 consecutive n (4 kg ..).
         f32x4_t acc[MI][NJ];
@@ -356,8 +374,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
                 const uint32_t k2 = (uint32_t)((kt + 2 < nk ? kt + 2 : kt) * kBK);
 #pragma unroll
                 for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-                __syncthreads();
+                ZO2_TIMED(wait_vm, asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"));
+                ZO2_TIMED(wait_bar, __syncthreads());
 #pragma unroll
                 for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, cur, k2, lanes);
                 return;
@@ -365,13 +383,16 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
             const uint32_t soff = min((uint32_t)((kt + 3) * kBK) * (uint32_t)sizeof(T), last_slab);
 #pragma unroll
             for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);
-            if constexpr (XA + WB == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-            else if constexpr (XA + WB == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
-            __syncthreads();
+            ZO2_TIMED(wait_vm, {
+                if constexpr (XA + WB == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+                else if constexpr (XA + WB == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            });
+            ZO2_TIMED(wait_bar, __syncthreads());
 #pragma unroll
             for (int i = 0; i < MI; ++i) mgroup(i, 1, 0, frag_x[cur ^ 1][0], frag_w[cur ^ 1][0], true, cur, soff);
         };
+        ZO2_STAMP();
         // slab 1 of a later tile: stage 1 held the previous tile's epilogue staging and is free once the barrier above is passed
         if (!slab1_in_flight) issue_slab(1, kBK);
         slab1_in_flight = false;
@@ -398,6 +419,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
         __syncthreads();
         // the last MFMAs' results must have left the pipeline before the epilogue reads them (see Mfma16)
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        ZO2_STAMP();
 
         // Both stages are free now (all fragment reads are behind the last barrier).  Start the
         // next tile's k-slab 0 into stage 0 so that its latency hides under this tile's epilogue,
@@ -609,6 +631,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
             }
         }
         }
+        ZO2_STAMP();
+#ifdef ZO2_GEMM_STAMPS
+        if (tlog && blockIdx.x == kStampWorkgroup && threadIdx.x == 0) { tlog[60] = wait_vm; tlog[61] = wait_bar; tlog[62] = (unsigned long long)(tcount / 4); }
+#endif
         if (!have_next) break;
         // the epilogue's LDS reads must be done in every wavefront before stage 1 is loaded again;
         // the barrier at the top of the loop (after the wait for slab 0) provides that

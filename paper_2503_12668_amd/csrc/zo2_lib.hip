@@ -1634,6 +1634,25 @@ extern "C" zo2_status zo2_op_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K
     return gemm_launch(a, dtype, as_stream(stream));
 }
 
+// zo2_op_gemm on the 256 x 256 kernel with one workgroup's cycle stamps (measurement build only)
+extern "C" zo2_status zo2_op_gemm_phases(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                                         const float* residual, void* Y, int32_t out_dtype, int64_t ldy, uint64_t* stamps, void* stream) {
+#ifdef ZO2_GEMM_STAMPS
+    ZO2_OP_CHECK(stamps != nullptr, ZO2_EINVAL, "gemm_phases: stamps is NULL");
+    ZO2_OP_CHECK(out_dtype == ZO2_F32 || out_dtype == dtype, ZO2_EINVAL, "gemm_phases: output dtype must be F32 or the input dtype");
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M; a.N = N; a.K = K; a.ldx = ldx; a.ldw = ldw; a.ldy = ldy; a.out_f32 = out_dtype == ZO2_F32; a.nprob = 1;
+    a.p[0].X = X; a.p[0].W = W; a.p[0].residual = residual; a.p[0].Y = Y; a.p[0].out_scale = 1.0f;
+    a.stamps = reinterpret_cast<unsigned long long*>(stamps);
+    return gemm_launch_256(a, dtype, as_stream(stream));
+#else
+    (void)dtype; (void)M; (void)N; (void)K; (void)X; (void)ldx; (void)W; (void)ldw; (void)residual; (void)Y; (void)out_dtype; (void)ldy; (void)stamps; (void)stream;
+    set_op_error("zo2_op_gemm_phases: this library was built without cycle stamps (build.py --gemm-stamps builds libzo2_stamps.so)");
+    return ZO2_ESTATE;
+#endif
+}
+
 extern "C" size_t zo2_op_gemm_split_k_workspace_bytes(int32_t M, int32_t N, int32_t splits) { return gemm_splitk_workspace_bytes(M, N, 1, splits); }
 
 extern "C" int32_t zo2_op_gemm_split_k_pieces(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t nprob) { return gemm_pick_splits(M, N, K, nprob, dtype); }

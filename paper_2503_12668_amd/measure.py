@@ -6,6 +6,12 @@ counter output into the traffic figures bench.py reports.
         --const: operands filled with one value instead of random ones; --cold: every launch takes operands from a
         ring of buffers larger than the memory-side cache (the situation inside a step) instead of the same ones;
         --library: a last column with torch.matmul (the vendor BLAS) on the same buffers, as a yardstick.
+    python3 paper_2503_12668_amd/measure.py gemm-phases [--n N] [--k K] [--m M] [--f32-residual]
+        needs libzo2_stamps.so (python3 paper_2503_12668_amd/build.py --gemm-stamps).  The large-tile GEMM with one
+        workgroup's shader-clock stamps: cycles per tile for the wait for its first k-slab, the k loop (and, inside it, the
+        waits for loads and at the barriers in the middle of the slabs) and the epilogue, for four or eight wavefronts per
+        workgroup and with both operands, only X, or only W taken from a ring of cold buffers; the launch time next to
+        it gives the clock the chip ran at.
     python3 paper_2503_12668_amd/measure.py streams
         what this machine delivers for plain HBM streams issued by the library's own kernels, nothing computed:
         copy (zo2_op_convert float32 -> float32: read 1, write 1), next to the perturbation alone (zo2_op_update_perturb
@@ -90,6 +96,46 @@ def cmd_gemm(args):
             us_l = _time_launches(lambda i: torch.matmul(Xs[i % nbuf], WT[i % nbuf], out=Y), args.launches)
             extra = f" {2.0 * m * args.n * args.k / us_l / 1e6:.1f} |"
         print(f"| {m} | {tiles} | {min(active, cus)} | {us:.1f} | {tf:.1f} | {tf / min(active, cus):.2f} |" + extra, flush=True)
+
+
+def cmd_gemm_phases(args):
+    import torch
+
+    from paper_2503_12668_amd import binding, build
+    if not os.path.exists(build.LIB_STAMPS):
+        sys.exit("measure.py gemm-phases: libzo2_stamps.so is not built (python3 paper_2503_12668_amd/build.py --gemm-stamps)")
+    binding.LIB_PATH = build.LIB_STAMPS
+    M, N, K = args.m, args.n, args.k
+    g = torch.Generator(device="cuda").manual_seed(3)
+    ring = max(2, int(600e6 // ((M + N) * K * 2)) + 1)
+    Xs = [torch.randn(M, K, device="cuda", generator=g).bfloat16() for _ in range(ring)]
+    Ws = [torch.randn(N, K, device="cuda", generator=g).bfloat16() for _ in range(ring)]
+    out32 = args.f32_residual
+    Y = torch.empty(M, N, device="cuda", dtype=torch.float32 if out32 else torch.bfloat16)
+    R = torch.zeros(M, N, device="cuda") if out32 else None
+    stamps = torch.zeros(64, dtype=torch.int64, device="cuda")
+    tiles_per_cu = ((M + 255) // 256) * ((N + 255) // 256) / torch.cuda.get_device_properties(0).multi_processor_count
+    print(f"M {M}  N {N}  K {K}  bf16, random N(0, 1) operands, {'float32 output + residual' if out32 else 'bf16 output'}; "
+          f"{tiles_per_cu:.2f} tiles of 256 x 256 per compute unit; pure MFMA issue of a tile's k loop: {K // 32 * 64 * 16} cycles per SIMD")
+    print("| wavefronts | X | W | us per launch | TFLOP/s | cycles per tile: wait for first slab | k loop | of it: waiting for loads | at the mid-slab barrier | epilogue | clock GHz |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    for i in range(1000):        # the first launches of a process run at another clock: let it settle before the first row
+        binding.op_gemm_phases(Xs[0], Ws[0], Y, stamps, residual=R)
+    for waves in (4, 8):
+        binding.op_set_gemm_wavefronts(waves)
+        for cx, cw in ((False, False), (False, True), (True, False), (True, True)):
+            f = lambda i: binding.op_gemm_phases(Xs[i % ring if cx else 0], Ws[i % ring if cw else 0], Y, stamps, residual=R)
+            for i in range(5):
+                f(i)
+            us = _time_launches(f, args.launches)
+            st = stamps.cpu().numpy().astype("int64")
+            nt = int(st[62])
+            ph = [[int(st[4 * t + k + 1] - st[4 * t + k]) for k in range(3)] for t in range(nt)]
+            mean = [sum(p[k] for p in ph) / nt for k in range(3)]
+            total = int(st[4 * nt - 1] - st[0])
+            print(f"| {waves} | {'cold' if cx else 'hot'} | {'cold' if cw else 'hot'} | {us:.1f} | {2.0 * M * N * K / us / 1e6:.0f} | {mean[0]:.0f} | {mean[1]:.0f} | "
+                  f"{st[60] / nt:.0f} | {st[61] / nt:.0f} | {mean[2]:.0f} | {total / us / 1e3:.2f} |", flush=True)
+    binding.op_set_gemm_wavefronts(0)
 
 
 def cmd_streams(args):
@@ -274,6 +320,12 @@ def main():
     g.add_argument("--launches", type=int, default=50)
     g.add_argument("--waves", type=int, default=0, choices=[0, 4, 8], help="wavefronts per workgroup for 256-row tiles (0: chosen per launch)")
     g.add_argument("--rows", type=int, nargs="*", default=None, help="row counts M to run (default: 512 .. 16384)")
+    gp = sub.add_parser("gemm-phases")
+    gp.add_argument("--m", type=int, default=8192)
+    gp.add_argument("--n", type=int, default=8192)
+    gp.add_argument("--k", type=int, default=2048)
+    gp.add_argument("--f32-residual", action="store_true", help="float32 output with a residual (the attention-output / FC2 epilogue)")
+    gp.add_argument("--launches", type=int, default=100)
     s = sub.add_parser("streams")
     s.add_argument("--elements", type=int, default=100 * 1024 * 1024)
     s.add_argument("--ring", type=int, default=4)
@@ -292,7 +344,7 @@ def main():
     t.add_argument("--steps", type=int, required=True)
     t.add_argument("--workload", default="opt-1.3b shape, bf16 resident, batch 16 x seq 256 (bench.py)")
     args = ap.parse_args()
-    {"gemm": cmd_gemm, "streams": cmd_streams, "copy": cmd_copy, "link": cmd_link, "small-steps": cmd_small_steps, "traffic": cmd_traffic}[args.cmd](args)
+    {"gemm": cmd_gemm, "gemm-phases": cmd_gemm_phases, "streams": cmd_streams, "copy": cmd_copy, "link": cmd_link, "small-steps": cmd_small_steps, "traffic": cmd_traffic}[args.cmd](args)
 
 
 if __name__ == "__main__":

@@ -177,3 +177,14 @@ def test_lm_head_ce_small_and_bad_shapes():
         b.op_lm_head_ce(X.float().cuda(), W.float().cuda(), lab.cuda())      # float32 has no fused path
     with pytest.raises(b.Zo2Error):
         b.op_lm_head_ce(X[:, :64].contiguous().cuda(), W[:, :64].contiguous().cuda(), lab.cuda())   # K is not a multiple of 128
+
+
+def test_gemm_phases_needs_the_instrumented_build():
+    """The ordinary library carries no cycle stamps: the measurement entry point says so instead of running."""
+    b = _b()
+    X = torch.zeros(256, 128, dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros(256, 128, dtype=torch.bfloat16, device="cuda")
+    Y = torch.empty(256, 256, dtype=torch.bfloat16, device="cuda")
+    stamps = torch.zeros(64, dtype=torch.int64, device="cuda")
+    with pytest.raises(b.Zo2Error):
+        b.op_gemm_phases(X, W, Y, stamps)

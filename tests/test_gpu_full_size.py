@@ -224,6 +224,32 @@ def test_one_block_model_at_full_width_and_batch_matches_oracle():
     ctx.close()
 
 
+@pytest.mark.timeout(1500)
+def test_benchmark_model_in_depth_matches_oracle():
+    """The benchmark's configuration itself (OPT-1.3B width, vocabulary, batch 16 x 256, bf16) over 6 of its 24 decoder
+    blocks by default - the oracle takes 20 - 25 s per step at this depth - two steps, the second with a pending update.
+    ZO2_TEST_FULL_DEPTH_LAYERS=24 runs the full depth (about 75 + 100 s of oracle time): measured there, l+ / l- of the
+    library against the oracle 11.186573 / 11.289658 against 11.186556 / 11.289668 in the first step and 11.234412 /
+    11.234637 against 11.234462 / 11.234437 in the second, i.e. 2e-6 - 2e-5 relative, far inside the bf16 bar."""
+    import os
+    b = _b()
+    layers = int(os.environ.get("ZO2_TEST_FULL_DEPTH_LAYERS", "6"))
+    cfg = si.opt_config("opt-1.3b", n_layers=layers)
+    P = si.make_weights(cfg, seed=1)
+    tok = si.make_tokens(V, B, S, seed=2, dist="zipf")
+    lab = si.next_token_labels(tok)
+    Po = {n: codec.round_to(a, "bf16") for n, a in P.items()}
+    oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), Po, store="bf16", compute="bf16")
+    ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=20 << 30)
+    for j in range(2):
+        a = oz.step(tok, lab, 42 + j, 1e-3, 1e-7)
+        g = ctx.step(tok, lab, 42 + j, 1e-3, 1e-7)
+        print(j, a, g, flush=True)
+        assert abs(float(g[0]) - float(a[0])) <= 2e-3 * abs(float(a[0]))      # a tenth of the bf16 bar: measured 2e-5
+        assert abs(float(g[1]) - float(a[1])) <= 2e-3 * abs(float(a[1]))
+    ctx.close()
+
+
 @pytest.mark.parametrize("n_seq,seq,heads,dh", [(2, 2048, 4, 128), (2, 2048, 4, 80), (1, 8192, 2, 64)])
 def test_attention_long_sequences_sampled_queries(n_seq, seq, heads, dh):
     """Sequence lengths of the paper's main setting (2048: OPT-2.7B's d_head 80, the d_head 128 of 6.7B-175B) and of

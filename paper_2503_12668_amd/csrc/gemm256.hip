@@ -103,8 +103,12 @@ __device__ __forceinline__ void m0_set(uint32_t lds_base) { asm volatile("s_mov_
 // `lanes` (wave-uniform: all ones or zero) is the execution mask of the load: zero turns it into a no-op without a
 // branch, so that the compiler sees straight-line code and keeps one register assignment for the accumulators over the
 // whole k loop (see Mfma16).  The k loop runs with all 64 lanes active, which is what the mask is restored to.
-__device__ __forceinline__ void load_to_lds_masked(const void* sbase, uint32_t voff, uint32_t lds_base, uint64_t lanes) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_mov_b64 exec, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, -1" : : "s"(lds_base), "v"(voff), "s"(sbase), "s"(lanes) : "memory");
+// (`lanes`: all ones or zero, wave-uniform; both halves of the execution mask are set from it.  It is pinned into a scalar
+// register here: left to the register allocator, a mask that lives across the k loop can end up in a vector register when
+// scalar registers run short, which this instruction cannot take.)
+__device__ __forceinline__ void load_to_lds_masked(const void* sbase, uint32_t voff, uint32_t lds_base, uint32_t lanes) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_mov_b32 exec_lo, %3\n\ts_mov_b32 exec_hi, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, -1"
+                 : : "s"(lds_base), "v"(voff), "s"(sbase), "s"(__builtin_amdgcn_readfirstlane(lanes)) : "memory");
 }
 __device__ __forceinline__ void load_to_lds_at_m0_masked(const void* sbase, uint32_t voff, uint64_t lanes) {
     asm volatile("s_mov_b64 exec, %2\n\tglobal_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1" : : "v"(voff), "s"(sbase), "s"(lanes) : "memory");
@@ -274,7 +278,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
         // with the same pieces of the slab at byte offset `soff` of the panels.
         // stage_out, eight wavefronts: the group issues one of the wavefront's eight direct-to-LDS loads of the slab at k
         // offset `soff` (elements) into stage `st`; `lanes` is all ones, or zero where that slab does not exist.
-        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff, uint64_t lanes = 0) {
+        auto mgroup = [&](int i, int buf, int nbuf, const char* sa, const char* sb, bool stage_out, int st, uint32_t soff, uint32_t lanes = 0) {
           if constexpr (NW == 8) {
             // four MFMAs per group; group i issues load i of the incoming slab (W rows in groups 0 - 3, X rows in
             // groups 4 - 7: inside a step the weights come from HBM and the activations from the caches, so the weights
@@ -369,8 +373,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_mfma256_kernel(const GemmArgs
         auto slab_iter = [&](int kt, auto stage_c) {
             constexpr int cur = decltype(stage_c)::value;          // kt & 1
             if constexpr (!kStaged) {
-                const uint32_t lm = __builtin_amdgcn_readfirstlane(kt + 2 < nk ? 0xffffffffu : 0u);
-                const uint64_t lanes = ((uint64_t)lm << 32) | lm;
+                const uint32_t lanes = __builtin_amdgcn_readfirstlane(kt + 2 < nk ? 0xffffffffu : 0u);
                 const uint32_t k2 = (uint32_t)((kt + 2 < nk ? kt + 2 : kt) * kBK);
 #pragma unroll
                 for (int i = 0; i < MI; ++i) mgroup(i, 0, 1, frag_x[cur][1], frag_w[cur][1], false, 0, 0u);

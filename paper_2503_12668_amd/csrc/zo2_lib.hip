@@ -1274,69 +1274,69 @@ static zo2_status model_pass(zo2_ctx* c, const char* who, const int32_t* tokens,
     // DualForward(LM head): final LayerNorm, (tied) vocabulary matrix, loss
     TraceRange head_range("lm_head + loss");
     for (int j = 0; j < ndirs; ++j) {
-    const uint64_t seed = seeds[j];
-    set_dir(j);
-    if (c->apply_now)
-        for (int k = 0; k + 1 < c->n_pend; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
-    { zo2_status s = k1_final_ln(c, true, seed, eps); if (s != ZO2_OK) return s; }
-    const size_t boff = (size_t)c->fln_off_b * c->csz;
-    OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, ns * T, T, d, g.ln_eps, c->sc));
-    {
-        const int sb = g.n_layers & 1;
-        c->wp = c->wps[sb];
-        c->wm = c->wms[sb];
-        hipStream_t st = c->sc;
-        if (c->overlap_k1) {      // the vocabulary matrix is swept under the last block's forwards
-            st = c->sk;
-            HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_embed, 0));                  // the gather read the table before its update
-            if (g.n_layers >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
+        const uint64_t seed = seeds[j];
+        set_dir(j);
+        if (c->apply_now)
+            for (int k = 0; k + 1 < c->n_pend; ++k) { zo2_status s = k1_final_ln(c, false, 0, 0.f, k); if (s != ZO2_OK) return s; }
+        { zo2_status s = k1_final_ln(c, true, seed, eps); if (s != ZO2_OK) return s; }
+        const size_t boff = (size_t)c->fln_off_b * c->csz;
+        OPK(c, ZO2_KC_LN, layernorm(dt, c->h, c->fln_wp, c->fln_wp + boff, c->fln_wm, c->fln_wm + boff, c->x, ns * T, T, d, g.ln_eps, c->sc));
+        {
+            const int sb = g.n_layers & 1;
+            c->wp = c->wps[sb];
+            c->wm = c->wms[sb];
+            hipStream_t st = c->sc;
+            if (c->overlap_k1) {      // the vocabulary matrix is swept under the last block's forwards
+                st = c->sk;
+                HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_embed, 0));                  // the gather read the table before its update
+                if (g.n_layers >= 2) HIPCHK(c, hipStreamWaitEvent(c->sk, c->ev_fwd_done[sb], 0));
+            }
+            if (!g.tied_lm_head) { zo2_status es = earlier_updates_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), st); if (es != ZO2_OK) return es; }
+            zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps, st)
+                                          : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps, st);
+            if (s != ZO2_OK) return s;
+            if (c->overlap_k1) {
+                HIPCHK(c, hipEventRecord(c->ev_k1done[sb], c->sk));
+                HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_k1done[sb], 0));
+            }
         }
-        if (!g.tied_lm_head) { zo2_status es = earlier_updates_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), st); if (es != ZO2_OK) return es; }
-        zo2_status s = g.tied_lm_head ? k1_tensor(c, c->d_tok, c->tok_elems, 0, true, c->wp, c->wm, seed, eps, st)
-                                      : k1_tensor(c, c->d_lm, c->tok_elems, lm_tid(c), true, c->wp, c->wm, seed, eps, st);
-        if (s != ZO2_OK) return s;
-        if (c->overlap_k1) {
-            HIPCHK(c, hipEventRecord(c->ev_k1done[sb], c->sk));
-            HIPCHK(c, hipStreamWaitEvent(c->sc, c->ev_k1done[sb], 0));
+        if (c->fused_ce) {
+            // logits are never written: the GEMM epilogue reduces each 64-column span to (max, sum exp) and picks the label's logit
+            GemmArgs ga;
+            memset(&ga, 0, sizeof(ga));
+            ga.M = T; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns; ga.ce_mode = 1; ga.part_ld = 2 * (int64_t)T;
+            for (int s = 0; s < ns; ++s) {
+                GemmProblem& p = ga.p[s];
+                p.X = c->x + (size_t)s * T * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr; p.Y = nullptr;
+                p.out_scale = 1.0f; p.labels = c->d_labels;
+                p.part_max = c->ce_pmax + (size_t)s * T; p.part_sum = c->ce_psum + (size_t)s * T;
+                p.label_logit = c->ce_lab + (size_t)s * T;
+            }
+            OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+            OPK(c, ZO2_KC_CE, ce_combine(c->ce_pmax, c->ce_psum, c->ce_lab, c->d_labels, ns * T, c->ce_parts, 2 * (int64_t)T, 0, T, c->row_loss, c->sc));
+        } else {
+            const int R = c->logit_rows;
+            for (int r0 = 0; r0 < T; r0 += R) {
+                const int rows = std::min(R, T - r0);
+                GemmArgs ga;
+                memset(&ga, 0, sizeof(ga));
+                ga.M = rows; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;
+                for (int s = 0; s < ns; ++s) {
+                    GemmProblem& p = ga.p[s];
+                    p.X = c->x + ((size_t)s * T + r0) * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr;
+                    p.Y = c->logits + (size_t)s * R * g.vocab; p.out_scale = 1.0f;
+                }
+                OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
+                for (int s = 0; s < ns; ++s)
+                    OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
+            }
         }
-    }
-    if (c->fused_ce) {
-        // logits are never written: the GEMM epilogue reduces each 64-column span to (max, sum exp) and picks the label's logit
-        GemmArgs ga;
-        memset(&ga, 0, sizeof(ga));
-        ga.M = T; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns; ga.ce_mode = 1; ga.part_ld = 2 * (int64_t)T;
-        for (int s = 0; s < ns; ++s) {
-            GemmProblem& p = ga.p[s];
-            p.X = c->x + (size_t)s * T * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr; p.Y = nullptr;
-            p.out_scale = 1.0f; p.labels = c->d_labels;
-            p.part_max = c->ce_pmax + (size_t)s * T; p.part_sum = c->ce_psum + (size_t)s * T;
-            p.label_logit = c->ce_lab + (size_t)s * T;
-        }
-        OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-        OPK(c, ZO2_KC_CE, ce_combine(c->ce_pmax, c->ce_psum, c->ce_lab, c->d_labels, ns * T, c->ce_parts, 2 * (int64_t)T, 0, T, c->row_loss, c->sc));
-    } else {
-    const int R = c->logit_rows;
-    for (int r0 = 0; r0 < T; r0 += R) {
-        const int rows = std::min(R, T - r0);
-        GemmArgs ga;
-        memset(&ga, 0, sizeof(ga));
-        ga.M = rows; ga.N = g.vocab; ga.K = d; ga.ldx = d; ga.ldw = d; ga.ldy = g.vocab; ga.relu = 0; ga.out_f32 = 1; ga.nprob = ns;
-        for (int s = 0; s < ns; ++s) {
-            GemmProblem& p = ga.p[s];
-            p.X = c->x + ((size_t)s * T + r0) * d * c->csz; p.W = s ? c->wm : c->wp; p.bias = nullptr; p.residual = nullptr;
-            p.Y = c->logits + (size_t)s * R * g.vocab; p.out_scale = 1.0f;
-        }
-        OPK(c, ZO2_KC_GEMM, gemm_launch(ga, dt, c->sc));
-        for (int s = 0; s < ns; ++s)
-            OPK(c, ZO2_KC_CE, cross_entropy_rows(c->logits + (size_t)s * R * g.vocab, g.vocab, c->d_labels, rows, s * T + r0, T, g.vocab, c->row_loss, c->sc));
-    }
-    }
-    // eta g of this pass: deferred update 0 of a new round (every older one has been applied on the way), or one more of
-    // the current round
-    if (j == 0 && !c->resident && upd && !c->pass_writes_back)      // the coefficients of the updates the blocks' host copies now lack, before slot 0 is rewritten
-        HIPCHK(c, hipMemcpyAsync(stale_slot(c, c->n_stale), coef_slot(c, 0), (size_t)c->n_pend * sizeof(float), hipMemcpyDeviceToDevice, c->sc));
-    OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : j), c->sc));
-    HIPCHK(c, hipMemcpyAsync(pass_result(c, j), c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
+        // eta g of this pass: deferred update 0 of a new round (every older one has been applied on the way), or one more of
+        // the current round
+        if (j == 0 && !c->resident && upd && !c->pass_writes_back)      // the coefficients of the updates the blocks' host copies now lack, before slot 0 is rewritten
+            HIPCHK(c, hipMemcpyAsync(stale_slot(c, c->n_stale), coef_slot(c, 0), (size_t)c->n_pend * sizeof(float), hipMemcpyDeviceToDevice, c->sc));
+        OPK(c, ZO2_KC_CE, loss_epilogue(c->row_loss, c->d_labels, T, eps, lr, ns, c->d_state + 4, coef_slot(c, extra ? c->n_pend : j), c->sc));
+        HIPCHK(c, hipMemcpyAsync(pass_result(c, j), c->d_state + 4, 4 * sizeof(float), hipMemcpyDeviceToHost, c->sc));
     }
     set_dir(0);
     HIPCHK(c, hipEventRecord(c->ev_c1, c->sc));

@@ -390,7 +390,7 @@ zo2_status zo2_op_gemm_phases(int32_t dtype, int32_t M, int32_t N, int32_t K, co
                               const float* residual, void* Y, int32_t out_dtype, int64_t ldy, uint64_t* stamps, void* stream);
 
 /* Launches of 256-row tiles run with eight wavefronts per workgroup (two per SIMD, one k-slab of prefetch) or with
- * four (a further slab in flight in registers), chosen per launch by the length of k.  waves = 4 or 8 forces one form
+ * four (a further slab in flight in registers), chosen per launch by the length of k and the number of rows.  waves = 4 or 8 forces one form
  * for every later launch of the process, step calls included; 0 restores the choice per launch.  For tests and
  * measurements: results are the same bit for bit either way.  Returns ZO2_EINVAL for any other value. */
 zo2_status zo2_op_set_gemm_wavefronts(int32_t waves);

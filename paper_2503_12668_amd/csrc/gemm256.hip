@@ -692,10 +692,12 @@ static int pick_tile_rows(const GemmArgs& a) {
 // (FC2), where a panel's rows lie 16 KB apart and a slab takes longer to arrive from HBM.
 static int g_forced_waves = 0;          // 0: per launch; 4 / 8: every launch of 256-row tiles (tests and measurements)
 void gemm256_force_waves(int waves) { g_forced_waves = waves; }
-static constexpr int kLongK = 6144;
+// With at most 2048 rows per problem a launch leans on reading its weights, and four are ahead again or level (whole
+// steps at 1024 - 2048 tokens per stream, OPT-1.3B / 6.7B / 13B shapes: 0 - 1.5 %).
+static constexpr int kLongK = 6144, kFewRows = 2048;
 static int pick_waves(const GemmArgs& a) {
     if (g_forced_waves == 4 || g_forced_waves == 8) return g_forced_waves;
-    return a.K >= kLongK ? 4 : 8;
+    return (a.K >= kLongK || a.M <= kFewRows) ? 4 : 8;
 }
 
 bool gemm256_applicable(const GemmArgs& a, int dtype) {

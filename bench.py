@@ -203,13 +203,13 @@ def offload_leg(steps=3, budget_legs=True):
 
 def small_steps_leg(ctx, cfg, steps=10):
     """Steps of few tokens on the benchmark's resident context: the perturbation written by the sweep kernel (as in the
-    benchmark step) against generated in the projections' weight loader (what the library does by default up to 128
+    benchmark step) against generated in the projections' weight loader (what the library does by default up to 64
     tokens per stream).  ms per step, wall clock around `steps` steps each."""
     import torch
 
     import synth_inputs as si
     out = {"note": "same resident bf16 context; 'sweep_copies' = zo2_set_loader_fusion(-1), 'loader' = the default", "steps": steps}
-    for (b, s_) in ((1, 16), (1, 128)):
+    for (b, s_) in ((1, 16), (1, 64)):
         tok = si.make_tokens(cfg["vocab"], b, s_, seed=2, dist="zipf")
         lab = si.next_token_labels(tok)
         row = {}
@@ -237,7 +237,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offload", action="store_true", help="skip the streamed (offload-mode) leg")
-    ap.add_argument("--no-small-steps", action="store_true", help="skip the leg with steps of 16 and 128 tokens")
+    ap.add_argument("--no-small-steps", action="store_true", help="skip the leg with steps of 16 and 64 tokens")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a benchmark number)")
     ap.add_argument("--gemm-wavefronts", type=int, default=0, choices=[0, 4, 8],
                     help="measurement aid: run every 256-row GEMM tile with this many wavefronts (0: chosen per launch, the library's default)")

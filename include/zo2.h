@@ -211,7 +211,7 @@ zo2_status zo2_get_scratch_plan(const zo2_ctx* ctx, int32_t* sweeps_per_block, i
  * block slots fit.  Takes effect at the next step.  ZO2_EINVAL for any other value. */
 zo2_status zo2_set_scratch_plan(zo2_ctx* ctx, int32_t sweeps);
 
-/* Where the perturbation of a block's six weight matrices is generated.  By default (mode 0) a step of at most 128
+/* Where the perturbation of a block's six weight matrices is generated.  By default (mode 0) a step of at most 64
  * tokens per stream - where the projections are bound by reading the weights - lets the projections read the stored
  * weights and form W+ / W- in their loader (zo2_op_gemm_perturbed), the sweep kernel then only applies the pending
  * update and perturbs the block's one-dimensional tensors; larger steps write the perturbed copies with the sweep kernel,

@@ -71,7 +71,7 @@ struct TraceRange {
 };
 static constexpr int64_t kTensorAlign = 256;   // elements
 static constexpr int kDefaultSweeps = 1;       // update + perturb sweeps per block when the budget leaves the choice
-static constexpr int kFuseMaxTokens = 128;     // up to this many tokens per stream the projections perturb in their weight loader (measured: steps 1.1 - 1.4x faster up to 128, 0.8x at 256)
+static constexpr int kFuseMaxTokens = 64;      // up to this many tokens per stream the projections perturb in their weight loader (measured, OPT-1.3B shape: steps 1.06 - 1.23x faster up to 64 tokens, 0.96x at 80, 0.93x at 128)
 
 static bool config_ok(const zo2_config* c, char* why, size_t n) {
 #define BAD(...) do { snprintf(why, n, __VA_ARGS__); return false; } while (0)

@@ -35,6 +35,7 @@ def test_fused_loader_steps_track_oracle_and_the_sweep_path(dt, tied):
     Po = {n: codec.round_to(a, dt) for n, a in P.items()}
     oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), copy.deepcopy(Po), store=dt, compute=dt)
     fused = b.Zo2Context(cfg, P, wire=dt, compute=dt, arena_bytes=64 << 20)
+    fused.set_loader_fusion(1)          # 69 tokens: above the default's 64
     plain = b.Zo2Context(cfg, P, wire=dt, compute=dt, arena_bytes=64 << 20)
     plain.set_loader_fusion(-1)
     for j in range(4):
@@ -57,7 +58,7 @@ def test_first_step_of_both_paths_is_the_same_update_free_forward():
     b = _b()
     cfg, P, tok, lab = _tiny(n_layers=2)
     res = []
-    for mode in (0, -1):
+    for mode in (1, -1):
         ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
         ctx.set_loader_fusion(mode)
         res.append(ctx.step(tok, lab, 7, 1e-3, 0.0))
@@ -73,6 +74,7 @@ def test_fused_loader_streamed_equals_resident_bitwise(sr):
     runs = {}
     for name in ("resident", "streamed"):
         ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
+        ctx.set_loader_fusion(1)
         ctx.set_wire_rounding(sr)
         r = [ctx.step(tok, lab, 5, 1e-3, 1e-3)]
         if name == "streamed":
@@ -98,6 +100,7 @@ def test_zero_lr_leaves_parameters_in_the_fused_path():
     b = _b()
     cfg, P, tok, lab = _tiny(n_layers=2)
     ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
+    ctx.set_loader_fusion(1)
     r1 = ctx.step(tok, lab, 5, 1e-3, 0.0)
     r2 = ctx.step(tok, lab, 5, -1e-3, 0.0)
     assert ctx.plan()["loader_fusion"]
@@ -122,6 +125,7 @@ def test_fused_loader_one_block_at_opt1p3b_width_matches_oracle():
     Po = {n: codec.round_to(a, "bf16") for n, a in P.items()}
     oz = zo_step.Zo2Blockwise(opt_model.OptShape(**cfg), Po, store="bf16", compute="bf16")
     ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=2 << 30)
+    ctx.set_loader_fusion(1)
     for j in range(2):
         a = oz.step(tok, lab, 42 + j, 1e-3, 1e-4)
         g = ctx.step(tok, lab, 42 + j, 1e-3, 1e-4)
@@ -129,4 +133,15 @@ def test_fused_loader_one_block_at_opt1p3b_width_matches_oracle():
         assert abs(float(g[0]) - float(a[0])) <= 2e-2 * abs(float(a[0]))
         assert abs(float(g[1]) - float(a[1])) <= 2e-2 * abs(float(a[1]))
     assert ctx.plan()["loader_fusion"]
+    ctx.close()
+
+
+def test_default_takes_the_loader_path_up_to_64_tokens_per_stream():
+    b = _b()
+    cfg, P, tok, lab = _tiny(n_layers=2)
+    ctx = b.Zo2Context(cfg, P, wire="bf16", compute="bf16", arena_bytes=64 << 20)
+    for batch, seq, want in ((2, 32, True), (4, 16, True), (3, 23, False), (5, 13, False)):
+        t = si.make_tokens(cfg["vocab"], batch, seq, seed=3)
+        ctx.step(t, si.next_token_labels(t), 9, 1e-3, 0.0)
+        assert ctx.plan()["loader_fusion"] == want, (batch, seq)
     ctx.close()

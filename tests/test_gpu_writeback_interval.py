@@ -19,13 +19,13 @@ def _b():
 def _tiny(n_layers=6, d_model=64, d_ffn=128):
     cfg = si.tiny_config(n_layers=n_layers, d_model=d_model, n_heads=4, d_ffn=d_ffn, vocab=211, max_pos=48)
     P = si.make_weights(cfg, seed=11, std=0.08, ln_jitter=True)
-    tok = si.make_tokens(cfg["vocab"], 3, 37, seed=12)         # 111 tokens: the loader path is active for 16-bit storage
+    tok = si.make_tokens(cfg["vocab"], 3, 37, seed=12)         # 111 tokens: with zo2_set_loader_fusion(1) (below) the loader path is active for 16-bit storage
     lab = si.next_token_labels(tok)
     lab[1, 4] = -100
     return cfg, P, tok, lab
 
 
-def _run(b, cfg, P, tok, lab, wire, compute, mode, interval, sr=False, scales=None, fusion=0):
+def _run(b, cfg, P, tok, lab, wire, compute, mode, interval, sr=False, scales=None, fusion=1):
     ctx = b.Zo2Context(cfg, P, wire=wire, compute=compute, arena_bytes=64 << 20, scales=scales)
     ctx.set_wire_rounding(sr)
     ctx.set_loader_fusion(fusion)
